@@ -1,0 +1,244 @@
+"""CPU oracle for the denoise-step path of masked-diffusion LLM decoding.  TEST INFRASTRUCTURE ONLY.
+
+This file is the plain definition of what the HIP path computes, written out in numpy float64.
+It is slow on purpose, shares no code with the HIP path, and must only be imported by tests, by
+the smoke check and by the benchmark's CPU-baseline leg.  Nothing in the product path may call it.
+
+What follows which passage of the paper (d3LLM, arxiv 2601.07568):
+  * bidirectional (unmasked) attention between all tokens present in a forward  -- Section 1
+    ("bidirectional attention") and the appendix on the serving-engine integration, item (i);
+  * a cache of the key/value states of the prompt and of completed blocks, and forward passes
+    that do not use the cache and rewrite it -- Section 3.2, "KV-Cache and KV-Refresh Mechanism"
+    and the description of the "Completed but Stabilizing" state;
+  * selecting, in every forward, the tokens whose prediction is confident enough, and decoding
+    at least a minimum number per forward regardless of the threshold -- Section 3.2,
+    "Entropy-Based Multi-Block Parallel Decoding"; the max-probability form of the rule is the
+    threshold rule Section 2 attributes to Fast-dLLM;
+  * unmasking exactly one token per step (the teacher's trajectory) -- Section 3.1; this is the
+    same step with a threshold above 1 and a floor of 1;
+  * block size 32, greedy decoding -- appendix, "Inference Settings".
+The paper does not describe the transformer itself (it names LLaDA / Dream).  The layer used here
+is the usual pre-norm one: RMSNorm, rotary position embedding in the half-split pairing,
+multi-/grouped-query attention, SwiGLU MLP, untied LM head, no biases.
+
+Parity pins (tests/test_oracle_*.py): brute-force attention, an independent float64 composition
+out of torch library routines, closed forms of the confidence, cache == recompute, rotary shift
+invariance, non-causality, selection invariants and a sort-based selection.  The paper prints no
+numerical value for any of these functions, so beyond those pins the numbers are unpinned by the
+paper itself.
+
+Weights are dicts of arrays, linear weights [out_features, in_features].  `model` is any object
+with .ms (shape record with n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab,
+mask_id, rms_eps, rope_base), .layer(l) -> dict and ["tok_emb" | "final_norm" | "lm_head"].
+All inputs are converted to float64 on entry (the conversion function is passed in by the
+caller, default: numpy's astype).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _f64(a, widen=None):
+    if widen is not None:
+        a = widen(a)
+    return np.asarray(a, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- layer pieces
+
+def rmsnorm(x, gain, eps):
+    """x * rsqrt(mean(x^2) + eps) * gain over the last axis."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * gain
+
+
+def rope(v, pos, base):
+    """Rotary embedding, half-split pairing.  v: [S, H, dh]; pos: [S] absolute positions.
+    Pair (j, j + dh/2) is rotated by the angle pos * base**(-2j/dh)."""
+    v = np.asarray(v, dtype=np.float64)
+    S, H, dh = v.shape
+    half = dh // 2
+    j = np.arange(half, dtype=np.float64)
+    theta = base ** (-2.0 * j / dh)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * theta[None, :]       # [S, half]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    a, b = v[..., :half], v[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def attention(q, k, v):
+    """softmax(q k^T / sqrt(dh)) v with no mask.  q: [Sq, H, dh]; k, v: [Sk, Hkv, dh].
+    Query head h reads key/value head h // (H / Hkv)."""
+    Sq, H, dh = q.shape
+    Hkv = k.shape[1]
+    group = H // Hkv
+    out = np.empty((Sq, H, dh), dtype=np.float64)
+    for h in range(H):
+        kh = h // group
+        s = q[:, h, :] @ k[:, kh, :].T / np.sqrt(dh)                        # [Sq, Sk]
+        s = s - s.max(axis=-1, keepdims=True)
+        p = np.exp(s)
+        p = p / p.sum(axis=-1, keepdims=True)
+        out[:, h, :] = p @ v[:, kh, :]
+    return out
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def layer_qkv(ms, lw, x, pos, widen=None):
+    """Normalised input -> rotated q, rotated k, v for the rows of x at absolute positions pos."""
+    S = x.shape[0]
+    h = rmsnorm(x, _f64(lw["attn_norm"], widen), ms.rms_eps)
+    q = (h @ _f64(lw["wq"], widen).T).reshape(S, ms.n_q_heads, ms.head_dim)
+    k = (h @ _f64(lw["wk"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
+    v = (h @ _f64(lw["wv"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
+    return rope(q, pos, ms.rope_base), rope(k, pos, ms.rope_base), v
+
+
+def layer_finish(ms, lw, x, o, widen=None):
+    """Output projection + residual, then SwiGLU MLP + residual."""
+    S = x.shape[0]
+    x = x + o.reshape(S, -1) @ _f64(lw["wo"], widen).T
+    h = rmsnorm(x, _f64(lw["mlp_norm"], widen), ms.rms_eps)
+    g = h @ _f64(lw["w_gate"], widen).T
+    u = h @ _f64(lw["w_up"], widen).T
+    return x + (silu(g) * u) @ _f64(lw["w_down"], widen).T
+
+
+def head_logits(model, x, widen=None):
+    """Final norm and LM head: raw logits [rows, vocab] (row i predicts position i, no shift)."""
+    ms = model.ms
+    h = rmsnorm(x, _f64(model["final_norm"], widen), ms.rms_eps)
+    return h @ _f64(model["lm_head"], widen).T
+
+
+# --------------------------------------------------------------------------- forwards
+
+def forward_full(model, tokens, n_layers=None, widen=None, want_logits=True, pos0=0):
+    """No-cache forward over one sequence: every token attends to every token.
+    Returns (logits [S, V] or None, K [L][S, Hkv, dh], V [L][...], hidden [S, d])."""
+    ms = model.ms
+    L = ms.n_layers if n_layers is None else n_layers
+    tokens = np.asarray(tokens)
+    S = tokens.shape[0]
+    pos = np.arange(S) + pos0
+    x = _f64(np.asarray(model["tok_emb"])[tokens], widen)
+    Ks, Vs = [], []
+    for l in range(L):
+        lw = model.layer(l)
+        q, k, v = layer_qkv(ms, lw, x, pos, widen)
+        Ks.append(k)
+        Vs.append(v)
+        x = layer_finish(ms, lw, x, attention(q, k, v), widen)
+    logits = head_logits(model, x, widen) if want_logits else None
+    return logits, Ks, Vs, x
+
+
+def prefill(model, tokens, n_cache=None, n_layers=None, widen=None):
+    """Key/value states of the first n_cache positions taken from a no-cache forward over
+    `tokens` (which may extend past n_cache, e.g. include in-flight blocks)."""
+    _, Ks, Vs, _ = forward_full(model, tokens, n_layers, widen, want_logits=False)
+    n = len(tokens) if n_cache is None else n_cache
+    return [k[:n] for k in Ks], [v[:n] for v in Vs]
+
+
+def forward_cached(model, block_tokens, cache_k, cache_v, n_layers=None, widen=None,
+                   want_logits=True, stop_layer=None):
+    """Denoise-step forward: the Q block tokens sit at positions P..P+Q-1 and attend to the
+    cached prefix (P = cache length) and to themselves.  Returns (logits [Q, V], hidden [Q, d])."""
+    ms = model.ms
+    L = ms.n_layers if n_layers is None else n_layers
+    if stop_layer is not None:
+        L = stop_layer
+    block_tokens = np.asarray(block_tokens)
+    Q = block_tokens.shape[0]
+    P = cache_k[0].shape[0] if len(cache_k) else 0
+    pos = np.arange(Q) + P
+    x = _f64(np.asarray(model["tok_emb"])[block_tokens], widen)
+    for l in range(L):
+        lw = model.layer(l)
+        q, k, v = layer_qkv(ms, lw, x, pos, widen)
+        kk = np.concatenate([_f64(cache_k[l], widen), k], axis=0)
+        vv = np.concatenate([_f64(cache_v[l], widen), v], axis=0)
+        x = layer_finish(ms, lw, x, attention(q, kk, vv), widen)
+    logits = head_logits(model, x, widen) if want_logits else None
+    return logits, x
+
+
+# --------------------------------------------------------------------------- confidence + select
+
+def confidence(logits, mask_id):
+    """Per row: candidate token (arg max, lowest id on ties), its softmax probability, and the
+    entropy of the row in nats.  The mask id itself can never be predicted: its column is
+    taken out of the softmax."""
+    z = np.array(logits, dtype=np.float64, copy=True)
+    z[:, mask_id] = -np.inf
+    cand = np.argmax(z, axis=-1)
+    zmax = z[np.arange(z.shape[0]), cand]
+    e = np.exp(z - zmax[:, None])
+    lse = np.log(e.sum(axis=-1)) + zmax
+    p = np.exp(z - lse[:, None])
+    conf = np.exp(zmax - lse)
+    zz = np.where(np.isfinite(z), z, 0.0)
+    entropy = lse - (p * zz).sum(axis=-1)
+    return cand.astype(np.int64), conf, entropy, p
+
+
+def unmask(tokens, cand, conf, mask_id, tau, m):
+    """Threshold + floor selection on one block.  Masked positions with conf >= tau are
+    unmasked, and so are the m' = min(m, #masked) most confident masked positions (highest
+    confidence first, lowest index first among equals).  Returns (new tokens, chosen indices)."""
+    tokens = np.array(tokens, copy=True)
+    masked = [i for i in range(len(tokens)) if tokens[i] == mask_id]
+    chosen = {i for i in masked if conf[i] >= tau}
+    order = sorted(masked, key=lambda i: (-conf[i], i))
+    chosen.update(order[:min(m, len(masked))])
+    for i in chosen:
+        tokens[i] = cand[i]
+    return tokens, sorted(chosen)
+
+
+def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, widen=None,
+                 n_layers=None):
+    """One whole step on a window of one or more blocks: forward, confidence of the masked
+    rows, selection per block.  Returns dict with new tokens, cand, conf, entropy, chosen,
+    logits."""
+    ms = model.ms
+    block_tokens = np.asarray(block_tokens)
+    Q = len(block_tokens)
+    bl = Q if block_len is None else block_len
+    logits, _ = forward_cached(model, block_tokens, cache_k, cache_v, n_layers, widen)
+    cand, conf, ent, _ = confidence(logits, ms.mask_id)
+    new = np.array(block_tokens, copy=True)
+    chosen_all = []
+    for b0 in range(0, Q, bl):
+        sl = slice(b0, b0 + bl)
+        new[sl], ch = unmask(block_tokens[sl], cand[sl], conf[sl], ms.mask_id, tau, m)
+        chosen_all += [b0 + i for i in ch]
+    return {"tokens": new, "cand": cand, "conf": conf, "entropy": ent, "chosen": chosen_all,
+            "logits": logits}
+
+
+def decode(model, prompt, n_blocks, block_len, tau, m, widen=None, n_layers=None,
+           record=None):
+    """Sequential-block decoding: cache the prompt, then for each block append block_len mask
+    ids, run denoise steps until none is left, refresh the cache with a no-cache forward over
+    everything decoded so far, go on.  Returns (all tokens, number of forwards with cache)."""
+    ms = model.ms
+    seq = np.array(prompt, dtype=np.int64, copy=True)
+    ck, cv = prefill(model, seq, None, n_layers, widen)
+    steps = 0
+    for _ in range(n_blocks):
+        blk = np.full(block_len, ms.mask_id, dtype=np.int64)
+        while (blk == ms.mask_id).any():
+            r = denoise_step(model, blk, ck, cv, tau, m, None, widen, n_layers)
+            if record is not None:
+                record.append({"before": blk.copy(), **r})
+            blk = r["tokens"]
+            steps += 1
+        seq = np.concatenate([seq, blk])
+        ck, cv = prefill(model, seq, None, n_layers, widen)      # refresh at the block boundary
+    return seq, steps

@@ -1,0 +1,368 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself.
+
+Brute force with python loops, an independent float64 composition out of torch library routines
+(a different library, a different rotary formulation via complex numbers), closed forms of the
+softmax statistics, and invariants that follow from the definition of the cached step."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dllm_oracle as O
+from paper_2601_07568_amd import synth
+
+TINY = synth.TINY
+
+
+class DictModel:
+    def __init__(self, ms, layers, glob):
+        self.ms, self._layers, self._g = ms, layers, glob
+
+    def layer(self, l):
+        return self._layers[l]
+
+    def __getitem__(self, k):
+        return self._g[k]
+
+
+def small_model(seed=3, **kw):
+    ms = synth.ModelShape(2, 32, 4, 2, 8, 48, 50, 49, dtype="f32", lm_head_scale=8.0, **kw)
+    w = synth.Weights(ms, seed)
+    layers = [dict(w.layer(l)) for l in range(ms.n_layers)]
+    # non-trivial gains so that a dropped gain fails
+    rng = np.random.default_rng(seed)
+    for lw in layers:
+        lw["attn_norm"] = (1 + 0.3 * rng.standard_normal(ms.d_model)).astype(np.float32)
+        lw["mlp_norm"] = (1 + 0.3 * rng.standard_normal(ms.d_model)).astype(np.float32)
+        for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            lw[n] = lw[n] * 10                                 # make every sub-block matter
+    g = {k: np.array(w[k]) for k in ("tok_emb", "lm_head", "final_norm")}
+    g["tok_emb"] = g["tok_emb"] * 30
+    g["final_norm"] = (1 + 0.3 * rng.standard_normal(ms.d_model)).astype(np.float32)
+    return DictModel(ms, layers, g)
+
+
+# ------------------------------------------------------------------ attention: brute force
+
+def brute_attention(q, k, v):
+    Sq, H, dh = q.shape
+    Sk, Hkv, _ = k.shape
+    out = np.zeros((Sq, H, dh))
+    for i in range(Sq):
+        for h in range(H):
+            kh = h // (H // Hkv)
+            sc = [sum(q[i, h, t] * k[j, kh, t] for t in range(dh)) / math.sqrt(dh) for j in range(Sk)]
+            mx = max(sc)
+            w = [math.exp(s - mx) for s in sc]
+            tot = sum(w)
+            for j in range(Sk):
+                for t in range(dh):
+                    out[i, h, t] += w[j] / tot * v[j, kh, t]
+    return out
+
+
+def test_attention_brute_force_mha_and_gqa():
+    rng = np.random.default_rng(0)
+    for H, Hkv in ((3, 3), (4, 2), (6, 1)):
+        q = rng.standard_normal((5, H, 4))
+        k = rng.standard_normal((7, Hkv, 4))
+        v = rng.standard_normal((7, Hkv, 4))
+        np.testing.assert_allclose(O.attention(q, k, v), brute_attention(q, k, v), rtol=1e-12, atol=1e-13)
+
+
+def test_gqa_equals_mha_with_replicated_heads():
+    rng = np.random.default_rng(1)
+    q = rng.standard_normal((6, 8, 4))
+    k = rng.standard_normal((9, 2, 4))
+    v = rng.standard_normal((9, 2, 4))
+    np.testing.assert_allclose(O.attention(q, k, v),
+                               O.attention(q, np.repeat(k, 4, axis=1), np.repeat(v, 4, axis=1)),
+                               rtol=1e-13)
+
+
+def test_attention_rows_are_convex_combinations():
+    rng = np.random.default_rng(2)
+    q = rng.standard_normal((4, 2, 8)) * 3
+    k = rng.standard_normal((10, 2, 8))
+    v = np.ones((10, 2, 8))
+    np.testing.assert_allclose(O.attention(q, k, v), 1.0, rtol=1e-13)      # weights sum to one
+
+
+# ------------------------------------------------------------------ rotary
+
+def test_rope_closed_forms():
+    # dh = 2: a single pair, theta = 1: plain rotation by pos radians
+    v = np.array([[[1.0, 0.0]], [[1.0, 0.0]], [[0.0, 1.0]]])
+    out = O.rope(v, np.array([0.0, math.pi / 2, math.pi / 2]), 10000.0)
+    np.testing.assert_allclose(out[0, 0], [1, 0], atol=1e-15)
+    np.testing.assert_allclose(out[1, 0], [0, 1], atol=1e-15)
+    np.testing.assert_allclose(out[2, 0], [-1, 0], atol=1e-15)
+    # dh = 4, base 100: second pair (1, 3) turns by pos * 100**(-2/4) = pos / 10
+    v = np.zeros((1, 1, 4)); v[0, 0, 1] = 1.0
+    out = O.rope(v, np.array([5.0]), 100.0)
+    np.testing.assert_allclose(out[0, 0], [0, math.cos(0.5), 0, math.sin(0.5)], atol=1e-15)
+
+
+def test_rope_inner_product_depends_on_relative_position():
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((1, 1, 16)); k = rng.standard_normal((1, 1, 16))
+    d0 = (O.rope(q, [7], 10000.0) * O.rope(k, [3], 10000.0)).sum()
+    d1 = (O.rope(q, [107], 10000.0) * O.rope(k, [103], 10000.0)).sum()
+    assert abs(d0 - d1) < 1e-12
+    assert abs(d0 - (q * k).sum()) > 1e-3
+
+
+# ------------------------------------------------------------------ independent library witness
+
+def torch_forward_full(model, tokens):
+    """Same network from torch library routines in float64; rotary through complex numbers."""
+    ms = model.ms
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    S = len(tokens)
+    x = t(model["tok_emb"])[torch.as_tensor(tokens, dtype=torch.long)]
+    half = ms.head_dim // 2
+    inv = 1.0 / (ms.rope_base ** (torch.arange(0, ms.head_dim, 2, dtype=torch.float64) / ms.head_dim))
+    rot = torch.polar(torch.ones(S, half, dtype=torch.float64),
+                      torch.arange(S, dtype=torch.float64)[:, None] * inv[None, :])        # e^{i pos theta}
+
+    def rope_c(v):                                   # v [S, H, dh] -> pairs (j, j+half) as complex
+        c = torch.complex(v[..., :half], v[..., half:]) * rot[:, None, :]
+        return torch.cat([c.real, c.imag], dim=-1)
+
+    for l in range(ms.n_layers):
+        lw = model.layer(l)
+        h = F.rms_norm(x, (ms.d_model,), t(lw["attn_norm"]), ms.rms_eps)
+        q = rope_c(F.linear(h, t(lw["wq"])).view(S, ms.n_q_heads, ms.head_dim))
+        k = rope_c(F.linear(h, t(lw["wk"])).view(S, ms.n_kv_heads, ms.head_dim))
+        v = F.linear(h, t(lw["wv"])).view(S, ms.n_kv_heads, ms.head_dim)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], enable_gqa=True)[0]
+        x = x + F.linear(o.transpose(0, 1).reshape(S, -1), t(lw["wo"]))
+        h = F.rms_norm(x, (ms.d_model,), t(lw["mlp_norm"]), ms.rms_eps)
+        x = x + F.linear(F.silu(F.linear(h, t(lw["w_gate"]))) * F.linear(h, t(lw["w_up"])), t(lw["w_down"]))
+    h = F.rms_norm(x, (ms.d_model,), t(model["final_norm"]), ms.rms_eps)
+    return F.linear(h, t(model["lm_head"])).numpy()
+
+
+def test_forward_full_matches_torch_composition_small():
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 5, 11)
+    logits, _, _, _ = O.forward_full(model, toks)
+    ref = torch_forward_full(model, toks)
+    assert np.abs(ref).max() > 1.0
+    np.testing.assert_allclose(logits, ref, rtol=1e-9, atol=1e-9)
+
+
+def test_forward_full_matches_torch_composition_tiny_config():
+    w = synth.Weights(TINY, 0)
+    toks = np.concatenate([synth.random_tokens(TINY, 0, 64), np.full(32, TINY.mask_id, dtype=np.int32)])
+    logits, _, _, _ = O.forward_full(w, toks)
+    ref = torch_forward_full(w, toks)
+    scale = np.abs(ref).max()
+    assert np.abs(logits - ref).max() / scale < 1e-9
+
+
+# ------------------------------------------------------------------ confidence: closed forms
+
+def test_confidence_closed_forms():
+    V, mask_id = 50, 49
+    z = np.full((1, V), 3.25)
+    cand, conf, ent, p = O.confidence(z, mask_id)
+    assert cand[0] == 0
+    assert abs(conf[0] - 1 / (V - 1)) < 1e-15 and abs(ent[0] - math.log(V - 1)) < 1e-12
+    assert p[0, mask_id] == 0
+    z = np.zeros((1, V)); z[0, 17] = 60.0; z[0, mask_id] = 1000.0       # mask column is ignored
+    cand, conf, ent, _ = O.confidence(z, mask_id)
+    assert cand[0] == 17 and abs(conf[0] - 1) < 1e-12 and ent[0] < 1e-10
+    # two-way tie -> lowest id, conf from the closed form
+    z = np.zeros((1, V)); z[0, 30] = z[0, 7] = math.log(4.0)
+    cand, conf, _, _ = O.confidence(z, mask_id)
+    assert cand[0] == 7 and abs(conf[0] - 4.0 / (8 + V - 3)) < 1e-15
+
+
+def test_confidence_rows_sum_to_one_and_bounds():
+    rng = np.random.default_rng(5)
+    z = rng.standard_normal((9, 200)) * 4
+    cand, conf, ent, p = O.confidence(z, 199)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(conf, p.max(-1), rtol=1e-13)
+    ref_ent = -(p[:, :199] * np.log(p[:, :199])).sum(-1)
+    np.testing.assert_allclose(ent, ref_ent, rtol=1e-10)
+    assert (conf > 1 / 199).all() and (conf <= 1).all()
+    # torch witness for the softmax itself
+    pt = torch.softmax(torch.from_numpy(z[:, :199]), dim=-1).numpy()
+    np.testing.assert_allclose(p[:, :199], pt, rtol=1e-12)
+
+
+def test_zero_output_projections_isolate_the_head():
+    model = small_model()
+    for lw in model._layers:
+        lw["wo"] = np.zeros_like(lw["wo"]); lw["w_down"] = np.zeros_like(lw["w_down"])
+    toks = synth.random_tokens(model.ms, 9, 6)
+    logits, _, _, _ = O.forward_full(model, toks)
+    e = np.asarray(model["tok_emb"], dtype=np.float64)[toks]
+    hn = e / np.sqrt((e * e).mean(-1, keepdims=True) + model.ms.rms_eps) * model["final_norm"]
+    np.testing.assert_allclose(logits, hn @ np.asarray(model["lm_head"], dtype=np.float64).T, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ cache invariants
+
+def test_cache_equals_recompute():
+    model = small_model()
+    ms = model.ms
+    P, Q = 9, 5
+    toks = synth.random_tokens(ms, 1, P + Q)
+    toks[P + 1] = ms.mask_id; toks[P + 3] = ms.mask_id
+    full, Ks, Vs, _ = O.forward_full(model, toks)
+    ck, cv = [k[:P] for k in Ks], [v[:P] for v in Vs]                     # refresh(tokens, n_commit=P)
+    got, _ = O.forward_cached(model, toks[P:], ck, cv)
+    np.testing.assert_allclose(got, full[P:], rtol=1e-10, atol=1e-12)
+    ck2, cv2 = O.prefill(model, toks, n_cache=P)
+    for a, b in zip(ck, ck2):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_prompt_only_prefill_differs_from_joint_forward():
+    # A cache taken from the prompt alone is a different function (prompt rows did not see the block).
+    model = small_model()
+    P, Q = 9, 5
+    toks = synth.random_tokens(model.ms, 1, P + Q)
+    full, _, _, _ = O.forward_full(model, toks)
+    ck, cv = O.prefill(model, toks[:P])
+    got, _ = O.forward_cached(model, toks[P:], ck, cv)
+    assert np.abs(got - full[P:]).max() > 1e-6
+    # ... and equals a forward in which prompt rows attend to the prompt only: build it by hand
+    ms = model.ms
+    x = np.asarray(model["tok_emb"], dtype=np.float64)[toks]
+    pos = np.arange(P + Q)
+    for l in range(ms.n_layers):
+        lw = model.layer(l)
+        q, k, v = O.layer_qkv(ms, lw, x, pos)
+        o = np.concatenate([O.attention(q[:P], k[:P], v[:P]), O.attention(q[P:], k, v)], axis=0)
+        x = O.layer_finish(ms, lw, x, o)
+    np.testing.assert_allclose(got, O.head_logits(model, x)[P:], rtol=1e-10, atol=1e-12)
+
+
+def test_rope_shift_invariance_of_logits():
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 2, 8)
+    a, _, _, _ = O.forward_full(model, toks, pos0=0)
+    b, _, _, _ = O.forward_full(model, toks, pos0=37)
+    np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-11)
+
+
+def test_attention_is_not_causal():
+    model = small_model()
+    P, Q = 6, 4
+    toks = synth.random_tokens(model.ms, 4, P + Q)
+    ck, cv = O.prefill(model, toks[:P])
+    a, _ = O.forward_cached(model, toks[P:], ck, cv)
+    t2 = toks[P:].copy(); t2[-1] = (t2[-1] + 1) % (model.ms.vocab - 1)
+    b, _ = O.forward_cached(model, t2, ck, cv)
+    assert np.abs(a[0] - b[0]).max() > 1e-6                               # first row sees the last token
+
+
+def test_sequences_are_independent_of_batching():
+    # the oracle is per sequence by construction; a cached step must not depend on other calls
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 6, 12)
+    ck, cv = O.prefill(model, toks[:8])
+    a, _ = O.forward_cached(model, toks[8:], ck, cv)
+    O.forward_cached(model, synth.random_tokens(model.ms, 7, 4), ck, cv)
+    b, _ = O.forward_cached(model, toks[8:], ck, cv)
+    np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------------------ selection
+
+def sort_reference_unmask(tokens, cand, conf, mask_id, tau, m):
+    tokens = np.array(tokens, copy=True)
+    idx = np.nonzero(tokens == mask_id)[0]
+    if len(idx) == 0:
+        return tokens, []
+    order = idx[np.lexsort((idx, -conf[idx]))]                # primary: conf desc, secondary: index asc
+    take = set(order[:min(m, len(idx))].tolist()) | set(idx[conf[idx] >= tau].tolist())
+    for i in take:
+        tokens[i] = cand[i]
+    return tokens, sorted(take)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_unmask_against_sort_reference_with_ties(seed):
+    rng = np.random.default_rng(seed)
+    n, mask_id = 32, 999
+    tokens = np.where(rng.random(n) < 0.6, mask_id, rng.integers(0, 900, n))
+    conf = rng.choice([0.1, 0.5, 0.85, 0.9, 0.95], size=n) if seed % 2 else rng.random(n)
+    cand = rng.integers(0, 900, n)
+    for tau in (0.0, 0.85, 0.9, 1.5):
+        for m in (1, 2, 5, 40):
+            a, ca = O.unmask(tokens, cand, conf, mask_id, tau, m)
+            b, cb = sort_reference_unmask(tokens, cand, conf, mask_id, tau, m)
+            np.testing.assert_array_equal(a, b)
+            assert ca == cb
+            nm = int((tokens == mask_id).sum())
+            assert len(ca) >= min(m, nm)
+            assert (a[tokens != mask_id] == tokens[tokens != mask_id]).all()         # never touched
+            if tau > 1:
+                assert len(ca) == min(m, nm)
+            if tau <= 0:
+                assert len(ca) == nm
+
+
+def test_unmask_set_is_monotone_in_threshold():
+    rng = np.random.default_rng(11)
+    tokens = np.full(32, 7); conf = rng.random(32); cand = np.arange(32)
+    prev = None
+    for tau in (0.95, 0.8, 0.5, 0.2, 0.0):
+        _, ch = O.unmask(tokens, cand, conf, 7, tau, 1)
+        if prev is not None:
+            assert set(prev) <= set(ch)
+        prev = ch
+
+
+def test_unmask_tie_break_lowest_index():
+    tokens = np.array([5, 5, 5, 5]); conf = np.array([0.3, 0.7, 0.7, 0.1]); cand = np.array([10, 11, 12, 13])
+    out, ch = O.unmask(tokens, cand, conf, 5, 0.9, 1)
+    assert ch == [1] and out.tolist() == [5, 11, 5, 5]
+    out, ch = O.unmask(tokens, cand, conf, 5, 0.7, 1)           # threshold is inclusive
+    assert ch == [1, 2]
+
+
+# ------------------------------------------------------------------ decode loop invariants
+
+@pytest.mark.parametrize("tau,m", [(0.9, 1), (0.9, 2), (1.5, 1), (0.0, 1), (0.2, 1)])
+def test_decode_invariants(tau, m):
+    model = small_model()
+    ms = model.ms
+    prompt = synth.random_tokens(ms, 3, 7)
+    rec = []
+    seq, steps = O.decode(model, prompt, n_blocks=2, block_len=8, tau=tau, m=m, record=rec)
+    assert len(seq) == 7 + 16 and (seq != ms.mask_id).all()
+    assert (seq[:7] == prompt).all()
+    assert steps <= 2 * math.ceil(8 / m)
+    for r in rec:
+        before, after = r["before"], r["tokens"]
+        nm = int((before == ms.mask_id).sum())
+        assert len(r["chosen"]) >= min(m, nm)
+        keep = before != ms.mask_id
+        assert (after[keep] == before[keep]).all()
+        assert (after[r["chosen"]] == r["cand"][r["chosen"]]).all()
+        assert (r["cand"] != ms.mask_id).all()
+        if tau > 1:
+            assert len(r["chosen"]) == min(m, nm)
+    if tau <= 0:
+        assert steps == 2
+    if tau > 1 and m == 1:
+        assert steps == 16                       # one token per forward: the teacher-trajectory mode
+
+
+def test_threshold_branch_fires_on_tiny_config():
+    # recorded expectation: with the x8 head some rows of the tiny model do cross 0.2
+    w = synth.Weights(TINY, 0)
+    prompt = synth.random_tokens(TINY, 0, 64)
+    ck, cv = O.prefill(w, prompt)
+    r = O.denoise_step(w, np.full(32, TINY.mask_id), ck, cv, tau=0.9, m=1)
+    assert len(r["chosen"]) >= 1
+    assert 0 < r["conf"].max() <= 1
