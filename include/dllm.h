@@ -1,0 +1,183 @@
+/*
+ * dllm.h -- C ABI of the MI355X (gfx950) denoise-step library for masked-diffusion LLM decoding.
+ *
+ * The calls follow the decoding problem as the d3LLM paper (arxiv 2601.07568) states it in
+ * Section 3.2: a block of query tokens, some of them the special mask id, is run through a
+ * bidirectional transformer against a cache of the key/value states of the prompt and of the
+ * completed blocks ("KV-Cache and KV-Refresh Mechanism"); for every masked position the model's
+ * distribution over the vocabulary is reduced to a candidate token and a confidence, and the
+ * positions that are confident enough, but never fewer than a floor, are unmasked in parallel
+ * ("Entropy-Based Multi-Block Parallel Decoding").  From time to time a forward pass that does
+ * not use the cache recomputes the cached states.
+ *
+ * General rules
+ *   - Every pointer named "dev" is DEVICE memory owned by the caller (e.g. a PyTorch-ROCm
+ *     tensor's data_ptr()).  The library allocates no device memory and frees none.  Pointers in
+ *     dllm_weights, the KV pool and the workspace are borrowed for the life of the context; all
+ *     other pointers for the duration of the call (the call is asynchronous: "duration" ends
+ *     when the work enqueued on the stream has run).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue; they never synchronise and read no device value on the host, so a sequence of
+ *     calls can be captured into a HIP graph.
+ *   - Return value: DLLM_OK or a negative DLLM_E* code.  Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued.  Values that live in
+ *     device memory (token ids, block-table entries, lengths) are bounds-checked by the kernels:
+ *     an offending access is skipped and a bit is set in the context's device status word
+ *     (dllm_read_status).  Nothing aborts, throws or prints.
+ *   - Calls on one context must not overlap in time (they share the workspace).
+ *
+ * Data layout
+ *   - dtype DLLM_F32: weights, KV pool and inter-kernel activations are float.  DLLM_BF16: they
+ *     are bfloat16 (the residual stream, softmax statistics and all accumulators stay float).
+ *   - Linear weights are [out_features, in_features] row-major, no biases; norm gains [d_model];
+ *     tok_emb and lm_head are [vocab, d_model] (untied).
+ *   - KV pool: element (layer l, which in {0 = K, 1 = V}, page p, kv head h, slot s, channel c)
+ *     at index ((((l * 2 + which) * n_pages + p) * n_kv_heads + h) * page_tokens + s) * head_dim + c.
+ *     K is stored after the rotary embedding.  Position j of sequence b lives in page
+ *     block_table[b * max_pages_per_seq + j / page_tokens], slot j % page_tokens.
+ *   - Rotary embedding: half-split pairing (c, c + head_dim/2), angle = position * rope_base^(-2c/head_dim),
+ *     positions counted from the start of the sequence.
+ */
+#ifndef DLLM_H
+#define DLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DLLM_OK        0
+#define DLLM_EINVAL   (-1)  /* null pointer, negative or inconsistent argument                  */
+#define DLLM_ESHAPE   (-2)  /* shape not supported (see dllm_create) or above the configured max */
+#define DLLM_ENOSPACE (-3)  /* workspace or KV pool smaller than required                        */
+#define DLLM_EHIP     (-4)  /* a launch failed; dllm_last_hip_error() has the runtime's text     */
+
+#define DLLM_F32  0
+#define DLLM_BF16 1
+
+/* bits of the device status word */
+#define DLLM_STATUS_BAD_TOKEN 1  /* a token id outside [0, vocab) was read (row 0 was used)       */
+#define DLLM_STATUS_BAD_PAGE  2  /* a block-table entry outside [0, n_pages), or a position beyond
+                                    max_pages_per_seq * page_tokens (access skipped)              */
+#define DLLM_STATUS_ROWS_CAP  4  /* more masked rows than max_batch * max_q in a refresh call      */
+
+typedef struct dllm_ctx dllm_ctx; /* opaque, host memory; holds descriptors only */
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, mask_id;
+  float   rms_eps, rope_base;
+  int32_t dtype;             /* DLLM_F32 or DLLM_BF16                                             */
+  int32_t page_tokens;       /* tokens per KV page, >= 1                                          */
+  int32_t max_pages_per_seq; /* row length of every block table                                   */
+  int32_t n_pages;           /* pages in the pool                                                 */
+  int32_t max_batch;         /* largest B of any call                                             */
+  int32_t max_q;             /* largest Q of a denoise step                                       */
+  int32_t max_tokens;        /* largest total token count of a prefill / refresh call (0: unused) */
+} dllm_config;
+
+typedef struct {
+  const void *attn_norm, *wq, *wk, *wv, *wo, *mlp_norm, *w_gate, *w_up, *w_down;
+} dllm_layer_w;
+
+typedef struct {
+  const void *tok_emb, *final_norm, *lm_head; /* dev */
+  const dllm_layer_w *layers;                 /* HOST array of n_layers records of dev pointers; copied by dllm_create */
+} dllm_weights;
+
+/* Bytes of workspace / KV pool a context with this configuration needs; 0 if the configuration
+ * is invalid. */
+size_t dllm_workspace_bytes(const dllm_config *cfg);
+size_t dllm_kv_pool_bytes(const dllm_config *cfg);
+
+/* Creates a context.  Supported: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads;
+ * for DLLM_BF16 d_model, d_ff and n_*_heads * head_dim must be multiples of 8; mask_id in
+ * [0, vocab).  kv_pool (dev) holds dllm_kv_pool_bytes, workspace (dev, 256-byte aligned) holds
+ * dllm_workspace_bytes; the workspace's status word must be cleared once with
+ * dllm_reset_status before the first call.  Performs no HIP call. */
+int dllm_create(dllm_ctx **out, const dllm_config *cfg, const dllm_weights *w,
+                void *kv_pool, size_t kv_pool_bytes, void *workspace, size_t workspace_bytes);
+void dllm_destroy(dllm_ctx *ctx);
+
+/* Prefill (Section 3.2, "KV-Cache"): one bidirectional forward without cache over B packed
+ * sequences -- sequence b is tokens[cu_seqlens[b] .. cu_seqlens[b+1]), every token attends to every
+ * token of its sequence -- and stores the K/V states of its first n_cache[b] positions (all of
+ * them if n_cache is NULL) of every layer into the pages block_table maps.  No LM head.
+ *   tokens      dev int32 [total_tokens]      cu_seqlens  dev int32 [B+1], cu_seqlens[0] = 0
+ *   n_cache     dev int32 [B] or NULL         block_table dev int32 [B, max_pages_per_seq]
+ *   total_tokens = cu_seqlens[B] and max_seqlen >= every sequence length are passed by value
+ *   (host), they size the launches. */
+int dllm_prefill_kv(dllm_ctx *ctx, void *stream, int B, int total_tokens, int max_seqlen,
+                    const int32_t *tokens, const int32_t *cu_seqlens, const int32_t *n_cache,
+                    const int32_t *block_table);
+
+/* One denoising forward (Section 3.2): for each sequence b, Q query tokens at positions
+ * prefix_len[b] .. prefix_len[b]+Q-1 attend, without any mask, to the cached prefix
+ * [0, prefix_len[b]) and to one another.  Their K/V are written into the pages the block table
+ * maps for those positions (in-flight pages; nothing below prefix_len[b] is written).  For
+ * every row whose token is mask_id the distribution over the vocabulary (mask_id column
+ * excluded) is reduced on the fly -- the logits are never stored --
+ * to cand_token = arg max (lowest id on ties), conf = its softmax probability, and optionally
+ * entropy (nats).  Rows that are not masked get cand_token = their own token, conf = 1,
+ * entropy = 0.
+ *   q_tokens dev int32 [B, Q]    prefix_len dev int32 [B]    block_table dev int32 [B, max_pages_per_seq]
+ *   cand_token dev int32 [B, Q]  conf dev float [B, Q]       entropy dev float [B, Q] or NULL
+ *   max_prefix_len (host) >= every prefix_len[b]; it only sizes the launch. */
+int dllm_denoise_step(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len,
+                      const int32_t *q_tokens, const int32_t *prefix_len,
+                      const int32_t *block_table, int32_t *cand_token, float *conf,
+                      float *entropy);
+
+/* Threshold-based parallel unmasking with a floor (Section 3.2: tokens that pass the threshold
+ * are decoded, and at least a minimum number per forward regardless of the threshold; with
+ * threshold > 1 and min_unmask = 1 this is the one-token-per-step rule of Section 3.1).
+ * The Q positions of each sequence are treated as Q / block_len independent blocks.  Within a
+ * block, every masked position with conf >= threshold is unmasked, and so are the
+ * min(min_unmask, #masked) masked positions that come first when ordered by confidence
+ * descending, index ascending (NaN confidences come last).  Unmasking position i sets
+ * q_tokens[i] = cand_token[i]; other positions are left untouched.
+ *   q_tokens dev int32 [B, Q] in/out    n_unmasked, n_remaining dev int32 [B, Q / block_len] or NULL
+ *   Requires Q % block_len == 0, 1 <= block_len <= 1024, min_unmask >= 1. */
+int dllm_unmask(dllm_ctx *ctx, void *stream, int B, int Q, int block_len, int32_t *q_tokens,
+                const int32_t *cand_token, const float *conf, float threshold, int min_unmask,
+                int32_t *n_unmasked, int32_t *n_remaining);
+
+/* KV refresh (Section 3.2, "KV-Refresh"; the forward passes of the "Completed but Stabilizing"
+ * state): the same no-cache forward as dllm_prefill_kv over the committed tokens, optionally
+ * followed by in-flight ones, overwriting the cached K/V of positions [0, n_commit[b]) (all if
+ * NULL).  If cand_token is not NULL the rows at positions >= n_commit[b] are treated as a
+ * denoise step without cache: cand_token / conf / entropy (dev, [total_tokens], entropy may be
+ * NULL) are written for them as in dllm_denoise_step; rows below n_commit[b] are left
+ * untouched.  At most max_batch * max_q masked rows are reduced per call. */
+int dllm_refresh_cache(dllm_ctx *ctx, void *stream, int B, int total_tokens, int max_seqlen,
+                       const int32_t *tokens, const int32_t *cu_seqlens, const int32_t *n_commit,
+                       const int32_t *block_table, int32_t *cand_token, float *conf,
+                       float *entropy);
+
+/* Test hooks.  dllm_debug_logits runs the same forward as dllm_denoise_step and stores the raw
+ * logits (mask_id column included) of all B*Q rows as float [B, Q, vocab].  dllm_debug_hidden
+ * stops after n_layers_run layers and stores the residual stream as float [B, Q, d_model]. */
+int dllm_debug_logits(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len,
+                      const int32_t *q_tokens, const int32_t *prefix_len,
+                      const int32_t *block_table, float *logits);
+int dllm_debug_hidden(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len,
+                      const int32_t *q_tokens, const int32_t *prefix_len,
+                      const int32_t *block_table, int n_layers_run, float *hidden);
+
+/* Device status word: reset enqueues a clear; read enqueues a copy to *host_out and waits for
+ * the stream (the only call here that synchronises). */
+int dllm_reset_status(dllm_ctx *ctx, void *stream);
+int dllm_read_status(dllm_ctx *ctx, void *stream, int32_t *host_out);
+
+/* Selects kernels: 0 = automatic (MFMA kernels where the shape allows), 1 = force the generic
+ * scalar-FMA kernels (test aid). */
+int dllm_set_kernel_mode(dllm_ctx *ctx, int mode);
+
+const char *dllm_strerror(int code);
+const char *dllm_last_hip_error(const dllm_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLLM_H */

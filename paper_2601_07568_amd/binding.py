@@ -1,0 +1,217 @@
+"""ctypes binding of libdllm.so: same names as include/dllm.h, argument marshalling only.
+
+`Engine` is a convenience that owns the torch tensors (weights, KV pool, workspace) a context
+borrows.  Every step of the path runs inside the library's kernels; nothing here computes.
+The library must be built (python -m paper_2601_07568_amd.build); loading fails loudly if not.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdllm.so")
+
+DLLM_OK, DLLM_EINVAL, DLLM_ESHAPE, DLLM_ENOSPACE, DLLM_EHIP = 0, -1, -2, -3, -4
+DLLM_F32, DLLM_BF16 = 0, 1
+STATUS_BAD_TOKEN, STATUS_BAD_PAGE, STATUS_ROWS_CAP = 1, 2, 4
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
+                                          "d_ff", "vocab", "mask_id")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float)] + \
+               [(n, C.c_int32) for n in ("dtype", "page_tokens", "max_pages_per_seq", "n_pages",
+                                          "max_batch", "max_q", "max_tokens")]
+
+
+class LayerW(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate",
+                                          "w_up", "w_down")]
+
+
+class Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(LayerW))]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libdllm.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_07568_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, f32, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+    pcfg = C.POINTER(Config)
+    sig = {
+        "dllm_workspace_bytes": (sz, [pcfg]),
+        "dllm_kv_pool_bytes": (sz, [pcfg]),
+        "dllm_create": (i32, [C.POINTER(vp), pcfg, C.POINTER(Weights), vp, sz, vp, sz]),
+        "dllm_destroy": (None, [vp]),
+        "dllm_prefill_kv": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
+        "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
+        "dllm_refresh_cache": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "dllm_debug_logits": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
+        "dllm_debug_hidden": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp]),
+        "dllm_reset_status": (i32, [vp, vp]),
+        "dllm_read_status": (i32, [vp, vp, C.POINTER(C.c_int32)]),
+        "dllm_set_kernel_mode": (i32, [vp, i32]),
+        "dllm_strerror": (C.c_char_p, [i32]),
+        "dllm_last_hip_error": (C.c_char_p, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+class DllmError(RuntimeError):
+    def __init__(self, code, detail=""):
+        self.code = code
+        super().__init__(f"dllm error {code}: {lib().dllm_strerror(code).decode()} {detail}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def make_config(ms, page_tokens, max_pages_per_seq, n_pages, max_batch, max_q, max_tokens) -> Config:
+    return Config(ms.n_layers, ms.d_model, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.d_ff, ms.vocab,
+                  ms.mask_id, ms.rms_eps, ms.rope_base, DLLM_BF16 if ms.dtype == "bf16" else DLLM_F32,
+                  page_tokens, max_pages_per_seq, n_pages, max_batch, max_q, max_tokens)
+
+
+class Engine:
+    """Owns device tensors and a dllm context.  `weights` provides .layer(l) -> dict of numpy arrays
+    (float32, or uint16 bfloat16 bits) and ["tok_emb"|"final_norm"|"lm_head"]; alternatively pass
+    device tensors through `device_weights` = (globals dict, list of layer dicts)."""
+
+    def __init__(self, ms, weights=None, *, page_tokens=32, max_pages_per_seq=8, n_pages=16, max_batch=1,
+                 max_q=32, max_tokens=0, device="cuda:0", device_weights=None):
+        import torch
+        self.torch, self.ms, self.device = torch, ms, torch.device(device)
+        self.cfg = make_config(ms, page_tokens, max_pages_per_seq, n_pages, max_batch, max_q, max_tokens)
+        L = lib()
+        self.tdtype = torch.bfloat16 if ms.dtype == "bf16" else torch.float32
+
+        def up(a):
+            t = torch.from_numpy(np.ascontiguousarray(a))
+            if a.dtype == np.uint16:
+                t = t.view(torch.bfloat16)
+            return t.to(self.device)
+
+        if device_weights is not None:
+            self.g, self.layers = device_weights
+        else:
+            self.g = {k: up(weights[k]) for k in ("tok_emb", "final_norm", "lm_head")}
+            self.layers = [{k: up(v) for k, v in weights.layer(l).items()} for l in range(ms.n_layers)]
+        self._lw = (LayerW * max(1, ms.n_layers))()
+        for l, lw in enumerate(self.layers):
+            for name, _ in LayerW._fields_:
+                assert lw[name].dtype == self.tdtype and lw[name].is_contiguous()
+                setattr(self._lw[l], name, lw[name].data_ptr())
+        self._w = Weights(self.g["tok_emb"].data_ptr(), self.g["final_norm"].data_ptr(),
+                          self.g["lm_head"].data_ptr(), self._lw)
+        ws_bytes = L.dllm_workspace_bytes(C.byref(self.cfg))
+        kv_bytes = L.dllm_kv_pool_bytes(C.byref(self.cfg))
+        if ws_bytes == 0:
+            raise DllmError(DLLM_ESHAPE, "(configuration rejected)")
+        self.workspace = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=self.device)
+        self._ws_off = (-self.workspace.data_ptr()) % 256
+        self.kv_pool = torch.zeros(max(kv_bytes, 1), dtype=torch.uint8, device=self.device)
+        self.ctx = C.c_void_p()
+        rc = L.dllm_create(C.byref(self.ctx), C.byref(self.cfg), C.byref(self._w), self.kv_pool.data_ptr(),
+                           kv_bytes, self.workspace.data_ptr() + self._ws_off, ws_bytes)
+        if rc != DLLM_OK:
+            raise DllmError(rc)
+        self._check(L.dllm_reset_status(self.ctx, self._stream()))
+
+    # -- helpers
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _check(self, rc):
+        if rc != DLLM_OK:
+            raise DllmError(rc, lib().dllm_last_hip_error(self.ctx).decode() if rc == DLLM_EHIP else "")
+
+    def close(self):
+        if self.ctx:
+            lib().dllm_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def i32(self, a):
+        return self.torch.as_tensor(np.asarray(a, dtype=np.int32)).to(self.device)
+
+    def kv_slab(self, layer, which):
+        """View of the pool: [n_pages, n_kv_heads, page_tokens, head_dim] of layer, which (0=K, 1=V)."""
+        c = self.cfg
+        es = 2 if self.ms.dtype == "bf16" else 4
+        n = c.n_pages * c.n_kv_heads * c.page_tokens * c.head_dim
+        off = (layer * 2 + which) * n * es
+        return self.kv_pool[off:off + n * es].view(self.tdtype).view(c.n_pages, c.n_kv_heads, c.page_tokens,
+                                                                     c.head_dim)
+
+    # -- the calls of include/dllm.h
+    def prefill_kv(self, tokens, cu_seqlens, block_table, n_cache=None, *, total_tokens, max_seqlen):
+        B = cu_seqlens.numel() - 1
+        self._check(lib().dllm_prefill_kv(self.ctx, self._stream(), B, total_tokens, max_seqlen, _ptr(tokens),
+                                          _ptr(cu_seqlens), _ptr(n_cache), _ptr(block_table)))
+
+    def denoise_step(self, q_tokens, prefix_len, block_table, cand, conf, entropy=None, *, max_prefix_len):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_denoise_step(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                            _ptr(prefix_len), _ptr(block_table), _ptr(cand), _ptr(conf),
+                                            _ptr(entropy)))
+
+    def unmask(self, q_tokens, cand, conf, threshold, min_unmask, block_len=None, n_unmasked=None,
+               n_remaining=None):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_unmask(self.ctx, self._stream(), B, Q, block_len or Q, _ptr(q_tokens), _ptr(cand),
+                                      _ptr(conf), threshold, min_unmask, _ptr(n_unmasked), _ptr(n_remaining)))
+
+    def refresh_cache(self, tokens, cu_seqlens, block_table, n_commit=None, cand=None, conf=None, entropy=None,
+                      *, total_tokens, max_seqlen):
+        B = cu_seqlens.numel() - 1
+        self._check(lib().dllm_refresh_cache(self.ctx, self._stream(), B, total_tokens, max_seqlen, _ptr(tokens),
+                                             _ptr(cu_seqlens), _ptr(n_commit), _ptr(block_table), _ptr(cand),
+                                             _ptr(conf), _ptr(entropy)))
+
+    def debug_logits(self, q_tokens, prefix_len, block_table, *, max_prefix_len):
+        B, Q = q_tokens.shape
+        out = self.torch.empty(B, Q, self.ms.vocab, dtype=self.torch.float32, device=self.device)
+        self._check(lib().dllm_debug_logits(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                            _ptr(prefix_len), _ptr(block_table), _ptr(out)))
+        return out
+
+    def debug_hidden(self, q_tokens, prefix_len, block_table, n_layers_run, *, max_prefix_len):
+        B, Q = q_tokens.shape
+        out = self.torch.empty(B, Q, self.ms.d_model, dtype=self.torch.float32, device=self.device)
+        self._check(lib().dllm_debug_hidden(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                            _ptr(prefix_len), _ptr(block_table), n_layers_run, _ptr(out)))
+        return out
+
+    def read_status(self) -> int:
+        v = C.c_int32(-1)
+        self._check(lib().dllm_read_status(self.ctx, self._stream(), C.byref(v)))
+        return v.value
+
+    def reset_status(self):
+        self._check(lib().dllm_reset_status(self.ctx, self._stream()))
+
+    def set_kernel_mode(self, mode: int):
+        self._check(lib().dllm_set_kernel_mode(self.ctx, mode))

@@ -1,0 +1,299 @@
+// extern "C" surface of the library: argument validation (host only, before anything is
+// launched), workspace map, and the chain of launches that makes up each call.
+#include "common.h"
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+using namespace dllm;
+
+namespace dllm {
+hipError_t launch_set_i32(hipStream_t s, int32_t* p, int n, int32_t v);
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool config_ok(const dllm_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 0 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ff < 1) return false;
+  if (c->vocab < 2 || c->mask_id < 0 || c->mask_id >= c->vocab) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->n_q_heads % c->n_kv_heads != 0) return false;
+  if (c->dtype != DLLM_F32 && c->dtype != DLLM_BF16) return false;
+  if (c->dtype == DLLM_BF16 && (c->d_model % 8 != 0 || c->d_ff % 8 != 0)) return false;
+  if (c->page_tokens < 1 || c->max_pages_per_seq < 1 || c->n_pages < 1) return false;
+  if (c->max_batch < 1 || c->max_q < 1 || c->max_tokens < 0) return false;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 1.f)) return false;
+  if ((int64_t)c->max_batch * c->max_q > (1 << 20) || c->max_tokens > (1 << 22)) return false;
+  return true;
+}
+
+static bool build_map(const dllm_config* c, Workspace* m) {
+  if (!config_ok(c)) return false;
+  const size_t es = elem_size(*c);
+  const size_t t_step = (size_t)c->max_batch * c->max_q;
+  const size_t t_max = t_step > (size_t)c->max_tokens ? t_step : (size_t)c->max_tokens;
+  const size_t dq = (size_t)c->n_q_heads * c->head_dim, dkv = (size_t)c->n_kv_heads * c->head_dim;
+  const size_t half = c->head_dim / 2;
+  m->t_max = (int64_t)t_max;
+  m->t_step = (int64_t)t_step;
+  m->r_max = (int64_t)t_step;
+  m->n_vtiles = (c->vocab + LM_TILE_N - 1) / LM_TILE_N;
+  m->max_splits = ATTN_MAX_SPLITS;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  m->status = take(64);
+  m->x = take(t_max * c->d_model * 4);
+  m->xn = take(t_max * c->d_model * es);
+  m->q = take(t_max * dq * es);
+  m->k = take(t_max * dkv * es);
+  m->v = take(t_max * dkv * es);
+  m->o = take(t_max * dq * es);
+  m->g = take(t_max * c->d_ff * 4);
+  m->u = take(t_max * c->d_ff * 4);
+  m->h = take(t_max * c->d_ff * es);
+  m->rope_cos = take(t_max * half * 4);
+  m->rope_sin = take(t_max * half * 4);
+  m->tok_seq = take(t_max * 4);
+  m->tok_pos = take(t_max * 4);
+  m->rows = take((size_t)m->r_max * 4);
+  m->lm_part = take((size_t)m->r_max * m->n_vtiles * 4 * 4);
+  m->attn_part = take(0);
+  m->scratch_bytes = 0;
+  m->scratch = take(m->scratch_bytes);
+  m->total = off;
+  return true;
+}
+
+extern "C" size_t dllm_workspace_bytes(const dllm_config* cfg) {
+  Workspace m;
+  return build_map(cfg, &m) ? m.total : 0;
+}
+
+extern "C" size_t dllm_kv_pool_bytes(const dllm_config* cfg) {
+  if (!config_ok(cfg)) return 0;
+  return (size_t)cfg->n_layers * 2 * kv_slab_elems(*cfg) * elem_size(*cfg);
+}
+
+extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_weights* w, void* kv_pool,
+                           size_t kv_pool_bytes, void* workspace, size_t workspace_bytes) {
+  if (!out) return DLLM_EINVAL;
+  *out = nullptr;
+  if (!cfg || !w || !kv_pool || !workspace) return DLLM_EINVAL;
+  Workspace m;
+  if (!build_map(cfg, &m)) return DLLM_ESHAPE;
+  if (!w->tok_emb || !w->final_norm || !w->lm_head) return DLLM_EINVAL;
+  if (cfg->n_layers > 0 && !w->layers) return DLLM_EINVAL;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const dllm_layer_w& L = w->layers[l];
+    if (!L.attn_norm || !L.wq || !L.wk || !L.wv || !L.wo || !L.mlp_norm || !L.w_gate || !L.w_up || !L.w_down)
+      return DLLM_EINVAL;
+  }
+  if (((uintptr_t)workspace & 255) != 0) return DLLM_EINVAL;
+  if (workspace_bytes < m.total || kv_pool_bytes < dllm_kv_pool_bytes(cfg)) return DLLM_ENOSPACE;
+  dllm_ctx* c = (dllm_ctx*)calloc(1, sizeof(dllm_ctx));
+  if (!c) return DLLM_ENOSPACE;
+  c->cfg = *cfg;
+  c->layers = (dllm_layer_w*)calloc(cfg->n_layers > 0 ? cfg->n_layers : 1, sizeof(dllm_layer_w));
+  if (!c->layers) { free(c); return DLLM_ENOSPACE; }
+  for (int l = 0; l < cfg->n_layers; ++l) c->layers[l] = w->layers[l];
+  c->tok_emb = w->tok_emb;
+  c->final_norm = w->final_norm;
+  c->lm_head = w->lm_head;
+  c->kv_pool = (char*)kv_pool;
+  c->ws = (char*)workspace;
+  c->map = m;
+  c->kernel_mode = 0;
+  *out = c;
+  return DLLM_OK;
+}
+
+extern "C" void dllm_destroy(dllm_ctx* ctx) {
+  if (!ctx) return;
+  free(ctx->layers);
+  free(ctx);
+}
+
+extern "C" int dllm_set_kernel_mode(dllm_ctx* ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 1) return DLLM_EINVAL;
+  ctx->kernel_mode = mode;
+  return DLLM_OK;
+}
+
+extern "C" const char* dllm_strerror(int code) {
+  switch (code) {
+    case DLLM_OK: return "ok";
+    case DLLM_EINVAL: return "invalid argument";
+    case DLLM_ESHAPE: return "unsupported shape or above the configured maximum";
+    case DLLM_ENOSPACE: return "workspace or KV pool too small";
+    case DLLM_EHIP: return "HIP launch failed";
+    default: return "unknown error";
+  }
+}
+
+extern "C" const char* dllm_last_hip_error(const dllm_ctx* ctx) { return ctx ? ctx->hip_error : ""; }
+
+static int hip_fail(dllm_ctx* c, hipError_t e, const char* where) {
+  snprintf(c->hip_error, sizeof(c->hip_error), "%s: %s", where, hipGetErrorString(e));
+  return DLLM_EHIP;
+}
+#define TRY(call, where)                        \
+  do {                                          \
+    hipError_t e_ = (call);                     \
+    if (e_ != hipSuccess) return hip_fail(c, e_, where); \
+  } while (0)
+
+#define WSP(c, field, type) ((type*)((c)->ws + (c)->map.field))
+
+struct HeadOut {
+  int32_t* cand;
+  float* conf;
+  float* entropy;
+};
+
+// The forward shared by all calls: embed, n_layers_run transformer layers over the rows of g,
+// then optionally the residual stream, the raw logits or the fused confidence outputs.
+static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
+                       float* logits_out, float* hidden_out) {
+  const dllm_config& f = c->cfg;
+  const int T = g.T;
+  const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
+  TRY(launch_token_map(c, s, g), "token_map");
+  TRY(launch_embed(c, s, g), "embed");
+  TRY(launch_rope_table(c, s, g), "rope_table");
+  for (int l = 0; l < n_layers_run; ++l) {
+    const dllm_layer_w& L = c->layers[l];
+    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr), "rmsnorm");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q, T, dq, f.d_model, EPI_STORE), "wq");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k, T, dkv, f.d_model, EPI_STORE), "wk");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+    TRY(launch_rope_kv(c, s, g, l), "rope_kv");
+    TRY(launch_attention_generic(c, s, g, l), "attention");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr), "rmsnorm");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
+    TRY(launch_swiglu(c, s, T), "swiglu");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
+  }
+  if (hidden_out) TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
+  if (logits_out) {
+    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr), "final_norm");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
+  }
+  if (head) {
+    const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
+    TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
+    TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1), "final_norm");
+    TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
+    TRY(launch_lm_merge(c, s, max_rows, head->cand, head->conf, head->entropy), "lm_merge");
+  }
+  return DLLM_OK;
+}
+
+static int check_step_args(dllm_ctx* c, int B, int Q, int max_prefix_len, const void* q_tokens,
+                           const void* prefix_len, const void* block_table) {
+  if (!c || !q_tokens || !prefix_len || !block_table) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || max_prefix_len < 0) return DLLM_EINVAL;
+  if (B > c->cfg.max_batch || Q > c->cfg.max_q) return DLLM_ESHAPE;
+  if ((int64_t)max_prefix_len + Q > (int64_t)c->cfg.max_pages_per_seq * c->cfg.page_tokens) return DLLM_ESHAPE;
+  return DLLM_OK;
+}
+
+static StepGeom step_geom(int B, int Q, int max_prefix_len, const int32_t* q_tokens, const int32_t* prefix_len,
+                          const int32_t* block_table) {
+  StepGeom g;
+  g.B = B; g.T = B * Q; g.Q = Q; g.max_kv = max_prefix_len + Q;
+  g.tokens = q_tokens; g.prefix_len = prefix_len; g.cu_seqlens = nullptr; g.n_cache = nullptr;
+  g.block_table = block_table;
+  return g;
+}
+
+extern "C" int dllm_denoise_step(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                 const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* block_table,
+                                 int32_t* cand_token, float* conf, float* entropy) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  if (rc != DLLM_OK) return rc;
+  if (!cand_token || !conf) return DLLM_EINVAL;
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  HeadOut h{cand_token, conf, entropy};
+  return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, &h, nullptr, nullptr);
+}
+
+extern "C" int dllm_debug_logits(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                 const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* block_table,
+                                 float* logits) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  if (rc != DLLM_OK) return rc;
+  if (!logits) return DLLM_EINVAL;
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, nullptr, logits, nullptr);
+}
+
+extern "C" int dllm_debug_hidden(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                 const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* block_table,
+                                 int n_layers_run, float* hidden) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  if (rc != DLLM_OK) return rc;
+  if (!hidden || n_layers_run < 0 || n_layers_run > c->cfg.n_layers) return DLLM_EINVAL;
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  return run_forward(c, (hipStream_t)stream, g, n_layers_run, nullptr, nullptr, hidden);
+}
+
+static int packed_forward(dllm_ctx* c, void* stream, int B, int total_tokens, int max_seqlen,
+                          const int32_t* tokens, const int32_t* cu_seqlens, const int32_t* n_cache,
+                          const int32_t* block_table, const HeadOut* head) {
+  if (!c || !tokens || !cu_seqlens || !block_table) return DLLM_EINVAL;
+  if (B < 1 || total_tokens < 1 || max_seqlen < 1 || max_seqlen > total_tokens) return DLLM_EINVAL;
+  if (B > c->cfg.max_batch || total_tokens > c->cfg.max_tokens) return DLLM_ESHAPE;
+  if (n_cache == nullptr && (int64_t)max_seqlen > (int64_t)c->cfg.max_pages_per_seq * c->cfg.page_tokens)
+    return DLLM_ESHAPE;
+  StepGeom g;
+  g.B = B; g.T = total_tokens; g.Q = 0; g.max_kv = max_seqlen;
+  g.tokens = tokens; g.prefix_len = nullptr; g.cu_seqlens = cu_seqlens; g.n_cache = n_cache;
+  g.block_table = block_table;
+  return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, head, nullptr, nullptr);
+}
+
+extern "C" int dllm_prefill_kv(dllm_ctx* c, void* stream, int B, int total_tokens, int max_seqlen,
+                               const int32_t* tokens, const int32_t* cu_seqlens, const int32_t* n_cache,
+                               const int32_t* block_table) {
+  return packed_forward(c, stream, B, total_tokens, max_seqlen, tokens, cu_seqlens, n_cache, block_table, nullptr);
+}
+
+extern "C" int dllm_refresh_cache(dllm_ctx* c, void* stream, int B, int total_tokens, int max_seqlen,
+                                  const int32_t* tokens, const int32_t* cu_seqlens, const int32_t* n_commit,
+                                  const int32_t* block_table, int32_t* cand_token, float* conf, float* entropy) {
+  if (cand_token == nullptr)
+    return packed_forward(c, stream, B, total_tokens, max_seqlen, tokens, cu_seqlens, n_commit, block_table, nullptr);
+  if (!conf || !n_commit) return DLLM_EINVAL;   // step outputs only make sense for rows past n_commit
+  HeadOut h{cand_token, conf, entropy};
+  return packed_forward(c, stream, B, total_tokens, max_seqlen, tokens, cu_seqlens, n_commit, block_table, &h);
+}
+
+extern "C" int dllm_unmask(dllm_ctx* c, void* stream, int B, int Q, int block_len, int32_t* q_tokens,
+                           const int32_t* cand_token, const float* conf, float threshold, int min_unmask,
+                           int32_t* n_unmasked, int32_t* n_remaining) {
+  if (!c || !q_tokens || !cand_token || !conf) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || block_len < 1 || min_unmask < 1 || Q % block_len != 0) return DLLM_EINVAL;
+  if (threshold != threshold) return DLLM_EINVAL;
+  if (block_len > 1024 || (int64_t)B * (Q / block_len) > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_unmask((hipStream_t)stream, B, Q, block_len, q_tokens, cand_token, conf, threshold, min_unmask,
+                    c->cfg.mask_id, n_unmasked, n_remaining), "unmask");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_reset_status(dllm_ctx* c, void* stream) {
+  if (!c) return DLLM_EINVAL;
+  TRY(launch_set_i32((hipStream_t)stream, WSP(c, status, int32_t), 16, 0), "reset_status");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_read_status(dllm_ctx* c, void* stream, int32_t* host_out) {
+  if (!c || !host_out) return DLLM_EINVAL;
+  TRY(hipMemcpyAsync(host_out, WSP(c, status, int32_t), sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)stream),
+      "read_status");
+  TRY(hipStreamSynchronize((hipStream_t)stream), "read_status sync");
+  return DLLM_OK;
+}

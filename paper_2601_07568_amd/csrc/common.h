@@ -1,0 +1,148 @@
+// Shared declarations of the denoise-step library: context, workspace map, KV addressing,
+// bf16 helpers, and the internal launch functions that api.hip chains together.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/dllm.h"
+
+namespace dllm {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+  union { uint32_t u; float f; } c;
+  c.u = ((uint32_t)b) << 16;
+  return c.f;
+}
+// round to nearest, ties to even; NaN stays NaN
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  __device__ static inline float load(const float* p) { return *p; }
+  __device__ static inline void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  __device__ static inline float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static inline void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// Where the keys/values of a forward live.  Paged: position j of sequence b is in page
+// table[b*max_pages + j/page_tokens], slot j%page_tokens, of the per-layer K (or V) slab
+// [n_pages][n_kv_heads][page_tokens][head_dim].  Packed (table == nullptr): the forward's own
+// K/V scratch [total_tokens][n_kv_heads][head_dim], sequence b starting at row cu_seqlens[b].
+struct KVView {
+  const void* k;          // layer's K slab (paged) or packed K
+  const void* v;
+  const int32_t* table;   // nullptr = packed
+  const int32_t* cu_seqlens;  // packed only
+  int32_t page_tokens, max_pages, n_pages, n_kv_heads, head_dim;
+};
+
+// element offset of (sequence b, position pos, kv head h, channel 0); -1 if not addressable
+__device__ inline int64_t kv_offset(const KVView& kv, int b, int pos, int h) {
+  if (kv.table == nullptr) {
+    return ((int64_t)(kv.cu_seqlens[b] + pos) * kv.n_kv_heads + h) * kv.head_dim;
+  }
+  int pi = pos / kv.page_tokens;
+  if (pos < 0 || pi >= kv.max_pages) return -1;
+  int page = kv.table[(int64_t)b * kv.max_pages + pi];
+  if (page < 0 || page >= kv.n_pages) return -1;
+  return (((int64_t)page * kv.n_kv_heads + h) * kv.page_tokens + (pos - pi * kv.page_tokens)) * kv.head_dim;
+}
+
+// Workspace map (byte offsets from the workspace base), fixed at dllm_create.
+struct Workspace {
+  size_t status;       // int32[4]: [0] status bits, [1] number of LM-head rows
+  size_t x;            // float [Tmax, d]          residual stream
+  size_t xn;           // T     [Tmax, d]          normalised activations (GEMM input)
+  size_t q;            // T     [Tmax, Hq*dh]
+  size_t k;            // T     [Tmax, Hkv*dh]     this forward's K (rotated in place)
+  size_t v;            // T     [Tmax, Hkv*dh]
+  size_t o;            // T     [Tmax, Hq*dh]      attention output
+  size_t g;            // float [Tmax, F]          gate pre-activation (generic path)
+  size_t u;            // float [Tmax, F]          up projection (generic path)
+  size_t h;            // T     [Tmax, F]          silu(g)*u
+  size_t rope_cos;     // float [Tmax, dh/2]
+  size_t rope_sin;     // float [Tmax, dh/2]
+  size_t tok_seq;      // int32 [Tmax]             sequence of each packed token
+  size_t tok_pos;      // int32 [Tmax]             position of each token in its sequence
+  size_t rows;         // int32 [Rmax]             compacted list of LM-head rows
+  size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
+  size_t attn_part;    // float [Tstep, Hq, max_splits, dh + 2] split-KV partials
+  size_t scratch;      // general scratch for fast kernels (split-K partials)
+  size_t total;
+  int64_t t_max, r_max, t_step;
+  int32_t n_vtiles, max_splits;
+  size_t scratch_bytes;
+};
+
+}  // namespace dllm
+
+struct dllm_ctx {
+  dllm_config cfg;
+  dllm_layer_w* layers;      // host copy
+  const void *tok_emb, *final_norm, *lm_head;
+  char* kv_pool;
+  char* ws;
+  dllm::Workspace map;
+  int kernel_mode;
+  char hip_error[256];
+};
+
+namespace dllm {
+
+inline size_t elem_size(const dllm_config& c) { return c.dtype == DLLM_BF16 ? 2 : 4; }
+inline size_t kv_slab_elems(const dllm_config& c) {
+  return (size_t)c.n_pages * c.n_kv_heads * c.page_tokens * c.head_dim;
+}
+constexpr int LM_TILE_N = 512;      // vocabulary columns per LM-head partial
+constexpr int ATTN_MAX_SPLITS = 64;
+
+// ---- launchers implemented in kernels_generic.hip (any shape, both dtypes) -------------------
+struct StepGeom {           // which tokens a forward runs over
+  int B, T;                 // sequences, total rows
+  int Q;                    // rows per sequence (step) or 0 (packed, ragged)
+  int max_kv;               // upper bound of keys any row attends to (launch sizing)
+  const int32_t* tokens;    // dev [T]
+  const int32_t* prefix_len;   // dev [B] (step) or nullptr
+  const int32_t* cu_seqlens;   // dev [B+1] (packed) or nullptr
+  const int32_t* n_cache;      // dev [B] or nullptr (packed: how many positions go to the pool)
+  const int32_t* block_table;  // dev [B, max_pages]
+};
+
+hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g);
+hipError_t launch_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g);
+hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
+// out[T or n_rows, d] = rmsnorm(x[row]) * gain; rows == nullptr: identity row map, n = T
+hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
+                          const int32_t* n_rows_dev);
+enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
+// C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
+hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,
+                               int M, int N, int K, Epi epi);
+hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer);
+hipError_t launch_swiglu(dllm_ctx* c, hipStream_t s, int T);
+hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer);
+hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32_t* cand, float* conf,
+                            float* entropy);
+hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows);
+hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int32_t* cand, float* conf,
+                           float* entropy);
+hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
+                         const int32_t* cand, const float* conf, float thr, int min_unmask,
+                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining);
+hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
+
+// ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------
+bool mfma_supported(const dllm_ctx* c);
+
+}  // namespace dllm

@@ -1,0 +1,690 @@
+// Generic kernels of the denoise-step path: any shape, float or bfloat16 storage, scalar FMA
+// arithmetic in float.  They are the whole path for float models and the fallback for bfloat16
+// shapes the matrix-core kernels do not take; the small bookkeeping kernels (token map, rotary
+// table, row compaction, statistics merge, unmask) are shared by both.
+#include "common.h"
+#include <math.h>
+
+namespace dllm {
+
+#define DEV_INF (__builtin_inff())
+
+__device__ inline float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// block-wide reductions for blockDim.x <= 1024; red must hold 16 floats; result broadcast
+__device__ inline float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float r = 0.f;
+  for (int i = 0; i < nw; ++i) r += red[i];
+  return r;
+}
+__device__ inline float block_max(float v, float* red) {
+  v = wave_max(v);
+  int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float r = -DEV_INF;
+  for (int i = 0; i < nw; ++i) r = fmaxf(r, red[i]);
+  return r;
+}
+
+// ------------------------------------------------------------------------------------------
+// token map: sequence and position of every row of the forward
+__global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, const int32_t* cu,
+                            int32_t* tok_seq, int32_t* tok_pos) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  if (Q > 0) {
+    int b = t / Q;
+    tok_seq[t] = b;
+    tok_pos[t] = prefix_len[b] + (t - b * Q);
+  } else {
+    int lo = 0, hi = B;  // largest b with cu[b] <= t
+    while (hi - lo > 1) {
+      int mid = (lo + hi) >> 1;
+      if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    tok_seq[t] = lo;
+    tok_pos[t] = t - cu[lo];
+  }
+}
+
+template <typename T>
+__global__ void k_embed(int d, int vocab, const int32_t* tokens, const T* emb, float* x, int32_t* status) {
+  int t = blockIdx.x;
+  int tok = tokens[t];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, DLLM_STATUS_BAD_TOKEN);
+    tok = 0;
+  }
+  const T* row = emb + (int64_t)tok * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)t * d + i] = Elem<T>::load(row + i);
+}
+
+// cos/sin of position * base^(-2j/dh), evaluated in double so that long prefixes keep full
+// float accuracy
+__global__ void k_rope_table(int T, int half, double log2_base, const int32_t* tok_pos, float* cs, float* sn) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T * half) return;
+  int t = i / half, j = i - t * half;
+  double theta = exp2(-(double)j / (double)half * log2_base);
+  double a = (double)tok_pos[t] * theta;
+  double s, c;
+  sincos(a, &s, &c);
+  cs[i] = (float)c;
+  sn[i] = (float)s;
+}
+
+template <typename T>
+__global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* out, const int32_t* rows,
+                          const int32_t* n_rows_dev) {
+  __shared__ float red[16];
+  int r = blockIdx.x;
+  int src = r;
+  if (rows) {
+    if (r >= *n_rows_dev) return;
+    src = rows[r];
+  }
+  const float* xr = x + (int64_t)src * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) { float v = xr[i]; ss += v * v; }
+  ss = block_sum(ss, red);
+  float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += blockDim.x)
+    Elem<T>::store(out + (int64_t)r * d + i, xr[i] * rinv * Elem<T>::load(gain + i));
+}
+
+// ------------------------------------------------------------------------------------------
+// C[M,N] = A[M,K] * W[N,K]^T, 64x64 tile, 16-deep slices through LDS, 4x4 per thread
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void k_gemm(const T* __restrict__ A, const T* __restrict__ W, void* Cv,
+                                              int M, int N, int K) {
+  __shared__ float As[16][68];
+  __shared__ float Ws[16][68];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int lr = tid >> 2, lk = (tid & 3) * 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int kk = k0 + lk + i;
+      As[lk + i][lr] = (m0 + lr < M && kk < K) ? Elem<T>::load(A + (int64_t)(m0 + lr) * K + kk) : 0.f;
+      Ws[lk + i][lr] = (n0 + lr < N && kk < K) ? Elem<T>::load(W + (int64_t)(n0 + lr) * K + kk) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      int64_t idx = (int64_t)m * N + n;
+      if (EPI == EPI_STORE) Elem<T>::store((T*)Cv + idx, acc[i][j]);
+      else if (EPI == EPI_STORE_F32) ((float*)Cv)[idx] = acc[i][j];
+      else ((float*)Cv)[idx] += acc[i][j];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// rotary embedding of q and k (in place), and K/V write into the paged pool
+template <typename T>
+__global__ void k_rope_kv(int Hq, int Hkv, int dh, T* q, T* k, const T* v, const float* cs, const float* sn,
+                          const int32_t* tok_seq, const int32_t* tok_pos, const int32_t* n_cache,
+                          T* pool_k, T* pool_v, KVView kv, int32_t* status) {
+  const int t = blockIdx.x;
+  const int half = dh >> 1;
+  const float* c = cs + (int64_t)t * half;
+  const float* s = sn + (int64_t)t * half;
+  T* qt = q + (int64_t)t * Hq * dh;
+  for (int i = threadIdx.x; i < Hq * half; i += blockDim.x) {
+    int h = i / half, j = i - h * half;
+    T* p = qt + h * dh + j;
+    float a = Elem<T>::load(p), b = Elem<T>::load(p + half);
+    Elem<T>::store(p, a * c[j] - b * s[j]);
+    Elem<T>::store(p + half, b * c[j] + a * s[j]);
+  }
+  const int b = tok_seq[t], pos = tok_pos[t];
+  const bool cached = (n_cache == nullptr) || (pos < n_cache[b]);
+  T* kt = k + (int64_t)t * Hkv * dh;
+  const T* vt = v + (int64_t)t * Hkv * dh;
+  for (int i = threadIdx.x; i < Hkv * half; i += blockDim.x) {
+    int h = i / half, j = i - h * half;
+    T* p = kt + h * dh + j;
+    float a = Elem<T>::load(p), bb = Elem<T>::load(p + half);
+    float r0 = a * c[j] - bb * s[j], r1 = bb * c[j] + a * s[j];
+    Elem<T>::store(p, r0);
+    Elem<T>::store(p + half, r1);
+    if (cached) {
+      int64_t off = kv_offset(kv, b, pos, h);
+      if (off < 0) { atomicOr(status, DLLM_STATUS_BAD_PAGE); }
+      else { Elem<T>::store(pool_k + off + j, r0); Elem<T>::store(pool_k + off + j + half, r1); }
+    }
+  }
+  if (cached) {
+    for (int i = threadIdx.x; i < Hkv * dh; i += blockDim.x) {
+      int h = i / dh, j = i - h * dh;
+      int64_t off = kv_offset(kv, b, pos, h);
+      if (off >= 0) pool_v[off + j] = vt[h * dh + j];
+    }
+  }
+}
+
+template <typename T>
+__global__ void k_swiglu(int64_t n, const float* g, const float* u, T* h) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float x = g[i];
+  Elem<T>::store(h + i, x / (1.0f + expf(-x)) * u[i]);
+}
+
+// ------------------------------------------------------------------------------------------
+// attention, one workgroup per (row, query head): scores of a chunk of keys, running softmax,
+// weighted sum of values.  No mask: every key of the row's sequence takes part.
+constexpr int ATT_CHUNK = 1024;
+template <typename T>
+__global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const T* q, T* o,
+                                                   const int32_t* tok_seq, const int32_t* prefix_len,
+                                                   const int32_t* cu, KVView kv, int32_t* status) {
+  __shared__ float qs[128];
+  __shared__ float sc[ATT_CHUNK];
+  __shared__ int64_t offs[ATT_CHUNK];
+  __shared__ float red[16];
+  __shared__ float osum[256];
+  const int t = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+  const int b = tok_seq[t];
+  const int kv_len = (Q > 0) ? prefix_len[b] + Q : cu[b + 1] - cu[b];
+  const int kvh = h / (Hq / kv.n_kv_heads);
+  const T* kbase = (const T*)kv.k;
+  const T* vbase = (const T*)kv.v;
+  if (tid < dh) qs[tid] = Elem<T>::load(q + ((int64_t)t * Hq + h) * dh + tid);
+  __syncthreads();
+  const float scale = 1.0f / sqrtf((float)dh);
+  const int ng = 256 / dh, grp = tid / dh, d = tid - grp * dh;
+  float m = -DEV_INF, l = 0.f, oacc = 0.f;
+  bool bad = false;
+  for (int c0 = 0; c0 < kv_len; c0 += ATT_CHUNK) {
+    const int n = min(ATT_CHUNK, kv_len - c0);
+    float cm = -DEV_INF;
+    for (int j = tid; j < n; j += 256) {
+      int64_t off = kv_offset(kv, b, c0 + j, kvh);
+      float s = -DEV_INF;
+      if (off >= 0) {
+        const T* kr = kbase + off;
+        float a = 0.f;
+        for (int e = 0; e < dh; ++e) a = fmaf(qs[e], Elem<T>::load(kr + e), a);
+        s = a * scale;
+      } else bad = true;
+      sc[j] = s;
+      offs[j] = off;
+      cm = fmaxf(cm, s);
+    }
+    cm = block_max(cm, red);
+    if (cm == -DEV_INF) { __syncthreads(); continue; }
+    const float m_new = fmaxf(m, cm);
+    const float alpha = (m == -DEV_INF) ? 0.f : expf(m - m_new);
+    float ps = 0.f;
+    for (int j = tid; j < n; j += 256) {
+      float p = (sc[j] == -DEV_INF) ? 0.f : expf(sc[j] - m_new);
+      sc[j] = p;
+      ps += p;
+    }
+    ps = block_sum(ps, red);   // has the barriers that publish sc[]
+    l = l * alpha + ps;
+    oacc *= alpha;
+    if (grp < ng) {
+      for (int j = grp; j < n; j += ng) {
+        int64_t off = offs[j];
+        if (off >= 0) oacc = fmaf(sc[j], Elem<T>::load(vbase + off + d), oacc);
+      }
+    }
+    m = m_new;
+    __syncthreads();
+  }
+  osum[tid] = (grp < ng) ? oacc : 0.f;
+  __syncthreads();
+  if (tid < dh) {
+    float tot = 0.f;
+    for (int g2 = 0; g2 < ng; ++g2) tot += osum[g2 * dh + tid];
+    Elem<T>::store(o + ((int64_t)t * Hq + h) * dh + tid, l > 0.f ? tot / l : 0.f);
+  }
+  if (bad) atomicOr(status, DLLM_STATUS_BAD_PAGE);
+}
+
+// ------------------------------------------------------------------------------------------
+// Rows of the LM head: compacts, in ascending order, the rows whose token is the mask id (and,
+// in a refresh call, whose position is not below n_commit), and writes the fixed outputs of
+// the other eligible rows.  One workgroup of 1024 threads.
+__global__ __launch_bounds__(1024) void k_mask_rows(int T, int32_t mask_id, int cap, const int32_t* tokens,
+                                                    const int32_t* tok_seq, const int32_t* tok_pos,
+                                                    const int32_t* n_commit, int32_t* rows, int32_t* status,
+                                                    int32_t* cand, float* conf, float* entropy) {
+  __shared__ int wcount[16];
+  __shared__ int base_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) base_s = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < T; c0 += 1024) {
+    const int t = c0 + tid;
+    bool eligible = false, flag = false;
+    if (t < T) {
+      eligible = (n_commit == nullptr) || (tok_pos[t] >= n_commit[tok_seq[t]]);
+      flag = eligible && tokens[t] == mask_id;
+      if (eligible && !flag) {
+        cand[t] = tokens[t];
+        conf[t] = 1.0f;
+        if (entropy) entropy[t] = 0.f;
+      }
+    }
+    const unsigned long long bal = __ballot(flag);
+    const int lane_pre = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wcount[wave] = __popcll(bal);
+    __syncthreads();
+    int wave_pre = 0, total = 0;
+    for (int w = 0; w < 16; ++w) { int cw = wcount[w]; if (w < wave) wave_pre += cw; total += cw; }
+    const int base = base_s;
+    if (flag) {
+      int p = base + wave_pre + lane_pre;
+      if (p < cap) rows[p] = t;
+    }
+    __syncthreads();
+    if (tid == 0) base_s = base + total;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int n = base_s;
+    if (n > cap) { atomicOr(status, DLLM_STATUS_ROWS_CAP); n = cap; }
+    status[1] = n;
+  }
+}
+
+// Softmax statistics of a run of logits in ascending column order.
+struct RowStat {
+  float m, s, t;  // running max, sum exp(z-m), sum exp(z-m)*z
+  int idx;
+  __device__ inline void init() { m = -DEV_INF; s = 0.f; t = 0.f; idx = 0x7fffffff; }
+  __device__ inline void push(float z, int col) {
+    if (z > m) {
+      float a = expf(m - z);   // exp(-inf) = 0 on the first value
+      s = s * a + 1.0f;
+      t = t * a + z;
+      m = z;
+      idx = col;
+    } else {
+      float e = expf(z - m);
+      s += e;
+      t = fmaf(e, z, t);
+    }
+  }
+  // merge with another run; on equal maxima the lower column wins
+  __device__ inline void merge(float m2, int i2, float s2, float t2) {
+    if (!(s2 > 0.f) && !(s2 != s2)) return;   // empty run
+    if (!(s > 0.f) && !(s != s)) { m = m2; idx = i2; s = s2; t = t2; return; }
+    if (m2 > m || (m2 == m && i2 < idx)) {
+      float a = expf(m - m2);
+      s = s * a + s2;
+      t = t * a + t2;
+      m = m2;
+      idx = i2;
+    } else {
+      float a = expf(m2 - m);
+      s = fmaf(s2, a, s);
+      t = fmaf(t2, a, t);
+    }
+  }
+};
+
+// LM head on the compacted rows with the softmax statistics taken from the accumulators:
+// each workgroup computes 64 rows x LM_TILE_N vocabulary columns in 64-column slices and keeps
+// (max, argmax, sum exp, sum exp*z) per row.  The logits never leave the chip.
+template <typename T>
+__global__ __launch_bounds__(256) void k_lm_head(const T* __restrict__ A, const T* __restrict__ W, int V, int K,
+                                                 int32_t mask_id, const int32_t* n_rows_dev, float* part,
+                                                 int n_vtiles) {
+  __shared__ float As[16][68];
+  __shared__ float Ws[16][68];
+  __shared__ float Cs[64][65];
+  const int M = *n_rows_dev;
+  const int m0 = blockIdx.y * 64;
+  if (m0 >= M) return;
+  const int vt = blockIdx.x;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int lr = tid >> 2, lk = (tid & 3) * 4;
+  RowStat st;
+  st.init();
+  for (int sub = 0; sub < LM_TILE_N / 64; ++sub) {
+    const int n0 = vt * LM_TILE_N + sub * 64;
+    if (n0 >= V) break;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int kk = k0 + lk + i;
+        As[lk + i][lr] = (m0 + lr < M && kk < K) ? Elem<T>::load(A + (int64_t)(m0 + lr) * K + kk) : 0.f;
+        Ws[lk + i][lr] = (n0 + lr < V && kk < K) ? Elem<T>::load(W + (int64_t)(n0 + lr) * K + kk) : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < 16; ++kk) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) Cs[ty * 4 + i][tx * 4 + j] = acc[i][j];
+    __syncthreads();
+    if (tid < 64 && m0 + tid < M) {
+      for (int j = 0; j < 64; ++j) {
+        int col = n0 + j;
+        if (col < V && col != mask_id) st.push(Cs[tid][j], col);
+      }
+    }
+    __syncthreads();
+  }
+  if (tid < 64 && m0 + tid < M) {
+    float* p = part + ((int64_t)(m0 + tid) * n_vtiles + vt) * 4;
+    p[0] = st.m;
+    p[1] = __int_as_float(st.idx);
+    p[2] = st.s;
+    p[3] = st.t;
+  }
+}
+
+// one wavefront per compacted row: merge the per-tile statistics and emit the outputs
+__global__ __launch_bounds__(64) void k_lm_merge(const float* part, int n_vtiles, const int32_t* rows,
+                                                 const int32_t* n_rows_dev, int32_t* cand, float* conf,
+                                                 float* entropy) {
+  const int r = blockIdx.x;
+  if (r >= *n_rows_dev) return;
+  const int lane = threadIdx.x;
+  RowStat st;
+  st.init();
+  for (int v = lane; v < n_vtiles; v += 64) {
+    const float* p = part + ((int64_t)r * n_vtiles + v) * 4;
+    st.merge(p[0], __float_as_int(p[1]), p[2], p[3]);
+  }
+  for (int o = 1; o < 64; o <<= 1) {
+    float m2 = __shfl_xor(st.m, o, 64), s2 = __shfl_xor(st.s, o, 64), t2 = __shfl_xor(st.t, o, 64);
+    int i2 = __shfl_xor(st.idx, o, 64);
+    st.merge(m2, i2, s2, t2);
+  }
+  if (lane == 0) {
+    const int t = rows[r];
+    cand[t] = st.idx;
+    conf[t] = 1.0f / st.s;
+    if (entropy) entropy[t] = (st.m + logf(st.s)) - st.t / st.s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// threshold + floor selection: one wavefront per (sequence, block)
+__device__ inline bool conf_before(float a, int ia, float b, int ib) {
+  // ordering "confidence descending, index ascending", NaN last
+  bool an = (a != a), bn = (b != b);
+  if (an != bn) return bn;
+  if (!an && a != b) return a > b;
+  return ia < ib;
+}
+__global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
+                                               const float* conf, float thr, int min_unmask, int32_t mask_id,
+                                               int32_t* n_unmasked, int32_t* n_remaining) {
+  __shared__ float cf[1024];
+  __shared__ unsigned char msk[1024];
+  const int nblk = Q / block_len;
+  const int b = blockIdx.x / nblk, blk = blockIdx.x - b * nblk;
+  const int64_t base = (int64_t)b * Q + (int64_t)blk * block_len;
+  const int lane = threadIdx.x;
+  int n_masked = 0;
+  for (int i = lane; i < block_len; i += 64) {
+    bool mk = q_tokens[base + i] == mask_id;
+    msk[i] = mk;
+    cf[i] = conf[base + i];
+    n_masked += mk;
+  }
+  for (int o = 32; o > 0; o >>= 1) n_masked += __shfl_xor(n_masked, o, 64);
+  __syncthreads();
+  const int floor_n = min(min_unmask, n_masked);
+  int n_un = 0;
+  for (int i = lane; i < block_len; i += 64) {
+    if (!msk[i]) continue;
+    const float c = cf[i];
+    bool take = (c >= thr);
+    if (!take) {
+      int rank = 0;
+      for (int j = 0; j < block_len; ++j)
+        if (msk[j] && j != i && conf_before(cf[j], j, c, i)) ++rank;
+      take = rank < floor_n;
+    }
+    if (take) {
+      q_tokens[base + i] = cand[base + i];
+      ++n_un;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) n_un += __shfl_xor(n_un, o, 64);
+  if (lane == 0) {
+    if (n_unmasked) n_unmasked[blockIdx.x] = n_un;
+    if (n_remaining) n_remaining[blockIdx.x] = n_masked - n_un;
+  }
+}
+
+__global__ void k_copy_f32(const float* src, float* dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+__global__ void k_set_i32(int32_t* p, int n, int32_t v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ==========================================================================================
+// launchers
+#define WS(c, field, type) ((type*)((c)->ws + (c)->map.field))
+#define IS_BF16(c) ((c)->cfg.dtype == DLLM_BF16)
+
+hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
+  k_token_map<<<(g.T + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
+                                                WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t));
+  return hipGetLastError();
+}
+
+hipError_t launch_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
+  const dllm_config& f = c->cfg;
+  if (IS_BF16(c))
+    k_embed<bf16_t><<<g.T, 256, 0, s>>>(f.d_model, f.vocab, g.tokens, (const bf16_t*)c->tok_emb,
+                                        WS(c, x, float), WS(c, status, int32_t));
+  else
+    k_embed<float><<<g.T, 256, 0, s>>>(f.d_model, f.vocab, g.tokens, (const float*)c->tok_emb,
+                                       WS(c, x, float), WS(c, status, int32_t));
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
+  const int half = c->cfg.head_dim / 2;
+  const int n = g.T * half;
+  k_rope_table<<<(n + 255) / 256, 256, 0, s>>>(g.T, half, log2((double)c->cfg.rope_base),
+                                               WS(c, tok_pos, int32_t), WS(c, rope_cos, float),
+                                               WS(c, rope_sin, float));
+  return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
+                          const int32_t* n_rows_dev) {
+  const dllm_config& f = c->cfg;
+  if (IS_BF16(c))
+    k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
+                                        WS(c, xn, bf16_t), rows, n_rows_dev);
+  else
+    k_rmsnorm<float><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const float*)gain,
+                                       WS(c, xn, float), rows, n_rows_dev);
+  return hipGetLastError();
+}
+
+template <typename T>
+static void gemm_dispatch(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  if (epi == EPI_STORE) k_gemm<T, EPI_STORE><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
+  else if (epi == EPI_STORE_F32) k_gemm<T, EPI_STORE_F32><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
+  else k_gemm<T, EPI_RESID><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
+}
+
+hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C, int M, int N,
+                               int K, Epi epi) {
+  if (IS_BF16(c)) gemm_dispatch<bf16_t>(s, A, W, C, M, N, K, epi);
+  else gemm_dispatch<float>(s, A, W, C, M, N, K, epi);
+  return hipGetLastError();
+}
+
+static KVView make_view(dllm_ctx* c, const StepGeom& g, int layer, bool paged, void** pool_k, void** pool_v) {
+  const dllm_config& f = c->cfg;
+  const size_t slab = kv_slab_elems(f) * elem_size(f);
+  char* pk = c->kv_pool + (size_t)(layer * 2 + 0) * slab;
+  char* pv = c->kv_pool + (size_t)(layer * 2 + 1) * slab;
+  if (pool_k) *pool_k = pk;
+  if (pool_v) *pool_v = pv;
+  KVView kv;
+  kv.page_tokens = f.page_tokens;
+  kv.max_pages = f.max_pages_per_seq;
+  kv.n_pages = f.n_pages;
+  kv.n_kv_heads = f.n_kv_heads;
+  kv.head_dim = f.head_dim;
+  kv.cu_seqlens = g.cu_seqlens;
+  if (paged) { kv.k = pk; kv.v = pv; kv.table = g.block_table; }
+  else { kv.k = c->ws + c->map.k; kv.v = c->ws + c->map.v; kv.table = nullptr; }
+  return kv;
+}
+
+KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer) {
+  return make_view(c, g, layer, /*paged=*/g.Q > 0, nullptr, nullptr);
+}
+
+hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer) {
+  const dllm_config& f = c->cfg;
+  void *pk, *pv;
+  KVView kv = make_view(c, g, layer, true, &pk, &pv);
+  const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
+  // packed forward with n_cache == nullptr caches every position: same as the step case
+  if (IS_BF16(c))
+    k_rope_kv<bf16_t><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q, bf16_t), WS(c, k, bf16_t),
+                                          WS(c, v, bf16_t), WS(c, rope_cos, float), WS(c, rope_sin, float),
+                                          WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
+                                          (bf16_t*)pk, (bf16_t*)pv, kv, WS(c, status, int32_t));
+  else
+    k_rope_kv<float><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q, float), WS(c, k, float),
+                                         WS(c, v, float), WS(c, rope_cos, float), WS(c, rope_sin, float),
+                                         WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
+                                         (float*)pk, (float*)pv, kv, WS(c, status, int32_t));
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu(dllm_ctx* c, hipStream_t s, int T) {
+  const int64_t n = (int64_t)T * c->cfg.d_ff;
+  const unsigned grid = (unsigned)((n + 255) / 256);
+  if (IS_BF16(c)) k_swiglu<bf16_t><<<grid, 256, 0, s>>>(n, WS(c, g, float), WS(c, u, float), WS(c, h, bf16_t));
+  else k_swiglu<float><<<grid, 256, 0, s>>>(n, WS(c, g, float), WS(c, u, float), WS(c, h, float));
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer) {
+  const dllm_config& f = c->cfg;
+  KVView kv = attention_view(c, g, layer);
+  dim3 grid(g.T, f.n_q_heads);
+  if (IS_BF16(c))
+    k_attention<bf16_t><<<grid, 256, 0, s>>>(f.n_q_heads, f.head_dim, g.Q, WS(c, q, bf16_t), WS(c, o, bf16_t),
+                                             WS(c, tok_seq, int32_t), g.prefix_len, g.cu_seqlens, kv,
+                                             WS(c, status, int32_t));
+  else
+    k_attention<float><<<grid, 256, 0, s>>>(f.n_q_heads, f.head_dim, g.Q, WS(c, q, float), WS(c, o, float),
+                                            WS(c, tok_seq, int32_t), g.prefix_len, g.cu_seqlens, kv,
+                                            WS(c, status, int32_t));
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32_t* cand, float* conf,
+                            float* entropy) {
+  const int32_t* n_commit = (g.Q > 0) ? nullptr : g.n_cache;
+  k_mask_rows<<<1, 1024, 0, s>>>(g.T, c->cfg.mask_id, (int)c->map.r_max, g.tokens, WS(c, tok_seq, int32_t),
+                                 WS(c, tok_pos, int32_t), n_commit, WS(c, rows, int32_t),
+                                 WS(c, status, int32_t), cand, conf, entropy);
+  return hipGetLastError();
+}
+
+hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows) {
+  const dllm_config& f = c->cfg;
+  dim3 grid(c->map.n_vtiles, (max_rows + 63) / 64);
+  const int32_t* n_rows = WS(c, status, int32_t) + 1;
+  if (IS_BF16(c))
+    k_lm_head<bf16_t><<<grid, 256, 0, s>>>(WS(c, xn, bf16_t), (const bf16_t*)c->lm_head, f.vocab, f.d_model,
+                                           f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles);
+  else
+    k_lm_head<float><<<grid, 256, 0, s>>>(WS(c, xn, float), (const float*)c->lm_head, f.vocab, f.d_model,
+                                          f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int32_t* cand, float* conf, float* entropy) {
+  k_lm_merge<<<max_rows, 64, 0, s>>>(WS(c, lm_part, float), c->map.n_vtiles, WS(c, rows, int32_t),
+                                     WS(c, status, int32_t) + 1, cand, conf, entropy);
+  return hipGetLastError();
+}
+
+hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
+                         const float* conf, float thr, int min_unmask, int32_t mask_id, int32_t* n_unmasked,
+                         int32_t* n_remaining) {
+  k_unmask<<<B * (Q / block_len), 64, 0, s>>>(Q, block_len, q_tokens, cand, conf, thr, min_unmask, mask_id,
+                                              n_unmasked, n_remaining);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n) {
+  k_copy_f32<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_i32(hipStream_t s, int32_t* p, int n, int32_t v) {
+  k_set_i32<<<(n + 255) / 256, 256, 0, s>>>(p, n, v);
+  return hipGetLastError();
+}
+
+}  // namespace dllm

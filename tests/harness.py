@@ -1,0 +1,81 @@
+"""Shared helpers of the GPU parity tests: engine set-up from the seeded generator, block tables,
+and the comparison rules (per-row max-norm relative error of logits; token ids and unmask sets
+exact except where the oracle itself is within 1e-3 of a tie or of the threshold)."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import dllm_oracle as O
+from paper_2601_07568_amd import synth
+
+MARGIN = 1e-3          # top-2 probability margin below which a token id may differ
+LOGIT_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def make_engine(ms, weights, **kw):
+    from paper_2601_07568_amd.binding import Engine
+    return Engine(ms, weights, **kw)
+
+
+def identity_table(eng, B, perm=None):
+    """Block table [B, max_pages_per_seq]: sequence b owns pages b*mp .. (b+1)*mp-1 (optionally
+    sent through a permutation of the physical pages)."""
+    mp = eng.cfg.max_pages_per_seq
+    t = np.arange(B * mp, dtype=np.int32).reshape(B, mp)
+    assert B * mp <= eng.cfg.n_pages
+    if perm is not None:
+        t = np.asarray(perm, dtype=np.int32)[t]
+    return t
+
+
+def rel_err_rows(got, ref):
+    """max_v |got - ref| / max(max_v |ref|, 1e-6), per row."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return np.abs(got - ref).max(axis=-1) / np.maximum(np.abs(ref).max(axis=-1), 1e-6)
+
+
+def top2_margin(p):
+    s = np.sort(p, axis=-1)
+    return s[:, -1] - s[:, -2]
+
+
+def gather_cache(eng, table_row, n, layer, which):
+    """Positions 0..n-1 of one sequence out of the paged pool -> numpy [n, Hkv, dh] float32."""
+    slab = eng.kv_slab(layer, which).float().cpu().numpy()      # [pages, Hkv, pt, dh]
+    pt = eng.cfg.page_tokens
+    out = np.empty((n, slab.shape[1], slab.shape[3]), dtype=np.float32)
+    for j in range(n):
+        out[j] = slab[table_row[j // pt], :, j % pt, :]
+    return out
+
+
+def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, conf_tol=None):
+    """GPU cand/conf/entropy of the masked rows against an oracle step record r."""
+    _, oconf, oent, p = O.confidence(r["logits"], ms.mask_id)
+    margin = top2_margin(p)
+    tol = conf_tol if conf_tol is not None else (2e-4 if dtype == "f32" else 3e-2)
+    n_exact = 0
+    for i in np.nonzero(masked)[0]:
+        if margin[i] > MARGIN:
+            assert cand[i] == r["cand"][i], (i, cand[i], r["cand"][i], margin[i])
+            n_exact += 1
+        assert abs(conf[i] - oconf[i]) <= tol * max(oconf[i], 1e-3) + 1e-7, (i, conf[i], oconf[i])
+        if ent is not None:
+            assert abs(ent[i] - oent[i]) <= tol * max(abs(oent[i]), 1.0), (i, ent[i], oent[i])
+    return n_exact
+
+
+def selection_is_decided(conf, masked, tau, m):
+    """True if the oracle's unmask set is not within MARGIN of changing: no masked confidence within
+    MARGIN of tau, and the m'-th and (m'+1)-th confidences differ by more than MARGIN."""
+    c = np.asarray(conf)[np.asarray(masked)]
+    if len(c) == 0:
+        return True
+    if (np.abs(c - tau) <= MARGIN).any():
+        return False
+    mm = min(m, len(c))
+    s = np.sort(c)[::-1]
+    if mm < len(c) and s[mm - 1] - s[mm] <= MARGIN:
+        return False
+    return True

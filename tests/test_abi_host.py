@@ -1,0 +1,118 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+
+import pytest
+
+from paper_2601_07568_amd import binding as B
+from paper_2601_07568_amd import build, synth
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = build.declared_symbols()
+    assert {"dllm_prefill_kv", "dllm_denoise_step", "dllm_unmask", "dllm_refresh_cache"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def cfg_for(ms, **kw):
+    d = dict(page_tokens=16, max_pages_per_seq=8, n_pages=8, max_batch=2, max_q=32, max_tokens=128)
+    d.update(kw)
+    return B.make_config(ms, **d)
+
+
+def fake_ctx(cfg):
+    """A context over fake (never dereferenced) device addresses: creation makes no HIP call."""
+    L = B.lib()
+    lw = (B.LayerW * max(1, cfg.n_layers))()
+    for l in range(cfg.n_layers):
+        for name, _ in B.LayerW._fields_:
+            setattr(lw[l], name, 0x1000)
+    w = B.Weights(0x1000, 0x1000, 0x1000, lw)
+    ctx = C.c_void_p()
+    ws, kv = L.dllm_workspace_bytes(C.byref(cfg)), L.dllm_kv_pool_bytes(C.byref(cfg))
+    rc = L.dllm_create(C.byref(ctx), C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000 * 256, ws)
+    return rc, ctx, (lw, w), ws, kv
+
+
+def test_sizes_and_config_validation():
+    L = B.lib()
+    cfg = cfg_for(synth.TINY)
+    assert L.dllm_workspace_bytes(C.byref(cfg)) > 0
+    # pool: layers * 2 * pages * heads * page_tokens * head_dim * 4 bytes
+    assert L.dllm_kv_pool_bytes(C.byref(cfg)) == 2 * 2 * 8 * 4 * 16 * 64 * 4
+    for bad in (dict(page_tokens=0), dict(max_batch=0), dict(n_pages=0)):
+        assert L.dllm_workspace_bytes(C.byref(cfg_for(synth.TINY, **bad))) == 0
+    import dataclasses
+    for field, val in (("head_dim", 48), ("n_kv_heads", 3), ("mask_id", 4096), ("mask_id", -1)):
+        ms = dataclasses.replace(synth.TINY, **{field: val})
+        assert L.dllm_workspace_bytes(C.byref(cfg_for(ms))) == 0
+        rc, ctx, _, _, _ = fake_ctx(cfg_for(ms))
+        assert rc == B.DLLM_ESHAPE and not ctx
+    ms = dataclasses.replace(synth.TINY, dtype="bf16", d_ff=692)      # bf16 wants multiples of 8
+    assert L.dllm_workspace_bytes(C.byref(cfg_for(ms))) == 0
+
+
+def test_create_rejects_nulls_and_small_buffers():
+    L = B.lib()
+    cfg = cfg_for(synth.TINY)
+    rc, ctx, keep, ws, kv = fake_ctx(cfg)
+    assert rc == B.DLLM_OK and ctx
+    L.dllm_destroy(ctx)
+    lw, w = keep
+    out = C.c_void_p()
+    assert L.dllm_create(C.byref(out), C.byref(cfg), C.byref(w), 0x10000, kv - 1, 0x20000 * 256, ws) == B.DLLM_ENOSPACE
+    assert L.dllm_create(C.byref(out), C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000 * 256, ws - 1) == B.DLLM_ENOSPACE
+    assert L.dllm_create(C.byref(out), C.byref(cfg), C.byref(w), None, kv, 0x20000 * 256, ws) == B.DLLM_EINVAL
+    assert L.dllm_create(C.byref(out), C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000 * 256 + 8, ws) == B.DLLM_EINVAL
+    lw[1].wo = None
+    assert L.dllm_create(C.byref(out), C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000 * 256, ws) == B.DLLM_EINVAL
+    assert not out
+    assert L.dllm_create(None, C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000 * 256, ws) == B.DLLM_EINVAL
+
+
+def test_calls_validate_before_launching():
+    L = B.lib()
+    cfg = cfg_for(synth.TINY)
+    rc, ctx, keep, _, _ = fake_ctx(cfg)
+    assert rc == B.DLLM_OK
+    p = 0x3000
+    E, S = B.DLLM_EINVAL, B.DLLM_ESHAPE
+    # denoise step
+    assert L.dllm_denoise_step(ctx, None, 0, 32, 64, p, p, p, p, p, None) == E
+    assert L.dllm_denoise_step(ctx, None, 3, 32, 64, p, p, p, p, p, None) == S          # B > max_batch
+    assert L.dllm_denoise_step(ctx, None, 1, 33, 64, p, p, p, p, p, None) == S          # Q > max_q
+    assert L.dllm_denoise_step(ctx, None, 1, 32, 97, p, p, p, p, p, None) == S          # beyond the block table
+    assert L.dllm_denoise_step(ctx, None, 1, 32, -1, p, p, p, p, p, None) == E
+    assert L.dllm_denoise_step(ctx, None, 1, 32, 64, None, p, p, p, p, None) == E
+    assert L.dllm_denoise_step(ctx, None, 1, 32, 64, p, p, p, None, p, None) == E
+    assert L.dllm_denoise_step(None, None, 1, 32, 64, p, p, p, p, p, None) == E
+    assert L.dllm_debug_logits(ctx, None, 1, 32, 64, p, p, p, None) == E
+    assert L.dllm_debug_hidden(ctx, None, 1, 32, 64, p, p, p, 3, p) == E                # only 2 layers
+    # prefill / refresh
+    assert L.dllm_prefill_kv(ctx, None, 1, 129, 129, p, p, None, p) == S                # > max_tokens
+    assert L.dllm_prefill_kv(ctx, None, 1, 0, 0, p, p, None, p) == E
+    assert L.dllm_prefill_kv(ctx, None, 1, 64, 65, p, p, None, p) == E                  # max_seqlen > total
+    assert L.dllm_prefill_kv(ctx, None, 3, 64, 64, p, p, None, p) == S
+    assert L.dllm_prefill_kv(ctx, None, 1, 64, 64, None, p, None, p) == E
+    assert L.dllm_refresh_cache(ctx, None, 1, 64, 64, p, p, None, p, p, p, None) == E   # outputs need n_commit
+    assert L.dllm_refresh_cache(ctx, None, 1, 64, 64, p, p, p, p, p, None, None) == E
+    # unmask
+    assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, 0.9, 0, None, None) == E        # floor must be >= 1
+    assert L.dllm_unmask(ctx, None, 1, 32, 5, p, p, p, 0.9, 1, None, None) == E         # Q % block_len
+    assert L.dllm_unmask(ctx, None, 1, 32, 32, None, p, p, 0.9, 1, None, None) == E
+    assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E
+    assert L.dllm_unmask(ctx, None, 1, 4096, 2048, p, p, p, 0.9, 1, None, None) == S
+    assert L.dllm_set_kernel_mode(ctx, 7) == E
+    assert L.dllm_read_status(ctx, None, None) == E
+    assert L.dllm_strerror(B.DLLM_ESHAPE).decode().startswith("unsupported")
+    L.dllm_destroy(ctx)
+    L.dllm_destroy(None)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libdllm.so")
+    with pytest.raises(RuntimeError):
+        B.lib()

@@ -1,0 +1,192 @@
+"""GPU parity at the tiny float32 configuration (2 layers, d 256, 4 heads x 64, MLP 688, vocab
+4096, prompt 64, one block of 32): every call of the C ABI against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dllm_oracle as O
+from paper_2601_07568_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+TINY = synth.TINY
+P, Q = 64, 32
+
+
+@pytest.fixture(scope="module")
+def world():
+    w = synth.Weights(TINY, 0)
+    eng = H.make_engine(TINY, w, page_tokens=16, max_pages_per_seq=16, n_pages=48, max_batch=3, max_q=64,
+                        max_tokens=512)
+    prompt = synth.random_tokens(TINY, 0, P)
+    ck, cv = O.prefill(w, prompt)
+    return dict(w=w, eng=eng, prompt=prompt, ck=ck, cv=cv)
+
+
+def gpu_prefill(eng, seqs, table, n_cache=None):
+    toks = np.concatenate(seqs).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum([len(s) for s in seqs])]).astype(np.int32)
+    eng.prefill_kv(eng.i32(toks), eng.i32(cu), eng.i32(table), None if n_cache is None else eng.i32(n_cache),
+                   total_tokens=len(toks), max_seqlen=max(len(s) for s in seqs))
+
+
+def test_prefill_cache_matches_oracle(world):
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    assert eng.read_status() == 0
+    for l in range(TINY.n_layers):
+        for which, ref in ((0, world["ck"][l]), (1, world["cv"][l])):
+            got = H.gather_cache(eng, table[0], P, l, which)
+            assert np.abs(got - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+
+
+def test_teacher_forced_steps_logits_conf_and_unmask(world):
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    rec = []
+    O.decode(w, world["prompt"], 1, Q, 0.9, 1, record=rec)
+    assert len(rec) == 32
+    prefix = eng.i32([P]); tab = eng.i32(table)
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    n_exact = 0
+    for step, r in enumerate(rec):
+        qt = eng.i32(r["before"][None, :])
+        if step % 8 == 0:
+            logits = eng.debug_logits(qt, prefix, tab, max_prefix_len=P).cpu().numpy()[0]
+            assert H.rel_err_rows(logits, r["logits"]).max() <= H.LOGIT_TOL["f32"]
+        eng.denoise_step(qt, prefix, tab, cand, conf, ent, max_prefix_len=P)
+        masked = r["before"] == TINY.mask_id
+        c, cf, en = cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0]
+        n_exact += H.check_step_outputs(TINY, r, masked, c, cf, en, "f32")
+        # rows that are not masked report their own token with confidence 1
+        assert (c[~masked] == r["before"][~masked]).all() and (cf[~masked] == 1).all()
+        nun = torch.zeros(1, 1, dtype=torch.int32, device=eng.device)
+        nrem = torch.zeros(1, 1, dtype=torch.int32, device=eng.device)
+        eng.unmask(qt, cand, conf, 0.9, 1, n_unmasked=nun, n_remaining=nrem)
+        if H.selection_is_decided(r["conf"], masked, 0.9, 1):
+            after = qt.cpu().numpy()[0]
+            chosen = np.nonzero(after != r["before"])[0].tolist()
+            assert chosen == r["chosen"]
+            assert int(nun) == len(chosen) and int(nrem) == masked.sum() - len(chosen)
+    assert n_exact > 400
+    assert eng.read_status() == 0
+
+
+def test_free_running_decode_matches_oracle(world):
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    rec = []
+    seq, steps = O.decode(w, world["prompt"], 1, Q, 0.9, 1, record=rec)
+    qt = eng.i32(np.full((1, Q), TINY.mask_id))
+    prefix = eng.i32([P]); tab = eng.i32(table)
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    nrem = torch.ones(1, 1, dtype=torch.int32, device=eng.device)
+    n = 0
+    while int(nrem) > 0:
+        r = rec[n]
+        before = qt.cpu().numpy()[0]
+        assert (before == r["before"]).all()
+        if not H.selection_is_decided(r["conf"], before == TINY.mask_id, 0.9, 1):
+            break                 # the oracle itself is within 1e-3 of a tie: compared up to here
+        eng.denoise_step(qt, prefix, tab, cand, conf, max_prefix_len=P)
+        eng.unmask(qt, cand, conf, 0.9, 1, n_remaining=nrem)
+        n += 1
+        assert n <= 32
+    assert n >= 8
+    if int(nrem) == 0:
+        assert n == steps and (qt.cpu().numpy()[0] == seq[P:]).all()
+
+
+def test_refresh_rewrites_cache_and_cached_step_equals_recompute(world):
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    blk = synth.masked_block(TINY, 5, Q, 20)
+    seq = np.concatenate([world["prompt"], blk])
+    full, Ks, Vs, _ = O.forward_full(w, seq)
+    # refresh over prompt + in-flight block, committing only the prompt; step outputs for the block
+    n_tok = len(seq)
+    cand = torch.full((n_tok,), -7, dtype=torch.int32, device=eng.device)
+    conf = torch.full((n_tok,), -7.0, dtype=torch.float32, device=eng.device)
+    ent = torch.full((n_tok,), -7.0, dtype=torch.float32, device=eng.device)
+    eng.refresh_cache(eng.i32(seq), eng.i32([0, n_tok]), eng.i32(table), eng.i32([P]), cand, conf, ent,
+                      total_tokens=n_tok, max_seqlen=n_tok)
+    for l in range(TINY.n_layers):
+        got = H.gather_cache(eng, table[0], P, l, 0)
+        assert np.abs(got - Ks[l][:P]).max() <= 1e-5 * max(1.0, np.abs(Ks[l]).max())
+        got = H.gather_cache(eng, table[0], P, l, 1)
+        assert np.abs(got - Vs[l][:P]).max() <= 1e-5 * max(1.0, np.abs(Vs[l]).max())
+    c, cf, en = cand.cpu().numpy(), conf.cpu().numpy(), ent.cpu().numpy()
+    assert (c[:P] == -7).all() and (cf[:P] == -7).all()             # committed rows untouched
+    r = {"logits": full[P:], "cand": O.confidence(full[P:], TINY.mask_id)[0]}
+    H.check_step_outputs(TINY, r, blk == TINY.mask_id, c[P:], cf[P:], en[P:], "f32")
+    # now a cached step over the same block sees the same K/V: logits equal the no-cache rows
+    logits = eng.debug_logits(eng.i32(blk[None]), eng.i32([P]), eng.i32(table), max_prefix_len=P).cpu().numpy()[0]
+    assert H.rel_err_rows(logits, full[P:]).max() <= H.LOGIT_TOL["f32"]
+    assert eng.read_status() == 0
+
+
+def test_batch_of_ragged_sequences_and_page_permutation(world):
+    eng, w = world["eng"], world["w"]
+    lens = [64, 37, 50]
+    seqs = [synth.random_tokens(TINY, 10 + i, n) for i, n in enumerate(lens)]
+    blks = [synth.masked_block(TINY, 20 + i, Q, 12 + 4 * i) for i in range(3)]
+    rng = np.random.default_rng(0)
+    outs = []
+    for perm in (None, rng.permutation(eng.cfg.n_pages)):
+        table = H.identity_table(eng, 3, perm)
+        eng.kv_pool.zero_()
+        gpu_prefill(eng, seqs, table)
+        lg = eng.debug_logits(eng.i32(np.stack(blks)), eng.i32(lens), eng.i32(table), max_prefix_len=max(lens))
+        outs.append(lg.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])                        # physical page order is invisible
+    for b in range(3):
+        ck, cv = O.prefill(w, seqs[b])
+        ref, _ = O.forward_cached(w, blks[b], ck, cv)
+        assert H.rel_err_rows(outs[0][b], ref).max() <= H.LOGIT_TOL["f32"]
+    assert eng.read_status() == 0
+
+
+def test_two_blocks_in_flight_with_per_block_floor(world):
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    blk = synth.masked_block(TINY, 31, 64, 40)
+    r = O.denoise_step(w, blk, world["ck"], world["cv"], tau=0.15, m=2, block_len=32)
+    qt = eng.i32(blk[None])
+    cand = torch.zeros(1, 64, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, 64, dtype=torch.float32, device=eng.device)
+    eng.denoise_step(qt, eng.i32([P]), eng.i32(table), cand, conf, max_prefix_len=P)
+    masked = blk == TINY.mask_id
+    H.check_step_outputs(TINY, r, masked, cand.cpu().numpy()[0], conf.cpu().numpy()[0], None, "f32")
+    nun = torch.zeros(1, 2, dtype=torch.int32, device=eng.device)
+    eng.unmask(qt, cand, conf, 0.15, 2, block_len=32, n_unmasked=nun)
+    decided = all(H.selection_is_decided(r["conf"][s], masked[s], 0.15, 2) for s in (slice(0, 32), slice(32, 64)))
+    if decided:
+        after = qt.cpu().numpy()[0]
+        assert np.nonzero(after != blk)[0].tolist() == r["chosen"]
+        assert (after == r["tokens"]).all()
+        assert nun.cpu().numpy().sum() == len(r["chosen"])
+
+
+def test_device_side_bounds_checks_set_status_instead_of_faulting(world):
+    eng = world["eng"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    blk = synth.masked_block(TINY, 5, Q, 20)
+    bad = blk.copy(); bad[3] = TINY.vocab + 5; bad[4] = -2
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    eng.denoise_step(eng.i32(bad[None]), eng.i32([P]), eng.i32(table), cand, conf, max_prefix_len=P)
+    assert eng.read_status() & 1
+    eng.reset_status()
+    t2 = table.copy(); t2[0, 1] = eng.cfg.n_pages + 3; t2[0, 2] = -1
+    eng.denoise_step(eng.i32(blk[None]), eng.i32([P]), eng.i32(t2), cand, conf, max_prefix_len=P)
+    assert eng.read_status() & 2
+    eng.reset_status()
+    assert eng.read_status() == 0
