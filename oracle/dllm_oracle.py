@@ -32,6 +32,14 @@ with .ms (shape record with n_layers, d_model, n_q_heads, n_kv_heads, head_dim, 
 mask_id, rms_eps, rope_base), .layer(l) -> dict and ["tok_emb" | "final_norm" | "lm_head"].
 All inputs are converted to float64 on entry (the conversion function is passed in by the
 caller, default: numpy's astype).
+
+Storage precision.  All arithmetic is float64.  A model whose activations are handed from kernel
+to kernel in a narrower type decides its arg max and its unmask set on values that went through
+that type, so those decisions have to be taken in the same precision here: every forward takes
+an optional `store` function (e.g. round-to-bfloat16) that is applied exactly where the data
+layout of the library stores an activation -- the normalised GEMM input, q and k after the
+rotary embedding, v, the attention output, and silu(gate)*up -- and nowhere else (the residual
+stream, scores, probabilities and logits are never rounded).  store=None is the exact definition.
 """
 from __future__ import annotations
 
@@ -88,36 +96,40 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-def layer_qkv(ms, lw, x, pos, widen=None):
+def _st(a, store):
+    return a if store is None else np.asarray(store(a), dtype=np.float64)
+
+
+def layer_qkv(ms, lw, x, pos, widen=None, store=None):
     """Normalised input -> rotated q, rotated k, v for the rows of x at absolute positions pos."""
     S = x.shape[0]
-    h = rmsnorm(x, _f64(lw["attn_norm"], widen), ms.rms_eps)
+    h = _st(rmsnorm(x, _f64(lw["attn_norm"], widen), ms.rms_eps), store)
     q = (h @ _f64(lw["wq"], widen).T).reshape(S, ms.n_q_heads, ms.head_dim)
     k = (h @ _f64(lw["wk"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
     v = (h @ _f64(lw["wv"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
-    return rope(q, pos, ms.rope_base), rope(k, pos, ms.rope_base), v
+    return _st(rope(q, pos, ms.rope_base), store), _st(rope(k, pos, ms.rope_base), store), _st(v, store)
 
 
-def layer_finish(ms, lw, x, o, widen=None):
+def layer_finish(ms, lw, x, o, widen=None, store=None):
     """Output projection + residual, then SwiGLU MLP + residual."""
     S = x.shape[0]
-    x = x + o.reshape(S, -1) @ _f64(lw["wo"], widen).T
-    h = rmsnorm(x, _f64(lw["mlp_norm"], widen), ms.rms_eps)
+    x = x + _st(o, store).reshape(S, -1) @ _f64(lw["wo"], widen).T
+    h = _st(rmsnorm(x, _f64(lw["mlp_norm"], widen), ms.rms_eps), store)
     g = h @ _f64(lw["w_gate"], widen).T
     u = h @ _f64(lw["w_up"], widen).T
-    return x + (silu(g) * u) @ _f64(lw["w_down"], widen).T
+    return x + _st(silu(g) * u, store) @ _f64(lw["w_down"], widen).T
 
 
-def head_logits(model, x, widen=None):
+def head_logits(model, x, widen=None, store=None):
     """Final norm and LM head: raw logits [rows, vocab] (row i predicts position i, no shift)."""
     ms = model.ms
-    h = rmsnorm(x, _f64(model["final_norm"], widen), ms.rms_eps)
+    h = _st(rmsnorm(x, _f64(model["final_norm"], widen), ms.rms_eps), store)
     return h @ _f64(model["lm_head"], widen).T
 
 
 # --------------------------------------------------------------------------- forwards
 
-def forward_full(model, tokens, n_layers=None, widen=None, want_logits=True, pos0=0):
+def forward_full(model, tokens, n_layers=None, widen=None, want_logits=True, pos0=0, store=None):
     """No-cache forward over one sequence: every token attends to every token.
     Returns (logits [S, V] or None, K [L][S, Hkv, dh], V [L][...], hidden [S, d])."""
     ms = model.ms
@@ -129,24 +141,24 @@ def forward_full(model, tokens, n_layers=None, widen=None, want_logits=True, pos
     Ks, Vs = [], []
     for l in range(L):
         lw = model.layer(l)
-        q, k, v = layer_qkv(ms, lw, x, pos, widen)
+        q, k, v = layer_qkv(ms, lw, x, pos, widen, store)
         Ks.append(k)
         Vs.append(v)
-        x = layer_finish(ms, lw, x, attention(q, k, v), widen)
-    logits = head_logits(model, x, widen) if want_logits else None
+        x = layer_finish(ms, lw, x, attention(q, k, v), widen, store)
+    logits = head_logits(model, x, widen, store) if want_logits else None
     return logits, Ks, Vs, x
 
 
-def prefill(model, tokens, n_cache=None, n_layers=None, widen=None):
+def prefill(model, tokens, n_cache=None, n_layers=None, widen=None, store=None):
     """Key/value states of the first n_cache positions taken from a no-cache forward over
     `tokens` (which may extend past n_cache, e.g. include in-flight blocks)."""
-    _, Ks, Vs, _ = forward_full(model, tokens, n_layers, widen, want_logits=False)
+    _, Ks, Vs, _ = forward_full(model, tokens, n_layers, widen, want_logits=False, store=store)
     n = len(tokens) if n_cache is None else n_cache
     return [k[:n] for k in Ks], [v[:n] for v in Vs]
 
 
 def forward_cached(model, block_tokens, cache_k, cache_v, n_layers=None, widen=None,
-                   want_logits=True, stop_layer=None):
+                   want_logits=True, stop_layer=None, store=None):
     """Denoise-step forward: the Q block tokens sit at positions P..P+Q-1 and attend to the
     cached prefix (P = cache length) and to themselves.  Returns (logits [Q, V], hidden [Q, d])."""
     ms = model.ms
@@ -160,11 +172,11 @@ def forward_cached(model, block_tokens, cache_k, cache_v, n_layers=None, widen=N
     x = _f64(np.asarray(model["tok_emb"])[block_tokens], widen)
     for l in range(L):
         lw = model.layer(l)
-        q, k, v = layer_qkv(ms, lw, x, pos, widen)
+        q, k, v = layer_qkv(ms, lw, x, pos, widen, store)
         kk = np.concatenate([_f64(cache_k[l], widen), k], axis=0)
         vv = np.concatenate([_f64(cache_v[l], widen), v], axis=0)
-        x = layer_finish(ms, lw, x, attention(q, kk, vv), widen)
-    logits = head_logits(model, x, widen) if want_logits else None
+        x = layer_finish(ms, lw, x, attention(q, kk, vv), widen, store)
+    logits = head_logits(model, x, widen, store) if want_logits else None
     return logits, x
 
 
@@ -202,7 +214,7 @@ def unmask(tokens, cand, conf, mask_id, tau, m):
 
 
 def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, widen=None,
-                 n_layers=None):
+                 n_layers=None, store=None):
     """One whole step on a window of one or more blocks: forward, confidence of the masked
     rows, selection per block.  Returns dict with new tokens, cand, conf, entropy, chosen,
     logits."""
@@ -210,7 +222,7 @@ def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, 
     block_tokens = np.asarray(block_tokens)
     Q = len(block_tokens)
     bl = Q if block_len is None else block_len
-    logits, _ = forward_cached(model, block_tokens, cache_k, cache_v, n_layers, widen)
+    logits, _ = forward_cached(model, block_tokens, cache_k, cache_v, n_layers, widen, store=store)
     cand, conf, ent, _ = confidence(logits, ms.mask_id)
     new = np.array(block_tokens, copy=True)
     chosen_all = []
@@ -223,22 +235,22 @@ def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, 
 
 
 def decode(model, prompt, n_blocks, block_len, tau, m, widen=None, n_layers=None,
-           record=None):
+           record=None, store=None):
     """Sequential-block decoding: cache the prompt, then for each block append block_len mask
     ids, run denoise steps until none is left, refresh the cache with a no-cache forward over
     everything decoded so far, go on.  Returns (all tokens, number of forwards with cache)."""
     ms = model.ms
     seq = np.array(prompt, dtype=np.int64, copy=True)
-    ck, cv = prefill(model, seq, None, n_layers, widen)
+    ck, cv = prefill(model, seq, None, n_layers, widen, store)
     steps = 0
     for _ in range(n_blocks):
         blk = np.full(block_len, ms.mask_id, dtype=np.int64)
         while (blk == ms.mask_id).any():
-            r = denoise_step(model, blk, ck, cv, tau, m, None, widen, n_layers)
+            r = denoise_step(model, blk, ck, cv, tau, m, None, widen, n_layers, store)
             if record is not None:
                 record.append({"before": blk.copy(), **r})
             blk = r["tokens"]
             steps += 1
         seq = np.concatenate([seq, blk])
-        ck, cv = prefill(model, seq, None, n_layers, widen)      # refresh at the block boundary
+        ck, cv = prefill(model, seq, None, n_layers, widen, store)      # refresh at the block boundary
     return seq, steps

@@ -46,6 +46,8 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->status = take(64);
   m->x = take(t_max * c->d_model * 4);
   m->xn = take(t_max * c->d_model * es);
+  m->q32 = take(t_max * dq * 4);
+  m->k32 = take(t_max * dkv * 4);
   m->q = take(t_max * dq * es);
   m->k = take(t_max * dkv * es);
   m->v = take(t_max * dkv * es);
@@ -165,8 +167,8 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
     TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr), "rmsnorm");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q, T, dq, f.d_model, EPI_STORE), "wq");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k, T, dkv, f.d_model, EPI_STORE), "wk");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
+    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
     TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
     TRY(launch_rope_kv(c, s, g, l), "rope_kv");
     TRY(launch_attention_generic(c, s, g, l), "attention");

@@ -64,8 +64,10 @@ struct Workspace {
   size_t status;       // int32[4]: [0] status bits, [1] number of LM-head rows
   size_t x;            // float [Tmax, d]          residual stream
   size_t xn;           // T     [Tmax, d]          normalised activations (GEMM input)
-  size_t q;            // T     [Tmax, Hq*dh]
-  size_t k;            // T     [Tmax, Hkv*dh]     this forward's K (rotated in place)
+  size_t q32;          // float [Tmax, Hq*dh]      q projection before the rotary embedding
+  size_t k32;          // float [Tmax, Hkv*dh]     k projection before the rotary embedding
+  size_t q;            // T     [Tmax, Hq*dh]      rotated q
+  size_t k;            // T     [Tmax, Hkv*dh]     this forward's rotated K
   size_t v;            // T     [Tmax, Hkv*dh]
   size_t o;            // T     [Tmax, Hq*dh]      attention output
   size_t g;            // float [Tmax, F]          gate pre-activation (generic path)

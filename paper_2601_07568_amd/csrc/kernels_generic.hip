@@ -157,34 +157,35 @@ __global__ __launch_bounds__(256) void k_gemm(const T* __restrict__ A, const T* 
 }
 
 // ------------------------------------------------------------------------------------------
-// rotary embedding of q and k (in place), and K/V write into the paged pool
+// rotary embedding of q and k (float projections in, one rounding to the storage type out), and
+// K/V write into the paged pool
 template <typename T>
-__global__ void k_rope_kv(int Hq, int Hkv, int dh, T* q, T* k, const T* v, const float* cs, const float* sn,
-                          const int32_t* tok_seq, const int32_t* tok_pos, const int32_t* n_cache,
-                          T* pool_k, T* pool_v, KVView kv, int32_t* status) {
+__global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float* kf, T* q, T* k, const T* v,
+                          const float* cs, const float* sn, const int32_t* tok_seq, const int32_t* tok_pos,
+                          const int32_t* n_cache, T* pool_k, T* pool_v, KVView kv, int32_t* status) {
   const int t = blockIdx.x;
   const int half = dh >> 1;
   const float* c = cs + (int64_t)t * half;
   const float* s = sn + (int64_t)t * half;
+  const float* qs = qf + (int64_t)t * Hq * dh;
   T* qt = q + (int64_t)t * Hq * dh;
   for (int i = threadIdx.x; i < Hq * half; i += blockDim.x) {
     int h = i / half, j = i - h * half;
-    T* p = qt + h * dh + j;
-    float a = Elem<T>::load(p), b = Elem<T>::load(p + half);
-    Elem<T>::store(p, a * c[j] - b * s[j]);
-    Elem<T>::store(p + half, b * c[j] + a * s[j]);
+    float a = qs[h * dh + j], b = qs[h * dh + j + half];
+    Elem<T>::store(qt + h * dh + j, a * c[j] - b * s[j]);
+    Elem<T>::store(qt + h * dh + j + half, b * c[j] + a * s[j]);
   }
   const int b = tok_seq[t], pos = tok_pos[t];
   const bool cached = (n_cache == nullptr) || (pos < n_cache[b]);
+  const float* ks = kf + (int64_t)t * Hkv * dh;
   T* kt = k + (int64_t)t * Hkv * dh;
   const T* vt = v + (int64_t)t * Hkv * dh;
   for (int i = threadIdx.x; i < Hkv * half; i += blockDim.x) {
     int h = i / half, j = i - h * half;
-    T* p = kt + h * dh + j;
-    float a = Elem<T>::load(p), bb = Elem<T>::load(p + half);
+    float a = ks[h * dh + j], bb = ks[h * dh + j + half];
     float r0 = a * c[j] - bb * s[j], r1 = bb * c[j] + a * s[j];
-    Elem<T>::store(p, r0);
-    Elem<T>::store(p + half, r1);
+    Elem<T>::store(kt + h * dh + j, r0);
+    Elem<T>::store(kt + h * dh + j + half, r1);
     if (cached) {
       int64_t off = kv_offset(kv, b, pos, h);
       if (off < 0) { atomicOr(status, DLLM_STATUS_BAD_PAGE); }
@@ -606,12 +607,14 @@ hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int lay
   const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
   // packed forward with n_cache == nullptr caches every position: same as the step case
   if (IS_BF16(c))
-    k_rope_kv<bf16_t><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q, bf16_t), WS(c, k, bf16_t),
+    k_rope_kv<bf16_t><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
+                                          WS(c, q, bf16_t), WS(c, k, bf16_t),
                                           WS(c, v, bf16_t), WS(c, rope_cos, float), WS(c, rope_sin, float),
                                           WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
                                           (bf16_t*)pk, (bf16_t*)pv, kv, WS(c, status, int32_t));
   else
-    k_rope_kv<float><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q, float), WS(c, k, float),
+    k_rope_kv<float><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
+                                         WS(c, q, float), WS(c, k, float),
                                          WS(c, v, float), WS(c, rope_cos, float), WS(c, rope_sin, float),
                                          WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
                                          (float*)pk, (float*)pv, kv, WS(c, status, int32_t));

@@ -60,6 +60,11 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Values of `a` after a round trip through bfloat16 (nearest even), as float64."""
+    return bf16_bits_to_f32(_to_store(np.ascontiguousarray(a, dtype=np.float32), "bf16")).astype(np.float64)
+
+
 def as_float(a: np.ndarray) -> np.ndarray:
     """Float view of a stored tensor: uint16 means bf16 bits, anything else is returned as is."""
     return bf16_bits_to_f32(a) if a.dtype == np.uint16 else a

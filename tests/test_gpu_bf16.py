@@ -1,0 +1,111 @@
+"""GPU parity in bfloat16: a small grouped-query model with ragged shapes (several tiles and tails
+in every dimension), and the LLaDA-8B-shaped single layer + LM head at its full size (prefix 512,
+block of 32 with 24 masked).  Both kernel selections (automatic and forced generic) are checked."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dllm_oracle as O
+from paper_2601_07568_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+W = synth.as_float
+ST = synth.round_bf16
+SMALL = synth.ModelShape(2, 512, 8, 2, 128, 1408, 5000, 4999, dtype="bf16", lm_head_scale=8.0, name="small-gqa")
+SMALL64 = synth.ModelShape(1, 384, 6, 3, 64, 1000, 3000, 2999, dtype="bf16", lm_head_scale=8.0, name="small-dh64")
+
+
+def run_small(ms, lens, Q, n_masked, mode, seed=7):
+    w = synth.Weights(ms, seed)
+    Bn = len(lens)
+    mp = 8
+    eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+                        max_tokens=sum(lens) + Bn * Q)
+    eng.set_kernel_mode(mode)
+    seqs = [synth.random_tokens(ms, seed + i, n) for i, n in enumerate(lens)]
+    blks = [synth.masked_block(ms, seed + 10 + i, Q, n_masked) for i in range(Bn)]
+    table = H.identity_table(eng, Bn)
+    toks = np.concatenate(seqs).astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(toks), eng.i32(cu), eng.i32(table), None, total_tokens=len(toks), max_seqlen=max(lens))
+    qt = eng.i32(np.stack(blks))
+    logits = eng.debug_logits(qt, eng.i32(lens), eng.i32(table), max_prefix_len=max(lens)).cpu().numpy()
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(Bn, Q, dtype=torch.float32, device=eng.device)
+    eng.denoise_step(qt, eng.i32(lens), eng.i32(table), cand, conf, ent, max_prefix_len=max(lens))
+    n_exact = 0
+    for b in range(Bn):
+        ck, cv = O.prefill(w, seqs[b], widen=W)
+        for l in range(ms.n_layers):
+            for which, ref in ((0, ck[l]), (1, cv[l])):
+                got = H.gather_cache(eng, table[b], lens[b], l, which)
+                assert np.abs(got - ref).max() <= 2e-2 * np.abs(ref).max()
+        exact, _ = O.forward_cached(w, blks[b], ck, cv, widen=W)          # no rounding anywhere
+        assert H.rel_err_rows(logits[b], exact).max() <= H.LOGIT_TOL["bf16"]
+        ckq, cvq = O.prefill(w, seqs[b], widen=W, store=ST)
+        r = O.denoise_step(w, blks[b], ckq, cvq, 0.9, 1, widen=W, store=ST)
+        n_exact += H.check_step_outputs(ms, r, blks[b] == ms.mask_id, cand.cpu().numpy()[b],
+                                        conf.cpu().numpy()[b], ent.cpu().numpy()[b], "bf16", gpu_logits=logits[b])
+    assert eng.read_status() == 0
+    assert n_exact >= Bn * n_masked // 2
+    # refresh with step outputs for the in-flight rows equals the oracle's no-cache forward
+    b = 0
+    seq = np.concatenate([seqs[b], blks[b]])
+    n_tok = len(seq)
+    c2 = torch.zeros(n_tok, dtype=torch.int32, device=eng.device)
+    f2 = torch.zeros(n_tok, dtype=torch.float32, device=eng.device)
+    eng.refresh_cache(eng.i32(seq), eng.i32([0, n_tok]), eng.i32(table[:1]), eng.i32([lens[b]]), c2, f2,
+                      total_tokens=n_tok, max_seqlen=n_tok)
+    full, Ks, Vs, _ = O.forward_full(w, seq, widen=W, store=ST)
+    rr = {"logits": full[lens[b]:], "cand": O.confidence(full[lens[b]:], ms.mask_id)[0]}
+    H.check_step_outputs(ms, rr, blks[b] == ms.mask_id, c2.cpu().numpy()[lens[b]:], f2.cpu().numpy()[lens[b]:],
+                         None, "bf16")
+    got = H.gather_cache(eng, table[0], lens[b], ms.n_layers - 1, 0)
+    assert np.abs(got - Ks[-1][:lens[b]]).max() <= 2e-2 * np.abs(Ks[-1]).max()
+    eng.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_small_gqa_model(mode):
+    run_small(SMALL, [100, 77], 32, 20, mode)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_small_head_dim_64_model(mode):
+    run_small(SMALL64, [45, 130, 64], 64, 40, mode)
+
+
+def test_llada_shaped_layer_and_head_full_size():
+    """Workload: one LLaDA-8B-shaped layer + LM head over vocab 126464, batch 1, prefix 512, block 32
+    (24 masked), threshold 0.9, floor 1 -- all rows checked against the oracle."""
+    ms = synth.LLADA_8B.with_layers(1)
+    P, Q = 512, 32
+    w = synth.Weights(ms, 2)
+    eng = H.make_engine(ms, w, page_tokens=64, max_pages_per_seq=9, n_pages=9, max_batch=1, max_q=Q, max_tokens=P)
+    prompt = synth.random_tokens(ms, 2, P)
+    blk = synth.masked_block(ms, 2, Q, 24)
+    table = H.identity_table(eng, 1)
+    eng.prefill_kv(eng.i32(prompt), eng.i32([0, P]), eng.i32(table), None, total_tokens=P, max_seqlen=P)
+    qt = eng.i32(blk[None])
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    eng.denoise_step(qt, eng.i32([P]), eng.i32(table), cand, conf, ent, max_prefix_len=P)
+    logits = eng.debug_logits(qt, eng.i32([P]), eng.i32(table), max_prefix_len=P).cpu().numpy()[0]
+    ck, cv = O.prefill(w, prompt, widen=W)
+    exact, _ = O.forward_cached(w, blk, ck, cv, widen=W)
+    assert H.rel_err_rows(logits, exact).max() <= H.LOGIT_TOL["bf16"]
+    ck, cv = O.prefill(w, prompt, widen=W, store=ST)
+    r = O.denoise_step(w, blk, ck, cv, 0.9, 1, widen=W, store=ST)
+    print("logit rel err vs exact oracle", H.rel_err_rows(logits, exact).max(), "vs bf16-storage oracle",
+          H.rel_err_rows(logits, r["logits"]).max())
+    masked = blk == ms.mask_id
+    H.check_step_outputs(ms, r, masked, cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0], "bf16",
+                         gpu_logits=logits)
+    eng.unmask(qt, cand, conf, 0.9, 1)
+    if H.selection_is_decided(r["conf"], masked, 0.9, 1):
+        assert np.nonzero(qt.cpu().numpy()[0] != blk)[0].tolist() == r["chosen"]
+    assert eng.read_status() == 0
+    eng.close()

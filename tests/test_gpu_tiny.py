@@ -77,6 +77,8 @@ def test_teacher_forced_steps_logits_conf_and_unmask(world):
 
 
 def test_free_running_decode_matches_oracle(world):
+    """The GPU carries its own state from step to step; it is put back on the oracle's trajectory
+    only after a step whose selection the oracle itself leaves within 1e-3 of a tie."""
     eng, w = world["eng"], world["w"]
     table = H.identity_table(eng, 1)
     gpu_prefill(eng, [world["prompt"]], table)
@@ -87,20 +89,25 @@ def test_free_running_decode_matches_oracle(world):
     cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
     conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
     nrem = torch.ones(1, 1, dtype=torch.int32, device=eng.device)
-    n = 0
-    while int(nrem) > 0:
-        r = rec[n]
+    free = 0
+    for n, r in enumerate(rec):
         before = qt.cpu().numpy()[0]
         assert (before == r["before"]).all()
-        if not H.selection_is_decided(r["conf"], before == TINY.mask_id, 0.9, 1):
-            break                 # the oracle itself is within 1e-3 of a tie: compared up to here
         eng.denoise_step(qt, prefix, tab, cand, conf, max_prefix_len=P)
         eng.unmask(qt, cand, conf, 0.9, 1, n_remaining=nrem)
-        n += 1
-        assert n <= 32
-    assert n >= 8
-    if int(nrem) == 0:
-        assert n == steps and (qt.cpu().numpy()[0] == seq[P:]).all()
+        after = qt.cpu().numpy()[0]
+        masked = before == TINY.mask_id
+        assert (after[~masked] == before[~masked]).all() and (after != before).sum() >= 1
+        assert int(nrem) == (after == TINY.mask_id).sum()
+        _, _, _, p = O.confidence(r["logits"], TINY.mask_id)
+        sure_ids = (H.top2_margin(p) > H.MARGIN)[r["chosen"]].all()
+        if H.selection_is_decided(r["conf"], masked, 0.9, 1) and sure_ids:
+            assert (after == r["tokens"]).all()
+            free += 1
+        else:
+            qt = eng.i32(r["tokens"][None])
+    assert free >= 4            # the masked rows of this model are nearly alike: most steps are near-ties
+    assert int((qt.cpu().numpy()[0] == TINY.mask_id).sum()) == 0
 
 
 def test_refresh_rewrites_cache_and_cached_step_equals_recompute(world):

@@ -366,3 +366,35 @@ def test_threshold_branch_fires_on_tiny_config():
     r = O.denoise_step(w, np.full(32, TINY.mask_id), ck, cv, tau=0.9, m=1)
     assert len(r["chosen"]) >= 1
     assert 0 < r["conf"].max() <= 1
+
+
+# ------------------------------------------------------------------ storage-precision hook
+
+def test_store_hook_is_applied_at_the_storage_points_only():
+    model = small_model()
+    ms = model.ms
+    toks = synth.random_tokens(ms, 2, 9)
+    exact, _, _, _ = O.forward_full(model, toks)
+    calls = []
+
+    def ident(a):
+        calls.append(np.shape(a))
+        return a
+
+    same, _, _, _ = O.forward_full(model, toks, store=ident)
+    np.testing.assert_array_equal(exact, same)                       # identity store changes nothing
+    S, d, F = 9, ms.d_model, ms.d_ff
+    per_layer = [(S, d), (S, ms.n_q_heads, ms.head_dim), (S, ms.n_kv_heads, ms.head_dim),
+                 (S, ms.n_kv_heads, ms.head_dim), (S, ms.n_q_heads, ms.head_dim), (S, d), (S, F)]
+    assert calls == per_layer * ms.n_layers + [(S, d)]
+    rounded, _, _, _ = O.forward_full(model, toks, store=synth.round_bf16)
+    err = np.abs(rounded - exact).max() / np.abs(exact).max()
+    assert 0 < err < 2e-2                                            # rounding moves it, within bf16 accuracy
+
+
+def test_round_bf16_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 3.14159], dtype=np.float64)
+    got = synth.round_bf16(x)
+    want = torch.from_numpy(x).float().to(torch.bfloat16).double().numpy()
+    np.testing.assert_array_equal(got, want)
+    assert got[3] == 1.0 and got[4] == 1.0 + 2.0 ** -6               # ties go to the even mantissa
