@@ -31,10 +31,15 @@
  *     are bfloat16 (the residual stream, softmax statistics and all accumulators stay float).
  *   - Linear weights are [out_features, in_features] row-major, no biases; norm gains [d_model];
  *     tok_emb and lm_head are [vocab, d_model] (untied).
- *   - KV pool: element (layer l, which in {0 = K, 1 = V}, page p, kv head h, slot s, channel c)
- *     at index ((((l * 2 + which) * n_pages + p) * n_kv_heads + h) * page_tokens + s) * head_dim + c.
- *     K is stored after the rotary embedding.  Position j of sequence b lives in page
- *     block_table[b * max_pages_per_seq + j / page_tokens], slot j % page_tokens.
+ *   - KV pool: 2 * n_layers slabs of n_pages * n_kv_heads * page_tokens * head_dim elements, slab
+ *     2l = K of layer l, slab 2l+1 = V of layer l.  Within a slab, (page p, kv head h, slot s,
+ *     channel c) is at ((p * n_kv_heads + h) * page_tokens + s) * head_dim + c for K, and at
+ *     ((p * n_kv_heads + h) * head_dim + c) * page_tokens + s for V (V is stored transposed, the
+ *     slots of one channel contiguous, which is the operand layout of the P*V matrix
+ *     instruction).  K is stored after the rotary embedding.  Position j of sequence b lives in
+ *     page block_table[b * max_pages_per_seq + j / page_tokens], slot j % page_tokens.
+ *   - Rounding points of a DLLM_BF16 model (everything else is float): the normalised GEMM input,
+ *     q and k after the rotary embedding, v, the attention output, silu(gate) * up.
  *   - Rotary embedding: half-split pairing (c, c + head_dim/2), angle = position * rope_base^(-2c/head_dim),
  *     positions counted from the start of the sequence.
  */

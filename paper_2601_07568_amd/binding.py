@@ -158,13 +158,16 @@ class Engine:
         return self.torch.as_tensor(np.asarray(a, dtype=np.int32)).to(self.device)
 
     def kv_slab(self, layer, which):
-        """View of the pool: [n_pages, n_kv_heads, page_tokens, head_dim] of layer, which (0=K, 1=V)."""
+        """View of the pool as [n_pages, n_kv_heads, page_tokens, head_dim] of layer, which (0=K, 1=V);
+        the V slab is stored [.., head_dim, page_tokens] and is returned transposed back."""
         c = self.cfg
         es = 2 if self.ms.dtype == "bf16" else 4
         n = c.n_pages * c.n_kv_heads * c.page_tokens * c.head_dim
         off = (layer * 2 + which) * n * es
-        return self.kv_pool[off:off + n * es].view(self.tdtype).view(c.n_pages, c.n_kv_heads, c.page_tokens,
-                                                                     c.head_dim)
+        flat = self.kv_pool[off:off + n * es].view(self.tdtype)
+        if which == 1:
+            return flat.view(c.n_pages, c.n_kv_heads, c.head_dim, c.page_tokens).transpose(2, 3)
+        return flat.view(c.n_pages, c.n_kv_heads, c.page_tokens, c.head_dim)
 
     # -- the calls of include/dllm.h
     def prefill_kv(self, tokens, cu_seqlens, block_table, n_cache=None, *, total_tokens, max_seqlen):

@@ -49,8 +49,11 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->q32 = take(t_max * dq * 4);
   m->k32 = take(t_max * dkv * 4);
   m->q = take(t_max * dq * es);
-  m->k = take(t_max * dkv * es);
+  m->tpad = c->max_tokens > 0 ? (int64_t)c->max_tokens + 32 * (int64_t)c->max_batch : 0;
   m->v = take(t_max * dkv * es);
+  m->kpack = take((size_t)m->tpad * dkv * es);
+  m->vpack = take((size_t)m->tpad * dkv * es);
+  m->cu_pad = take(((size_t)c->max_batch + 1) * 4);
   m->o = take(t_max * dq * es);
   m->g = take(t_max * c->d_ff * 4);
   m->u = take(t_max * c->d_ff * 4);

@@ -35,28 +35,43 @@ template <> struct Elem<bf16_t> {
   __device__ static inline void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
-// Where the keys/values of a forward live.  Paged: position j of sequence b is in page
-// table[b*max_pages + j/page_tokens], slot j%page_tokens, of the per-layer K (or V) slab
-// [n_pages][n_kv_heads][page_tokens][head_dim].  Packed (table == nullptr): the forward's own
-// K/V scratch [total_tokens][n_kv_heads][head_dim], sequence b starting at row cu_seqlens[b].
+// Where the keys/values of a forward live.
+// Paged (table != nullptr): position j of sequence b is in page table[b*max_pages + j/page_tokens],
+// slot j%page_tokens.  Per layer the K slab is [n_pages][n_kv_heads][page_tokens][head_dim] and the
+// V slab is stored transposed, [n_pages][n_kv_heads][head_dim][page_tokens], so that the keys of
+// one channel are contiguous (the layout the P*V matrix instruction wants for its operand).
+// Packed (table == nullptr): the scratch of a no-cache forward, K [n_kv_heads][tpad][head_dim] and
+// V [n_kv_heads][head_dim][tpad]; sequence b starts at column cu_pad[b] (a multiple of 32).
 struct KVView {
-  const void* k;          // layer's K slab (paged) or packed K
+  const void* k;
   const void* v;
   const int32_t* table;   // nullptr = packed
-  const int32_t* cu_seqlens;  // packed only
-  int32_t page_tokens, max_pages, n_pages, n_kv_heads, head_dim;
+  const int32_t* cu_pad;  // packed only
+  int32_t page_tokens, max_pages, n_pages, n_kv_heads, head_dim, tpad;
 };
 
-// element offset of (sequence b, position pos, kv head h, channel 0); -1 if not addressable
-__device__ inline int64_t kv_offset(const KVView& kv, int b, int pos, int h) {
+// Element offsets of (sequence b, position pos, kv head h): k_off addresses channel 0 of the K
+// row; channel c of V is at v_off + c * v_stride.  Returns false if the position is not
+// addressable (beyond the block table, or a table entry outside the pool).
+__device__ inline bool kv_locate(const KVView& kv, int b, int pos, int h, int64_t& k_off, int64_t& v_off,
+                                 int& v_stride) {
   if (kv.table == nullptr) {
-    return ((int64_t)(kv.cu_seqlens[b] + pos) * kv.n_kv_heads + h) * kv.head_dim;
+    const int64_t col = (int64_t)kv.cu_pad[b] + pos;
+    k_off = ((int64_t)h * kv.tpad + col) * kv.head_dim;
+    v_off = (int64_t)h * kv.head_dim * kv.tpad + col;
+    v_stride = kv.tpad;
+    return true;
   }
-  int pi = pos / kv.page_tokens;
-  if (pos < 0 || pi >= kv.max_pages) return -1;
-  int page = kv.table[(int64_t)b * kv.max_pages + pi];
-  if (page < 0 || page >= kv.n_pages) return -1;
-  return (((int64_t)page * kv.n_kv_heads + h) * kv.page_tokens + (pos - pi * kv.page_tokens)) * kv.head_dim;
+  const int pi = pos / kv.page_tokens;
+  if (pos < 0 || pi >= kv.max_pages) return false;
+  const int page = kv.table[(int64_t)b * kv.max_pages + pi];
+  if (page < 0 || page >= kv.n_pages) return false;
+  const int slot = pos - pi * kv.page_tokens;
+  const int64_t ph = (int64_t)page * kv.n_kv_heads + h;
+  k_off = (ph * kv.page_tokens + slot) * kv.head_dim;
+  v_off = ph * kv.head_dim * kv.page_tokens + slot;
+  v_stride = kv.page_tokens;
+  return true;
 }
 
 // Workspace map (byte offsets from the workspace base), fixed at dllm_create.
@@ -67,8 +82,10 @@ struct Workspace {
   size_t q32;          // float [Tmax, Hq*dh]      q projection before the rotary embedding
   size_t k32;          // float [Tmax, Hkv*dh]     k projection before the rotary embedding
   size_t q;            // T     [Tmax, Hq*dh]      rotated q
-  size_t k;            // T     [Tmax, Hkv*dh]     this forward's rotated K
-  size_t v;            // T     [Tmax, Hkv*dh]
+  size_t v;            // T     [Tmax, Hkv*dh]     v projection, token-major
+  size_t kpack;        // T     [Hkv, tpad, dh]    rotated K of a no-cache forward
+  size_t vpack;        // T     [Hkv, dh, tpad]    V of a no-cache forward, transposed
+  size_t cu_pad;       // int32 [max_batch + 1]    padded column offset of each packed sequence
   size_t o;            // T     [Tmax, Hq*dh]      attention output
   size_t g;            // float [Tmax, F]          gate pre-activation (generic path)
   size_t u;            // float [Tmax, F]          up projection (generic path)
@@ -82,7 +99,7 @@ struct Workspace {
   size_t attn_part;    // float [Tstep, Hq, max_splits, dh + 2] split-KV partials
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
-  int64_t t_max, r_max, t_step;
+  int64_t t_max, r_max, t_step, tpad;
   int32_t n_vtiles, max_splits;
   size_t scratch_bytes;
 };

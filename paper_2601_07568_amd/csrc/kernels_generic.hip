@@ -42,8 +42,13 @@ __device__ inline float block_max(float v, float* red) {
 // ------------------------------------------------------------------------------------------
 // token map: sequence and position of every row of the forward
 __global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, const int32_t* cu,
-                            int32_t* tok_seq, int32_t* tok_pos) {
+                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t == 0 && Q == 0) {   // padded column offsets of the packed K/V scratch
+    int acc = 0;
+    for (int b = 0; b < B; ++b) { cu_pad[b] = acc; acc += (cu[b + 1] - cu[b] + 31) / 32 * 32; }
+    cu_pad[B] = acc;
+  }
   if (t >= T) return;
   if (Q > 0) {
     int b = t / Q;
@@ -158,11 +163,12 @@ __global__ __launch_bounds__(256) void k_gemm(const T* __restrict__ A, const T* 
 
 // ------------------------------------------------------------------------------------------
 // rotary embedding of q and k (float projections in, one rounding to the storage type out), and
-// K/V write into the paged pool
+// K/V write into the paged pool (cached positions) and into the packed scratch (no-cache forward)
 template <typename T>
-__global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float* kf, T* q, T* k, const T* v,
+__global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float* kf, T* q, const T* v,
                           const float* cs, const float* sn, const int32_t* tok_seq, const int32_t* tok_pos,
-                          const int32_t* n_cache, T* pool_k, T* pool_v, KVView kv, int32_t* status) {
+                          const int32_t* n_cache, T* pool_k, T* pool_v, KVView pool, T* pack_k, T* pack_v,
+                          KVView pack, bool to_pack, int32_t* status) {
   const int t = blockIdx.x;
   const int half = dh >> 1;
   const float* c = cs + (int64_t)t * half;
@@ -178,25 +184,33 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
   const int b = tok_seq[t], pos = tok_pos[t];
   const bool cached = (n_cache == nullptr) || (pos < n_cache[b]);
   const float* ks = kf + (int64_t)t * Hkv * dh;
-  T* kt = k + (int64_t)t * Hkv * dh;
   const T* vt = v + (int64_t)t * Hkv * dh;
   for (int i = threadIdx.x; i < Hkv * half; i += blockDim.x) {
     int h = i / half, j = i - h * half;
     float a = ks[h * dh + j], bb = ks[h * dh + j + half];
     float r0 = a * c[j] - bb * s[j], r1 = bb * c[j] + a * s[j];
-    Elem<T>::store(kt + h * dh + j, r0);
-    Elem<T>::store(kt + h * dh + j + half, r1);
+    int64_t ko, vo;
+    int vs;
     if (cached) {
-      int64_t off = kv_offset(kv, b, pos, h);
-      if (off < 0) { atomicOr(status, DLLM_STATUS_BAD_PAGE); }
-      else { Elem<T>::store(pool_k + off + j, r0); Elem<T>::store(pool_k + off + j + half, r1); }
+      if (kv_locate(pool, b, pos, h, ko, vo, vs)) {
+        Elem<T>::store(pool_k + ko + j, r0);
+        Elem<T>::store(pool_k + ko + j + half, r1);
+      } else atomicOr(status, DLLM_STATUS_BAD_PAGE);
+    }
+    if (to_pack) {
+      kv_locate(pack, b, pos, h, ko, vo, vs);
+      Elem<T>::store(pack_k + ko + j, r0);
+      Elem<T>::store(pack_k + ko + j + half, r1);
     }
   }
-  if (cached) {
-    for (int i = threadIdx.x; i < Hkv * dh; i += blockDim.x) {
-      int h = i / dh, j = i - h * dh;
-      int64_t off = kv_offset(kv, b, pos, h);
-      if (off >= 0) pool_v[off + j] = vt[h * dh + j];
+  for (int i = threadIdx.x; i < Hkv * dh; i += blockDim.x) {
+    int h = i / dh, j = i - h * dh;
+    int64_t ko, vo;
+    int vs;
+    if (cached && kv_locate(pool, b, pos, h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = vt[h * dh + j];
+    if (to_pack) {
+      kv_locate(pack, b, pos, h, ko, vo, vs);
+      pack_v[vo + (int64_t)j * vs] = vt[h * dh + j];
     }
   }
 }
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
                                                    const int32_t* cu, KVView kv, int32_t* status) {
   __shared__ float qs[128];
   __shared__ float sc[ATT_CHUNK];
-  __shared__ int64_t offs[ATT_CHUNK];
+  __shared__ int64_t offs[ATT_CHUNK];   // V offset of each key of the chunk, -1 = not addressable
   __shared__ float red[16];
   __shared__ float osum[256];
   const int t = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
@@ -231,6 +245,7 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
   if (tid < dh) qs[tid] = Elem<T>::load(q + ((int64_t)t * Hq + h) * dh + tid);
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)dh);
+  const int v_stride = kv.table ? kv.page_tokens : kv.tpad;
   const int ng = 256 / dh, grp = tid / dh, d = tid - grp * dh;
   float m = -DEV_INF, l = 0.f, oacc = 0.f;
   bool bad = false;
@@ -238,16 +253,17 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
     const int n = min(ATT_CHUNK, kv_len - c0);
     float cm = -DEV_INF;
     for (int j = tid; j < n; j += 256) {
-      int64_t off = kv_offset(kv, b, c0 + j, kvh);
+      int64_t ko, vo = -1;
+      int vs;
       float s = -DEV_INF;
-      if (off >= 0) {
-        const T* kr = kbase + off;
+      if (kv_locate(kv, b, c0 + j, kvh, ko, vo, vs)) {
+        const T* kr = kbase + ko;
         float a = 0.f;
         for (int e = 0; e < dh; ++e) a = fmaf(qs[e], Elem<T>::load(kr + e), a);
         s = a * scale;
-      } else bad = true;
+      } else { bad = true; vo = -1; }
       sc[j] = s;
-      offs[j] = off;
+      offs[j] = vo;
       cm = fmaxf(cm, s);
     }
     cm = block_max(cm, red);
@@ -266,7 +282,7 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
     if (grp < ng) {
       for (int j = grp; j < n; j += ng) {
         int64_t off = offs[j];
-        if (off >= 0) oacc = fmaf(sc[j], Elem<T>::load(vbase + off + d), oacc);
+        if (off >= 0) oacc = fmaf(sc[j], Elem<T>::load(vbase + off + (int64_t)d * v_stride), oacc);
       }
     }
     m = m_new;
@@ -526,7 +542,8 @@ __global__ void k_set_i32(int32_t* p, int n, int32_t v) {
 
 hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
   k_token_map<<<(g.T + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
-                                                WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t));
+                                                WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
+                                                WS(c, cu_pad, int32_t));
   return hipGetLastError();
 }
 
@@ -577,47 +594,62 @@ hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const 
   return hipGetLastError();
 }
 
-static KVView make_view(dllm_ctx* c, const StepGeom& g, int layer, bool paged, void** pool_k, void** pool_v) {
+static KVView pool_view(dllm_ctx* c, const StepGeom& g, int layer) {
   const dllm_config& f = c->cfg;
   const size_t slab = kv_slab_elems(f) * elem_size(f);
-  char* pk = c->kv_pool + (size_t)(layer * 2 + 0) * slab;
-  char* pv = c->kv_pool + (size_t)(layer * 2 + 1) * slab;
-  if (pool_k) *pool_k = pk;
-  if (pool_v) *pool_v = pv;
   KVView kv;
+  kv.k = c->kv_pool + (size_t)(layer * 2 + 0) * slab;
+  kv.v = c->kv_pool + (size_t)(layer * 2 + 1) * slab;
+  kv.table = g.block_table;
+  kv.cu_pad = nullptr;
   kv.page_tokens = f.page_tokens;
   kv.max_pages = f.max_pages_per_seq;
   kv.n_pages = f.n_pages;
   kv.n_kv_heads = f.n_kv_heads;
   kv.head_dim = f.head_dim;
-  kv.cu_seqlens = g.cu_seqlens;
-  if (paged) { kv.k = pk; kv.v = pv; kv.table = g.block_table; }
-  else { kv.k = c->ws + c->map.k; kv.v = c->ws + c->map.v; kv.table = nullptr; }
+  kv.tpad = 0;
   return kv;
 }
 
+static KVView pack_view(dllm_ctx* c) {
+  const dllm_config& f = c->cfg;
+  KVView kv;
+  kv.k = c->ws + c->map.kpack;
+  kv.v = c->ws + c->map.vpack;
+  kv.table = nullptr;
+  kv.cu_pad = (const int32_t*)(c->ws + c->map.cu_pad);
+  kv.page_tokens = 0;
+  kv.max_pages = 0;
+  kv.n_pages = 0;
+  kv.n_kv_heads = f.n_kv_heads;
+  kv.head_dim = f.head_dim;
+  kv.tpad = (int32_t)c->map.tpad;
+  return kv;
+}
+
+// keys/values a forward attends to: the paged pool in a denoise step, the packed scratch in a
+// no-cache forward
 KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer) {
-  return make_view(c, g, layer, /*paged=*/g.Q > 0, nullptr, nullptr);
+  return g.Q > 0 ? pool_view(c, g, layer) : pack_view(c);
 }
 
 hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer) {
   const dllm_config& f = c->cfg;
-  void *pk, *pv;
-  KVView kv = make_view(c, g, layer, true, &pk, &pv);
+  KVView pool = pool_view(c, g, layer), pack = pack_view(c);
+  const bool to_pack = g.Q == 0;
   const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
-  // packed forward with n_cache == nullptr caches every position: same as the step case
   if (IS_BF16(c))
     k_rope_kv<bf16_t><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
-                                          WS(c, q, bf16_t), WS(c, k, bf16_t),
-                                          WS(c, v, bf16_t), WS(c, rope_cos, float), WS(c, rope_sin, float),
-                                          WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
-                                          (bf16_t*)pk, (bf16_t*)pv, kv, WS(c, status, int32_t));
+                                          WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
+                                          WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
+                                          n_cache, (bf16_t*)pool.k, (bf16_t*)pool.v, pool, (bf16_t*)pack.k,
+                                          (bf16_t*)pack.v, pack, to_pack, WS(c, status, int32_t));
   else
     k_rope_kv<float><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
-                                         WS(c, q, float), WS(c, k, float),
-                                         WS(c, v, float), WS(c, rope_cos, float), WS(c, rope_sin, float),
-                                         WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t), n_cache,
-                                         (float*)pk, (float*)pv, kv, WS(c, status, int32_t));
+                                         WS(c, q, float), WS(c, v, float), WS(c, rope_cos, float),
+                                         WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
+                                         n_cache, (float*)pool.k, (float*)pool.v, pool, (float*)pack.k,
+                                         (float*)pack.v, pack, to_pack, WS(c, status, int32_t));
   return hipGetLastError();
 }
 

@@ -42,7 +42,7 @@ def top2_margin(p):
 
 def gather_cache(eng, table_row, n, layer, which):
     """Positions 0..n-1 of one sequence out of the paged pool -> numpy [n, Hkv, dh] float32."""
-    slab = eng.kv_slab(layer, which).float().cpu().numpy()      # [pages, Hkv, pt, dh]
+    slab = eng.kv_slab(layer, which).float().cpu().numpy()      # [pages, Hkv, pt, dh] (K), V transposed
     pt = eng.cfg.page_tokens
     out = np.empty((n, slab.shape[1], slab.shape[3]), dtype=np.float32)
     for j in range(n):
