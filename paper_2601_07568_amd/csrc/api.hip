@@ -63,7 +63,7 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->tok_seq = take(t_max * 4);
   m->tok_pos = take(t_max * 4);
   m->rows = take((size_t)m->r_max * 4);
-  m->lm_part = take((size_t)m->r_max * m->n_vtiles * 4 * 4);
+  m->lm_part = take((size_t)m->r_max * ((c->vocab + 63) / 64) * 4 * 4);   // finest split: 64 columns per partial
   m->attn_part = take(0);
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
@@ -167,32 +167,47 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   TRY(launch_token_map(c, s, g), "token_map");
   TRY(launch_embed(c, s, g), "embed");
   TRY(launch_rope_table(c, s, g), "rope_table");
+  // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
+  const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS;
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
     TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr), "rmsnorm");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
-    TRY(launch_rope_kv(c, s, g, l), "rope_kv");
+    if (sk) {
+      TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
+    } else {
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+      TRY(launch_rope_kv(c, s, g, l), "rope_kv");
+    }
     TRY(launch_attention_generic(c, s, g, l), "attention");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    if (sk) TRY(launch_sk_resid(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq), "wo");
+    else TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
     TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr), "rmsnorm");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
-    TRY(launch_swiglu(c, s, T), "swiglu");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
+    if (sk) {
+      TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
+      TRY(launch_sk_resid(c, s, c->ws + c->map.h, L.w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
+    } else {
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
+      TRY(launch_swiglu(c, s, T), "swiglu");
+      TRY(launch_gemm_generic(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
+    }
   }
   if (hidden_out) TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
   if (logits_out) {
     TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr), "final_norm");
-    TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
+    if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
+    else TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
     TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
     TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1), "final_norm");
-    TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
-    TRY(launch_lm_merge(c, s, max_rows, head->cand, head->conf, head->entropy), "lm_merge");
+    int n_parts = c->map.n_vtiles;
+    if (sk) TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
+    else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
+    TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy), "lm_merge");
   }
   return DLLM_OK;
 }

@@ -74,6 +74,44 @@ __device__ inline bool kv_locate(const KVView& kv, int b, int pos, int h, int64_
   return true;
 }
 
+#define DEV_INF (__builtin_inff())
+
+// Softmax statistics of a run of logits in ascending column order.
+struct RowStat {
+  float m, s, t;  // running max, sum exp(z-m), sum exp(z-m)*z
+  int idx;
+  __device__ inline void init() { m = -DEV_INF; s = 0.f; t = 0.f; idx = 0x7fffffff; }
+  __device__ inline void push(float z, int col) {
+    if (z > m) {
+      float a = expf(m - z);   // exp(-inf) = 0 on the first value
+      s = s * a + 1.0f;
+      t = t * a + z;
+      m = z;
+      idx = col;
+    } else {
+      float e = expf(z - m);
+      s += e;
+      t = fmaf(e, z, t);
+    }
+  }
+  // merge with another run; on equal maxima the lower column wins
+  __device__ inline void merge(float m2, int i2, float s2, float t2) {
+    if (!(s2 > 0.f) && !(s2 != s2)) return;   // empty run
+    if (!(s > 0.f) && !(s != s)) { m = m2; idx = i2; s = s2; t = t2; return; }
+    if (m2 > m || (m2 == m && i2 < idx)) {
+      float a = expf(m - m2);
+      s = s * a + s2;
+      t = t * a + t2;
+      m = m2;
+      idx = i2;
+    } else {
+      float a = expf(m2 - m);
+      s = fmaf(s2, a, s);
+      t = fmaf(t2, a, t);
+    }
+  }
+};
+
 // Workspace map (byte offsets from the workspace base), fixed at dllm_create.
 struct Workspace {
   size_t status;       // int32[4]: [0] status bits, [1] number of LM-head rows
@@ -154,7 +192,7 @@ hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& 
 hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32_t* cand, float* conf,
                             float* entropy);
 hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows);
-hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int32_t* cand, float* conf,
+hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts, int32_t* cand, float* conf,
                            float* entropy);
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
@@ -163,5 +201,12 @@ hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n
 
 // ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------
 bool mfma_supported(const dllm_ctx* c);
+constexpr int SK_MAX_ROWS = 64;   // the skinny (weight-streaming) kernels take at most this many rows
+KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer);
+hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K);
+hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K);
+hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool);
+hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
+hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 
 }  // namespace dllm

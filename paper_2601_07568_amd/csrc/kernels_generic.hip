@@ -7,7 +7,6 @@
 
 namespace dllm {
 
-#define DEV_INF (__builtin_inff())
 
 __device__ inline float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -345,42 +344,6 @@ __global__ __launch_bounds__(1024) void k_mask_rows(int T, int32_t mask_id, int 
   }
 }
 
-// Softmax statistics of a run of logits in ascending column order.
-struct RowStat {
-  float m, s, t;  // running max, sum exp(z-m), sum exp(z-m)*z
-  int idx;
-  __device__ inline void init() { m = -DEV_INF; s = 0.f; t = 0.f; idx = 0x7fffffff; }
-  __device__ inline void push(float z, int col) {
-    if (z > m) {
-      float a = expf(m - z);   // exp(-inf) = 0 on the first value
-      s = s * a + 1.0f;
-      t = t * a + z;
-      m = z;
-      idx = col;
-    } else {
-      float e = expf(z - m);
-      s += e;
-      t = fmaf(e, z, t);
-    }
-  }
-  // merge with another run; on equal maxima the lower column wins
-  __device__ inline void merge(float m2, int i2, float s2, float t2) {
-    if (!(s2 > 0.f) && !(s2 != s2)) return;   // empty run
-    if (!(s > 0.f) && !(s != s)) { m = m2; idx = i2; s = s2; t = t2; return; }
-    if (m2 > m || (m2 == m && i2 < idx)) {
-      float a = expf(m - m2);
-      s = s * a + s2;
-      t = t * a + t2;
-      m = m2;
-      idx = i2;
-    } else {
-      float a = expf(m2 - m);
-      s = fmaf(s2, a, s);
-      t = fmaf(t2, a, t);
-    }
-  }
-};
-
 // LM head on the compacted rows with the softmax statistics taken from the accumulators:
 // each workgroup computes 64 rows x LM_TILE_N vocabulary columns in 64-column slices and keeps
 // (max, argmax, sum exp, sum exp*z) per row.  The logits never leave the chip.
@@ -698,8 +661,9 @@ hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows) {
   return hipGetLastError();
 }
 
-hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int32_t* cand, float* conf, float* entropy) {
-  k_lm_merge<<<max_rows, 64, 0, s>>>(WS(c, lm_part, float), c->map.n_vtiles, WS(c, rows, int32_t),
+hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts, int32_t* cand, float* conf,
+                           float* entropy) {
+  k_lm_merge<<<max_rows, 64, 0, s>>>(WS(c, lm_part, float), n_parts, WS(c, rows, int32_t),
                                      WS(c, status, int32_t) + 1, cand, conf, entropy);
   return hipGetLastError();
 }
