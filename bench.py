@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the denoise-step path on one MI355X.
+
+Default workload ("c3"): LLaDA-8B-shaped model (32 layers, d 4096, 32 heads x 128, MLP 12288, vocab
+126464), bfloat16, random-init N(0, 0.02) weights drawn on the device, batch 1, prompt of 1024 random
+tokens, blocks of 32, threshold 0.9, at least 2 unmasked per step.  A "step" is one denoising
+forward over the in-flight block against the cached prefix (embed .. LM head with fused
+confidence) followed by the unmask selection.  The timed region is exactly --steps such steps with
+everything resident in HBM; the block is put back to all-[MASK] (a device-side copy) whenever it
+would run out of masked positions.  After that, untimed for `value`: one whole generation (prefill,
+8 blocks, refresh at block boundaries) for tokens/s, a pass with per-kernel HIP events for the
+roofline object, and the CPU oracle on a bounded sample for cpu_baseline.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+KCLASS = {0: "qkv", 1: "wo", 2: "gate_up", 3: "down", 4: "lm_head", 5: "attention"}
+
+
+def device_weights(ms, torch, device, seed):
+    """Random-init weights of the architecture, drawn on the device (never aliased between layers)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    dt = torch.bfloat16 if ms.dtype == "bf16" else torch.float32
+
+    def mat(rows, cols, std=0.02):
+        return (torch.randn(rows, cols, generator=gen, device=device, dtype=torch.float32) * std).to(dt)
+
+    d, dq, dkv, F = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff
+    ones = lambda: torch.ones(d, device=device, dtype=dt)
+    g = {"tok_emb": mat(ms.vocab, d), "lm_head": mat(ms.vocab, d, 0.02 * ms.lm_head_scale), "final_norm": ones()}
+    layers = []
+    for _ in range(ms.n_layers):
+        layers.append({"attn_norm": ones(), "wq": mat(dq, d), "wk": mat(dkv, d), "wv": mat(dkv, d),
+                       "wo": mat(d, dq), "mlp_norm": ones(), "w_gate": mat(F, d), "w_up": mat(F, d),
+                       "w_down": mat(d, F)})
+    return g, layers
+
+
+def cpu_baseline(ms, P, Q, n_masked, budget_s=20.0):
+    """The CPU oracle as it stands, timed on the host: denoise steps (one layer + LM head at full
+    shape, then extrapolated to the model's depth) on the same workload shape."""
+    import numpy as np
+    from oracle import dllm_oracle as O
+    from paper_2601_07568_amd import synth
+    one = ms.with_layers(1)
+    w = synth.Weights(one, 3)
+    prompt = synth.random_tokens(one, 3, P)
+    blk = synth.masked_block(one, 3, Q, n_masked)
+    ck, cv = O.prefill(w, prompt, widen=synth.as_float)
+    w.globals()
+    # time the layer part and the head part separately so that the depth can be scaled
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        _, x = O.forward_cached(w, blk, ck, cv, widen=synth.as_float, want_logits=False)
+        n += 1
+        if time.perf_counter() - t0 > budget_s / 3 or n >= 8:
+            break
+    t_layer = (time.perf_counter() - t0) / n
+    t0 = time.perf_counter()
+    logits = O.head_logits(w, x, widen=synth.as_float)
+    cand, conf, ent, _ = O.confidence(logits, one.mask_id)
+    O.unmask(blk, cand, conf, one.mask_id, 0.9, 2)
+    t_head = time.perf_counter() - t0
+    step_s = ms.n_layers * t_layer + t_head
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n} cached forwards of one full-shape layer ({t_layer*1e3:.0f} ms each) and one LM head + "
+                      f"confidence + unmask ({t_head*1e3:.0f} ms), numpy float64; step time extrapolated as "
+                      f"{ms.n_layers} x layer + head"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="c3", choices=["c3", "c2"])
+    ap.add_argument("--layers", type=int, default=None, help="override depth (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-generation", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_07568_amd import synth
+    from paper_2601_07568_amd.binding import Engine
+
+    dev = torch.device("cuda:0")
+    if args.workload == "c3":
+        ms, P, Q, n_blocks, tau, m_floor, n_masked0 = synth.LLADA_8B, 1024, 32, 8, 0.9, 2, 32
+        name = "LLaDA-8B-shaped 32 layers, bf16, batch 1, prompt 1024, block 32, tau 0.9, min 2 unmasks/step"
+    else:
+        ms, P, Q, n_blocks, tau, m_floor, n_masked0 = synth.LLADA_8B.with_layers(1), 512, 32, 1, 0.9, 1, 24
+        name = "one LLaDA-8B-shaped layer + LM head, bf16, batch 1, prefix 512, block 32 (24 masked), tau 0.9, min 1"
+    if args.layers is not None:
+        ms = ms.with_layers(args.layers)
+    pt = 64
+    max_len = P + n_blocks * Q
+    mp = (max_len + pt - 1) // pt
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=mp, max_batch=1, max_q=Q,
+                 max_tokens=max_len, device_weights=device_weights(ms, torch, dev, 1))
+    table = eng.i32(np.arange(mp)[None])
+    prompt = eng.i32(synth.random_tokens(ms, 3, P))
+    cu = eng.i32([0, P])
+    eng.prefill_kv(prompt, cu, table, None, total_tokens=P, max_seqlen=P)
+    torch.cuda.synchronize()
+
+    fresh = eng.i32(synth.masked_block(ms, 3, Q, n_masked0)[None])
+    qt = fresh.clone()
+    prefix = eng.i32([P])
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=dev)
+    nrem = torch.zeros(1, 1, dtype=torch.int32, device=dev)
+    steps_per_block = max(1, n_masked0 // m_floor)
+
+    def one_step(i):
+        if i % steps_per_block == 0:
+            qt.copy_(fresh)                       # device-side re-mask: keeps every step a full step
+        eng.denoise_step(qt, prefix, table, cand, conf, None, max_prefix_len=P)
+        eng.unmask(qt, cand, conf, tau, m_floor, n_remaining=nrem)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    assert eng.read_status() == 0
+
+    # ---- per-kernel HIP-event pass over the same steps (separate from the timed region above)
+    eng.profile_enable(True)
+    n_prof = min(args.steps, 16)
+    for i in range(n_prof):
+        one_step(i)
+    kern = {}
+    for cls, nm in KCLASS.items():
+        n, tms, by = eng.profile_read(cls)
+        if n:
+            kern[nm] = {"launches": n, "avg_us": tms / n * 1e3, "bytes_per_launch": by / n,
+                        "GBps": by / (tms * 1e-3) / 1e9 if tms > 0 else None}
+    eng.profile_enable(False)
+    weight_streamers = {k: v for k, v in kern.items() if k != "attention"}
+    dom = max(weight_streamers, key=lambda k: weight_streamers[k]["avg_us"] * weight_streamers[k]["launches"]) \
+        if weight_streamers else None
+    roofline = None
+    if dom:
+        a = kern[dom]["GBps"]
+        roofline = {"bound": "hbm", "kernel": f"k_skinny ({dom})", "achieved": a, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": a / HBM_PEAK_GBS, "traffic": None,
+                    "avg_us": kern[dom]["avg_us"], "bytes_per_launch": kern[dom]["bytes_per_launch"]}
+    d, dq, dkv, F = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff
+    step_bytes = ms.n_layers * 2 * (d * (dq + 2 * dkv) + dq * d + 3 * d * F) + 2 * ms.vocab * d \
+        + ms.n_layers * 2 * 2 * dkv * (P + Q)
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- one whole generation, end to end (prefill, blocks, refresh at each boundary)
+    gen = None
+    if not args.no_generation and n_blocks > 1:
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        seq = prompt.clone()
+        eng.prefill_kv(seq, cu, table, None, total_tokens=P, max_seqlen=P)
+        forwards = 0
+        cur = P
+        for b in range(n_blocks):
+            blk = torch.full((1, Q), ms.mask_id, dtype=torch.int32, device=dev)
+            pl = eng.i32([cur])
+            while True:
+                eng.denoise_step(blk, pl, table, cand, conf, None, max_prefix_len=cur)
+                eng.unmask(blk, cand, conf, tau, m_floor, n_remaining=nrem)
+                forwards += 1
+                if int(nrem.item()) == 0:
+                    break
+            seq = torch.cat([seq, blk[0]])
+            cur += Q
+            eng.refresh_cache(seq, eng.i32([0, cur]), table, None, total_tokens=cur, max_seqlen=cur)
+        torch.cuda.synchronize()
+        gsec = time.perf_counter() - g0
+        gen = {"tokens": n_blocks * Q, "forwards": forwards, "seconds": gsec, "tokens_per_s": n_blocks * Q / gsec,
+               "steps_per_s": forwards / gsec, "tokens_per_forward": n_blocks * Q / forwards}
+
+    out = {
+        "metric": "denoise_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "layers": ms.n_layers, "prefix": P, "block": Q, "page_tokens": pt},
+        "step_algorithmic_GB": step_bytes / 1e9, "step_GBps": step_gbs, "step_frac_of_hbm_peak": step_gbs / HBM_PEAK_GBS,
+        "roofline": roofline, "kernels": kern, "generation": gen,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ms, P, Q, n_masked0)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

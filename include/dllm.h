@@ -179,6 +179,18 @@ int dllm_read_status(dllm_ctx *ctx, void *stream, int32_t *host_out);
  * scalar-FMA kernels (test aid). */
 int dllm_set_kernel_mode(dllm_ctx *ctx, int mode);
 
+/* Per-kernel timing for benchmarks.  While enabled, every launch of the weight-streaming GEMMs
+ * and of the attention kernel inside dllm_denoise_step is bracketed by HIP events on the call's
+ * stream (this perturbs end-to-end time; do not enable it in a timed region or under graph
+ * capture).  dllm_profile_read waits for the stream and returns, for kernel class `cls`
+ * (0 = q/k/v projection, 1 = output projection, 2 = gate/up projection, 3 = down projection,
+ * 4 = LM head, 5 = attention), the number of launches since enabling, the sum of their
+ * event-to-event durations in milliseconds and the sum of their algorithmic bytes (weights, or
+ * K/V, read once).  At most 8192 launches are recorded; later ones are not bracketed. */
+int dllm_profile_enable(dllm_ctx *ctx, int on);
+int dllm_profile_read(dllm_ctx *ctx, void *stream, int cls, int32_t *n_launches, double *total_ms,
+                      double *total_bytes);
+
 const char *dllm_strerror(int code);
 const char *dllm_last_hip_error(const dllm_ctx *ctx);
 

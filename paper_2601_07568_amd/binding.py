@@ -64,6 +64,9 @@ def lib() -> C.CDLL:
         "dllm_reset_status": (i32, [vp, vp]),
         "dllm_read_status": (i32, [vp, vp, C.POINTER(C.c_int32)]),
         "dllm_set_kernel_mode": (i32, [vp, i32]),
+        "dllm_profile_enable": (i32, [vp, i32]),
+        "dllm_profile_read": (i32, [vp, vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                    C.POINTER(C.c_double)]),
         "dllm_strerror": (C.c_char_p, [i32]),
         "dllm_last_hip_error": (C.c_char_p, [vp]),
     }
@@ -215,6 +218,15 @@ class Engine:
 
     def reset_status(self):
         self._check(lib().dllm_reset_status(self.ctx, self._stream()))
+
+    def profile_enable(self, on: bool):
+        self._check(lib().dllm_profile_enable(self.ctx, 1 if on else 0))
+
+    def profile_read(self, cls: int):
+        """(launches, total milliseconds, total algorithmic bytes) of kernel class cls."""
+        n, ms, by = C.c_int32(0), C.c_double(0), C.c_double(0)
+        self._check(lib().dllm_profile_read(self.ctx, self._stream(), cls, C.byref(n), C.byref(ms), C.byref(by)))
+        return n.value, ms.value, by.value
 
     def set_kernel_mode(self, mode: int):
         self._check(lib().dllm_set_kernel_mode(self.ctx, mode))

@@ -64,7 +64,10 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->tok_pos = take(t_max * 4);
   m->rows = take((size_t)m->r_max * 4);
   m->lm_part = take((size_t)m->r_max * ((c->vocab + 63) / 64) * 4 * 4);   // finest split: 64 columns per partial
-  m->attn_part = take(0);
+  m->attn_rows = (int64_t)t_step * c->n_q_heads * 8;
+  if (m->attn_rows < 65536) m->attn_rows = 65536;
+  m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
+  if (c->dtype != DLLM_BF16) m->attn_rows = 0;
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
   m->total = off;
@@ -114,8 +117,20 @@ extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_we
   return DLLM_OK;
 }
 
+static void prof_free(dllm_ctx* c) {
+  if (c->prof_ev) {
+    for (int i = 0; i < 2 * c->prof_cap; ++i) (void)hipEventDestroy(c->prof_ev[i]);
+    free(c->prof_ev);
+    free(c->prof_cls);
+    free(c->prof_bytes);
+  }
+  c->prof_ev = nullptr; c->prof_cls = nullptr; c->prof_bytes = nullptr;
+  c->prof_on = c->prof_n = c->prof_cap = 0;
+}
+
 extern "C" void dllm_destroy(dllm_ctx* ctx) {
   if (!ctx) return;
+  prof_free(ctx);
   free(ctx->layers);
   free(ctx);
 }
@@ -151,6 +166,53 @@ static int hip_fail(dllm_ctx* c, hipError_t e, const char* where) {
 
 #define WSP(c, field, type) ((type*)((c)->ws + (c)->map.field))
 
+extern "C" int dllm_profile_enable(dllm_ctx* c, int on) {
+  if (!c) return DLLM_EINVAL;
+  if (!on) { c->prof_on = 0; return DLLM_OK; }
+  if (!c->prof_ev) {
+    const int cap = 8192;
+    c->prof_ev = (hipEvent_t*)calloc(2 * cap, sizeof(hipEvent_t));
+    c->prof_cls = (int*)calloc(cap, sizeof(int));
+    c->prof_bytes = (double*)calloc(cap, sizeof(double));
+    if (!c->prof_ev || !c->prof_cls || !c->prof_bytes) return DLLM_ENOSPACE;
+    for (int i = 0; i < 2 * cap; ++i) TRY(hipEventCreate(&c->prof_ev[i]), "hipEventCreate");
+    c->prof_cap = cap;
+  }
+  c->prof_n = 0;
+  c->prof_on = 1;
+  return DLLM_OK;
+}
+
+extern "C" int dllm_profile_read(dllm_ctx* c, void* stream, int cls, int32_t* n_launches, double* total_ms,
+                                 double* total_bytes) {
+  if (!c || !n_launches || !total_ms || !total_bytes) return DLLM_EINVAL;
+  TRY(hipStreamSynchronize((hipStream_t)stream), "profile sync");
+  int n = 0;
+  double ms = 0.0, bytes = 0.0;
+  for (int i = 0; i < c->prof_n; ++i) {
+    if (c->prof_cls[i] != cls) continue;
+    float t = 0.f;
+    TRY(hipEventElapsedTime(&t, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]), "hipEventElapsedTime");
+    ms += t; bytes += c->prof_bytes[i]; ++n;
+  }
+  *n_launches = n; *total_ms = ms; *total_bytes = bytes;
+  return DLLM_OK;
+}
+
+// brackets one launch with events when profiling is on
+struct ProfScope {
+  dllm_ctx* c; hipStream_t s; int slot;
+  ProfScope(dllm_ctx* c_, hipStream_t s_, int cls, double bytes) : c(c_), s(s_), slot(-1) {
+    if (c->prof_on && c->prof_n < c->prof_cap) {
+      slot = c->prof_n++;
+      c->prof_cls[slot] = cls;
+      c->prof_bytes[slot] = bytes;
+      (void)hipEventRecord(c->prof_ev[2 * slot], s);
+    }
+  }
+  ~ProfScope() { if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * slot + 1], s); }
+};
+
 struct HeadOut {
   int32_t* cand;
   float* conf;
@@ -173,6 +235,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     const dllm_layer_w& L = c->layers[l];
     TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr), "rmsnorm");
     if (sk) {
+      ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
     } else {
       TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
@@ -180,12 +243,22 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
       TRY(launch_rope_kv(c, s, g, l), "rope_kv");
     }
-    TRY(launch_attention_generic(c, s, g, l), "attention");
-    if (sk) TRY(launch_sk_resid(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq), "wo");
-    else TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    {
+      ProfScope p(c, s, 5, 2.0 * 2.0 * dkv * (double)g.max_kv * g.B);
+      if (attn_step_supported(c, g)) TRY(launch_attn_step(c, s, g, attention_view(c, g, l)), "attention");
+      else TRY(launch_attention_generic(c, s, g, l), "attention");
+    }
+    if (sk) {
+      ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
+      TRY(launch_sk_resid(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq), "wo");
+    } else TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
     TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr), "rmsnorm");
     if (sk) {
-      TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
+      {
+        ProfScope p(c, s, 2, 2.0 * 2.0 * f.d_ff * f.d_model);
+        TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
+      }
+      ProfScope p(c, s, 3, 2.0 * f.d_ff * f.d_model);
       TRY(launch_sk_resid(c, s, c->ws + c->map.h, L.w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
     } else {
       TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
@@ -205,8 +278,10 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
     TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1), "final_norm");
     int n_parts = c->map.n_vtiles;
-    if (sk) TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
-    else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
+    if (sk) {
+      ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);
+      TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
+    } else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
     TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy), "lm_merge");
   }
   return DLLM_OK;

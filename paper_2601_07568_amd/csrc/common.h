@@ -134,7 +134,8 @@ struct Workspace {
   size_t tok_pos;      // int32 [Tmax]             position of each token in its sequence
   size_t rows;         // int32 [Rmax]             compacted list of LM-head rows
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
-  size_t attn_part;    // float [Tstep, Hq, max_splits, dh + 2] split-KV partials
+  size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
+  int64_t attn_rows;   // capacity in (token, head, unit) rows
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
   int64_t t_max, r_max, t_step, tpad;
@@ -153,6 +154,11 @@ struct dllm_ctx {
   dllm::Workspace map;
   int kernel_mode;
   char hip_error[256];
+  // per-kernel event timing (dllm_profile_*)
+  int prof_on, prof_n, prof_cap;
+  hipEvent_t* prof_ev;       // 2 * prof_cap events
+  int* prof_cls;
+  double* prof_bytes;
 };
 
 namespace dllm {
@@ -208,5 +214,7 @@ hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* 
 hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool);
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
 hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
+bool attn_step_supported(const dllm_ctx* c, const StepGeom& g);
+hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv);
 
 }  // namespace dllm

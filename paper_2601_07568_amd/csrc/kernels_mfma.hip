@@ -385,4 +385,269 @@ hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_pa
   return sk_launch_mt<4, 4, SK_LMSTATS>(s, a, a.n_parts);
 }
 
+// ==========================================================================================
+// Block-query attention of a denoise step over the paged pool, register-direct: no LDS.
+//
+// One wave owns 16*QT query rows of one (sequence, kv head) -- with grouped-query attention the
+// rows are (head-in-group, token) pairs -- and walks 32-key blocks.  S^T = K Q^T is computed with
+// K rows as the A operand; A-row rho of tile t is given key 8*(rho/4) + rho%4 + 4t of the block,
+// so that the accumulator layout (column = query, rows 4g..4g+3) leaves lane group g holding
+// exactly keys 8g..8g+7 of each query: the B operand of O^T = V^T P^T without any shuffle.  V is
+// stored transposed in the pool, so the A operand of that product is a 16-byte load as well.
+// Softmax statistics of a query live in the lanes that hold its column.  Several units (waves)
+// may split the keys of one row group; each writes an unnormalised partial (m, l, O) and
+// k_attn_combine merges them.
+struct AttnArgs {
+  const bf16_t* q;          // [T, Hq, DH] rotated
+  const int32_t* prefix_len;
+  KVView kv;
+  int Q, Hq, Hkv, B;
+  int n_units;              // key-splitting units per row group (gridDim.x * waves along keys)
+  int kspl;                 // units inside a workgroup
+  int n_rg_wg;              // row groups per workgroup
+  float scale_log2;         // log2(e) / sqrt(DH)
+  float* part_o;            // [T*Hq, n_units, DH]
+  float* part_ml;           // [T*Hq, n_units, 2]
+  int32_t* status;
+};
+
+template <int DH, int QT>
+__global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
+  constexpr int KK = DH / 32;   // k-steps of Q K^T
+  constexpr int DT = DH / 16;   // 16-row tiles of O^T
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int rg = blockIdx.y * a.n_rg_wg + (w % a.n_rg_wg);
+  const int unit = blockIdx.x * a.kspl + (w / a.n_rg_wg);
+  const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
+  const int G = a.Hq / a.Hkv;
+  const int R = a.Q * G;
+  if (rg * 16 * QT >= R) return;
+  const int kv_len = a.prefix_len[b] + a.Q;
+  const KVView& kv = a.kv;
+  const int pt = kv.page_tokens;
+  const bf16_t* kslab = (const bf16_t*)kv.k;
+  const bf16_t* vslab = (const bf16_t*)kv.v;
+  const int32_t* table = kv.table + (int64_t)b * kv.max_pages;
+
+  // query fragments: B operand, column c = row of this wave's tile
+  u32x4 qf[QT][KK];
+  int64_t row_out[QT];        // (token * Hq + head) of the lane's query, -1 if beyond R
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int r = rg * 16 * QT + t * 16 + c;
+    const bool ok = r < R;
+    if (!ok) r = 0;
+    const int hg = r / a.Q, j = r - hg * a.Q;
+    const int64_t ro = (int64_t)(b * a.Q + j) * a.Hq + kvh * G + hg;
+    row_out[t] = ok ? ro : -1;
+    const bf16_t* qp = a.q + ro * DH + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[t][kk] = *(const u32x4*)(qp + kk * 32);
+  }
+
+  f32x4 oacc[DT][QT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int t = 0; t < QT; ++t) oacc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) { m_run[t] = -DEV_INF; l_run[t] = 0.f; }
+  bool bad = false;
+
+  const int nkb = (kv_len + 31) >> 5;
+  for (int kb = unit; kb < nkb; kb += a.n_units) {
+    const int k0 = kb << 5;
+    // ---- K fragments (A operand): tile tt row c <-> key k0 + 8*(c/4) + c%4 + 4*tt
+    u32x4 kf[2][KK];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      int key = k0 + 8 * (c >> 2) + (c & 3) + 4 * tt;
+      if (key >= kv_len) key = kv_len - 1;                     // masked below; keeps the load in bounds
+      const int pi = key / pt;
+      int page = pi < kv.max_pages ? table[pi] : -1;
+      if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
+      const bf16_t* kp = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + g * 8;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[tt][kk] = *(const u32x4*)(kp + kk * 32);
+    }
+    // ---- V^T fragments (A operand of the second product): row = channel d*16 + c, keys k0+8g..+7
+    u32x4 vf[DT];
+    {
+      int key = k0 + 8 * g;
+      if (key >= kv_len) key = (kv_len - 1) & ~7;
+      const int pi = key / pt;
+      int page = pi < kv.max_pages ? table[pi] : -1;
+      bool pbad = false;
+      if (page < 0 || page >= kv.n_pages) { page = 0; pbad = true; }
+      const bf16_t* vp = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + c) * pt + (key - pi * pt);
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vf[d] = *(const u32x4*)(vp + (int64_t)d * 16 * pt);
+      if (pbad || k0 + 32 > kv_len) {
+        // zero what lies beyond the sequence (or in a page that is not addressable): the slots may
+        // hold anything, and 0 * NaN would poison the row
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            uint32_t v = vf[d][e];
+            const int ke = k0 + 8 * g + 2 * e;
+            if (pbad || ke >= kv_len) v &= 0xffff0000u;
+            if (pbad || ke + 1 >= kv_len) v &= 0x0000ffffu;
+            vf[d][e] = v;
+          }
+        }
+      }
+    }
+    // ---- S^T tiles
+    f32x4 s[2][QT];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) acc = mfma16(kf[tt][kk], qf[t][kk], acc);
+        s[tt][t] = acc;
+      }
+    // ---- online softmax per query column; lane holds keys k0 + 8g + 4tt + i
+    // Probabilities enter the second product as a bfloat16 pair hi + lo (two instructions): a
+    // single rounding of p would be the largest error of the whole attention and would flip the
+    // rounding of a good fraction of the stored outputs.
+    u32x4 pf[QT], pl[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      float mx = -DEV_INF;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = k0 + 8 * g + 4 * tt + i;
+          float v = s[tt][t][i] * a.scale_log2;
+          if (key >= kv_len) v = -DEV_INF;
+          s[tt][t][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[t], mx);       // finite: every block has at least one valid key
+      const float alpha = exp2f(m_run[t] - m_new);   // exp2(-inf) = 0 on the first block
+      float ps = 0.f;
+      float p[8];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float e = exp2f(s[tt][t][i] - m_new);
+          p[tt * 4 + i] = e;
+          ps += e;
+        }
+      l_run[t] = l_run[t] * alpha + ps;
+      m_run[t] = m_new;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        oacc[d][t][0] *= alpha; oacc[d][t][1] *= alpha; oacc[d][t][2] *= alpha; oacc[d][t][3] *= alpha;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16_t h0 = f32_to_bf16(p[2 * e]), h1 = f32_to_bf16(p[2 * e + 1]);
+        const bf16_t l0 = f32_to_bf16(p[2 * e] - bf16_to_f32(h0)), l1 = f32_to_bf16(p[2 * e + 1] - bf16_to_f32(h1));
+        pf[t][e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        pl[t][e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+      }
+    }
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        oacc[d][t] = mfma16(vf[d], pf[t], oacc[d][t]);
+        oacc[d][t] = mfma16(vf[d], pl[t], oacc[d][t]);
+      }
+  }
+
+  // ---- write the unit's partial: lane holds query column c, channels d*16 + 4g + i
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    float l = l_run[t];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (row_out[t] < 0) continue;
+    const int64_t slot = row_out[t] * a.n_units + unit;
+    float* po = a.part_o + slot * DH + 4 * g;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) *(f32x4*)(po + d * 16) = oacc[d][t];
+    if (g == 0) { a.part_ml[slot * 2] = m_run[t]; a.part_ml[slot * 2 + 1] = l; }
+  }
+  if (bad) atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
+}
+
+// merges the units' partials of one (token, head) row and stores the normalised output
+template <int DH>
+__global__ __launch_bounds__(DH) void k_attn_combine(const float* part_o, const float* part_ml, int n_units,
+                                                     bf16_t* o) {
+  const int64_t row = blockIdx.x;
+  const int d = threadIdx.x;
+  float M = -DEV_INF;
+  for (int u = 0; u < n_units; ++u) M = fmaxf(M, part_ml[(row * n_units + u) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int u = 0; u < n_units; ++u) {
+    const float mu = part_ml[(row * n_units + u) * 2];
+    if (mu == -DEV_INF) continue;                      // unit had no key block
+    const float sc = exp2f(mu - M);
+    den = fmaf(part_ml[(row * n_units + u) * 2 + 1], sc, den);
+    num = fmaf(part_o[(row * n_units + u) * DH + d], sc, num);
+  }
+  o[row * DH + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+}
+
+bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
+  const dllm_config& f = c->cfg;
+  return mfma_supported(c) && g.Q > 0 && f.page_tokens % 8 == 0 && c->map.attn_rows > 0;
+}
+
+hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv) {
+  const dllm_config& f = c->cfg;
+  const int G = f.n_q_heads / f.n_kv_heads;
+  const int R = g.Q * G;
+  constexpr int QT = 2;
+  const int n_rg = (R + 16 * QT - 1) / (16 * QT);
+  const int n_rg_wg = n_rg < 8 ? n_rg : 8;
+  const int n_chunks = (n_rg + n_rg_wg - 1) / n_rg_wg;
+  const int nkb = (g.max_kv + 31) / 32;
+  // units along the keys: enough waves to cover the chip, at least four key blocks each, and
+  // within the partial buffer
+  int64_t want = 1024 / ((int64_t)g.B * f.n_kv_heads * n_rg);
+  if (want < 1) want = 1;
+  int64_t by_work = nkb / 4 > 0 ? nkb / 4 : 1;
+  int64_t by_space = c->map.attn_rows / ((int64_t)g.T * f.n_q_heads);
+  int64_t units = want < by_work ? want : by_work;
+  if (units > by_space) units = by_space;
+  if (units > ATTN_MAX_SPLITS) units = ATTN_MAX_SPLITS;
+  if (units < 1) return hipErrorInvalidValue;
+  int kspl = 8 / n_rg_wg;                                  // waves of a workgroup along the keys
+  while (kspl > 1 && units % kspl != 0) --kspl;
+  AttnArgs a;
+  a.q = WSM(c, q, bf16_t);
+  a.prefix_len = g.prefix_len;
+  a.kv = kv;
+  a.Q = g.Q; a.Hq = f.n_q_heads; a.Hkv = f.n_kv_heads; a.B = g.B;
+  a.n_units = (int)units; a.kspl = kspl; a.n_rg_wg = n_rg_wg;
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)f.head_dim);
+  a.part_o = WSM(c, attn_part, float);
+  a.part_ml = a.part_o + (size_t)c->map.attn_rows * f.head_dim;
+  a.status = WSM(c, status, int32_t);
+  dim3 grid((unsigned)(units / kspl), n_chunks, g.B * f.n_kv_heads);
+  const int threads = 64 * n_rg_wg * kspl;
+  if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
+  else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rows = g.T * f.n_q_heads;
+  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t));
+  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t));
+  return hipGetLastError();
+}
+
 }  // namespace dllm
