@@ -105,6 +105,19 @@ int dllm_create(dllm_ctx **out, const dllm_config *cfg, const dllm_weights *w,
                 void *kv_pool, size_t kv_pool_bytes, void *workspace, size_t workspace_bytes);
 void dllm_destroy(dllm_ctx *ctx);
 
+/* Weight packing for the matrix-core path of DLLM_BF16 models.  Batch-1 denoise steps are bound by
+ * reading every weight once from HBM (the forward of Section 3.2 is run once per step on a 32-token
+ * block); the kernels reach HBM speed only if a wavefront's loads are contiguous, so the linear
+ * weights are re-ordered once into the operand order of the matrix instruction: 16-byte unit
+ * ((rt * ceil(K/128) + kb) * 4 + j) * 64 + g*16 + c of a matrix holds row rt*16 + c, columns
+ * kb*128 + j*32 + g*8 .. +7 (rows padded to 16, columns to 128, with zeros).
+ * dllm_pack_weights enqueues the re-ordering of all projection matrices and of the LM head into
+ * `packed` (dev, 256-byte aligned, dllm_packed_weight_bytes, borrowed for the life of the context).
+ * The original weights stay in use (prefill, refresh and steps of more than 64 rows read them).
+ * Until this call has been made, bfloat16 denoise steps run on the generic kernels. */
+size_t dllm_packed_weight_bytes(const dllm_config *cfg);
+int dllm_pack_weights(dllm_ctx *ctx, void *stream, void *packed, size_t packed_bytes);
+
 /* Prefill (Section 3.2, "KV-Cache"): one bidirectional forward without cache over B packed
  * sequences -- sequence b is tokens[cu_seqlens[b] .. cu_seqlens[b+1]), every token attends to every
  * token of its sequence -- and stores the K/V states of its first n_cache[b] positions (all of

@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         "dllm_kv_pool_bytes": (sz, [pcfg]),
         "dllm_create": (i32, [C.POINTER(vp), pcfg, C.POINTER(Weights), vp, sz, vp, sz]),
         "dllm_destroy": (None, [vp]),
+        "dllm_packed_weight_bytes": (sz, [pcfg]),
+        "dllm_pack_weights": (i32, [vp, vp, vp, sz]),
         "dllm_prefill_kv": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
@@ -99,7 +101,7 @@ class Engine:
     device tensors through `device_weights` = (globals dict, list of layer dicts)."""
 
     def __init__(self, ms, weights=None, *, page_tokens=32, max_pages_per_seq=8, n_pages=16, max_batch=1,
-                 max_q=32, max_tokens=0, device="cuda:0", device_weights=None):
+                 max_q=32, max_tokens=0, device="cuda:0", device_weights=None, pack=True):
         import torch
         self.torch, self.ms, self.device = torch, ms, torch.device(device)
         self.cfg = make_config(ms, page_tokens, max_pages_per_seq, n_pages, max_batch, max_q, max_tokens)
@@ -137,6 +139,12 @@ class Engine:
         if rc != DLLM_OK:
             raise DllmError(rc)
         self._check(L.dllm_reset_status(self.ctx, self._stream()))
+        self.packed = None
+        if ms.dtype == "bf16" and pack:
+            pb = L.dllm_packed_weight_bytes(C.byref(self.cfg))
+            self.packed = torch.empty(pb + 256, dtype=torch.uint8, device=self.device)
+            off = (-self.packed.data_ptr()) % 256
+            self._check(L.dllm_pack_weights(self.ctx, self._stream(), self.packed.data_ptr() + off, pb))
 
     # -- helpers
     def _stream(self):

@@ -45,7 +45,7 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   m->status = take(64);
   m->x = take(t_max * c->d_model * 4);
-  m->xn = take(t_max * c->d_model * es);
+  m->xn = take((t_max + 16) * ((size_t)c->d_model + 128) * es);
   m->q32 = take(t_max * dq * 4);
   m->k32 = take(t_max * dkv * 4);
   m->q = take(t_max * dq * es);
@@ -54,10 +54,10 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->kpack = take((size_t)m->tpad * dkv * es);
   m->vpack = take((size_t)m->tpad * dkv * es);
   m->cu_pad = take(((size_t)c->max_batch + 1) * 4);
-  m->o = take(t_max * dq * es);
+  m->o = take((t_max + 16) * (dq + 128) * es);
   m->g = take(t_max * c->d_ff * 4);
   m->u = take(t_max * c->d_ff * 4);
-  m->h = take(t_max * c->d_ff * es);
+  m->h = take((t_max + 16) * ((size_t)c->d_ff + 128) * es);
   m->rope_cos = take(t_max * half * 4);
   m->rope_sin = take(t_max * half * 4);
   m->tok_seq = take(t_max * 4);
@@ -83,6 +83,16 @@ extern "C" size_t dllm_kv_pool_bytes(const dllm_config* cfg) {
   if (!config_ok(cfg)) return 0;
   return (size_t)cfg->n_layers * 2 * kv_slab_elems(*cfg) * elem_size(*cfg);
 }
+
+static int hip_fail(dllm_ctx* c, hipError_t e, const char* where) {
+  snprintf(c->hip_error, sizeof(c->hip_error), "%s: %s", where, hipGetErrorString(e));
+  return DLLM_EHIP;
+}
+#define TRY(call, where)                        \
+  do {                                          \
+    hipError_t e_ = (call);                     \
+    if (e_ != hipSuccess) return hip_fail(c, e_, where); \
+  } while (0)
 
 extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_weights* w, void* kv_pool,
                            size_t kv_pool_bytes, void* workspace, size_t workspace_bytes) {
@@ -128,9 +138,56 @@ static void prof_free(dllm_ctx* c) {
   c->prof_on = c->prof_n = c->prof_cap = 0;
 }
 
+static size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+extern "C" size_t dllm_packed_weight_bytes(const dllm_config* f) {
+  if (!config_ok(f) || f->dtype != DLLM_BF16) return 0;
+  const int dq = f->n_q_heads * f->head_dim, dkv = f->n_kv_heads * f->head_dim;
+  size_t per_layer = align256(packed_weight_bytes(dq, f->d_model)) + 2 * align256(packed_weight_bytes(dkv, f->d_model)) +
+                     align256(packed_weight_bytes(f->d_model, dq)) + 2 * align256(packed_weight_bytes(f->d_ff, f->d_model)) +
+                     align256(packed_weight_bytes(f->d_model, f->d_ff));
+  return per_layer * f->n_layers + align256(packed_weight_bytes(f->vocab, f->d_model));
+}
+
+extern "C" int dllm_pack_weights(dllm_ctx* c, void* stream, void* packed, size_t packed_bytes) {
+  if (!c || !packed) return DLLM_EINVAL;
+  const dllm_config& f = c->cfg;
+  if (f.dtype != DLLM_BF16) return DLLM_ESHAPE;
+  if (((uintptr_t)packed & 255) != 0) return DLLM_EINVAL;
+  if (packed_bytes < dllm_packed_weight_bytes(&f)) return DLLM_ENOSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
+  if (!c->packed_layers) {
+    c->packed_layers = (dllm_layer_w*)calloc(f.n_layers > 0 ? f.n_layers : 1, sizeof(dllm_layer_w));
+    if (!c->packed_layers) return DLLM_ENOSPACE;
+  }
+  char* p = (char*)packed;
+  auto pack = [&](const void* W, int N, int K, const void** dst) -> hipError_t {
+    *dst = p;
+    hipError_t e = launch_pack_weight(s, W, p, N, K);
+    p += align256(packed_weight_bytes(N, K));
+    return e;
+  };
+  for (int l = 0; l < f.n_layers; ++l) {
+    const dllm_layer_w& L = c->layers[l];
+    dllm_layer_w& P = c->packed_layers[l];
+    TRY(pack(L.wq, dq, f.d_model, &P.wq), "pack wq");
+    TRY(pack(L.wk, dkv, f.d_model, &P.wk), "pack wk");
+    TRY(pack(L.wv, dkv, f.d_model, &P.wv), "pack wv");
+    TRY(pack(L.wo, f.d_model, dq, &P.wo), "pack wo");
+    TRY(pack(L.w_gate, f.d_ff, f.d_model, &P.w_gate), "pack w_gate");
+    TRY(pack(L.w_up, f.d_ff, f.d_model, &P.w_up), "pack w_up");
+    TRY(pack(L.w_down, f.d_model, f.d_ff, &P.w_down), "pack w_down");
+  }
+  TRY(pack(c->lm_head, f.vocab, f.d_model, &c->packed_lm_head), "pack lm_head");
+  c->packed = (char*)packed;
+  return DLLM_OK;
+}
+
 extern "C" void dllm_destroy(dllm_ctx* ctx) {
   if (!ctx) return;
   prof_free(ctx);
+  free(ctx->packed_layers);
   free(ctx->layers);
   free(ctx);
 }
@@ -153,16 +210,6 @@ extern "C" const char* dllm_strerror(int code) {
 }
 
 extern "C" const char* dllm_last_hip_error(const dllm_ctx* ctx) { return ctx ? ctx->hip_error : ""; }
-
-static int hip_fail(dllm_ctx* c, hipError_t e, const char* where) {
-  snprintf(c->hip_error, sizeof(c->hip_error), "%s: %s", where, hipGetErrorString(e));
-  return DLLM_EHIP;
-}
-#define TRY(call, where)                        \
-  do {                                          \
-    hipError_t e_ = (call);                     \
-    if (e_ != hipSuccess) return hip_fail(c, e_, where); \
-  } while (0)
 
 #define WSP(c, field, type) ((type*)((c)->ws + (c)->map.field))
 
@@ -230,10 +277,11 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   TRY(launch_embed(c, s, g), "embed");
   TRY(launch_rope_table(c, s, g), "rope_table");
   // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
-  const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS;
+  // (their activation operands are kept in fragment order, which only these kernels write)
+  const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS && attn_step_supported(c, g);
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
-    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr), "rmsnorm");
+    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "rmsnorm");
     if (sk) {
       ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
@@ -245,21 +293,21 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     }
     {
       ProfScope p(c, s, 5, 2.0 * 2.0 * dkv * (double)g.max_kv * g.B);
-      if (attn_step_supported(c, g)) TRY(launch_attn_step(c, s, g, attention_view(c, g, l)), "attention");
+      if (attn_step_supported(c, g)) TRY(launch_attn_step(c, s, g, attention_view(c, g, l), sk), "attention");
       else TRY(launch_attention_generic(c, s, g, l), "attention");
     }
     if (sk) {
       ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
-      TRY(launch_sk_resid(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq), "wo");
+      TRY(launch_sk_resid(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, x, float), T, f.d_model, dq), "wo");
     } else TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
-    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr), "rmsnorm");
+    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "rmsnorm");
     if (sk) {
       {
         ProfScope p(c, s, 2, 2.0 * 2.0 * f.d_ff * f.d_model);
         TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
       }
       ProfScope p(c, s, 3, 2.0 * f.d_ff * f.d_model);
-      TRY(launch_sk_resid(c, s, c->ws + c->map.h, L.w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
+      TRY(launch_sk_resid(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
     } else {
       TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
       TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
@@ -269,14 +317,15 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   }
   if (hidden_out) TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
   if (logits_out) {
-    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr), "final_norm");
-    if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
+    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "final_norm");
+    if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->packed_lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
     else TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
     TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
-    TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1), "final_norm");
+    TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1,
+                       sk ? (max_rows + 15) / 16 : 0), "final_norm");
     int n_parts = c->map.n_vtiles;
     if (sk) {
       ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);

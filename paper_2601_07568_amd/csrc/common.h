@@ -25,6 +25,15 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// Fragment order of a bfloat16 activation matrix [rows, K] that feeds the weight-streaming GEMM:
+// element (row, k) lives at frag_offset(row, k, mt), mt = 16-row tiles of the matrix.  The 16-byte
+// unit of (128-element block kb, instruction j, tile m, lane g*16 + c) holds row m*16 + c,
+// k = kb*128 + j*32 + g*8 .. +7, so that every operand fetch of a wave is one contiguous KiB.
+__host__ __device__ inline int64_t frag_offset(int row, int k, int mt) {
+  const int kb = k >> 7, j = (k >> 5) & 3, g = (k >> 3) & 3;
+  return ((((int64_t)kb * 4 + j) * mt + (row >> 4)) * 64 + g * 16 + (row & 15)) * 8 + (k & 7);
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   __device__ static inline float load(const float* p) { return *p; }
@@ -114,7 +123,7 @@ struct RowStat {
 
 // Workspace map (byte offsets from the workspace base), fixed at dllm_create.
 struct Workspace {
-  size_t status;       // int32[4]: [0] status bits, [1] number of LM-head rows
+  size_t status;       // int32[16]: [0] status bits, [1] number of LM-head rows
   size_t x;            // float [Tmax, d]          residual stream
   size_t xn;           // T     [Tmax, d]          normalised activations (GEMM input)
   size_t q32;          // float [Tmax, Hq*dh]      q projection before the rotary embedding
@@ -149,6 +158,10 @@ struct dllm_ctx {
   dllm_config cfg;
   dllm_layer_w* layers;      // host copy
   const void *tok_emb, *final_norm, *lm_head;
+  // weights in fragment order (dllm_pack_weights); nullptr until packed
+  char* packed;
+  dllm_layer_w* packed_layers;   // host array; norm gains are not packed and left null
+  const void* packed_lm_head;
   char* kv_pool;
   char* ws;
   dllm::Workspace map;
@@ -186,8 +199,9 @@ hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 hipError_t launch_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 // out[T or n_rows, d] = rmsnorm(x[row]) * gain; rows == nullptr: identity row map, n = T
+// frag_mt > 0: write in fragment order for frag_mt 16-row tiles (bfloat16 only)
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
-                          const int32_t* n_rows_dev);
+                          const int32_t* n_rows_dev, int frag_mt);
 enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
 // C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,
@@ -207,6 +221,8 @@ hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n
 
 // ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------
 bool mfma_supported(const dllm_ctx* c);
+size_t packed_weight_bytes(int N, int K);
+hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int K);
 constexpr int SK_MAX_ROWS = 64;   // the skinny (weight-streaming) kernels take at most this many rows
 KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer);
 hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K);
@@ -215,6 +231,6 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
 hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g);
-hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv);
+hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out);
 
 }  // namespace dllm

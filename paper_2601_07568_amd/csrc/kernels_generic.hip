@@ -92,7 +92,7 @@ __global__ void k_rope_table(int T, int half, double log2_base, const int32_t* t
 
 template <typename T>
 __global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* out, const int32_t* rows,
-                          const int32_t* n_rows_dev) {
+                          const int32_t* n_rows_dev, int frag_mt) {
   __shared__ float red[16];
   int r = blockIdx.x;
   int src = r;
@@ -105,8 +105,10 @@ __global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* ou
   for (int i = threadIdx.x; i < d; i += blockDim.x) { float v = xr[i]; ss += v * v; }
   ss = block_sum(ss, red);
   float rinv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += blockDim.x)
-    Elem<T>::store(out + (int64_t)r * d + i, xr[i] * rinv * Elem<T>::load(gain + i));
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const int64_t at = frag_mt > 0 ? frag_offset(r, i, frag_mt) : (int64_t)r * d + i;
+    Elem<T>::store(out + at, xr[i] * rinv * Elem<T>::load(gain + i));
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -531,14 +533,14 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
 }
 
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
-                          const int32_t* n_rows_dev) {
+                          const int32_t* n_rows_dev, int frag_mt) {
   const dllm_config& f = c->cfg;
   if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
-                                        WS(c, xn, bf16_t), rows, n_rows_dev);
+                                        WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt);
   else
     k_rmsnorm<float><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const float*)gain,
-                                       WS(c, xn, float), rows, n_rows_dev);
+                                       WS(c, xn, float), rows, n_rows_dev, 0);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@
 #include "common.h"
 #include <math.h>
 #include <string.h>
+#include <stdlib.h>
 
 namespace dllm {
 
@@ -33,7 +34,7 @@ struct SkArgs {
   const bf16_t* X;          // activations [M, K]
   const int32_t* m_dev;     // optional device row count (<= M)
   int M, K;
-  const bf16_t* W0;         // main weight / Wq / W_gate / lm_head
+  const bf16_t* W0;         // main weight / Wq / W_gate / lm_head   (all in packed fragment order)
   const bf16_t* W1;         // Wk / W_up
   const bf16_t* W2;         // Wv
   int N0, N1, N2;           // rows of W0, W1, W2
@@ -63,21 +64,22 @@ struct SkFrag {
   u32x4 b[MT][4];
 };
 
+// Weights: lane (c, g) reads 16 bytes of row c at element kb + j*32 + g*8 (64 contiguous bytes per
+// row and instruction).  Activations are stored in fragment order (frag_offset), so the operand
+// of (block, j, m-tile) is one contiguous KiB for the wave: xf points at the lane's 16 bytes of
+// fragment 0.
 template <int NT, int MT, bool TAIL>
-__device__ inline void sk_load(SkFrag<NT, MT>& f, const bf16_t* const (&wrow)[NT], const bf16_t* const (&xrow)[MT],
-                               int kb, int g, int K) {
+__device__ inline void sk_load(SkFrag<NT, MT>& f, const u32x4* const (&wt)[NT], const u32x4* xf, int blk, int g,
+                               int K) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int k = kb + j * 32;   // lane's element offset is k + g*8 (g*8 is folded into the row pointers)
-    const bool ok = !TAIL || (k + g * 8 + 8 <= K);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      if (ok) f.a[t][j] = *(const u32x4*)(wrow[t] + k);
-      else f.a[t][j] = u32x4{0, 0, 0, 0};
-    }
+    for (int t = 0; t < NT; ++t) f.a[t][j] = wt[t][(blk * 4 + j) * 64];   // packed weights are zero beyond K
+    // the activation buffer is not: beyond K it holds whatever was there, and 0 * NaN is NaN
+    const bool ok = !TAIL || (blk * SK_KB + j * 32 + g * 8 + 8 <= K);
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-      if (ok) f.b[t][j] = *(const u32x4*)(xrow[t] + k);
+      if (ok) f.b[t][j] = xf[((blk * 4 + j) * MT + t) * 64];
       else f.b[t][j] = u32x4{0, 0, 0, 0};
     }
   }
@@ -138,20 +140,18 @@ __global__ __launch_bounds__(NW * 64) void k_skinny(const SkArgs a) {
   const bf16_t* wbase[NT];
   int row0[NT], nrows[NT];
   sk_tile_rows<NT, EPI>(a, wg, wbase, row0, nrows);
-  const bf16_t* wrow[NT];
-  const bf16_t* xrow[MT];
+  // packed weights: the 16-row tile rt of a matrix with kpb 128-element blocks starts at unit
+  // rt * kpb * 256; inside, (block, j, lane) is unit (block*4 + j)*64 + lane: one contiguous stream
+  const int kpb = (K + SK_KB - 1) / SK_KB;
+  const u32x4* wt[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    int r = row0[t] + c;
-    r = r < nrows[t] ? r : nrows[t] - 1;
-    wrow[t] = wbase[t] + (int64_t)r * K + g * 8;
+    int rt = row0[t] >> 4;
+    const int rt_max = (nrows[t] + 15) / 16 - 1;
+    rt = rt < rt_max ? rt : rt_max;
+    wt[t] = (const u32x4*)wbase[t] + (int64_t)rt * kpb * 256 + lane;
   }
-#pragma unroll
-  for (int m = 0; m < MT; ++m) {
-    int r = m * 16 + c;
-    r = r < M ? r : M - 1;
-    xrow[m] = a.X + (int64_t)r * K + g * 8;
-  }
+  const u32x4* xf = (const u32x4*)a.X + lane;   // rows >= M of the last tile hold stale data: their columns are dropped
 
   f32x4 acc[NT][MT];
 #pragma unroll
@@ -159,24 +159,35 @@ __global__ __launch_bounds__(NW * 64) void k_skinny(const SkArgs a) {
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int stride = NW * SK_KB;
-  const int k_full = K / SK_KB * SK_KB;   // blocks below k_full need no tail guard
-  SkFrag<NT, MT> f0, f1;
-  int kb = w * SK_KB;
-  if (kb < k_full) sk_load<NT, MT, false>(f0, wrow, xrow, kb, g, K);
-  while (kb < k_full) {
-    const int k1 = kb + stride;
-    if (k1 < k_full) sk_load<NT, MT, false>(f1, wrow, xrow, k1, g, K);
-    sk_mma<NT, MT>(f0, acc);
-    if (k1 >= k_full) { kb = k1; break; }
-    const int k2 = k1 + stride;
-    if (k2 < k_full) sk_load<NT, MT, false>(f0, wrow, xrow, k2, g, K);
-    sk_mma<NT, MT>(f1, acc);
-    kb = k2;
+  // Software pipeline over this wave's k-blocks (w, w+NW, ...): the next block is always in flight
+  // while the current one is multiplied.  No load sits inside a branch of the steady-state loop (a
+  // branch around a load makes the compiler wait for every outstanding load at the join).
+  const int n_full = K / SK_KB;                       // blocks that need no tail guard
+  const int ws = __builtin_amdgcn_readfirstlane(w);   // wave index as a scalar
+  const int n_w = n_full > ws ? (n_full - ws + NW - 1) / NW : 0;
+  if (n_w > 0) {
+    SkFrag<NT, MT> f0, f1;
+    sk_load<NT, MT, false>(f0, wt, xf, ws, g, K);
+    int i = 0;
+    while (i + 2 < n_w) {
+      sk_load<NT, MT, false>(f1, wt, xf, ws + (i + 1) * NW, g, K);
+      sk_mma<NT, MT>(f0, acc);
+      sk_load<NT, MT, false>(f0, wt, xf, ws + (i + 2) * NW, g, K);
+      sk_mma<NT, MT>(f1, acc);
+      i += 2;
+    }
+    if (n_w - i == 2) {
+      sk_load<NT, MT, false>(f1, wt, xf, ws + (i + 1) * NW, g, K);
+      sk_mma<NT, MT>(f0, acc);
+      sk_mma<NT, MT>(f1, acc);
+    } else {
+      sk_mma<NT, MT>(f0, acc);
+    }
   }
-  if (k_full < K && w == (k_full / SK_KB) % NW) {   // ragged last block
-    sk_load<NT, MT, true>(f0, wrow, xrow, k_full, g, K);
-    sk_mma<NT, MT>(f0, acc);
+  if (n_full * SK_KB < K && ws == n_full % NW) {      // ragged last block
+    SkFrag<NT, MT> ft;
+    sk_load<NT, MT, true>(ft, wt, xf, n_full, g, K);
+    sk_mma<NT, MT>(ft, acc);
   }
 
   // sum the waves' partial tiles in wave order
@@ -214,7 +225,7 @@ __global__ __launch_bounds__(NW * 64) void k_skinny(const SkArgs a) {
       const int n = row0[0] + fr;
       if (tok_ok && n < a.N0) {
         const float gt = val[0];
-        a.out_bf16[(int64_t)tok * a.N0 + n] = f32_to_bf16(gt / (1.0f + expf(-gt)) * val[NT - 1]);
+        a.out_bf16[frag_offset(tok, n, MT)] = f32_to_bf16(gt / (1.0f + expf(-gt)) * val[NT - 1]);
       }
     } else if (EPI == SK_QKV) {
       if (tok_ok) {
@@ -304,11 +315,37 @@ static hipError_t sk_launch_mt(hipStream_t s, const SkArgs& a, int grid) {
   return hipGetLastError();
 }
 
+// ---- weight packing ---------------------------------------------------------------------------
+// [N, K] row-major -> fragment order, rows padded to 16 and K to 128 with zeros.  Unit (16 bytes)
+// index ((rt * kpb + kb) * 4 + j) * 64 + g*16 + c holds row rt*16 + c, k = kb*128 + j*32 + g*8 .. +7.
+__global__ void k_pack_weight(const bf16_t* __restrict__ W, u32x4* __restrict__ P, int N, int K, int64_t n_units) {
+  const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= n_units) return;
+  const int kpb = (K + SK_KB - 1) / SK_KB;
+  const int lane = (int)(u & 63), j = (int)((u >> 6) & 3);
+  const int64_t t = u >> 8;
+  const int kb = (int)(t % kpb), rt = (int)(t / kpb);
+  const int r = rt * 16 + (lane & 15), k = kb * SK_KB + j * 32 + (lane >> 4) * 8;
+  u32x4 v = u32x4{0, 0, 0, 0};
+  if (r < N && k + 8 <= K) v = *(const u32x4*)(W + (int64_t)r * K + k);
+  P[u] = v;
+}
+
+size_t packed_weight_bytes(int N, int K) {
+  return (size_t)((N + 15) / 16) * ((K + SK_KB - 1) / SK_KB) * 256 * 16;
+}
+
+hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int K) {
+  const int64_t n_units = (int64_t)(packed_weight_bytes(N, K) / 16);
+  k_pack_weight<<<(unsigned)((n_units + 255) / 256), 256, 0, s>>>((const bf16_t*)W, (u32x4*)P, N, K, n_units);
+  return hipGetLastError();
+}
+
 #define WSM(c, field, type) ((type*)((c)->ws + (c)->map.field))
 
 bool mfma_supported(const dllm_ctx* c) {
   const dllm_config& f = c->cfg;
-  return f.dtype == DLLM_BF16 && c->kernel_mode == 0 && f.d_model % 8 == 0 && f.d_ff % 8 == 0 &&
+  return f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->packed != nullptr && f.d_model % 8 == 0 && f.d_ff % 8 == 0 &&
          (f.head_dim == 64 || f.head_dim == 128);
 }
 
@@ -321,10 +358,10 @@ static SkArgs sk_base(const void* X, int M, int K) {
   return a;
 }
 
-// x[M,N] += A[M,K] * W[N,K]^T
+// x[M,N] += A[M,K] * W[N,K]^T        (A in fragment order, see frag_offset)
 hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K) {
   SkArgs a = sk_base(A, M, K);
-  a.W0 = (const bf16_t*)W;
+  a.W0 = (const bf16_t*)W;   // packed
   a.N0 = N;
   a.out_f32 = x;
   return sk_launch_mt<1, 8, SK_RESID>(s, a, (N + 15) / 16);
@@ -345,7 +382,8 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
   const dllm_config& f = c->cfg;
   const dllm_layer_w& L = c->layers[layer];
   SkArgs a = sk_base(c->ws + c->map.xn, g.T, f.d_model);
-  a.W0 = (const bf16_t*)L.wq; a.W1 = (const bf16_t*)L.wk; a.W2 = (const bf16_t*)L.wv;
+  const dllm_layer_w& P = c->packed_layers[layer];
+  a.W0 = (const bf16_t*)P.wq; a.W1 = (const bf16_t*)P.wk; a.W2 = (const bf16_t*)P.wv;
   a.N0 = f.n_q_heads * f.head_dim; a.N1 = a.N2 = f.n_kv_heads * f.head_dim;
   a.out_bf16 = WSM(c, q, bf16_t);
   a.dh = f.head_dim;
@@ -360,12 +398,13 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
   return sk_launch_mt<2, 8, SK_QKV>(s, a, a.n_q_wg + a.n_k_wg + n_v_wg);
 }
 
-// h[M,F] = silu(xn Wg^T) * (xn Wu^T)
+// h[M,F] = silu(xn Wg^T) * (xn Wu^T), written in fragment order for the down projection
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M) {
   const dllm_config& f = c->cfg;
   const dllm_layer_w& L = c->layers[layer];
   SkArgs a = sk_base(c->ws + c->map.xn, M, f.d_model);
-  a.W0 = (const bf16_t*)L.w_gate; a.W1 = (const bf16_t*)L.w_up;
+  const dllm_layer_w& P = c->packed_layers[layer];
+  a.W0 = (const bf16_t*)P.w_gate; a.W1 = (const bf16_t*)P.w_up;
   a.N0 = f.d_ff;
   a.out_bf16 = WSM(c, h, bf16_t);
   return sk_launch_mt<2, 8, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
@@ -376,7 +415,7 @@ hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_pa
   const dllm_config& f = c->cfg;
   SkArgs a = sk_base(c->ws + c->map.xn, max_rows, f.d_model);
   a.m_dev = WSM(c, status, int32_t) + 1;
-  a.W0 = (const bf16_t*)c->lm_head;
+  a.W0 = (const bf16_t*)c->packed_lm_head;
   a.N0 = f.vocab;
   a.part = WSM(c, lm_part, float);
   a.n_parts = (f.vocab + 63) / 64;
@@ -584,9 +623,10 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
 }
 
 // merges the units' partials of one (token, head) row and stores the normalised output
+// (fragment order of the [T, Hq*DH] matrix: it is the activation operand of the output projection)
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_combine(const float* part_o, const float* part_ml, int n_units,
-                                                     bf16_t* o) {
+                                                     bf16_t* o, int Hq, int mt) {
   const int64_t row = blockIdx.x;
   const int d = threadIdx.x;
   float M = -DEV_INF;
@@ -599,7 +639,9 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const float* part_o, const 
     den = fmaf(part_ml[(row * n_units + u) * 2 + 1], sc, den);
     num = fmaf(part_o[(row * n_units + u) * DH + d], sc, num);
   }
-  o[row * DH + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+  const int tok = (int)(row / Hq), head = (int)(row - (int64_t)tok * Hq);
+  const int64_t at = mt > 0 ? frag_offset(tok, head * DH + d, mt) : row * DH + d;
+  o[at] = f32_to_bf16(den > 0.f ? num / den : 0.f);
 }
 
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
@@ -607,7 +649,7 @@ bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
   return mfma_supported(c) && g.Q > 0 && f.page_tokens % 8 == 0 && c->map.attn_rows > 0;
 }
 
-hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv) {
+hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out) {
   const dllm_config& f = c->cfg;
   const int G = f.n_q_heads / f.n_kv_heads;
   const int R = g.Q * G;
@@ -645,8 +687,8 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rows = g.T * f.n_q_heads;
-  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t));
-  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t));
+  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t), f.n_q_heads, frag_out ? (g.T + 15) / 16 : 0);
+  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t), f.n_q_heads, frag_out ? (g.T + 15) / 16 : 0);
   return hipGetLastError();
 }
 
