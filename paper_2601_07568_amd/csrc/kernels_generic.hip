@@ -111,6 +111,52 @@ __global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* ou
   }
 }
 
+// RMSNorm of one row per workgroup into fragment order: each thread owns whole 16-byte units (8
+// consecutive channels), two float4 loads in, one 16-byte store out.  d % 8 == 0.
+__global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, const float* x, const bf16_t* gain,
+                                                      bf16_t* out, const int32_t* rows, const int32_t* n_rows_dev,
+                                                      int frag_mt) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  int src = r;
+  if (rows) {
+    if (r >= *n_rows_dev) return;
+    src = rows[r];
+  }
+  const float4* xr = (const float4*)(x + (int64_t)src * d);
+  const int n_units = d >> 3;
+  float4 v[4][2];          // up to 4 units per thread (d <= 16384)
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int u = threadIdx.x + q * 512;
+    if (u < n_units) {
+      v[q][0] = xr[2 * u];
+      v[q][1] = xr[2 * u + 1];
+      ss += v[q][0].x * v[q][0].x + v[q][0].y * v[q][0].y + v[q][0].z * v[q][0].z + v[q][0].w * v[q][0].w +
+            v[q][1].x * v[q][1].x + v[q][1].y * v[q][1].y + v[q][1].z * v[q][1].z + v[q][1].w * v[q][1].w;
+    }
+  }
+  ss = block_sum(ss, red);
+  const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int u = threadIdx.x + q * 512;
+    if (u < n_units) {
+      const uint4 gv = *(const uint4*)(gain + 8 * u);
+      const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+      const float xv[8] = {v[q][0].x, v[q][0].y, v[q][0].z, v[q][0].w, v[q][1].x, v[q][1].y, v[q][1].z, v[q][1].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float g0 = bf16_to_f32((bf16_t)(gw[e] & 0xffffu)), g1 = bf16_to_f32((bf16_t)(gw[e] >> 16));
+        o[e] = (uint32_t)f32_to_bf16(xv[2 * e] * rinv * g0) | ((uint32_t)f32_to_bf16(xv[2 * e + 1] * rinv * g1) << 16);
+      }
+      *(uint4*)(out + frag_offset(r, 8 * u, frag_mt)) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // C[M,N] = A[M,K] * W[N,K]^T, 64x64 tile, 16-deep slices through LDS, 4x4 per thread
 template <typename T, int EPI>
@@ -535,7 +581,10 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
                           const int32_t* n_rows_dev, int frag_mt) {
   const dllm_config& f = c->cfg;
-  if (IS_BF16(c))
+  if (IS_BF16(c) && frag_mt > 0 && f.d_model <= 16384)
+    k_rmsnorm_frag<<<T, 512, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t),
+                                     rows, n_rows_dev, frag_mt);
+  else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
                                         WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt);
   else

@@ -57,38 +57,41 @@ struct SkArgs {
 };
 
 constexpr int SK_KB = 128;  // k-elements per block: 4 matrix instructions deep
+constexpr int SK_NW = 8;    // waves of a workgroup (they split K among themselves)
 
-template <int NT, int MT>
+// One pipeline stage: JB matrix-instruction steps (JB*32 k-elements) of NT weight tiles and MT
+// activation tiles.
+template <int NT, int MT, int JB>
 struct SkFrag {
-  u32x4 a[NT][4];
-  u32x4 b[MT][4];
+  u32x4 a[NT][JB];
+  u32x4 b[MT][JB];
 };
 
-// Weights: lane (c, g) reads 16 bytes of row c at element kb + j*32 + g*8 (64 contiguous bytes per
-// row and instruction).  Activations are stored in fragment order (frag_offset), so the operand
-// of (block, j, m-tile) is one contiguous KiB for the wave: xf points at the lane's 16 bytes of
-// fragment 0.
-template <int NT, int MT, bool TAIL>
-__device__ inline void sk_load(SkFrag<NT, MT>& f, const u32x4* const (&wt)[NT], const u32x4* xf, int blk, int g,
+// Both operands are in fragment order: step u (32 k-elements) of weight tile t is the KiB at
+// wt[t] + u*64 units, of activation tile m the KiB at xf + (u*MT + m)*64 units (lane offset folded
+// into the pointers), so every load instruction of the wave is contiguous.
+template <int NT, int MT, int JB, bool TAIL>
+__device__ inline void sk_load(SkFrag<NT, MT, JB>& f, const u32x4* const (&wt)[NT], const u32x4* xf, int stage, int g,
                                int K) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < JB; ++j) {
+    const int u = stage * JB + j;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) f.a[t][j] = wt[t][(blk * 4 + j) * 64];   // packed weights are zero beyond K
+    for (int t = 0; t < NT; ++t) f.a[t][j] = wt[t][u * 64];   // packed weights are zero beyond K
     // the activation buffer is not: beyond K it holds whatever was there, and 0 * NaN is NaN
-    const bool ok = !TAIL || (blk * SK_KB + j * 32 + g * 8 + 8 <= K);
+    const bool ok = !TAIL || (u * 32 + g * 8 + 8 <= K);
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-      if (ok) f.b[t][j] = xf[((blk * 4 + j) * MT + t) * 64];
+      if (ok) f.b[t][j] = xf[(u * MT + t) * 64];
       else f.b[t][j] = u32x4{0, 0, 0, 0};
     }
   }
 }
 
-template <int NT, int MT>
-__device__ inline void sk_mma(const SkFrag<NT, MT>& f, f32x4 (&acc)[NT][MT]) {
+template <int NT, int MT, int JB>
+__device__ inline void sk_mma(const SkFrag<NT, MT, JB>& f, f32x4 (&acc)[NT][MT]) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int j = 0; j < JB; ++j)
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -125,8 +128,11 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
   }
 }
 
+// (second launch bound: at least 4 waves per SIMD, i.e. two 8-wave workgroups per CU, so that one
+// workgroup's prologue and reduction overlap the other's streaming)
 template <int NT, int MT, int NW, int EPI>
-__global__ __launch_bounds__(NW * 64) void k_skinny(const SkArgs a) {
+__global__ __launch_bounds__(NW * 64, (NT + MT <= 4 && NW == 8) ? 4 : 1) void k_skinny(const SkArgs a) {
+  constexpr int JB = 2;   // stage depth chosen so that three buffers stay within 128 registers
   __shared__ float red[NW][NT][MT][4][64];
   __shared__ float lmst[EPI == SK_LMSTATS ? MT : 1][4][16][4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -159,35 +165,42 @@ __global__ __launch_bounds__(NW * 64) void k_skinny(const SkArgs a) {
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Software pipeline over this wave's k-blocks (w, w+NW, ...): the next block is always in flight
-  // while the current one is multiplied.  No load sits inside a branch of the steady-state loop (a
-  // branch around a load makes the compiler wait for every outstanding load at the join).
-  const int n_full = K / SK_KB;                       // blocks that need no tail guard
+  // Software pipeline over this wave's stages (w, w+NW, ...): two stages are in flight while a third
+  // is multiplied.  No load sits inside a branch of the steady-state loop (a branch around a load
+  // makes the compiler wait for every outstanding load at the join); the drain is straight-line code.
+  constexpr int SKB = JB * 32;                        // k-elements per stage
+  const int n_full = K / SKB;                         // stages that need no tail guard
   const int ws = __builtin_amdgcn_readfirstlane(w);   // wave index as a scalar
   const int n_w = n_full > ws ? (n_full - ws + NW - 1) / NW : 0;
-  if (n_w > 0) {
-    SkFrag<NT, MT> f0, f1;
-    sk_load<NT, MT, false>(f0, wt, xf, ws, g, K);
+#define SK_LD(F, I) sk_load<NT, MT, JB, false>(F, wt, xf, ws + (I) * NW, g, K)
+#define SK_MM(F) sk_mma<NT, MT, JB>(F, acc)
+  if (n_w == 1) {
+    SkFrag<NT, MT, JB> f0;
+    SK_LD(f0, 0);
+    SK_MM(f0);
+  } else if (n_w > 1) {
+    SkFrag<NT, MT, JB> f0, f1, f2;
+    SK_LD(f0, 0);
+    SK_LD(f1, 1);
     int i = 0;
-    while (i + 2 < n_w) {
-      sk_load<NT, MT, false>(f1, wt, xf, ws + (i + 1) * NW, g, K);
-      sk_mma<NT, MT>(f0, acc);
-      sk_load<NT, MT, false>(f0, wt, xf, ws + (i + 2) * NW, g, K);
-      sk_mma<NT, MT>(f1, acc);
-      i += 2;
+    while (i + 4 < n_w) {          // stages i .. i+4 exist
+      SK_LD(f2, i + 2); SK_MM(f0);
+      SK_LD(f0, i + 3); SK_MM(f1);
+      SK_LD(f1, i + 4); SK_MM(f2);
+      i += 3;
     }
-    if (n_w - i == 2) {
-      sk_load<NT, MT, false>(f1, wt, xf, ws + (i + 1) * NW, g, K);
-      sk_mma<NT, MT>(f0, acc);
-      sk_mma<NT, MT>(f1, acc);
-    } else {
-      sk_mma<NT, MT>(f0, acc);
+    switch (n_w - i) {             // 2, 3 or 4 stages left; f0 = stage i, f1 = stage i+1 in flight
+      case 2: SK_MM(f0); SK_MM(f1); break;
+      case 3: SK_LD(f2, i + 2); SK_MM(f0); SK_MM(f1); SK_MM(f2); break;
+      default: SK_LD(f2, i + 2); SK_MM(f0); SK_LD(f0, i + 3); SK_MM(f1); SK_MM(f2); SK_MM(f0); break;
     }
   }
-  if (n_full * SK_KB < K && ws == n_full % NW) {      // ragged last block
-    SkFrag<NT, MT> ft;
-    sk_load<NT, MT, true>(ft, wt, xf, n_full, g, K);
-    sk_mma<NT, MT>(ft, acc);
+#undef SK_LD
+#undef SK_MM
+  if (n_full * SKB < K && ws == n_full % NW) {        // ragged last stage
+    SkFrag<NT, MT, JB> ft;
+    sk_load<NT, MT, JB, true>(ft, wt, xf, n_full, g, K);
+    sk_mma<NT, MT, JB>(ft, acc);
   }
 
   // sum the waves' partial tiles in wave order
@@ -364,7 +377,7 @@ hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void
   a.W0 = (const bf16_t*)W;   // packed
   a.N0 = N;
   a.out_f32 = x;
-  return sk_launch_mt<1, 8, SK_RESID>(s, a, (N + 15) / 16);
+  return sk_launch_mt<1, SK_NW, SK_RESID>(s, a, (N + 15) / 16);
 }
 
 // out[M,N] = A[M,K] * W[N,K]^T in float (debug logits)
@@ -395,7 +408,7 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
   a.pool_k = (bf16_t*)pool.k; a.pool_v = (bf16_t*)pool.v; a.pool = pool;
   a.status = WSM(c, status, int32_t);
   const int n_v_wg = (a.N2 + 31) / 32;
-  return sk_launch_mt<2, 8, SK_QKV>(s, a, a.n_q_wg + a.n_k_wg + n_v_wg);
+  return sk_launch_mt<2, SK_NW, SK_QKV>(s, a, a.n_q_wg + a.n_k_wg + n_v_wg);
 }
 
 // h[M,F] = silu(xn Wg^T) * (xn Wu^T), written in fragment order for the down projection
@@ -407,7 +420,7 @@ hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M) {
   a.W0 = (const bf16_t*)P.w_gate; a.W1 = (const bf16_t*)P.w_up;
   a.N0 = f.d_ff;
   a.out_bf16 = WSM(c, h, bf16_t);
-  return sk_launch_mt<2, 8, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
+  return sk_launch_mt<2, SK_NW, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
 }
 
 // LM head on the compacted rows (ws.xn) -> per-64-column softmax statistics
@@ -658,18 +671,18 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   const int n_rg_wg = n_rg < 8 ? n_rg : 8;
   const int n_chunks = (n_rg + n_rg_wg - 1) / n_rg_wg;
   const int nkb = (g.max_kv + 31) / 32;
-  // units along the keys: enough waves to cover the chip, at least four key blocks each, and
-  // within the partial buffer
-  int64_t want = 1024 / ((int64_t)g.B * f.n_kv_heads * n_rg);
+  // units along the keys: short dependent chains matter more than partial traffic here (a step's
+  // attention is a few MB), so give every unit about two 32-key blocks, within the partial buffer
+  int64_t want = 2048 / ((int64_t)g.B * f.n_kv_heads * n_rg);
   if (want < 1) want = 1;
-  int64_t by_work = nkb / 4 > 0 ? nkb / 4 : 1;
+  int64_t by_work = (nkb + 1) / 2;
   int64_t by_space = c->map.attn_rows / ((int64_t)g.T * f.n_q_heads);
   int64_t units = want < by_work ? want : by_work;
   if (units > by_space) units = by_space;
   if (units > ATTN_MAX_SPLITS) units = ATTN_MAX_SPLITS;
   if (units < 1) return hipErrorInvalidValue;
-  int kspl = 8 / n_rg_wg;                                  // waves of a workgroup along the keys
-  while (kspl > 1 && units % kspl != 0) --kspl;
+  // waves of a workgroup along the keys: only when there are many row groups to share K/V through L1
+  const int kspl = 1;
   AttnArgs a;
   a.q = WSM(c, q, bf16_t);
   a.prefix_len = g.prefix_len;
