@@ -260,6 +260,14 @@ struct ProfScope {
   ~ProfScope() { if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * slot + 1], s); }
 };
 
+// plain GEMM of the non-skinny path: matrix cores for bfloat16 (any M), scalar FMA otherwise
+static hipError_t gemm_any(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K,
+                           Epi epi) {
+  if (c->cfg.dtype == DLLM_BF16 && c->kernel_mode == 0 && N % 4 == 0 && K % 8 == 0)
+    return launch_gemm_mfma(s, A, W, C, M, N, K, epi);
+  return launch_gemm_generic(c, s, A, W, C, M, N, K, epi);
+}
+
 struct HeadOut {
   int32_t* cand;
   float* conf;
@@ -286,9 +294,9 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
     } else {
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
+      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
+      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
       TRY(launch_rope_kv(c, s, g, l), "rope_kv");
     }
     {
@@ -299,7 +307,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     if (sk) {
       ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
       TRY(launch_sk_resid(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, x, float), T, f.d_model, dq), "wo");
-    } else TRY(launch_gemm_generic(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    } else TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
     TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "rmsnorm");
     if (sk) {
       {
@@ -309,17 +317,17 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       ProfScope p(c, s, 3, 2.0 * f.d_ff * f.d_model);
       TRY(launch_sk_resid(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
     } else {
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
+      TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
+      TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
       TRY(launch_swiglu(c, s, T), "swiglu");
-      TRY(launch_gemm_generic(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
+      TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
     }
   }
   if (hidden_out) TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
   if (logits_out) {
     TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "final_norm");
     if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->packed_lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
-    else TRY(launch_gemm_generic(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
+    else TRY(gemm_any(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;

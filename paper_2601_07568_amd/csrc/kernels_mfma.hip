@@ -451,7 +451,10 @@ hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_pa
 // k_attn_combine merges them.
 struct AttnArgs {
   const bf16_t* q;          // [T, Hq, DH] rotated
-  const int32_t* prefix_len;
+  const int32_t* prefix_len;  // denoise step: keys = prefix_len[b] + Q
+  const int32_t* cu;          // no-cache forward (Q == 0): sequence b is rows cu[b] .. cu[b+1], keys = its length
+  bf16_t* o;                // output when n_units == 1 (row-major, or fragment order if out_mt > 0)
+  int out_mt;
   KVView kv;
   int Q, Hq, Hkv, B;
   int n_units;              // key-splitting units per row group (gridDim.x * waves along keys)
@@ -473,14 +476,19 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
   const int unit = blockIdx.x * a.kspl + (w / a.n_rg_wg);
   const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
   const int G = a.Hq / a.Hkv;
-  const int R = a.Q * G;
+  const bool paged = a.Q > 0;
+  const int row_base = paged ? b * a.Q : a.cu[b];               // first row of the sequence in q / o
+  const int n_q = paged ? a.Q : a.cu[b + 1] - a.cu[b];          // its query rows
+  const int R = n_q * G;
   if (rg * 16 * QT >= R) return;
-  const int kv_len = a.prefix_len[b] + a.Q;
+  const int kv_len = paged ? a.prefix_len[b] + a.Q : n_q;
   const KVView& kv = a.kv;
-  const int pt = kv.page_tokens;
+  const int pt = paged ? kv.page_tokens : 1;
   const bf16_t* kslab = (const bf16_t*)kv.k;
   const bf16_t* vslab = (const bf16_t*)kv.v;
-  const int32_t* table = kv.table + (int64_t)b * kv.max_pages;
+  const int32_t* table = paged ? kv.table + (int64_t)b * kv.max_pages : nullptr;
+  // packed scratch: K [Hkv][tpad][DH], V [Hkv][DH][tpad], the sequence starts at column cu_pad[b]
+  const int64_t pcol = paged ? 0 : kv.cu_pad[b];
 
   // query fragments: B operand, column c = row of this wave's tile
   u32x4 qf[QT][KK];
@@ -490,8 +498,8 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
     int r = rg * 16 * QT + t * 16 + c;
     const bool ok = r < R;
     if (!ok) r = 0;
-    const int hg = r / a.Q, j = r - hg * a.Q;
-    const int64_t ro = (int64_t)(b * a.Q + j) * a.Hq + kvh * G + hg;
+    const int hg = r / n_q, j = r - hg * n_q;
+    const int64_t ro = (int64_t)(row_base + j) * a.Hq + kvh * G + hg;
     row_out[t] = ok ? ro : -1;
     const bf16_t* qp = a.q + ro * DH + g * 8;
 #pragma unroll
@@ -517,10 +525,15 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
     for (int tt = 0; tt < 2; ++tt) {
       int key = k0 + 8 * (c >> 2) + (c & 3) + 4 * tt;
       if (key >= kv_len) key = kv_len - 1;                     // masked below; keeps the load in bounds
-      const int pi = key / pt;
-      int page = pi < kv.max_pages ? table[pi] : -1;
-      if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
-      const bf16_t* kp = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + g * 8;
+      const bf16_t* kp;
+      if (paged) {
+        const int pi = key / pt;
+        int page = pi < kv.max_pages ? table[pi] : -1;
+        if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
+        kp = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + g * 8;
+      } else {
+        kp = kslab + ((int64_t)kvh * kv.tpad + pcol + key) * DH + g * 8;
+      }
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) kf[tt][kk] = *(const u32x4*)(kp + kk * 32);
     }
@@ -529,13 +542,21 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
     {
       int key = k0 + 8 * g;
       if (key >= kv_len) key = (kv_len - 1) & ~7;
-      const int pi = key / pt;
-      int page = pi < kv.max_pages ? table[pi] : -1;
       bool pbad = false;
-      if (page < 0 || page >= kv.n_pages) { page = 0; pbad = true; }
-      const bf16_t* vp = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + c) * pt + (key - pi * pt);
+      const bf16_t* vp;
+      int64_t vstep;                                           // elements between channels d*16 and (d+1)*16
+      if (paged) {
+        const int pi = key / pt;
+        int page = pi < kv.max_pages ? table[pi] : -1;
+        if (page < 0 || page >= kv.n_pages) { page = 0; pbad = true; }
+        vp = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + c) * pt + (key - pi * pt);
+        vstep = (int64_t)16 * pt;
+      } else {
+        vp = vslab + ((int64_t)kvh * DH + c) * kv.tpad + pcol + key;
+        vstep = (int64_t)16 * kv.tpad;
+      }
 #pragma unroll
-      for (int d = 0; d < DT; ++d) vf[d] = *(const u32x4*)(vp + (int64_t)d * 16 * pt);
+      for (int d = 0; d < DT; ++d) vf[d] = *(const u32x4*)(vp + d * vstep);
       if (pbad || k0 + 32 > kv_len) {
         // zero what lies beyond the sequence (or in a page that is not addressable): the slots may
         // hold anything, and 0 * NaN would poison the row
@@ -626,6 +647,21 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
     if (row_out[t] < 0) continue;
+    if (a.n_units == 1) {
+      // the only unit of its rows: normalise and store the output itself
+      const float inv = l > 0.f ? 1.0f / l : 0.f;
+      const int64_t ro = row_out[t];
+      const int tok = (int)(ro / a.Hq), head = (int)(ro - (int64_t)tok * a.Hq);
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        const int ch = d * 16 + 4 * g;
+        const int64_t at = a.out_mt > 0 ? frag_offset(tok, head * DH + ch, a.out_mt) : ro * DH + ch;
+        *(uint2*)(a.o + at) = make_uint2(
+            (uint32_t)f32_to_bf16(oacc[d][t][0] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][1] * inv) << 16),
+            (uint32_t)f32_to_bf16(oacc[d][t][2] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][3] * inv) << 16));
+      }
+      continue;
+    }
     const int64_t slot = row_out[t] * a.n_units + unit;
     float* po = a.part_o + slot * DH + 4 * g;
 #pragma unroll
@@ -659,13 +695,16 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const float* part_o, const 
 
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
   const dllm_config& f = c->cfg;
-  return mfma_supported(c) && g.Q > 0 && f.page_tokens % 8 == 0 && c->map.attn_rows > 0;
+  if (!(f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->map.attn_rows > 0)) return false;
+  return g.Q > 0 ? f.page_tokens % 8 == 0 : true;
 }
 
+// Attention of a denoise step (paged pool) or of a no-cache forward (packed scratch).
 hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out) {
   const dllm_config& f = c->cfg;
   const int G = f.n_q_heads / f.n_kv_heads;
-  const int R = g.Q * G;
+  const int max_q = g.Q > 0 ? g.Q : g.max_kv;                 // most query rows of a sequence
+  const int R = max_q * G;
   constexpr int QT = 2;
   const int n_rg = (R + 16 * QT - 1) / (16 * QT);
   const int n_rg_wg = n_rg < 8 ? n_rg : 8;
@@ -680,12 +719,14 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   int64_t units = want < by_work ? want : by_work;
   if (units > by_space) units = by_space;
   if (units > ATTN_MAX_SPLITS) units = ATTN_MAX_SPLITS;
-  if (units < 1) return hipErrorInvalidValue;
-  // waves of a workgroup along the keys: only when there are many row groups to share K/V through L1
+  if (units < 1) units = 1;                                   // a single unit needs no partial buffer
   const int kspl = 1;
   AttnArgs a;
   a.q = WSM(c, q, bf16_t);
   a.prefix_len = g.prefix_len;
+  a.cu = g.cu_seqlens;
+  a.o = WSM(c, o, bf16_t);
+  a.out_mt = frag_out ? (g.T + 15) / 16 : 0;
   a.kv = kv;
   a.Q = g.Q; a.Hq = f.n_q_heads; a.Hkv = f.n_kv_heads; a.B = g.B;
   a.n_units = (int)units; a.kspl = kspl; a.n_rg_wg = n_rg_wg;
@@ -698,10 +739,145 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
   else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || units == 1) return e;
   const int rows = g.T * f.n_q_heads;
-  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t), f.n_q_heads, frag_out ? (g.T + 15) / 16 : 0);
-  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, WSM(c, o, bf16_t), f.n_q_heads, frag_out ? (g.T + 15) / 16 : 0);
+  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt);
+  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt);
+  return hipGetLastError();
+}
+
+}  // namespace dllm
+
+// ==========================================================================================
+// Large-M bfloat16 GEMM on the matrix cores: C[M,N] = A[M,K] * W[N,K]^T (both K-contiguous).
+// 128x128 tile per workgroup of 4 waves (2x2, 64x64 each), 64-deep K slices staged through LDS in
+// fragment order (every operand read is 64 lanes x 16 contiguous bytes), global loads of the next
+// slice in flight while the current one is multiplied.  The weight tile is the A operand of the
+// instruction so that a lane ends up with 4 consecutive output features of one row (vector stores).
+namespace dllm {
+
+constexpr int LG_BM = 128, LG_BN = 128, LG_BK = 64;
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                   void* Cv, int M, int N, int K, int tiles_m, int tiles_n) {
+  __shared__ u32x4 sa[2][2][8][64];   // [buffer][k-step][16-row tile of the token block][lane]
+  __shared__ u32x4 sw[2][2][8][64];   // same for the weight block
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
+  // contiguous run of tiles (m fastest) and let its L2 keep the weight block they share
+  const int n_tiles = tiles_m * tiles_n;
+  const int per_xcd = (n_tiles + 7) / 8;
+  int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= n_tiles) return;
+  const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+  const int m0 = tm * LG_BM, n0 = tn * LG_BN;
+  const int wm = (w & 1) * 64, wn = (w >> 1) * 64;   // this wave's 64x64 quadrant
+
+  // loader: 4 pieces of A and 4 of W per thread; piece p = tid + 256*q: row p/8, 16-byte column p%8
+  const bf16_t* ga[4];
+  const bf16_t* gw[4];
+  int dst[4], kc8[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
+    kc8[q] = kc * 8;
+    dst[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
+    int ra = m0 + r; ra = ra < M ? ra : M - 1;
+    int rw = n0 + r; rw = rw < N ? rw : N - 1;
+    ga[q] = A + (int64_t)ra * K;
+    gw[q] = W + (int64_t)rw * K;
+  }
+  auto issue = [&](u32x4 (&ra)[4], u32x4 (&rw)[4], int k0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int k = k0 + kc8[q];
+      const bool ok = k + 8 <= K;
+      k = ok ? k : K - 8;
+      const u32x4 va = *(const u32x4*)(ga[q] + k), vw = *(const u32x4*)(gw[q] + k);
+      ra[q] = ok ? va : u32x4{0, 0, 0, 0};
+      rw[q] = ok ? vw : u32x4{0, 0, 0, 0};
+    }
+  };
+  auto commit = [&](const u32x4 (&ra)[4], const u32x4 (&rw)[4], int buf) {
+    u32x4* da = &sa[buf][0][0][0];
+    u32x4* dw = &sw[buf][0][0][0];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { da[dst[q]] = ra[q]; dw[dst[q]] = rw[q]; }
+  };
+
+  f32x4 acc[4][4];   // [weight 16-row tile][token 16-row tile]
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nk = (K + LG_BK - 1) / LG_BK;
+  u32x4 ra[4], rw[4];
+  issue(ra, rw, 0);
+  commit(ra, rw, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    __syncthreads();
+    issue(ra, rw, (kt + 1 < nk ? kt + 1 : kt) * LG_BK);   // unconditional (re-reads the last slice at the end)
+    const int buf = kt & 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      u32x4 fa[4], fw[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        fw[i] = sw[buf][ks][(wn >> 4) + i][lane];
+        fa[i] = sa[buf][ks][(wm >> 4) + i][lane];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(fw[i], fa[j], acc[i][j]);
+    }
+    commit(ra, rw, buf ^ 1);
+  }
+
+  // lane holds token column c of token tile j, features 4g..4g+3 of weight tile i
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int m = m0 + wm + j * 16 + c;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n0 + wn + i * 16 + 4 * g;
+      if (n + 4 <= N) {
+        const int64_t at = (int64_t)m * N + n;
+        if (EPI == EPI_STORE) {
+          *(uint2*)((bf16_t*)Cv + at) =
+              make_uint2((uint32_t)f32_to_bf16(acc[i][j][0]) | ((uint32_t)f32_to_bf16(acc[i][j][1]) << 16),
+                         (uint32_t)f32_to_bf16(acc[i][j][2]) | ((uint32_t)f32_to_bf16(acc[i][j][3]) << 16));
+        } else if (EPI == EPI_STORE_F32) {
+          *(f32x4*)((float*)Cv + at) = acc[i][j];
+        } else {
+          f32x4* p = (f32x4*)((float*)Cv + at);
+          *p = *p + acc[i][j];
+        }
+      } else {
+        for (int e = 0; e < 4; ++e) {
+          if (n + e >= N) break;
+          const int64_t at = (int64_t)m * N + n + e;
+          if (EPI == EPI_STORE) ((bf16_t*)Cv)[at] = f32_to_bf16(acc[i][j][e]);
+          else if (EPI == EPI_STORE_F32) ((float*)Cv)[at] = acc[i][j][e];
+          else ((float*)Cv)[at] += acc[i][j][e];
+        }
+      }
+    }
+  }
+}
+
+// C[M,N] (=, +=) A[M,K] W[N,K]^T for bfloat16 operands; N % 4 == 0 and K % 8 == 0
+hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi) {
+  const int tiles_m = (M + LG_BM - 1) / LG_BM, tiles_n = (N + LG_BN - 1) / LG_BN;
+  const int n_tiles = tiles_m * tiles_n;
+  const int grid = (n_tiles + 7) / 8 * 8;
+  if (epi == EPI_STORE) k_gemm_mfma<EPI_STORE><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
+  else if (epi == EPI_STORE_F32) k_gemm_mfma<EPI_STORE_F32><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
+  else k_gemm_mfma<EPI_RESID><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
