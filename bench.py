@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override depth (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-generation", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (known traffic) so that a rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -124,6 +127,14 @@ def main():
     cu = eng.i32([0, P])
     eng.prefill_kv(prompt, cu, table, None, total_tokens=P, max_seqlen=P)
     torch.cuda.synchronize()
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     fresh = eng.i32(synth.masked_block(ms, 3, Q, n_masked0)[None])
     qt = fresh.clone()
@@ -168,8 +179,16 @@ def main():
     roofline = None
     if dom:
         a = kern[dom]["GBps"]
+        traffic = None
+        # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+        # scaled by a 1 GiB copy); measured offline with the commands that file lists, not in this run
+        pmc = os.path.join(ROOT, "profiles", "denoise_step_c3_hbm_traffic_pmc.txt")
+        if args.workload == "c3" and args.layers is None and os.path.exists(pmc):
+            for line in open(pmc):
+                if line.startswith(f"traffic_bytes_per_launch k_skinny({dom}):"):
+                    traffic = float(line.split(":")[1])
         roofline = {"bound": "hbm", "kernel": f"k_skinny ({dom})", "achieved": a, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": a / HBM_PEAK_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": a / HBM_PEAK_GBS, "traffic": traffic,
                     "avg_us": kern[dom]["avg_us"], "bytes_per_launch": kern[dom]["bytes_per_launch"]}
     d, dq, dkv, F = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff
     step_bytes = ms.n_layers * 2 * (d * (dq + 2 * dkv) + dq * d + 3 * d * F) + 2 * ms.vocab * d \
