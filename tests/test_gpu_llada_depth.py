@@ -1,0 +1,118 @@
+"""LLaDA-8B-shaped model at full width: a 4-layer slice against the oracle (teacher-forced steps of a
+block, refresh, next block), and the full 32-layer model in the launch configuration of bench.py
+checked through properties that hold at any size (the oracle cannot run 32 such layers in a test)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dllm_oracle as O
+from paper_2601_07568_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+W = synth.as_float
+ST = synth.round_bf16
+
+
+def test_four_full_width_layers_two_blocks_against_oracle():
+    ms = synth.LLADA_8B.with_layers(4)
+    P, Q = 192, 32
+    w = synth.Weights(ms, 5)
+    eng = H.make_engine(ms, w, page_tokens=64, max_pages_per_seq=5, n_pages=5, max_batch=1, max_q=Q,
+                        max_tokens=P + 2 * Q)
+    table = H.identity_table(eng, 1)
+    tab = eng.i32(table)
+    prompt = synth.random_tokens(ms, 5, P)
+    eng.prefill_kv(eng.i32(prompt), eng.i32([0, P]), tab, None, total_tokens=P, max_seqlen=P)
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    seq = prompt.copy()
+    for blk_no in range(2):
+        cur = len(seq)
+        ck_exact, cv_exact = O.prefill(w, seq, widen=W)
+        ck, cv = O.prefill(w, seq, widen=W, store=ST)
+        # cache of the last layer after prefill / refresh
+        got = H.gather_cache(eng, table[0], cur, ms.n_layers - 1, 0)
+        assert np.abs(got - ck_exact[-1]).max() <= 2e-2 * np.abs(ck_exact[-1]).max()
+        blk = synth.masked_block(ms, 5 + blk_no, Q, 32 if blk_no == 0 else 11)
+        for step in range(2):                                   # teacher-forced: start from the oracle's state
+            qt = eng.i32(blk[None])
+            r = O.denoise_step(w, blk, ck, cv, 0.9, 2, widen=W, store=ST)
+            exact, _ = O.forward_cached(w, blk, ck_exact, cv_exact, widen=W)
+            eng.denoise_step(qt, eng.i32([cur]), tab, cand, conf, ent, max_prefix_len=cur)
+            logits = eng.debug_logits(qt, eng.i32([cur]), tab, max_prefix_len=cur).cpu().numpy()[0]
+            err = H.rel_err_rows(logits, exact).max()
+            print(f"block {blk_no} step {step}: logit rel err vs exact oracle {err:.3e}, "
+                  f"vs bf16-storage oracle {H.rel_err_rows(logits, r['logits']).max():.3e}")
+            assert err <= H.LOGIT_TOL["bf16"]
+            masked = blk == ms.mask_id
+            H.check_step_outputs(ms, r, masked, cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0],
+                                 "bf16", gpu_logits=logits)
+            nun = torch.zeros(1, 1, dtype=torch.int32, device=eng.device)
+            eng.unmask(qt, cand, conf, 0.9, 2, n_unmasked=nun)
+            assert int(nun) == min(2, int(masked.sum()))        # tau never fires at this vocabulary size
+            if H.selection_is_decided(r["conf"], masked, 0.9, 2):
+                assert np.nonzero(qt.cpu().numpy()[0] != blk)[0].tolist() == r["chosen"]
+            blk = r["tokens"]
+        # finish the block with arbitrary tokens, refresh, go on
+        done = np.where(blk == ms.mask_id, synth.random_tokens(ms, 9 + blk_no, Q), blk)
+        seq = np.concatenate([seq, done])
+        n = len(seq)
+        eng.refresh_cache(eng.i32(seq), eng.i32([0, n]), tab, None, total_tokens=n, max_seqlen=n)
+    assert eng.read_status() == 0
+    eng.close()
+
+
+def test_full_depth_bench_configuration_properties():
+    """32 layers, prompt 1024, block 32, threshold 0.9, floor 2 -- device-drawn weights as in bench.py."""
+    import bench
+    ms = synth.LLADA_8B
+    P, Q, pt = 1024, 32, 64
+    dev = torch.device("cuda:0")
+    mp = (P + 8 * Q + pt - 1) // pt
+    from paper_2601_07568_amd.binding import Engine
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=2 * mp, max_batch=1, max_q=Q,
+                 max_tokens=P + 8 * Q, device_weights=bench.device_weights(ms, torch, dev, 1))
+    prompt = eng.i32(synth.random_tokens(ms, 3, P))
+    blk_np = synth.masked_block(ms, 3, Q, 20)
+    outs = []
+    for perm in (np.arange(2 * mp), np.random.default_rng(1).permutation(2 * mp)):
+        table = eng.i32(perm[:mp][None])
+        eng.prefill_kv(prompt, eng.i32([0, P]), table, None, total_tokens=P, max_seqlen=P)
+        qt = eng.i32(blk_np[None])
+        cand = torch.zeros(1, Q, dtype=torch.int32, device=dev)
+        conf = torch.zeros(1, Q, dtype=torch.float32, device=dev)
+        ent = torch.zeros(1, Q, dtype=torch.float32, device=dev)
+        eng.denoise_step(qt, eng.i32([P]), table, cand, conf, ent, max_prefix_len=P)
+        logits = eng.debug_logits(qt, eng.i32([P]), table, max_prefix_len=P)
+        nun = torch.zeros(1, 1, dtype=torch.int32, device=dev)
+        nrem = torch.zeros(1, 1, dtype=torch.int32, device=dev)
+        eng.unmask(qt, cand, conf, 0.9, 2, n_unmasked=nun, n_remaining=nrem)
+        outs.append((cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0], qt.cpu().numpy()[0],
+                     logits.cpu().numpy()[0], int(nun), int(nrem)))
+    a, b = outs
+    for x, y in zip(a[:5], b[:5]):
+        assert np.array_equal(x, y)                       # physical page order is invisible, runs are bit-stable
+    cand, conf, ent, after, logits, nun, nrem = a
+    masked = blk_np == ms.mask_id
+    assert np.isfinite(logits).all()
+    assert ((conf[masked] > 1.0 / ms.vocab) & (conf[masked] <= 1.0)).all()
+    assert ((ent[masked] > 0) & (ent[masked] <= np.log(ms.vocab))).all()
+    assert ((cand[masked] >= 0) & (cand[masked] < ms.vocab) & (cand[masked] != ms.mask_id)).all()
+    assert (cand[~masked] == blk_np[~masked]).all() and (conf[~masked] == 1).all()
+    # fused statistics == softmax statistics of the materialised logits of the same forward
+    g = logits.astype(np.float64)
+    g[:, ms.mask_id] = -np.inf
+    gm = g.max(-1)
+    gl = gm + np.log(np.exp(g - gm[:, None]).sum(-1))
+    assert np.abs(conf[masked] / np.exp(gm - gl)[masked] - 1).max() <= 2e-3
+    srt = np.sort(g, axis=-1)
+    sure = masked & (srt[:, -1] - srt[:, -2] > 1e-3 * np.abs(srt[:, -1]))
+    assert (cand[sure] == np.argmax(g, -1)[sure]).all()
+    # selection: exactly the floor (threshold cannot fire), the two most confident masked rows
+    assert nun == 2 and nrem == masked.sum() - 2
+    order = sorted(np.nonzero(masked)[0], key=lambda i: (-conf[i], i))[:2]
+    assert sorted(np.nonzero(after != blk_np)[0].tolist()) == sorted(order)
+    assert eng.read_status() == 0
+    eng.close()
