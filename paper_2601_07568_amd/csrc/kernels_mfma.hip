@@ -131,8 +131,8 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
 // (second launch bound: at least 4 waves per SIMD, i.e. two 8-wave workgroups per CU, so that one
 // workgroup's prologue and reduction overlap the other's streaming)
 template <int NT, int MT, int NW, int EPI>
-__global__ __launch_bounds__(NW * 64, (NT + MT <= 4 && NW == 8) ? 4 : 1) void k_skinny(const SkArgs a) {
-  constexpr int JB = 2;   // stage depth chosen so that three buffers stay within 128 registers
+__global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_skinny(const SkArgs a) {
+  constexpr int JB = (NT == 1) ? 4 : 2;   // weight bytes in flight per wave: two stages of NT*JB KiB
   __shared__ float red[NW][NT][MT][4][64];
   __shared__ float lmst[EPI == SK_LMSTATS ? MT : 1][4][16][4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -674,19 +674,39 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
 // merges the units' partials of one (token, head) row and stores the normalised output
 // (fragment order of the [T, Hq*DH] matrix: it is the activation operand of the output projection)
 template <int DH>
-__global__ __launch_bounds__(DH) void k_attn_combine(const float* part_o, const float* part_ml, int n_units,
-                                                     bf16_t* o, int Hq, int mt) {
-  const int64_t row = blockIdx.x;
-  const int d = threadIdx.x;
-  float M = -DEV_INF;
-  for (int u = 0; u < n_units; ++u) M = fmaxf(M, part_ml[(row * n_units + u) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int u = 0; u < n_units; ++u) {
-    const float mu = part_ml[(row * n_units + u) * 2];
-    if (mu == -DEV_INF) continue;                      // unit had no key block
-    const float sc = exp2f(mu - M);
-    den = fmaf(part_ml[(row * n_units + u) * 2 + 1], sc, den);
-    num = fmaf(part_o[(row * n_units + u) * DH + d], sc, num);
+__global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const float* part_ml, int n_units,
+                                                      bf16_t* o, int Hq, int mt, int64_t n_rows) {
+  const int64_t row = (int64_t)blockIdx.x * (512 / DH) + threadIdx.x / DH;
+  if (row >= n_rows) return;
+  const int d = threadIdx.x % DH;
+  // eight units at a time: their loads are independent and issued together, the running
+  // (max, numerator, denominator) is rescaled between chunks
+  float M = -DEV_INF, num = 0.f, den = 0.f;
+  for (int u0 = 0; u0 < n_units; u0 += 8) {
+    float mu[8], lu[8], ou[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool ok = u0 + i < n_units;
+      const int64_t slot = row * n_units + (ok ? u0 + i : n_units - 1);
+      const float2 ml = *(const float2*)(part_ml + slot * 2);
+      mu[i] = ok ? ml.x : -DEV_INF;
+      lu[i] = ml.y;
+      ou[i] = part_o[slot * DH + d];
+    }
+    float Mn = M;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) Mn = fmaxf(Mn, mu[i]);
+    if (Mn == -DEV_INF) continue;                       // nothing but empty units so far
+    const float r = exp2f(M - Mn);                      // exp2(-inf) = 0 on the first chunk
+    num *= r;
+    den *= r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float sc = exp2f(mu[i] - Mn);               // 0 for empty units
+      den = fmaf(lu[i], sc, den);
+      num = fmaf(ou[i], sc, num);
+    }
+    M = Mn;
   }
   const int tok = (int)(row / Hq), head = (int)(row - (int64_t)tok * Hq);
   const int64_t at = mt > 0 ? frag_offset(tok, head * DH + d, mt) : row * DH + d;
@@ -720,6 +740,7 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   if (units > by_space) units = by_space;
   if (units > ATTN_MAX_SPLITS) units = ATTN_MAX_SPLITS;
   if (units < 1) units = 1;                                   // a single unit needs no partial buffer
+  if (const char* e = getenv("DLLM_ATTN_UNITS")) { int v = atoi(e); if (v >= 1 && v <= by_space && v <= ATTN_MAX_SPLITS) units = v; }
   const int kspl = 1;
   AttnArgs a;
   a.q = WSM(c, q, bf16_t);
@@ -741,8 +762,10 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || units == 1) return e;
   const int rows = g.T * f.n_q_heads;
-  if (f.head_dim == 128) k_attn_combine<128><<<rows, 128, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt);
-  else k_attn_combine<64><<<rows, 64, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt);
+  if (f.head_dim == 128)
+    k_attn_combine<128><<<(rows + 3) / 4, 512, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt, rows);
+  else
+    k_attn_combine<64><<<(rows + 7) / 8, 512, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt, rows);
   return hipGetLastError();
 }
 
