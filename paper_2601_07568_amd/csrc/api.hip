@@ -68,6 +68,8 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   if (m->attn_rows < 65536) m->attn_rows = 65536;
   m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
   if (c->dtype != DLLM_BF16) m->attn_rows = 0;
+  m->delta_stride = (int64_t)SK_MAX_ROWS * c->d_model;
+  m->delta = take(c->dtype == DLLM_BF16 ? (size_t)SK_MAX_DELTA * m->delta_stride * 4 : 0);
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
   m->total = off;
@@ -287,9 +289,11 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
   // (their activation operands are kept in fragment order, which only these kernels write)
   const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS && attn_step_supported(c, g);
+  int pending = 0;   // open residual sums (K splits of the last residual projection) not yet added to x
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
-    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "rmsnorm");
+    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
+    pending = 0;
     if (sk) {
       ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
@@ -306,16 +310,19 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     }
     if (sk) {
       ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
-      TRY(launch_sk_resid(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, x, float), T, f.d_model, dq), "wo");
+      TRY(launch_sk_delta(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, delta, float), c->map.delta_stride,
+                          SK_MAX_DELTA, T, f.d_model, dq, &pending), "wo");
     } else TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
-    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "rmsnorm");
+    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
+    pending = 0;
     if (sk) {
       {
         ProfScope p(c, s, 2, 2.0 * 2.0 * f.d_ff * f.d_model);
         TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
       }
       ProfScope p(c, s, 3, 2.0 * f.d_ff * f.d_model);
-      TRY(launch_sk_resid(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, x, float), T, f.d_model, f.d_ff), "w_down");
+      TRY(launch_sk_delta(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, delta, float),
+                          c->map.delta_stride, SK_MAX_DELTA, T, f.d_model, f.d_ff, &pending), "w_down");
     } else {
       TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
       TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
@@ -323,9 +330,13 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
     }
   }
-  if (hidden_out) TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
+  if (hidden_out) {
+    if (pending) { TRY(launch_fold_delta(c, s, T, pending), "fold_delta"); pending = 0; }
+    TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
+  }
   if (logits_out) {
-    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0), "final_norm");
+    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "final_norm");
+    pending = 0;
     if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->packed_lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
     else TRY(gemm_any(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
   }
@@ -333,7 +344,8 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
     TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
     TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1,
-                       sk ? (max_rows + 15) / 16 : 0), "final_norm");
+                       sk ? (max_rows + 15) / 16 : 0, pending), "final_norm");
+    pending = 0;
     int n_parts = c->map.n_vtiles;
     if (sk) {
       ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);

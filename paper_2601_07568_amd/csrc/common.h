@@ -145,6 +145,8 @@ struct Workspace {
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
   size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
   int64_t attn_rows;   // capacity in (token, head, unit) rows
+  size_t delta;        // float [SK_MAX_DELTA][64, d] open residual sums of the skinny path
+  int64_t delta_stride;
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
   int64_t t_max, r_max, t_step, tpad;
@@ -200,8 +202,13 @@ hipError_t launch_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 // out[T or n_rows, d] = rmsnorm(x[row]) * gain; rows == nullptr: identity row map, n = T
 // frag_mt > 0: write in fragment order for frag_mt 16-row tiles (bfloat16 only)
+// n_delta > 0 (fragment path only): first add the open residual sums delta_0 .. to x
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
-                          const int32_t* n_rows_dev, int frag_mt);
+                          const int32_t* n_rows_dev, int frag_mt, int n_delta);
+hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta);
+constexpr int SK_MAX_DELTA = 8;   // most K splits of a residual projection
+hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* delta,
+                           int64_t delta_stride, int max_splits, int M, int N, int K, int* n_splits);
 enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
 // C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,

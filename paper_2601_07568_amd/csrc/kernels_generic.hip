@@ -113,9 +113,12 @@ __global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* ou
 
 // RMSNorm of one row per workgroup into fragment order: each thread owns whole 16-byte units (8
 // consecutive channels), two float4 loads in, one 16-byte store out.  d % 8 == 0.
-__global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, const float* x, const bf16_t* gain,
+// If n_delta > 0 the row first takes up the open residual sums: x += delta_0 + delta_1 + .. (in that
+// order), and the updated row is written back.
+__global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, float* x, const bf16_t* gain,
                                                       bf16_t* out, const int32_t* rows, const int32_t* n_rows_dev,
-                                                      int frag_mt) {
+                                                      int frag_mt, const float* delta, int n_delta,
+                                                      int64_t delta_stride) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   int src = r;
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, const fl
     if (r >= *n_rows_dev) return;
     src = rows[r];
   }
-  const float4* xr = (const float4*)(x + (int64_t)src * d);
+  float4* xr = (float4*)(x + (int64_t)src * d);
   const int n_units = d >> 3;
   float4 v[4][2];          // up to 4 units per thread (d <= 16384)
   float ss = 0.f;
@@ -133,6 +136,16 @@ __global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, const fl
     if (u < n_units) {
       v[q][0] = xr[2 * u];
       v[q][1] = xr[2 * u + 1];
+      if (n_delta > 0) {
+        for (int sd = 0; sd < n_delta; ++sd) {
+          const float4* dr = (const float4*)(delta + sd * delta_stride + (int64_t)src * d);
+          const float4 d0 = dr[2 * u], d1 = dr[2 * u + 1];
+          v[q][0].x += d0.x; v[q][0].y += d0.y; v[q][0].z += d0.z; v[q][0].w += d0.w;
+          v[q][1].x += d1.x; v[q][1].y += d1.y; v[q][1].z += d1.z; v[q][1].w += d1.w;
+        }
+        xr[2 * u] = v[q][0];
+        xr[2 * u + 1] = v[q][1];
+      }
       ss += v[q][0].x * v[q][0].x + v[q][0].y * v[q][0].y + v[q][0].z * v[q][0].z + v[q][0].w * v[q][0].w +
             v[q][1].x * v[q][1].x + v[q][1].y * v[q][1].y + v[q][1].z * v[q][1].z + v[q][1].w * v[q][1].w;
     }
@@ -578,12 +591,28 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
   return hipGetLastError();
 }
 
+// x[T, d] += delta_0 + delta_1 + ..  (open residual sums; used where no RMSNorm follows)
+__global__ void k_fold_delta(int64_t n, float* x, const float* delta, int n_delta, int64_t delta_stride) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = x[i];
+  for (int sd = 0; sd < n_delta; ++sd) v += delta[sd * delta_stride + i];
+  x[i] = v;
+}
+
+hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta) {
+  const int64_t n = (int64_t)T * c->cfg.d_model;
+  k_fold_delta<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(n, WS(c, x, float), WS(c, delta, float), n_delta,
+                                                          c->map.delta_stride);
+  return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
-                          const int32_t* n_rows_dev, int frag_mt) {
+                          const int32_t* n_rows_dev, int frag_mt, int n_delta) {
   const dllm_config& f = c->cfg;
   if (IS_BF16(c) && frag_mt > 0 && f.d_model <= 16384)
     k_rmsnorm_frag<<<T, 512, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t),
-                                     rows, n_rows_dev, frag_mt);
+                                     rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta, c->map.delta_stride);
   else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
                                         WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt);

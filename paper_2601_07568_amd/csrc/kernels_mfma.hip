@@ -28,7 +28,7 @@ __device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
                                                  0, 0);
 }
 
-enum SkEpi { SK_RESID = 0, SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4 };
+enum SkEpi { SK_RESID = 0, SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4, SK_DELTA = 5 };
 
 struct SkArgs {
   const bf16_t* X;          // activations [M, K]
@@ -50,6 +50,10 @@ struct SkArgs {
   bf16_t* pool_v;
   KVView pool;
   int32_t* status;
+  // DELTA: grid.y splits K; split y stores its partial product to out_f32 + y * delta_stride, [M, N0];
+  // the consumer of the residual stream adds the splits up in order
+  int sps;                  // stages per split (0: no split)
+  int64_t delta_stride;
   // LMSTATS
   float* part;              // [rows, n_parts, 4]
   int n_parts;
@@ -171,8 +175,11 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
   constexpr int SKB = JB * 32;                        // k-elements per stage
   const int n_full = K / SKB;                         // stages that need no tail guard
   const int ws = __builtin_amdgcn_readfirstlane(w);   // wave index as a scalar
-  const int n_w = n_full > ws ? (n_full - ws + NW - 1) / NW : 0;
-#define SK_LD(F, I) sk_load<NT, MT, JB, false>(F, wt, xf, ws + (I) * NW, g, K)
+  const int s_lo = a.sps > 0 ? (int)blockIdx.y * a.sps : 0;          // this workgroup's range of stages
+  const int s_hi = a.sps > 0 ? (s_lo + a.sps < n_full ? s_lo + a.sps : n_full) : n_full;
+  const int n_loc = s_hi > s_lo ? s_hi - s_lo : 0;
+  const int n_w = n_loc > ws ? (n_loc - ws + NW - 1) / NW : 0;
+#define SK_LD(F, I) sk_load<NT, MT, JB, false>(F, wt, xf, s_lo + ws + (I) * NW, g, K)
 #define SK_MM(F) sk_mma<NT, MT, JB>(F, acc)
   if (n_w == 1) {
     SkFrag<NT, MT, JB> f0;
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
   }
 #undef SK_LD
 #undef SK_MM
-  if (n_full * SKB < K && ws == n_full % NW) {        // ragged last stage
+  if (n_full * SKB < K && blockIdx.y == gridDim.y - 1 && ws == n_loc % NW) {   // ragged last stage
     SkFrag<NT, MT, JB> ft;
     sk_load<NT, MT, JB, true>(ft, wt, xf, n_full, g, K);
     sk_mma<NT, MT, JB>(ft, acc);
@@ -225,13 +232,15 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
       val[t] = s;
     }
     const bool tok_ok = tok < M;
-    if (EPI == SK_RESID || EPI == SK_F32) {
+    if (EPI == SK_RESID || EPI == SK_F32 || EPI == SK_DELTA) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = row0[t] + fr;
         if (tok_ok && n < a.N0) {
           float* p = a.out_f32 + (int64_t)tok * a.N0 + n;
-          if (EPI == SK_RESID) *p += val[t]; else *p = val[t];
+          if (EPI == SK_DELTA) p[(int64_t)blockIdx.y * a.delta_stride] = val[t];
+          else if (EPI == SK_RESID) *p += val[t];
+          else *p = val[t];
         }
       }
     } else if (EPI == SK_SWIGLU) {
@@ -358,7 +367,7 @@ hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int 
 
 bool mfma_supported(const dllm_ctx* c) {
   const dllm_config& f = c->cfg;
-  return f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->packed != nullptr && f.d_model % 8 == 0 && f.d_ff % 8 == 0 &&
+  return f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->packed != nullptr && f.d_model <= 16384 && f.d_model % 8 == 0 && f.d_ff % 8 == 0 &&
          (f.head_dim == 64 || f.head_dim == 128);
 }
 
@@ -378,6 +387,42 @@ hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void
   a.N0 = N;
   a.out_f32 = x;
   return sk_launch_mt<1, SK_NW, SK_RESID>(s, a, (N + 15) / 16);
+}
+
+// Residual projection with the sum over K left open: split y of K writes A*W^T restricted to its
+// K range into delta + y*delta_stride ([M, N] float); the next RMSNorm adds x + delta_0 + delta_1 ..
+// in that order.  With K split across workgroups a workgroup can own 64 weight rows instead of 16
+// (the activation operand is re-read a quarter as often) and small N still fills the chip.
+// Returns the number of splits through n_splits.
+hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* delta,
+                           int64_t delta_stride, int max_splits, int M, int N, int K, int* n_splits) {
+  SkArgs a = sk_base(A, M, K);
+  a.W0 = (const bf16_t*)W;   // packed
+  a.N0 = N;
+  a.out_f32 = delta;
+  a.delta_stride = delta_stride;
+  const int groups = (N + 63) / 64;
+  const int n_full = K / 64;                       // stages of JB = 2 steps
+  int ks = (256 + groups - 1) / groups;
+  if (ks > max_splits) ks = max_splits;
+  if (ks > n_full / (2 * SK_NW)) ks = n_full / (2 * SK_NW);   // at least two stages per wave
+  if (ks < 1) ks = 1;
+  int sps = (n_full + ks - 1) / ks;
+  sps = (sps + SK_NW - 1) / SK_NW * SK_NW;         // every wave the same number of stages
+  if (sps < SK_NW) sps = SK_NW;
+  ks = n_full > 0 ? (n_full + sps - 1) / sps : 1;
+  a.sps = sps;
+  *n_splits = ks;
+  const int mt = (M + 15) / 16;
+  dim3 grid(groups, ks);
+  switch (mt) {
+    case 1: k_skinny<4, 1, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
+    case 2: k_skinny<4, 2, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
+    case 3: k_skinny<4, 3, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
+    case 4: k_skinny<4, 4, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 // out[M,N] = A[M,K] * W[N,K]^T in float (debug logits)
