@@ -289,6 +289,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
   // (their activation operands are kept in fragment order, which only these kernels write)
   const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS && attn_step_supported(c, g);
+  const bool big_mfma = f.dtype == DLLM_BF16 && c->kernel_mode == 0 && f.d_ff % 4 == 0 && f.vocab % 4 == 0;
   int pending = 0;   // open residual sums (K splits of the last residual projection) not yet added to x
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
@@ -324,9 +325,13 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       TRY(launch_sk_delta(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, delta, float),
                           c->map.delta_stride, SK_MAX_DELTA, T, f.d_model, f.d_ff, &pending), "w_down");
     } else {
-      TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
-      TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
-      TRY(launch_swiglu(c, s, T), "swiglu");
+      if (big_mfma) {
+        TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model), "gate_up");
+      } else {
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
+        TRY(launch_swiglu(c, s, T), "swiglu");
+      }
       TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
     }
   }
@@ -350,6 +355,8 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     if (sk) {
       ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);
       TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
+    } else if (big_mfma) {
+      TRY(launch_gemm_lmstats(c, s, max_rows, &n_parts), "lm_head");
     } else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
     TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy), "lm_merge");
   }

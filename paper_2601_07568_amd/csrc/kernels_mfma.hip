@@ -818,135 +818,263 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
 
 // ==========================================================================================
 // Large-M bfloat16 GEMM on the matrix cores: C[M,N] = A[M,K] * W[N,K]^T (both K-contiguous).
-// 128x128 tile per workgroup of 4 waves (2x2, 64x64 each), 64-deep K slices staged through LDS in
-// fragment order (every operand read is 64 lanes x 16 contiguous bytes), global loads of the next
-// slice in flight while the current one is multiplied.  The weight tile is the A operand of the
-// instruction so that a lane ends up with 4 consecutive output features of one row (vector stores).
+// A workgroup of 4 waves computes a BM x 128 tile (BM = 256 or 128 token rows; waves 2x2, each
+// BM/2 x 64), 64-deep K slices are staged through LDS in fragment order (every operand read is 64
+// lanes x 16 contiguous bytes, no bank conflicts), double-buffered in LDS and double-buffered in
+// registers on the way there, so two slices are in flight from memory while a third is multiplied.
+// The weight tile is the A operand of the instruction: a lane ends up with 4 consecutive output
+// features of one token row (vector stores).  Epilogues: store, residual add, SiLU(gate)*up over two
+// weight matrices, and the softmax statistics of the LM head per 64 columns.
 namespace dllm {
 
-constexpr int LG_BM = 128, LG_BN = 128, LG_BK = 64;
+constexpr int LG_BN = 128, LG_BK = 64;
+enum LgEpi { LG_STORE = 0, LG_STORE_F32 = 1, LG_RESID = 2, LG_SWIGLU = 3, LG_LMSTATS = 4 };
 
-template <int EPI>
-__global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                   void* Cv, int M, int N, int K, int tiles_m, int tiles_n) {
-  __shared__ u32x4 sa[2][2][8][64];   // [buffer][k-step][16-row tile of the token block][lane]
-  __shared__ u32x4 sw[2][2][8][64];   // same for the weight block
+struct LgArgs {
+  const bf16_t* A;
+  const bf16_t* W;
+  const bf16_t* W2;        // SWIGLU: up projection
+  void* C;
+  const int32_t* m_dev;    // optional device row count
+  int M, N, K, tiles_m, tiles_n;
+  float* part;             // LMSTATS: [rows, n_parts, 4]
+  int n_parts;
+  int32_t mask_id;
+};
+
+template <int BM, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
+  constexpr int TM = BM / 16;                 // 16-row token tiles of the block
+  constexpr int WT = BM / 32;                 // token tiles per wave
+  constexpr int NW2 = (EPI == LG_SWIGLU) ? 2 : 1;
+  constexpr int PA = BM / 32;                 // 16-byte pieces of A per thread and slice (BM*8/256)
+  __shared__ u32x4 sa[2][2][TM][64];          // [buffer][k-step][token tile][lane]
+  __shared__ u32x4 sw[2][NW2][2][8][64];      // [buffer][matrix][k-step][weight tile][lane]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
+  int M = a.M;
+  if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
+  const int N = a.N, K = a.K;
   // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
   // contiguous run of tiles (m fastest) and let its L2 keep the weight block they share
-  const int n_tiles = tiles_m * tiles_n;
+  const int n_tiles = a.tiles_m * a.tiles_n;
   const int per_xcd = (n_tiles + 7) / 8;
-  int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile >= n_tiles) return;
-  const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
-  const int m0 = tm * LG_BM, n0 = tn * LG_BN;
-  const int wm = (w & 1) * 64, wn = (w >> 1) * 64;   // this wave's 64x64 quadrant
+  const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
+  const int m0 = tm * BM, n0 = tn * LG_BN;
+  if (m0 >= M) return;
+  const int wm = (w & 1) * (BM / 2), wn = (w >> 1) * 64;
 
-  // loader: 4 pieces of A and 4 of W per thread; piece p = tid + 256*q: row p/8, 16-byte column p%8
-  const bf16_t* ga[4];
-  const bf16_t* gw[4];
-  int dst[4], kc8[4];
+  // loader: piece p = tid + 256*q of a [rows][8 pieces] slice: row p/8, 16-byte column p%8
+  const bf16_t* ga[PA];
+  const bf16_t* gw[NW2][4];
+  int dsta[PA], dstw[4], kca[PA], kcw[4];
+#pragma unroll
+  for (int q = 0; q < PA; ++q) {
+    const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
+    kca[q] = kc * 8;
+    dsta[q] = ((kc >> 2) * TM + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
+    int ra = m0 + r; ra = ra < M ? ra : M - 1;
+    ga[q] = a.A + (int64_t)ra * K;
+  }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
-    kc8[q] = kc * 8;
-    dst[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
-    int ra = m0 + r; ra = ra < M ? ra : M - 1;
+    kcw[q] = kc * 8;
+    dstw[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
     int rw = n0 + r; rw = rw < N ? rw : N - 1;
-    ga[q] = A + (int64_t)ra * K;
-    gw[q] = W + (int64_t)rw * K;
+    gw[0][q] = a.W + (int64_t)rw * K;
+    if (NW2 == 2) gw[1][q] = a.W2 + (int64_t)rw * K;
   }
-  auto issue = [&](u32x4 (&ra)[4], u32x4 (&rw)[4], int k0) {
+  struct Stage { u32x4 ra[PA]; u32x4 rw[NW2][4]; };
+  auto issue = [&](Stage& st, int k0) {   // loads are clamped, never branched
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      int k = k0 + kc8[q];
+    for (int q = 0; q < PA; ++q) {
+      int k = k0 + kca[q];
       const bool ok = k + 8 <= K;
       k = ok ? k : K - 8;
-      const u32x4 va = *(const u32x4*)(ga[q] + k), vw = *(const u32x4*)(gw[q] + k);
-      ra[q] = ok ? va : u32x4{0, 0, 0, 0};
-      rw[q] = ok ? vw : u32x4{0, 0, 0, 0};
+      const u32x4 v = *(const u32x4*)(ga[q] + k);
+      st.ra[q] = ok ? v : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int x = 0; x < NW2; ++x)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int k = k0 + kcw[q];
+        const bool ok = k + 8 <= K;
+        k = ok ? k : K - 8;
+        const u32x4 v = *(const u32x4*)(gw[x][q] + k);
+        st.rw[x][q] = ok ? v : u32x4{0, 0, 0, 0};
+      }
+  };
+  auto commit = [&](const Stage& st, int buf) {
+    u32x4* da = &sa[buf][0][0][0];
+#pragma unroll
+    for (int q = 0; q < PA; ++q) da[dsta[q]] = st.ra[q];
+#pragma unroll
+    for (int x = 0; x < NW2; ++x) {
+      u32x4* dw = &sw[buf][x][0][0][0];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) dw[dstw[q]] = st.rw[x][q];
     }
   };
-  auto commit = [&](const u32x4 (&ra)[4], const u32x4 (&rw)[4], int buf) {
-    u32x4* da = &sa[buf][0][0][0];
-    u32x4* dw = &sw[buf][0][0][0];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { da[dst[q]] = ra[q]; dw[dst[q]] = rw[q]; }
-  };
 
-  f32x4 acc[4][4];   // [weight 16-row tile][token 16-row tile]
+  f32x4 acc[NW2][4][WT];   // [matrix][weight 16-row tile][token 16-row tile]
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int x = 0; x < NW2; ++x)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < WT; ++j) acc[x][i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (K + LG_BK - 1) / LG_BK;
-  u32x4 ra[4], rw[4];
-  issue(ra, rw, 0);
-  commit(ra, rw, 0);
-  for (int kt = 0; kt < nk; ++kt) {
-    __syncthreads();
-    issue(ra, rw, (kt + 1 < nk ? kt + 1 : kt) * LG_BK);   // unconditional (re-reads the last slice at the end)
-    const int buf = kt & 1;
+  auto compute = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      u32x4 fa[4], fw[4];
+      u32x4 fa[WT];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fw[i] = sw[buf][ks][(wn >> 4) + i][lane];
-        fa[i] = sa[buf][ks][(wm >> 4) + i][lane];
+      for (int j = 0; j < WT; ++j) fa[j] = sa[buf][ks][(wm >> 4) + j][lane];
+#pragma unroll
+      for (int x = 0; x < NW2; ++x) {
+        u32x4 fw[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fw[i] = sw[buf][x][ks][(wn >> 4) + i][lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < WT; ++j) acc[x][i][j] = mfma16(fw[i], fa[j], acc[x][i][j]);
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(fw[i], fa[j], acc[i][j]);
     }
-    commit(ra, rw, buf ^ 1);
+  };
+
+  const int nk = (K + LG_BK - 1) / LG_BK;
+  const int last = nk - 1;
+  Stage s0, s1;
+  issue(s0, 0);
+  issue(s1, (1 < last ? 1 : last) * LG_BK);
+  commit(s0, 0);
+  // slice kt is multiplied from LDS[kt&1] while slice kt+1 waits in registers and slice kt+2 is in flight
+  for (int kt = 0; kt < nk; kt += 2) {
+    __syncthreads();
+    issue(s0, (kt + 2 < last ? kt + 2 : last) * LG_BK);
+    compute(0);
+    commit(s1, 1);
+    __syncthreads();
+    issue(s1, (kt + 3 < last ? kt + 3 : last) * LG_BK);
+    if (kt + 1 < nk) compute(1);
+    commit(s0, 0);
   }
 
   // lane holds token column c of token tile j, features 4g..4g+3 of weight tile i
+  if (EPI == LG_LMSTATS) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < WT; ++j) {
+      const int m = m0 + wm + j * 16 + c;
+      RowStat st;
+      st.init();
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int n = n0 + wn + i * 16 + 4 * g + e;
+          if (n < N && n != a.mask_id) st.merge(acc[0][i][j][e], n, 1.0f, acc[0][i][j][e]);
+        }
+#pragma unroll
+      for (int o = 16; o < 64; o <<= 1) {
+        const float m2 = __shfl_xor(st.m, o, 64), s2 = __shfl_xor(st.s, o, 64), t2 = __shfl_xor(st.t, o, 64);
+        const int i2 = __shfl_xor(st.idx, o, 64);
+        st.merge(m2, i2, s2, t2);
+      }
+      if (g == 0 && m < M && n0 + wn < N) {
+        float* o = a.part + ((int64_t)m * a.n_parts + (n0 + wn) / 64) * 4;
+        *(f32x4*)o = f32x4{st.m, __int_as_float(st.idx), st.s, st.t};
+      }
+    }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < WT; ++j) {
     const int m = m0 + wm + j * 16 + c;
     if (m >= M) continue;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int n = n0 + wn + i * 16 + 4 * g;
+      f32x4 v = acc[0][i][j];
+      if (EPI == LG_SWIGLU) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * acc[NW2 - 1][i][j][e];
+      }
       if (n + 4 <= N) {
         const int64_t at = (int64_t)m * N + n;
-        if (EPI == EPI_STORE) {
-          *(uint2*)((bf16_t*)Cv + at) =
-              make_uint2((uint32_t)f32_to_bf16(acc[i][j][0]) | ((uint32_t)f32_to_bf16(acc[i][j][1]) << 16),
-                         (uint32_t)f32_to_bf16(acc[i][j][2]) | ((uint32_t)f32_to_bf16(acc[i][j][3]) << 16));
-        } else if (EPI == EPI_STORE_F32) {
-          *(f32x4*)((float*)Cv + at) = acc[i][j];
+        if (EPI == LG_STORE || EPI == LG_SWIGLU) {
+          *(uint2*)((bf16_t*)a.C + at) = make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
+                                                    (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
+        } else if (EPI == LG_STORE_F32) {
+          *(f32x4*)((float*)a.C + at) = v;
         } else {
-          f32x4* p = (f32x4*)((float*)Cv + at);
-          *p = *p + acc[i][j];
+          f32x4* p = (f32x4*)((float*)a.C + at);
+          *p = *p + v;
         }
       } else {
         for (int e = 0; e < 4; ++e) {
           if (n + e >= N) break;
           const int64_t at = (int64_t)m * N + n + e;
-          if (EPI == EPI_STORE) ((bf16_t*)Cv)[at] = f32_to_bf16(acc[i][j][e]);
-          else if (EPI == EPI_STORE_F32) ((float*)Cv)[at] = acc[i][j][e];
-          else ((float*)Cv)[at] += acc[i][j][e];
+          if (EPI == LG_STORE || EPI == LG_SWIGLU) ((bf16_t*)a.C)[at] = f32_to_bf16(v[e]);
+          else if (EPI == LG_STORE_F32) ((float*)a.C)[at] = v[e];
+          else ((float*)a.C)[at] += v[e];
         }
       }
     }
   }
 }
 
+template <int EPI>
+static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256) {
+  // 256-row tiles when they still give every CU a workgroup
+  const int t256 = ((a.M + 255) / 256) * ((a.N + LG_BN - 1) / LG_BN);
+  const bool big = allow_256 && t256 >= 256;
+  const int bm = big ? 256 : 128;
+  a.tiles_m = (a.M + bm - 1) / bm;
+  a.tiles_n = (a.N + LG_BN - 1) / LG_BN;
+  const int grid = (a.tiles_m * a.tiles_n + 7) / 8 * 8;
+  if constexpr (EPI != LG_SWIGLU) {     // two weight matrices at 256 rows would not fit the register file
+    if (big) { k_gemm_mfma<256, EPI><<<grid, 256, 0, s>>>(a); return hipGetLastError(); }
+  }
+  k_gemm_mfma<128, EPI><<<grid, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
 // C[M,N] (=, +=) A[M,K] W[N,K]^T for bfloat16 operands; N % 4 == 0 and K % 8 == 0
 hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi) {
-  const int tiles_m = (M + LG_BM - 1) / LG_BM, tiles_n = (N + LG_BN - 1) / LG_BN;
-  const int n_tiles = tiles_m * tiles_n;
-  const int grid = (n_tiles + 7) / 8 * 8;
-  if (epi == EPI_STORE) k_gemm_mfma<EPI_STORE><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
-  else if (epi == EPI_STORE_F32) k_gemm_mfma<EPI_STORE_F32><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
-  else k_gemm_mfma<EPI_RESID><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, tiles_m, tiles_n);
-  return hipGetLastError();
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = C; a.M = M; a.N = N; a.K = K;
+  if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a, true);
+  if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a, true);
+  return lg_launch<LG_RESID>(s, a, true);
+}
+
+// h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
+hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
+                              int K) {
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
+  return lg_launch<LG_SWIGLU>(s, a, false);
+}
+
+// LM head on the compacted rows (row-major ws.xn) -> softmax statistics per 64 columns
+hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out) {
+  const dllm_config& f = c->cfg;
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = WSM(c, xn, bf16_t); a.W = (const bf16_t*)c->lm_head; a.M = max_rows; a.N = f.vocab; a.K = f.d_model;
+  a.m_dev = WSM(c, status, int32_t) + 1;
+  a.part = WSM(c, lm_part, float);
+  a.n_parts = (f.vocab + 63) / 64;
+  a.mask_id = f.mask_id;
+  *n_parts_out = a.n_parts;
+  return lg_launch<LG_LMSTATS>(s, a, true);
 }
 
 }  // namespace dllm
