@@ -85,12 +85,88 @@ def cpu_baseline(ms, P, Q, n_masked, budget_s=20.0):
                       f"{ms.n_layers} x layer + head"}
 
 
+MFMA_PEAK_TFLOPS = 2500.0
+
+
+def large_batch(args, torch, np, synth, Engine, dev):
+    """Long-context large-batch step (not the default workload): Dream-7B-shaped model, batch 32, prefix KV of
+    8192 tokens per sequence drawn directly on the device, one block of 32 per sequence with 16 masked:
+    1024 query rows, LM head on the 512 masked ones.  Bound by the matrix cores."""
+    ms = synth.DREAM_7B if args.layers is None else synth.DREAM_7B.with_layers(args.layers)
+    Bn, P, Q, pt = 32, 8192, 32, 64
+    mp = (P + Q + pt - 1) // pt
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+                 max_tokens=0, device_weights=device_weights(ms, torch, dev, 5), pack=False)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    pool = eng.kv_pool.view(torch.bfloat16)
+    for i in range(0, pool.numel(), 1 << 28):                      # N(0,1) K and V for every slot
+        n = min(1 << 28, pool.numel() - i)
+        pool[i:i + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    table = eng.i32(np.arange(Bn * mp).reshape(Bn, mp))
+    prefix = eng.i32([P] * Bn)
+    fresh = eng.i32(np.stack([synth.masked_block(ms, 5, Q, 16, stream=b) for b in range(Bn)]))
+    qt = fresh.clone()
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+
+    def one_step(i):
+        if i % 8 == 0:
+            qt.copy_(fresh)
+        eng.denoise_step(qt, prefix, table, cand, conf, None, max_prefix_len=P)
+        eng.unmask(qt, cand, conf, 0.9, 1)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert eng.read_status() == 0
+    eng.profile_enable(True)
+    for i in range(min(args.steps, 4)):
+        one_step(8 + i)                                             # no re-mask: steady masked counts differ little
+    kern = {}
+    for cls, nm in KCLASS.items():
+        n, tms, work = eng.profile_read(cls)
+        if n:
+            kern[nm] = {"launches": n, "avg_us": tms / n * 1e3,
+                        ("GBps" if nm == "attention" else "TFLOPs"): work / (tms * 1e-3) / (1e9 if nm == "attention" else 1e12)}
+    eng.profile_enable(False)
+    T = Bn * Q
+    d, dq, dkv, F, G = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff, ms.n_q_heads // ms.n_kv_heads
+    per_layer = 2 * T * (d * (dq + 2 * dkv) + dq * d + 3 * d * F)
+    attn = 4 * (Q * G) * (P + Q) * ms.head_dim * ms.n_kv_heads * Bn
+    flops = ms.n_layers * (per_layer + attn) + 2 * (Bn * 16) * ms.vocab * d
+    ms_per_step = elapsed / args.steps * 1e3
+    gemm = {k: v for k, v in kern.items() if k not in ("attention", "lm_head")}
+    dom = max(gemm, key=lambda k: gemm[k]["avg_us"] * gemm[k]["launches"]) if gemm else None
+    roofline = None
+    if dom:
+        a = kern[dom]["TFLOPs"]
+        roofline = {"bound": "mfma", "kernel": f"k_gemm_mfma ({dom})", "achieved": a, "peak": MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": a / MFMA_PEAK_TFLOPS, "traffic": None, "avg_us": kern[dom]["avg_us"]}
+    out = {"metric": "denoise_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "Dream-7B-shaped %d layers, bf16, batch 32, prefix KV 8192 drawn N(0,1), block 32 with "
+                                  "16 masked, tau 0.9, min 1" % ms.n_layers, "layers": ms.n_layers, "prefix": P,
+                      "block": Q, "batch": Bn, "page_tokens": pt},
+           "query_tokens_per_s": T * args.steps / elapsed, "step_algorithmic_TFLOP": flops / 1e12,
+           "step_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12,
+           "step_frac_of_mfma_peak": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+           "roofline": roofline, "kernels": kern}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="c3", choices=["c3", "c2"])
+    ap.add_argument("--workload", default="c3", choices=["c3", "c2", "c5"])
     ap.add_argument("--layers", type=int, default=None, help="override depth (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-generation", action="store_true")
@@ -109,6 +185,9 @@ def main():
     from paper_2601_07568_amd.binding import Engine
 
     dev = torch.device("cuda:0")
+    if args.workload == "c5":
+        large_batch(args, torch, np, synth, Engine, dev)
+        return
     if args.workload == "c3":
         ms, P, Q, n_blocks, tau, m_floor, n_masked0 = synth.LLADA_8B, 1024, 32, 8, 0.9, 2, 32
         name = "LLaDA-8B-shaped 32 layers, bf16, batch 1, prompt 1024, block 32, tau 0.9, min 2 unmasks/step"

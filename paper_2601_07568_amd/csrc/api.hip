@@ -299,6 +299,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
     } else {
+      ProfScope p(c, s, 0, 2.0 * T * (dq + 2.0 * dkv) * f.d_model);   // large path: work recorded in flops
       TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
       TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
       TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
@@ -313,7 +314,10 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
       TRY(launch_sk_delta(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, delta, float), c->map.delta_stride,
                           SK_MAX_DELTA, T, f.d_model, dq, &pending), "wo");
-    } else TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    } else {
+      ProfScope p(c, s, 1, 2.0 * T * (double)dq * f.d_model);
+      TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+    }
     TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
     pending = 0;
     if (sk) {
@@ -326,12 +330,14 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
                           c->map.delta_stride, SK_MAX_DELTA, T, f.d_model, f.d_ff, &pending), "w_down");
     } else {
       if (big_mfma) {
+        ProfScope p(c, s, 2, 2.0 * T * 2.0 * f.d_ff * f.d_model);
         TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model), "gate_up");
       } else {
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
         TRY(launch_swiglu(c, s, T), "swiglu");
       }
+      ProfScope p(c, s, 3, 2.0 * T * (double)f.d_ff * f.d_model);
       TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
     }
   }
@@ -356,6 +362,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);
       TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
     } else if (big_mfma) {
+      ProfScope p(c, s, 4, 2.0 * max_rows * (double)f.vocab * f.d_model);   // upper bound: max_rows rows
       TRY(launch_gemm_lmstats(c, s, max_rows, &n_parts), "lm_head");
     } else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
     TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy), "lm_merge");

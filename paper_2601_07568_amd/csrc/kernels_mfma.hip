@@ -1030,9 +1030,12 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
 
 template <int EPI>
 static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256) {
-  // 256-row tiles when they still give every CU a workgroup
+  // Two 128-row workgroups per CU measure 2.3x faster than one 256-row workgroup (LM head, 512 rows):
+  // with a single wave per SIMD nothing covers the LDS and barrier waits.  The 256-row form stays
+  // selectable for tuning.
+  static const int force256 = getenv("DLLM_LG_256") ? 1 : 0;
   const int t256 = ((a.M + 255) / 256) * ((a.N + LG_BN - 1) / LG_BN);
-  const bool big = allow_256 && t256 >= 256;
+  const bool big = allow_256 && t256 >= 256 && force256;
   const int bm = big ? 256 : 128;
   a.tiles_m = (a.M + bm - 1) / bm;
   a.tiles_n = (a.N + LG_BN - 1) / LG_BN;
