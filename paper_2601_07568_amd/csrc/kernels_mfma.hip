@@ -107,22 +107,24 @@ template <int NT, int EPI>
 __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wbase)[NT], int (&row0)[NT],
                                     int (&nrows)[NT]) {
   if (EPI == SK_QKV) {
+    // NT == 3: tiles 0 and 1 are the two halves of rotary pair-tile wg (rows h*dh + j0 .. and the same
+    // + dh/2) of Wq or Wk, tile 2 is 16-row tile wg of Wv: pair tiles and value tiles are handed out
+    // together so that the grid is max(pair tiles, value tiles) equal workgroups
     const int half = a.dh >> 1, per_head = half / 16;
-    if (wg < a.n_q_wg + a.n_k_wg) {
-      const bool isq = wg < a.n_q_wg;
-      const int lw = isq ? wg : wg - a.n_q_wg;
-      const int h = lw / per_head, j0 = (lw - h * per_head) * 16;
+    const int n_pairs = a.n_q_wg + a.n_k_wg;
+    const int pw = wg < n_pairs ? wg : n_pairs - 1;            // clamped: the result is dropped
+    const bool isq = pw < a.n_q_wg;
+    const int lw = isq ? pw : pw - a.n_q_wg;
+    const int h = lw / per_head, j0 = (lw - h * per_head) * 16;
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        wbase[t] = isq ? a.W0 : a.W1;
-        nrows[t] = isq ? a.N0 : a.N1;
-        row0[t] = h * a.dh + j0 + t * half;
-      }
-    } else {
-      const int lw = wg - a.n_q_wg - a.n_k_wg;
-#pragma unroll
-      for (int t = 0; t < NT; ++t) { wbase[t] = a.W2; nrows[t] = a.N2; row0[t] = lw * 16 * NT + t * 16; }
+    for (int t = 0; t < 2; ++t) {
+      wbase[t] = isq ? a.W0 : a.W1;
+      nrows[t] = isq ? a.N0 : a.N1;
+      row0[t] = h * a.dh + j0 + t * half;
     }
+    wbase[NT - 1] = a.W2;
+    nrows[NT - 1] = a.N2;
+    row0[NT - 1] = wg * 16;                                    // beyond N2: clamped by the caller, dropped below
   } else if (EPI == SK_SWIGLU) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) { wbase[t] = (t == 0) ? a.W0 : a.W1; nrows[t] = a.N0; row0[t] = wg * 16; }
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
           const int hj = row0[0] + fr;                 // h*dh + j, j < half
           const int h = hj / a.dh, j = hj - h * a.dh;
           const float cs = a.rope_cos[(int64_t)tok * half + j], sn = a.rope_sin[(int64_t)tok * half + j];
-          const float v0 = val[0], v1 = val[NT - 1];
+          const float v0 = val[0], v1 = val[1];
           const bf16_t r0 = f32_to_bf16(v0 * cs - v1 * sn), r1 = f32_to_bf16(v1 * cs + v0 * sn);
           if (isq) {
             a.out_bf16[(int64_t)tok * a.N0 + hj] = r0;
@@ -270,18 +272,14 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
               a.pool_k[ko + j + half] = r1;
             } else atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
           }
-        } else {
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            const int n = row0[t] + fr;
-            if (n < a.N2) {
-              const int h = n / a.dh, ch = n - h * a.dh;
-              int64_t ko, vo;
-              int vs;
-              if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs))
-                a.pool_v[vo + (int64_t)ch * vs] = f32_to_bf16(val[t]);
-            }
-          }
+        }
+        const int n = row0[NT - 1] + fr;               // value row
+        if (n < a.N2) {
+          const int h = n / a.dh, ch = n - h * a.dh;
+          int64_t ko, vo;
+          int vs;
+          if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs))
+            a.pool_v[vo + (int64_t)ch * vs] = f32_to_bf16(val[NT - 1]);
         }
       }
     } else if (EPI == SK_LMSTATS) {
@@ -452,8 +450,8 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
   a.tok_seq = WSM(c, tok_seq, int32_t); a.tok_pos = WSM(c, tok_pos, int32_t);
   a.pool_k = (bf16_t*)pool.k; a.pool_v = (bf16_t*)pool.v; a.pool = pool;
   a.status = WSM(c, status, int32_t);
-  const int n_v_wg = (a.N2 + 31) / 32;
-  return sk_launch_mt<2, SK_NW, SK_QKV>(s, a, a.n_q_wg + a.n_k_wg + n_v_wg);
+  const int n_pairs = a.n_q_wg + a.n_k_wg, n_vt = (a.N2 + 15) / 16;
+  return sk_launch_mt<3, SK_NW, SK_QKV>(s, a, n_pairs > n_vt ? n_pairs : n_vt);
 }
 
 // h[M,F] = silu(xn Wg^T) * (xn Wu^T), written in fragment order for the down projection
