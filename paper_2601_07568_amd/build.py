@@ -35,7 +35,8 @@ def build(verbose: bool = False) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+            errs = [l for l in err.splitlines() if "error" in l]
+            raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(errs[:20] or err.splitlines()[-20:]))
         if verbose and err.strip():
             print(err, file=sys.stderr)
         return obj

@@ -106,7 +106,7 @@ __device__ inline void sk_mma(const SkFrag<NT, MT, JB>& f, f32x4 (&acc)[NT][MT])
 template <int NT, int EPI>
 __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wbase)[NT], int (&row0)[NT],
                                     int (&nrows)[NT]) {
-  if (EPI == SK_QKV) {
+  if constexpr (EPI == SK_QKV) {
     // NT == 3: tiles 0 and 1 are the two halves of rotary pair-tile wg (rows h*dh + j0 .. and the same
     // + dh/2) of Wq or Wk, tile 2 is 16-row tile wg of Wv: pair tiles and value tiles are handed out
     // together so that the grid is max(pair tiles, value tiles) equal workgroups
@@ -125,9 +125,14 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
     wbase[NT - 1] = a.W2;
     nrows[NT - 1] = a.N2;
     row0[NT - 1] = wg * 16;                                    // beyond N2: clamped by the caller, dropped below
-  } else if (EPI == SK_SWIGLU) {
+  } else if constexpr (EPI == SK_SWIGLU) {
+    // NT = 2*P: tiles 0..P-1 are P consecutive 16-row tiles of the gate matrix, tiles P..2P-1 the same rows of up
 #pragma unroll
-    for (int t = 0; t < NT; ++t) { wbase[t] = (t == 0) ? a.W0 : a.W1; nrows[t] = a.N0; row0[t] = wg * 16; }
+    for (int t = 0; t < NT; ++t) {
+      wbase[t] = (t < NT / 2) ? a.W0 : a.W1;
+      nrows[t] = a.N0;
+      row0[t] = (wg * (NT / 2) + (t % (NT / 2))) * 16;
+    }
   } else {
 #pragma unroll
     for (int t = 0; t < NT; ++t) { wbase[t] = a.W0; nrows[t] = a.N0; row0[t] = wg * 16 * NT + t * 16; }
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
       val[t] = s;
     }
     const bool tok_ok = tok < M;
-    if (EPI == SK_RESID || EPI == SK_F32 || EPI == SK_DELTA) {
+    if constexpr (EPI == SK_RESID || EPI == SK_F32 || EPI == SK_DELTA) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = row0[t] + fr;
@@ -245,13 +250,16 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
           else *p = val[t];
         }
       }
-    } else if (EPI == SK_SWIGLU) {
-      const int n = row0[0] + fr;
-      if (tok_ok && n < a.N0) {
-        const float gt = val[0];
-        a.out_bf16[frag_offset(tok, n, MT)] = f32_to_bf16(gt / (1.0f + expf(-gt)) * val[NT - 1]);
+    } else if constexpr (EPI == SK_SWIGLU) {
+#pragma unroll
+      for (int t = 0; t < NT / 2; ++t) {
+        const int n = row0[t] + fr;
+        if (tok_ok && n < a.N0) {
+          const float gt = val[t];
+          a.out_bf16[frag_offset(tok, n, MT)] = f32_to_bf16(gt / (1.0f + expf(-gt)) * val[t + NT / 2]);
+        }
       }
-    } else if (EPI == SK_QKV) {
+    } else if constexpr (EPI == SK_QKV) {
       if (tok_ok) {
         if (wg < a.n_q_wg + a.n_k_wg) {
           const bool isq = wg < a.n_q_wg;
@@ -282,7 +290,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
             a.pool_v[vo + (int64_t)ch * vs] = f32_to_bf16(val[NT - 1]);
         }
       }
-    } else if (EPI == SK_LMSTATS) {
+    } else if constexpr (EPI == SK_LMSTATS) {
       RowStat st;
       st.init();
 #pragma unroll
@@ -463,6 +471,7 @@ hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M) {
   a.W0 = (const bf16_t*)P.w_gate; a.W1 = (const bf16_t*)P.w_up;
   a.N0 = f.d_ff;
   a.out_bf16 = WSM(c, h, bf16_t);
+  // (three tile pairs per workgroup -- 256 equal workgroups at F = 12288 -- measured no faster than one)
   return sk_launch_mt<2, SK_NW, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
 }
 
@@ -883,7 +892,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     dstw[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
     int rw = n0 + r; rw = rw < N ? rw : N - 1;
     gw[0][q] = a.W + (int64_t)rw * K;
-    if (NW2 == 2) gw[1][q] = a.W2 + (int64_t)rw * K;
+    if constexpr (NW2 == 2) gw[1][q] = a.W2 + (int64_t)rw * K;
   }
   struct Stage { u32x4 ra[PA]; u32x4 rw[NW2][4]; };
   auto issue = [&](Stage& st, int k0) {   // loads are clamped, never branched
