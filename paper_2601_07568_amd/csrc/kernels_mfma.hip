@@ -518,6 +518,65 @@ struct AttnArgs {
   int32_t* status;
 };
 
+// two floats -> packed bfloat16 pair (round to nearest even, in hardware)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+
+// Online softmax of one 32-key block for QT query tiles; the lane holds raw scores of keys
+// k0 + 8g + 4tt + i.  Updates the running maximum (in log2 units), the lane's share of the
+// denominator and rescales the accumulators only when some maximum of the wave moved.
+// Probabilities enter the second product as a bfloat16 pair hi + lo (two instructions): a
+// single rounding of p would be the largest error of the whole attention and would flip the
+// rounding of a good fraction of the stored outputs.
+template <int DT, int QT>
+__device__ __forceinline__ void attn_softmax_block(f32x4 (&s)[2][QT], int k0, int kv_len, int g, float scale_log2,
+                                                   float (&m_run)[QT], float (&l_run)[QT], f32x4 (&oacc)[DT][QT],
+                                                   u32x4 (&pf)[QT], u32x4 (&pl)[QT]) {
+  if (k0 + 32 > kv_len) {                               // only a sequence's last block has keys to mask
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (k0 + 8 * g + 4 * tt + i >= kv_len) s[tt][t][i] = -DEV_INF;
+  }
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    float mx = fmaxf(fmaxf(fmaxf(s[0][t][0], s[0][t][1]), fmaxf(s[0][t][2], s[0][t][3])),
+                     fmaxf(fmaxf(s[1][t][0], s[1][t][1]), fmaxf(s[1][t][2], s[1][t][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run[t], mx * scale_log2);   // finite: every block has at least one valid key
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run[t]) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_new);   // exp2(-inf) = 0 on the first block
+      l_run[t] *= alpha;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) oacc[d][t] = oacc[d][t] * alpha;
+      m_run[t] = m_new;
+    }
+    float p[8], ps = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(s[tt][t][i], scale_log2, -m_new));
+        p[tt * 4 + i] = e;
+        ps += e;
+      }
+    l_run[t] += ps;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t h = pack_bf16x2(p[2 * e], p[2 * e + 1]);
+      pf[t][e] = h;
+      pl[t][e] = pack_bf16x2(p[2 * e] - __uint_as_float(h << 16), p[2 * e + 1] - __uint_as_float(h & 0xffff0000u));
+    }
+  }
+}
+
 template <int DH, int QT>
 __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
   constexpr int KK = DH / 32;   // k-steps of Q K^T
@@ -636,52 +695,9 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
         for (int kk = 0; kk < KK; ++kk) acc = mfma16(kf[tt][kk], qf[t][kk], acc);
         s[tt][t] = acc;
       }
-    // ---- online softmax per query column; lane holds keys k0 + 8g + 4tt + i
-    // Probabilities enter the second product as a bfloat16 pair hi + lo (two instructions): a
-    // single rounding of p would be the largest error of the whole attention and would flip the
-    // rounding of a good fraction of the stored outputs.
+    // ---- online softmax per query column
     u32x4 pf[QT], pl[QT];
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      float mx = -DEV_INF;
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int key = k0 + 8 * g + 4 * tt + i;
-          float v = s[tt][t][i] * a.scale_log2;
-          if (key >= kv_len) v = -DEV_INF;
-          s[tt][t][i] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[t], mx);       // finite: every block has at least one valid key
-      const float alpha = exp2f(m_run[t] - m_new);   // exp2(-inf) = 0 on the first block
-      float ps = 0.f;
-      float p[8];
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float e = exp2f(s[tt][t][i] - m_new);
-          p[tt * 4 + i] = e;
-          ps += e;
-        }
-      l_run[t] = l_run[t] * alpha + ps;
-      m_run[t] = m_new;
-#pragma unroll
-      for (int d = 0; d < DT; ++d) {
-        oacc[d][t][0] *= alpha; oacc[d][t][1] *= alpha; oacc[d][t][2] *= alpha; oacc[d][t][3] *= alpha;
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const bf16_t h0 = f32_to_bf16(p[2 * e]), h1 = f32_to_bf16(p[2 * e + 1]);
-        const bf16_t l0 = f32_to_bf16(p[2 * e] - bf16_to_f32(h0)), l1 = f32_to_bf16(p[2 * e + 1] - bf16_to_f32(h1));
-        pf[t][e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        pl[t][e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-      }
-    }
+    attn_softmax_block<DT, QT>(s, k0, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int d = 0; d < DT; ++d)
@@ -765,6 +781,215 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const
   o[at] = f32_to_bf16(den > 0.f ? num / den : 0.f);
 }
 
+// ------------------------------------------------------------------------------------------
+// The same attention for many query rows per KV head (grouped-query models at large batch, and
+// every no-cache forward): the waves of a workgroup are row groups of 32 rows that all need the
+// same keys, so each 64-key block of K and V^T is fetched from memory once per workgroup, by all
+// threads together, and laid out in LDS in operand order (every fragment read is 64 lanes x 16
+// contiguous bytes); two LDS buffers, the next block in flight in registers while the current one
+// is multiplied.  Arithmetic, masking and outputs are those of k_attn_step.
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
+  constexpr int KK = DH / 32, DT = DH / 16, QT = 2;
+  constexpr int KP = DH / 8;                 // 16-byte pieces of a K row
+  constexpr int KPB = 64 * KP, VPB = DH * 8; // pieces of a 64-key block: K rows, V^T channel rows
+  constexpr int NP = KPB + VPB, nthr = NW * 64, MAXP = (NP + nthr - 1) / nthr;
+  __shared__ u32x4 sk[2][2][2][KK][64];      // [buffer][32-key half][tile][k-step][lane]
+  __shared__ u32x4 sv[2][2][DT][64];         // [buffer][32-key half][channel tile][lane]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int rg = blockIdx.y * a.n_rg_wg + w;
+  const int unit = blockIdx.x;
+  const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
+  const int G = a.Hq / a.Hkv;
+  const bool paged = a.Q > 0;
+  const int row_base = paged ? b * a.Q : a.cu[b];
+  const int n_q = paged ? a.Q : a.cu[b + 1] - a.cu[b];
+  const int R = n_q * G;
+  const int kv_len = paged ? a.prefix_len[b] + a.Q : n_q;
+  const bool active = w < a.n_rg_wg && rg * 16 * QT < R;     // waves beyond the rows only help loading
+  if (blockIdx.y * a.n_rg_wg * 16 * QT >= R) return;         // whole workgroup beyond this sequence's rows
+  const KVView& kv = a.kv;
+  const int pt = paged ? kv.page_tokens : 1;
+  const bf16_t* kslab = (const bf16_t*)kv.k;
+  const bf16_t* vslab = (const bf16_t*)kv.v;
+  const int32_t* table = paged ? kv.table + (int64_t)b * kv.max_pages : nullptr;
+  const int64_t pcol = paged ? 0 : kv.cu_pad[b];
+  bool bad = false;
+
+  u32x4 qf[QT][KK];
+  int64_t row_out[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int r = rg * 16 * QT + t * 16 + c;
+    const bool ok = active && r < R;
+    if (!ok) r = 0;
+    const int hg = r / n_q, j = r - hg * n_q;
+    const int64_t ro = (int64_t)(row_base + j) * a.Hq + kvh * G + hg;
+    row_out[t] = ok ? ro : -1;
+    const bf16_t* qp = a.q + ro * DH + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[t][kk] = *(const u32x4*)(qp + kk * 32);
+  }
+
+  // ---- cooperative loader: piece p of a block -> (source address, LDS unit, zero mask)
+  auto issue = [&](u32x4 (&reg)[MAXP], int kb64) {
+    const int k0 = kb64 << 6;
+#pragma unroll
+    for (int i = 0; i < MAXP; ++i) {
+      int p = tid + i * nthr;
+      p = p < NP ? p : NP - 1;                                  // clamped: a duplicate load, never a branch
+      const bf16_t* src;
+      if (p < KPB) {
+        const int r = p / KP, pc = p - r * KP;
+        int key = k0 + r;
+        if (key >= kv_len) key = kv_len - 1;                    // masked at the scores
+        if (paged) {
+          const int pi = key / pt;
+          int page = pi < kv.max_pages ? table[pi] : -1;
+          if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
+          src = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + pc * 8;
+        } else {
+          src = kslab + ((int64_t)kvh * kv.tpad + pcol + key) * DH + pc * 8;
+        }
+      } else {
+        const int q = p - KPB, ch = q >> 3, kg = q & 7;
+        int key = k0 + kg * 8;
+        if (key >= kv_len) key = (kv_len - 1) & ~7;             // zeroed when it is put into LDS
+        if (paged) {
+          const int pi = key / pt;
+          int page = pi < kv.max_pages ? table[pi] : -1;
+          if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
+          src = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + ch) * pt + (key - pi * pt);
+        } else {
+          src = vslab + ((int64_t)kvh * DH + ch) * kv.tpad + pcol + key;
+        }
+      }
+      reg[i] = *(const u32x4*)src;
+    }
+  };
+  // V^T elements of keys beyond the sequence become zero here: their probability is zero, and
+  // zero times whatever the pool holds there must stay zero
+  auto commit = [&](const u32x4 (&reg)[MAXP], int buf, int kb64) {
+    u32x4* dk = &sk[buf][0][0][0][0];
+    u32x4* dv = &sv[buf][0][0][0];
+#pragma unroll
+    for (int i = 0; i < MAXP; ++i) {
+      int p = tid + i * nthr;
+      p = p < NP ? p : NP - 1;
+      if (p < KPB) {
+        const int r = p / KP, pc = p - r * KP;
+        const int half = r >> 5, r32 = r & 31, aa = r32 >> 3, bb = r32 & 7;
+        const int tt = bb >> 2, cc = 4 * aa + (bb & 3);         // key 8a+b of a half sits in tile b/4, row 4a + b%4
+        dk[(((half * 2 + tt) * KK + (pc >> 2)) * 64) + (pc & 3) * 16 + cc] = reg[i];
+      } else {
+        const int q = p - KPB, ch = q >> 3, kg = q & 7;
+        const int valid = kv_len - ((kb64 << 6) + kg * 8);      // elements of this piece inside the sequence
+        u32x4 v = reg[i];
+        if (valid < 8) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (valid <= 2 * e) v[e] = 0u;
+            else if (valid == 2 * e + 1) v[e] &= 0x0000ffffu;
+          }
+        }
+        dv[(((kg >> 2) * DT + (ch >> 4)) * 64) + (kg & 3) * 16 + (ch & 15)] = v;
+      }
+    }
+  };
+
+  f32x4 oacc[DT][QT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int t = 0; t < QT; ++t) oacc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) { m_run[t] = -DEV_INF; l_run[t] = 0.f; }
+
+  auto compute = [&](int buf, int kb64) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int k0 = (kb64 << 6) + half * 32;
+      if (k0 >= kv_len) break;
+      f32x4 s[2][QT];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        u32x4 kf[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kf[kk] = sk[buf][half][tt][kk][lane];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) acc = mfma16(kf[kk], qf[t][kk], acc);
+          s[tt][t] = acc;
+        }
+      }
+      u32x4 pf[QT], pl[QT];
+      attn_softmax_block<DT, QT>(s, k0, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        const u32x4 vf = sv[buf][half][d][lane];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+          oacc[d][t] = mfma16(vf, pf[t], oacc[d][t]);
+          oacc[d][t] = mfma16(vf, pl[t], oacc[d][t]);
+        }
+      }
+    }
+  };
+
+  const int nkb = (kv_len + 63) >> 6;
+  if (unit < nkb) {
+    const int last = unit + ((nkb - 1 - unit) / a.n_units) * a.n_units;
+    u32x4 reg[MAXP];
+    issue(reg, unit);
+    commit(reg, 0, unit);
+    int buf = 0;
+    for (int kb = unit; kb < nkb; kb += a.n_units) {
+      __syncthreads();
+      int nxt = kb + a.n_units;
+      nxt = nxt <= last ? nxt : last;
+      issue(reg, nxt);
+      if (active) compute(buf, kb);
+      commit(reg, buf ^ 1, nxt);
+      buf ^= 1;
+    }
+  }
+
+  if (active) {
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      float l = l_run[t];
+      l += __shfl_xor(l, 16, 64);
+      l += __shfl_xor(l, 32, 64);
+      if (row_out[t] < 0) continue;
+      if (a.n_units == 1) {
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        const int64_t ro = row_out[t];
+        const int tok = (int)(ro / a.Hq), head = (int)(ro - (int64_t)tok * a.Hq);
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+          const int ch = d * 16 + 4 * g;
+          const int64_t at = a.out_mt > 0 ? frag_offset(tok, head * DH + ch, a.out_mt) : ro * DH + ch;
+          *(uint2*)(a.o + at) = make_uint2(
+              (uint32_t)f32_to_bf16(oacc[d][t][0] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][1] * inv) << 16),
+              (uint32_t)f32_to_bf16(oacc[d][t][2] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][3] * inv) << 16));
+        }
+        continue;
+      }
+      const int64_t slot = row_out[t] * a.n_units + unit;
+      float* po = a.part_o + slot * DH + 4 * g;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) *(f32x4*)(po + d * 16) = oacc[d][t];
+      if (g == 0) { a.part_ml[slot * 2] = m_run[t]; a.part_ml[slot * 2 + 1] = l; }
+    }
+  }
+  if (bad) atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
+}
+
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
   const dllm_config& f = c->cfg;
   if (!(f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->map.attn_rows > 0)) return false;
@@ -786,7 +1011,7 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   // attention is a few MB), so give every unit about two 32-key blocks, within the partial buffer
   int64_t want = 2048 / ((int64_t)g.B * f.n_kv_heads * n_rg);
   if (want < 1) want = 1;
-  int64_t by_work = (nkb + 1) / 2;
+  int64_t by_work = n_rg >= 4 ? (nkb + 7) / 8 : (nkb + 1) / 2;   // staged kernel: at least four 64-key blocks per unit
   int64_t by_space = c->map.attn_rows / ((int64_t)g.T * f.n_q_heads);
   int64_t units = want < by_work ? want : by_work;
   if (units > by_space) units = by_space;
@@ -809,7 +1034,17 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   a.status = WSM(c, status, int32_t);
   dim3 grid((unsigned)(units / kspl), n_chunks, g.B * f.n_kv_heads);
   const int threads = 64 * n_rg_wg * kspl;
-  if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
+  static const int no_lds = getenv("DLLM_NO_ATTN_LDS") ? 1 : 0;   // tuning aid
+  if (n_rg >= 4 && !no_lds) {
+    // many rows per kv head: K/V staged once per workgroup in LDS (at least 4 waves load)
+    if (f.head_dim == 128) {
+      if (n_rg_wg <= 4) k_attn_lds<128, 4><<<grid, 256, 0, s>>>(a);
+      else k_attn_lds<128, 8><<<grid, 512, 0, s>>>(a);
+    } else {
+      if (n_rg_wg <= 4) k_attn_lds<64, 4><<<grid, 256, 0, s>>>(a);
+      else k_attn_lds<64, 8><<<grid, 512, 0, s>>>(a);
+    }
+  } else if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
   else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || units == 1) return e;
