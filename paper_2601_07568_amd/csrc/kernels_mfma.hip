@@ -786,8 +786,10 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const
 // every no-cache forward): the waves of a workgroup are row groups of 32 rows that all need the
 // same keys, so each 64-key block of K and V^T is fetched from memory once per workgroup, by all
 // threads together, and laid out in LDS in operand order (every fragment read is 64 lanes x 16
-// contiguous bytes); two LDS buffers, the next block in flight in registers while the current one
-// is multiplied.  Arithmetic, masking and outputs are those of k_attn_step.
+// bytes of one KiB; inside the KiB the row index is xor-ed with the piece's column so that the
+// loader's consecutive lanes, which walk along a row, hit different banks); two LDS buffers, the
+// next block in flight in registers while the current one is multiplied.  Arithmetic, masking and
+// outputs are those of k_attn_step.
 template <int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   constexpr int KK = DH / 32, DT = DH / 16, QT = 2;
@@ -882,7 +884,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
         const int r = p / KP, pc = p - r * KP;
         const int half = r >> 5, r32 = r & 31, aa = r32 >> 3, bb = r32 & 7;
         const int tt = bb >> 2, cc = 4 * aa + (bb & 3);         // key 8a+b of a half sits in tile b/4, row 4a + b%4
-        dk[(((half * 2 + tt) * KK + (pc >> 2)) * 64) + (pc & 3) * 16 + cc] = reg[i];
+        dk[(((half * 2 + tt) * KK + (pc >> 2)) * 64) + (pc & 3) * 16 + (cc ^ (4 * (pc & 3)) ^ (pc >> 2))] = reg[i];
       } else {
         const int q = p - KPB, ch = q >> 3, kg = q & 7;
         const int valid = kv_len - ((kb64 << 6) + kg * 8);      // elements of this piece inside the sequence
@@ -894,7 +896,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
             else if (valid == 2 * e + 1) v[e] &= 0x0000ffffu;
           }
         }
-        dv[(((kg >> 2) * DT + (ch >> 4)) * 64) + (kg & 3) * 16 + (ch & 15)] = v;
+        dv[(((kg >> 2) * DT + (ch >> 4)) * 64) + (kg & 3) * 16 + ((ch & 15) ^ (4 * (kg & 3)) ^ (2 * (kg >> 2)))] = v;
       }
     }
   };
@@ -918,7 +920,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
       for (int tt = 0; tt < 2; ++tt) {
         u32x4 kf[KK];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kf[kk] = sk[buf][half][tt][kk][lane];
+        for (int kk = 0; kk < KK; ++kk) kf[kk] = sk[buf][half][tt][kk][lane ^ (4 * g) ^ kk];
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
           f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -931,7 +933,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
       attn_softmax_block<DT, QT>(s, k0, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
 #pragma unroll
       for (int d = 0; d < DT; ++d) {
-        const u32x4 vf = sv[buf][half][d][lane];
+        const u32x4 vf = sv[buf][half][d][lane ^ (4 * g) ^ (2 * half)];
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
           oacc[d][t] = mfma16(vf, pf[t], oacc[d][t]);
@@ -1070,6 +1072,10 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
 namespace dllm {
 
 constexpr int LG_BN = 128, LG_BK = 64;
+// Inside a fragment's KiB in LDS the unit of (k-group g, row c) of k-step ks sits at g*16 + (c ^ lg_swz(g, ks)):
+// reads stay a permutation of the KiB, and the loader's 16 consecutive lanes (two rows x eight
+// 16-byte columns of a slice) write 16 different bank groups instead of two.
+__device__ __forceinline__ int lg_swz(int g, int ks) { return (4 * g) ^ (2 * ks); }
 enum LgEpi { LG_STORE = 0, LG_STORE_F32 = 1, LG_RESID = 2, LG_SWIGLU = 3, LG_LMSTATS = 4 };
 
 struct LgArgs {
@@ -1116,7 +1122,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   for (int q = 0; q < PA; ++q) {
     const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
     kca[q] = kc * 8;
-    dsta[q] = ((kc >> 2) * TM + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
+    dsta[q] = ((kc >> 2) * TM + (r >> 4)) * 64 + (kc & 3) * 16 + ((r & 15) ^ lg_swz(kc & 3, kc >> 2));
     int ra = m0 + r; ra = ra < M ? ra : M - 1;
     ga[q] = a.A + (int64_t)ra * K;
   }
@@ -1124,7 +1130,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   for (int q = 0; q < 4; ++q) {
     const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
     kcw[q] = kc * 8;
-    dstw[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + (r & 15);
+    dstw[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + ((r & 15) ^ lg_swz(kc & 3, kc >> 2));
     int rw = n0 + r; rw = rw < N ? rw : N - 1;
     gw[0][q] = a.W + (int64_t)rw * K;
     if constexpr (NW2 == 2) gw[1][q] = a.W2 + (int64_t)rw * K;
@@ -1175,12 +1181,12 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     for (int ks = 0; ks < 2; ++ks) {
       u32x4 fa[WT];
 #pragma unroll
-      for (int j = 0; j < WT; ++j) fa[j] = sa[buf][ks][(wm >> 4) + j][lane];
+      for (int j = 0; j < WT; ++j) fa[j] = sa[buf][ks][(wm >> 4) + j][lane ^ lg_swz(g, ks)];
 #pragma unroll
       for (int x = 0; x < NW2; ++x) {
         u32x4 fw[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fw[i] = sw[buf][x][ks][(wn >> 4) + i][lane];
+        for (int i = 0; i < 4; ++i) fw[i] = sw[buf][x][ks][(wn >> 4) + i][lane ^ lg_swz(g, ks)];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
