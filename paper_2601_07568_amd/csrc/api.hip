@@ -69,7 +69,12 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
   if (c->dtype != DLLM_BF16) m->attn_rows = 0;
   m->delta_stride = (int64_t)SK_MAX_ROWS * c->d_model;
-  m->delta = take(c->dtype == DLLM_BF16 ? (size_t)SK_MAX_DELTA * m->delta_stride * 4 : 0);
+  m->lg_delta_rows = c->dtype == DLLM_BF16 ? (int64_t)(t_max < (size_t)LG_DELTA_ROWS ? t_max : (size_t)LG_DELTA_ROWS) : 0;
+  m->lg_delta_stride = m->lg_delta_rows * c->d_model;
+  {
+    size_t sk_floats = (size_t)SK_MAX_DELTA * m->delta_stride, lg_floats = (size_t)LG_MAX_DELTA * m->lg_delta_stride;
+    m->delta = take(c->dtype == DLLM_BF16 ? (sk_floats > lg_floats ? sk_floats : lg_floats) * 4 : 0);
+  }
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
   m->total = off;
@@ -300,9 +305,14 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
     } else {
       ProfScope p(c, s, 0, 2.0 * T * (dq + 2.0 * dkv) * f.d_model);   // large path: work recorded in flops
-      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
-      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
-      TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+      if (big_mfma && f.d_model % 8 == 0 && dq % 4 == 0 && dkv % 4 == 0) {
+        TRY(launch_gemm_qkv(s, c->ws + c->map.xn, L.wq, L.wk, L.wv, WSP(c, q32, float), WSP(c, k32, float),
+                            c->ws + c->map.v, T, dq, dkv, f.d_model), "wqkv");
+      } else {
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+      }
       TRY(launch_rope_kv(c, s, g, l), "rope_kv");
     }
     {
@@ -316,7 +326,9 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
                           SK_MAX_DELTA, T, f.d_model, dq, &pending), "wo");
     } else {
       ProfScope p(c, s, 1, 2.0 * T * (double)dq * f.d_model);
-      TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
+      if (big_mfma && f.d_model % 4 == 0 && dq % 8 == 0)
+        TRY(launch_gemm_resid_split(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq, &pending), "wo");
+      else TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
     }
     TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
     pending = 0;
@@ -338,11 +350,14 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
         TRY(launch_swiglu(c, s, T), "swiglu");
       }
       ProfScope p(c, s, 3, 2.0 * T * (double)f.d_ff * f.d_model);
-      TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
+      if (big_mfma && f.d_model % 4 == 0 && f.d_ff % 8 == 0)
+        TRY(launch_gemm_resid_split(c, s, c->ws + c->map.h, L.w_down, WSP(c, x, float), T, f.d_model, f.d_ff, &pending),
+            "w_down");
+      else TRY(gemm_any(c, s, c->ws + c->map.h, L.w_down, c->ws + c->map.x, T, f.d_model, f.d_ff, EPI_RESID), "w_down");
     }
   }
   if (hidden_out) {
-    if (pending) { TRY(launch_fold_delta(c, s, T, pending), "fold_delta"); pending = 0; }
+    if (pending) { TRY(launch_fold_delta(c, s, T, pending, sk), "fold_delta"); pending = 0; }
     TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
   }
   if (logits_out) {

@@ -145,8 +145,9 @@ struct Workspace {
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
   size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
   int64_t attn_rows;   // capacity in (token, head, unit) rows
-  size_t delta;        // float [SK_MAX_DELTA][64, d] open residual sums of the skinny path
+  size_t delta;        // float open residual sums: [SK_MAX_DELTA][64, d] (skinny path) or [LG_MAX_DELTA][lg_delta_rows, d]
   int64_t delta_stride;
+  int64_t lg_delta_rows, lg_delta_stride;   // large path: rows the buffer covers (0 = none), floats per split
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
   int64_t t_max, r_max, t_step, tpad;
@@ -205,7 +206,9 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 // n_delta > 0 (fragment path only): first add the open residual sums delta_0 .. to x
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
                           const int32_t* n_rows_dev, int frag_mt, int n_delta);
-hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta);
+hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta, bool frag_path);
+constexpr int LG_MAX_DELTA = 3;        // large path: a residual projection is split over K at most 4 ways
+constexpr int LG_DELTA_ROWS = 2048;    // ... and only when the token count leaves the chip underfilled
 constexpr int SK_MAX_DELTA = 8;   // most K splits of a residual projection
 hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* delta,
                            int64_t delta_stride, int max_splits, int M, int N, int K, int* n_splits);
@@ -238,6 +241,10 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
 hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi);
+hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
+                                   int* n_delta);
+hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
+                           float* k32, void* v, int M, int dq, int dkv, int K);
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
                               int K);
 hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);

@@ -91,8 +91,8 @@ __global__ void k_rope_table(int T, int half, double log2_base, const int32_t* t
 }
 
 template <typename T>
-__global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* out, const int32_t* rows,
-                          const int32_t* n_rows_dev, int frag_mt) {
+__global__ void k_rmsnorm(int d, float eps, float* x, const T* gain, T* out, const int32_t* rows,
+                          const int32_t* n_rows_dev, int frag_mt, const float* delta, int n_delta, int64_t delta_stride) {
   __shared__ float red[16];
   int r = blockIdx.x;
   int src = r;
@@ -100,12 +100,19 @@ __global__ void k_rmsnorm(int d, float eps, const float* x, const T* gain, T* ou
     if (r >= *n_rows_dev) return;
     src = rows[r];
   }
-  const float* xr = x + (int64_t)src * d;
+  float* xr = x + (int64_t)src * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) { float v = xr[i]; ss += v * v; }
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float v = xr[i];
+    if (n_delta > 0) {      // open K splits of the last residual projection, added in split order
+      for (int sd = 0; sd < n_delta; ++sd) v += delta[sd * delta_stride + (int64_t)src * d + i];
+      xr[i] = v;
+    }
+    ss += v * v;
+  }
   ss = block_sum(ss, red);
   float rinv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {   // a thread re-reads only what it wrote itself
     const int64_t at = frag_mt > 0 ? frag_offset(r, i, frag_mt) : (int64_t)r * d + i;
     Elem<T>::store(out + at, xr[i] * rinv * Elem<T>::load(gain + i));
   }
@@ -600,10 +607,10 @@ __global__ void k_fold_delta(int64_t n, float* x, const float* delta, int n_delt
   x[i] = v;
 }
 
-hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta) {
+hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta, bool frag_path) {
   const int64_t n = (int64_t)T * c->cfg.d_model;
   k_fold_delta<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(n, WS(c, x, float), WS(c, delta, float), n_delta,
-                                                          c->map.delta_stride);
+                                                          frag_path ? c->map.delta_stride : c->map.lg_delta_stride);
   return hipGetLastError();
 }
 
@@ -615,10 +622,11 @@ hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, c
                                      rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta, c->map.delta_stride);
   else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
-                                        WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt);
+                                        WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta,
+                                        frag_mt > 0 ? c->map.delta_stride : c->map.lg_delta_stride);
   else
     k_rmsnorm<float><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const float*)gain,
-                                       WS(c, xn, float), rows, n_rows_dev, 0);
+                                       WS(c, xn, float), rows, n_rows_dev, 0, nullptr, 0, 0);
   return hipGetLastError();
 }
 

@@ -512,6 +512,7 @@ struct AttnArgs {
   int n_units;              // key-splitting units per row group (gridDim.x * waves along keys)
   int kspl;                 // units inside a workgroup
   int n_rg_wg;              // row groups per workgroup
+  int pt_shift;             // log2(page_tokens) if that is a power of two (0 for the packed scratch), else -1
   float scale_log2;         // log2(e) / sqrt(DH)
   float* part_o;            // [T*Hq, n_units, DH]
   float* part_ml;           // [T*Hq, n_units, 2]
@@ -790,12 +791,13 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const
 // loader's consecutive lanes, which walk along a row, hit different banks); two LDS buffers, the
 // next block in flight in registers while the current one is multiplied.  Arithmetic, masking and
 // outputs are those of k_attn_step.
-template <int DH, int NW>
+template <int DH, int NW, bool PAGED>
 __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   constexpr int KK = DH / 32, DT = DH / 16, QT = 2;
   constexpr int KP = DH / 8;                 // 16-byte pieces of a K row
   constexpr int KPB = 64 * KP, VPB = DH * 8; // pieces of a 64-key block: K rows, V^T channel rows
-  constexpr int NP = KPB + VPB, nthr = NW * 64, MAXP = (NP + nthr - 1) / nthr;
+  constexpr int NP = KPB + VPB, nthr = NW * 64, MAXP = NP / nthr;
+  static_assert(KPB % nthr == 0 && VPB % nthr == 0, "a thread's i-th piece is K for all threads or V for all");
   __shared__ u32x4 sk[2][2][2][KK][64];      // [buffer][32-key half][tile][k-step][lane]
   __shared__ u32x4 sv[2][2][DT][64];         // [buffer][32-key half][channel tile][lane]
   const int tid = threadIdx.x;
@@ -805,19 +807,18 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   const int unit = blockIdx.x;
   const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
   const int G = a.Hq / a.Hkv;
-  const bool paged = a.Q > 0;
-  const int row_base = paged ? b * a.Q : a.cu[b];
-  const int n_q = paged ? a.Q : a.cu[b + 1] - a.cu[b];
+  const int row_base = PAGED ? b * a.Q : a.cu[b];
+  const int n_q = PAGED ? a.Q : a.cu[b + 1] - a.cu[b];
   const int R = n_q * G;
-  const int kv_len = paged ? a.prefix_len[b] + a.Q : n_q;
+  const int kv_len = PAGED ? a.prefix_len[b] + a.Q : n_q;
   const bool active = w < a.n_rg_wg && rg * 16 * QT < R;     // waves beyond the rows only help loading
   if (blockIdx.y * a.n_rg_wg * 16 * QT >= R) return;         // whole workgroup beyond this sequence's rows
   const KVView& kv = a.kv;
-  const int pt = paged ? kv.page_tokens : 1;
+  const int sh = a.pt_shift, pt = 1 << sh;                   // page size (a power of two)
   const bf16_t* kslab = (const bf16_t*)kv.k;
   const bf16_t* vslab = (const bf16_t*)kv.v;
-  const int32_t* table = paged ? kv.table + (int64_t)b * kv.max_pages : nullptr;
-  const int64_t pcol = paged ? 0 : kv.cu_pad[b];
+  const int32_t* table = PAGED ? kv.table + (int64_t)b * kv.max_pages : nullptr;
+  const int64_t pcol = PAGED ? 0 : kv.cu_pad[b];
   bool bad = false;
 
   u32x4 qf[QT][KK];
@@ -835,66 +836,84 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
     for (int kk = 0; kk < KK; ++kk) qf[t][kk] = *(const u32x4*)(qp + kk * 32);
   }
 
-  // ---- cooperative loader: piece p of a block -> (source address, LDS unit, zero mask)
-  auto issue = [&](u32x4 (&reg)[MAXP], int kb64) {
-    const int k0 = kb64 << 6;
+  // ---- cooperative loader.  Piece p = tid + i * nthr of a 64-key block: a 16-byte column of a K
+  // row (i-th pieces below KPB) or eight keys of a V^T channel row.  No branch anywhere on the
+  // way to a load, and the page ids of a block are fetched one block earlier than its data, so a
+  // wave never waits on two dependent memory round trips.
+  auto piece_key = [&](int i, int kb64) -> int {              // first key the piece addresses (clamped into the sequence)
+    const int p = tid + i * nthr;
+    if (i * nthr < KPB) {
+      const int key = (kb64 << 6) + p / KP;
+      return key < kv_len ? key : kv_len - 1;                   // masked at the scores
+    }
+    const int key = (kb64 << 6) + ((p - KPB) & 7) * 8;
+    return key < kv_len ? key : (kv_len - 1) & ~7;              // zeroed when it is put into LDS
+  };
+  auto fetch_pages = [&](int (&pg)[MAXP], int kb64) {
+    if constexpr (PAGED) {
 #pragma unroll
-    for (int i = 0; i < MAXP; ++i) {
-      int p = tid + i * nthr;
-      p = p < NP ? p : NP - 1;                                  // clamped: a duplicate load, never a branch
-      const bf16_t* src;
-      if (p < KPB) {
-        const int r = p / KP, pc = p - r * KP;
-        int key = k0 + r;
-        if (key >= kv_len) key = kv_len - 1;                    // masked at the scores
-        if (paged) {
-          const int pi = key / pt;
-          int page = pi < kv.max_pages ? table[pi] : -1;
-          if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
-          src = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + pc * 8;
-        } else {
-          src = kslab + ((int64_t)kvh * kv.tpad + pcol + key) * DH + pc * 8;
-        }
-      } else {
-        const int q = p - KPB, ch = q >> 3, kg = q & 7;
-        int key = k0 + kg * 8;
-        if (key >= kv_len) key = (kv_len - 1) & ~7;             // zeroed when it is put into LDS
-        if (paged) {
-          const int pi = key / pt;
-          int page = pi < kv.max_pages ? table[pi] : -1;
-          if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
-          src = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + ch) * pt + (key - pi * pt);
-        } else {
-          src = vslab + ((int64_t)kvh * DH + ch) * kv.tpad + pcol + key;
-        }
+      for (int i = 0; i < MAXP; ++i) {
+        const int pi = piece_key(i, kb64) >> sh;
+        const int v = table[pi < kv.max_pages ? pi : kv.max_pages - 1];
+        pg[i] = pi < kv.max_pages ? v : -1;
       }
-      reg[i] = *(const u32x4*)src;
     }
   };
-  // V^T elements of keys beyond the sequence become zero here: their probability is zero, and
-  // zero times whatever the pool holds there must stay zero
-  auto commit = [&](const u32x4 (&reg)[MAXP], int buf, int kb64) {
+  auto issue = [&](u32x4 (&reg)[MAXP], const int (&pg)[MAXP], int kb64, uint32_t& vbad) {
+    vbad = 0;
+#pragma unroll
+    for (int i = 0; i < MAXP; ++i) {
+      const int p = tid + i * nthr;
+      const int key = piece_key(i, kb64);
+      int64_t off;
+      if (i * nthr < KPB) {
+        const int pc = p % KP;
+        if constexpr (PAGED) {
+          const bool ok = (uint32_t)pg[i] < (uint32_t)kv.n_pages;
+          bad |= !ok;
+          off = ((((int64_t)(ok ? pg[i] : 0) * kv.n_kv_heads + kvh) << sh) + (key & (pt - 1))) * DH + pc * 8;
+        } else {
+          off = ((int64_t)kvh * kv.tpad + pcol + key) * DH + pc * 8;
+        }
+        reg[i] = *(const u32x4*)(kslab + off);
+      } else {
+        const int ch = (p - KPB) >> 3;
+        if constexpr (PAGED) {
+          const bool ok = (uint32_t)pg[i] < (uint32_t)kv.n_pages;
+          bad |= !ok;
+          vbad |= ok ? 0u : (1u << i);
+          off = ((((int64_t)(ok ? pg[i] : 0) * kv.n_kv_heads + kvh) * DH + ch) << sh) + (key & (pt - 1));
+        } else {
+          off = ((int64_t)kvh * DH + ch) * kv.tpad + pcol + key;
+        }
+        reg[i] = *(const u32x4*)(vslab + off);
+      }
+    }
+  };
+  // V^T elements of keys beyond the sequence (or of a page that is not addressable) become zero
+  // here: their probability is zero, and zero times whatever the pool holds there must stay zero
+  auto commit = [&](const u32x4 (&reg)[MAXP], int buf, int kb64, uint32_t vbad) {
     u32x4* dk = &sk[buf][0][0][0][0];
     u32x4* dv = &sv[buf][0][0][0];
 #pragma unroll
     for (int i = 0; i < MAXP; ++i) {
-      int p = tid + i * nthr;
-      p = p < NP ? p : NP - 1;
-      if (p < KPB) {
+      const int p = tid + i * nthr;
+      if (i * nthr < KPB) {
         const int r = p / KP, pc = p - r * KP;
         const int half = r >> 5, r32 = r & 31, aa = r32 >> 3, bb = r32 & 7;
         const int tt = bb >> 2, cc = 4 * aa + (bb & 3);         // key 8a+b of a half sits in tile b/4, row 4a + b%4
         dk[(((half * 2 + tt) * KK + (pc >> 2)) * 64) + (pc & 3) * 16 + (cc ^ (4 * (pc & 3)) ^ (pc >> 2))] = reg[i];
       } else {
         const int q = p - KPB, ch = q >> 3, kg = q & 7;
-        const int valid = kv_len - ((kb64 << 6) + kg * 8);      // elements of this piece inside the sequence
+        int valid = kv_len - ((kb64 << 6) + kg * 8);            // elements of this piece inside the sequence
+        if (vbad & (1u << i)) valid = 0;
         u32x4 v = reg[i];
-        if (valid < 8) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (valid <= 2 * e) v[e] = 0u;
-            else if (valid == 2 * e + 1) v[e] &= 0x0000ffffu;
-          }
+        for (int e = 0; e < 4; ++e) {
+          uint32_t x = v[e];
+          x = valid > 2 * e + 1 ? x : (x & 0x0000ffffu);
+          x = valid > 2 * e ? x : 0u;
+          v[e] = x;
         }
         dv[(((kg >> 2) * DT + (ch >> 4)) * 64) + (kg & 3) * 16 + ((ch & 15) ^ (4 * (kg & 3)) ^ (2 * (kg >> 2)))] = v;
       }
@@ -947,16 +966,26 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   if (unit < nkb) {
     const int last = unit + ((nkb - 1 - unit) / a.n_units) * a.n_units;
     u32x4 reg[MAXP];
-    issue(reg, unit);
-    commit(reg, 0, unit);
+    int pg[MAXP];
+    uint32_t vbad;
+    fetch_pages(pg, unit);
+    issue(reg, pg, unit, vbad);
+    {
+      const int nxt = unit + a.n_units;
+      fetch_pages(pg, nxt <= last ? nxt : last);
+    }
+    commit(reg, 0, unit, vbad);
     int buf = 0;
     for (int kb = unit; kb < nkb; kb += a.n_units) {
       __syncthreads();
       int nxt = kb + a.n_units;
       nxt = nxt <= last ? nxt : last;
-      issue(reg, nxt);
+      int nxt2 = nxt + a.n_units;
+      nxt2 = nxt2 <= last ? nxt2 : last;
+      issue(reg, pg, nxt, vbad);          // its page ids arrived during the previous block
+      fetch_pages(pg, nxt2);
       if (active) compute(buf, kb);
-      commit(reg, buf ^ 1, nxt);
+      commit(reg, buf ^ 1, nxt, vbad);
       buf ^= 1;
     }
   }
@@ -1030,6 +1059,11 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   a.kv = kv;
   a.Q = g.Q; a.Hq = f.n_q_heads; a.Hkv = f.n_kv_heads; a.B = g.B;
   a.n_units = (int)units; a.kspl = kspl; a.n_rg_wg = n_rg_wg;
+  a.pt_shift = 0;
+  if (g.Q > 0) {
+    a.pt_shift = -1;
+    for (int sft = 3; sft < 31; ++sft) if (f.page_tokens == (1 << sft)) a.pt_shift = sft;
+  }
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)f.head_dim);
   a.part_o = WSM(c, attn_part, float);
   a.part_ml = a.part_o + (size_t)c->map.attn_rows * f.head_dim;
@@ -1037,14 +1071,15 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   dim3 grid((unsigned)(units / kspl), n_chunks, g.B * f.n_kv_heads);
   const int threads = 64 * n_rg_wg * kspl;
   static const int no_lds = getenv("DLLM_NO_ATTN_LDS") ? 1 : 0;   // tuning aid
-  if (n_rg >= 4 && !no_lds) {
+  if (n_rg >= 4 && !no_lds && a.pt_shift >= 0) {
     // many rows per kv head: K/V staged once per workgroup in LDS (at least 4 waves load)
+    const bool paged = g.Q > 0;
     if (f.head_dim == 128) {
-      if (n_rg_wg <= 4) k_attn_lds<128, 4><<<grid, 256, 0, s>>>(a);
-      else k_attn_lds<128, 8><<<grid, 512, 0, s>>>(a);
+      if (n_rg_wg <= 4) { if (paged) k_attn_lds<128, 4, true><<<grid, 256, 0, s>>>(a); else k_attn_lds<128, 4, false><<<grid, 256, 0, s>>>(a); }
+      else { if (paged) k_attn_lds<128, 8, true><<<grid, 512, 0, s>>>(a); else k_attn_lds<128, 8, false><<<grid, 512, 0, s>>>(a); }
     } else {
-      if (n_rg_wg <= 4) k_attn_lds<64, 4><<<grid, 256, 0, s>>>(a);
-      else k_attn_lds<64, 8><<<grid, 512, 0, s>>>(a);
+      if (n_rg_wg <= 4) { if (paged) k_attn_lds<64, 4, true><<<grid, 256, 0, s>>>(a); else k_attn_lds<64, 4, false><<<grid, 256, 0, s>>>(a); }
+      else { if (paged) k_attn_lds<64, 8, true><<<grid, 512, 0, s>>>(a); else k_attn_lds<64, 8, false><<<grid, 512, 0, s>>>(a); }
     }
   } else if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
   else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
@@ -1076,13 +1111,20 @@ constexpr int LG_BN = 128, LG_BK = 64;
 // reads stay a permutation of the KiB, and the loader's 16 consecutive lanes (two rows x eight
 // 16-byte columns of a slice) write 16 different bank groups instead of two.
 __device__ __forceinline__ int lg_swz(int g, int ks) { return (4 * g) ^ (2 * ks); }
-enum LgEpi { LG_STORE = 0, LG_STORE_F32 = 1, LG_RESID = 2, LG_SWIGLU = 3, LG_LMSTATS = 4 };
+enum LgEpi { LG_STORE = 0, LG_STORE_F32 = 1, LG_RESID = 2, LG_SWIGLU = 3, LG_LMSTATS = 4, LG_QKV = 5 };
 
 struct LgArgs {
   const bf16_t* A;
   const bf16_t* W;
-  const bf16_t* W2;        // SWIGLU: up projection
+  const bf16_t* W2;        // SWIGLU: up projection; QKV: key projection
+  const bf16_t* W3;        // QKV: value projection
   void* C;
+  void* C2;                // QKV: float keys
+  void* C3;                // QKV: bfloat16 values
+  int N2, tiles_n1, tiles_n2;   // QKV: width of the key/value projections, column tiles of q and of k
+  int k_per;               // RESID: K range of one split (multiple of LG_BK); gridDim.y splits
+  float* delta;            // RESID: products of splits 1.. go to delta[(split - 1) * delta_stride + m * N + n]
+  int64_t delta_stride;
   const int32_t* m_dev;    // optional device row count
   int M, N, K, tiles_m, tiles_n;
   float* part;             // LMSTATS: [rows, n_parts, 4]
@@ -1094,7 +1136,8 @@ template <int BM, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   constexpr int TM = BM / 16;                 // 16-row token tiles of the block
   constexpr int WT = BM / 32;                 // token tiles per wave
-  constexpr int NW2 = (EPI == LG_SWIGLU) ? 2 : 1;
+  constexpr int NW2 = 1;
+  constexpr int TILE_N = (EPI == LG_SWIGLU) ? LG_BN / 2 : LG_BN;   // output features of a tile
   constexpr int PA = BM / 32;                 // 16-byte pieces of A per thread and slice (BM*8/256)
   __shared__ u32x4 sa[2][2][TM][64];          // [buffer][k-step][token tile][lane]
   __shared__ u32x4 sw[2][NW2][2][8][64];      // [buffer][matrix][k-step][weight tile][lane]
@@ -1102,16 +1145,33 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   const int c = lane & 15, g = lane >> 4;
   int M = a.M;
   if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
-  const int N = a.N, K = a.K;
+  int N = a.N;
+  const int K = a.K;
   // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
   // contiguous run of tiles (m fastest) and let its L2 keep the weight block they share
   const int n_tiles = a.tiles_m * a.tiles_n;
   const int per_xcd = (n_tiles + 7) / 8;
   const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile >= n_tiles) return;
-  const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
-  const int m0 = tm * BM, n0 = tn * LG_BN;
+  int tn = tile / a.tiles_m;
+  const int tm = tile - tn * a.tiles_m;
+  // QKV: the column tiles of the three projections follow each other; a tile belongs to one of them
+  const bf16_t* Wsel = a.W;
+  void* Csel = a.C;
+  bool out_f32 = EPI == LG_STORE_F32;
+  if constexpr (EPI == LG_QKV) {
+    out_f32 = true;
+    if (tn >= a.tiles_n1 + a.tiles_n2) { tn -= a.tiles_n1 + a.tiles_n2; Wsel = a.W3; Csel = a.C3; N = a.N2; out_f32 = false; }
+    else if (tn >= a.tiles_n1) { tn -= a.tiles_n1; Wsel = a.W2; Csel = a.C2; N = a.N2; }
+  }
+  const int m0 = tm * BM, n0 = tn * TILE_N;
   if (m0 >= M) return;
+  // RESID: this workgroup's share of K
+  int k_begin = 0, k_end = K;
+  if constexpr (EPI == LG_RESID) {
+    k_begin = blockIdx.y * a.k_per;
+    k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
+  }
   const int wm = (w & 1) * (BM / 2), wn = (w >> 1) * 64;
 
   // loader: piece p = tid + 256*q of a [rows][8 pieces] slice: row p/8, 16-byte column p%8
@@ -1131,16 +1191,22 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     const int p = tid + 256 * q, r = p >> 3, kc = p & 7;
     kcw[q] = kc * 8;
     dstw[q] = ((kc >> 2) * 8 + (r >> 4)) * 64 + (kc & 3) * 16 + ((r & 15) ^ lg_swz(kc & 3, kc >> 2));
-    int rw = n0 + r; rw = rw < N ? rw : N - 1;
-    gw[0][q] = a.W + (int64_t)rw * K;
-    if constexpr (NW2 == 2) gw[1][q] = a.W2 + (int64_t)rw * K;
+    if constexpr (EPI == LG_SWIGLU) {
+      // a wave's four weight tiles are gate, gate, up, up of the same 32 features: both factors of
+      // silu(gate) * up meet in one lane
+      int rw = n0 + (r >> 6) * 32 + ((r >> 4) & 1) * 16 + (r & 15); rw = rw < N ? rw : N - 1;
+      gw[0][q] = (((r >> 5) & 1) ? a.W2 : a.W) + (int64_t)rw * K;
+    } else {
+      int rw = n0 + r; rw = rw < N ? rw : N - 1;
+      gw[0][q] = Wsel + (int64_t)rw * K;
+    }
   }
   struct Stage { u32x4 ra[PA]; u32x4 rw[NW2][4]; };
   auto issue = [&](Stage& st, int k0) {   // loads are clamped, never branched
 #pragma unroll
     for (int q = 0; q < PA; ++q) {
       int k = k0 + kca[q];
-      const bool ok = k + 8 <= K;
+      const bool ok = k + 8 <= k_end;
       k = ok ? k : K - 8;
       const u32x4 v = *(const u32x4*)(ga[q] + k);
       st.ra[q] = ok ? v : u32x4{0, 0, 0, 0};
@@ -1150,7 +1216,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         int k = k0 + kcw[q];
-        const bool ok = k + 8 <= K;
+        const bool ok = k + 8 <= k_end;
         k = ok ? k : K - 8;
         const u32x4 v = *(const u32x4*)(gw[x][q] + k);
         st.rw[x][q] = ok ? v : u32x4{0, 0, 0, 0};
@@ -1195,25 +1261,47 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     }
   };
 
-  const int nk = (K + LG_BK - 1) / LG_BK;
+  const int nk = (k_end - k_begin + LG_BK - 1) / LG_BK;
   const int last = nk - 1;
   Stage s0, s1;
-  issue(s0, 0);
-  issue(s1, (1 < last ? 1 : last) * LG_BK);
+  issue(s0, k_begin);
+  issue(s1, k_begin + (1 < last ? 1 : last) * LG_BK);
   commit(s0, 0);
   // slice kt is multiplied from LDS[kt&1] while slice kt+1 waits in registers and slice kt+2 is in flight
   for (int kt = 0; kt < nk; kt += 2) {
     __syncthreads();
-    issue(s0, (kt + 2 < last ? kt + 2 : last) * LG_BK);
+    issue(s0, k_begin + (kt + 2 < last ? kt + 2 : last) * LG_BK);
     compute(0);
     commit(s1, 1);
     __syncthreads();
-    issue(s1, (kt + 3 < last ? kt + 3 : last) * LG_BK);
+    issue(s1, k_begin + (kt + 3 < last ? kt + 3 : last) * LG_BK);
     if (kt + 1 < nk) compute(1);
     commit(s0, 0);
   }
 
   // lane holds token column c of token tile j, features 4g..4g+3 of weight tile i
+  if (EPI == LG_SWIGLU) {
+#pragma unroll
+    for (int j = 0; j < WT; ++j) {
+      const int m = m0 + wm + j * 16 + c;
+      if (m >= M) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int n = n0 + (wn >> 1) + i * 16 + 4 * g;
+        f32x4 v = acc[0][i][j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * acc[0][i + 2][j][e];
+        if (n + 4 <= N) {
+          *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) =
+              make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
+                         (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
+        } else {
+          for (int e = 0; e < 4 && n + e < N; ++e) ((bf16_t*)a.C)[(int64_t)m * N + n + e] = f32_to_bf16(v[e]);
+        }
+      }
+    }
+    return;
+  }
   if (EPI == LG_LMSTATS) {
 #pragma unroll
     for (int j = 0; j < WT; ++j) {
@@ -1248,28 +1336,30 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     for (int i = 0; i < 4; ++i) {
       const int n = n0 + wn + i * 16 + 4 * g;
       f32x4 v = acc[0][i][j];
-      if (EPI == LG_SWIGLU) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * acc[NW2 - 1][i][j][e];
-      }
       if (n + 4 <= N) {
         const int64_t at = (int64_t)m * N + n;
-        if (EPI == LG_STORE || EPI == LG_SWIGLU) {
-          *(uint2*)((bf16_t*)a.C + at) = make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
-                                                    (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
-        } else if (EPI == LG_STORE_F32) {
-          *(f32x4*)((float*)a.C + at) = v;
+        if (EPI == LG_RESID) {
+          if (blockIdx.y == 0) {
+            f32x4* p = (f32x4*)((float*)a.C + at);
+            *p = *p + v;
+          } else {
+            *(f32x4*)(a.delta + (int64_t)(blockIdx.y - 1) * a.delta_stride + at) = v;
+          }
+        } else if (out_f32) {
+          *(f32x4*)((float*)Csel + at) = v;
         } else {
-          f32x4* p = (f32x4*)((float*)a.C + at);
-          *p = *p + v;
+          *(uint2*)((bf16_t*)Csel + at) = make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
+                                                     (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
         }
       } else {
         for (int e = 0; e < 4; ++e) {
           if (n + e >= N) break;
           const int64_t at = (int64_t)m * N + n + e;
-          if (EPI == LG_STORE || EPI == LG_SWIGLU) ((bf16_t*)a.C)[at] = f32_to_bf16(v[e]);
-          else if (EPI == LG_STORE_F32) ((float*)a.C)[at] = v[e];
-          else ((float*)a.C)[at] += v[e];
+          if (EPI == LG_RESID) {
+            if (blockIdx.y == 0) ((float*)a.C)[at] += v[e];
+            else a.delta[(int64_t)(blockIdx.y - 1) * a.delta_stride + at] = v[e];
+          } else if (out_f32) ((float*)Csel)[at] = v[e];
+          else ((bf16_t*)Csel)[at] = f32_to_bf16(v[e]);
         }
       }
     }
@@ -1277,7 +1367,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
 }
 
 template <int EPI>
-static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256) {
+static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256, int k_splits = 1) {
   // Two 128-row workgroups per CU measure 2.3x faster than one 256-row workgroup (LM head, 512 rows):
   // with a single wave per SIMD nothing covers the LDS and barrier waits.  The 256-row form stays
   // selectable for tuning.
@@ -1286,11 +1376,15 @@ static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256) {
   const bool big = allow_256 && t256 >= 256 && force256;
   const int bm = big ? 256 : 128;
   a.tiles_m = (a.M + bm - 1) / bm;
-  a.tiles_n = (a.N + LG_BN - 1) / LG_BN;
-  const int grid = (a.tiles_m * a.tiles_n + 7) / 8 * 8;
-  if constexpr (EPI != LG_SWIGLU) {     // two weight matrices at 256 rows would not fit the register file
-    if (big) { k_gemm_mfma<256, EPI><<<grid, 256, 0, s>>>(a); return hipGetLastError(); }
+  constexpr int tile_n = EPI == LG_SWIGLU ? LG_BN / 2 : LG_BN;
+  a.tiles_n = (a.N + tile_n - 1) / tile_n;
+  if constexpr (EPI == LG_QKV) {
+    a.tiles_n1 = a.tiles_n;
+    a.tiles_n2 = (a.N2 + LG_BN - 1) / LG_BN;
+    a.tiles_n = a.tiles_n1 + 2 * a.tiles_n2;
   }
+  const dim3 grid((a.tiles_m * a.tiles_n + 7) / 8 * 8, k_splits);
+  if (big) { k_gemm_mfma<256, EPI><<<grid, 256, 0, s>>>(a); return hipGetLastError(); }
   k_gemm_mfma<128, EPI><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -1302,7 +1396,39 @@ hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = C; a.M = M; a.N = N; a.K = K;
   if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a, true);
   if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a, true);
+  a.k_per = (K + LG_BK - 1) / LG_BK * LG_BK;
   return lg_launch<LG_RESID>(s, a, true);
+}
+
+// x[M,N] += A[M,K] W[N,K]^T with the sum over K split while that fills the chip better: split 0 adds
+// into x, the others store their products for the next RMSNorm (or fold) to add, in split order.
+hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
+                                   int* n_delta) {
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = x; a.M = M; a.N = N; a.K = K;
+  const int tiles = ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
+  int splits = 512 / tiles;                                   // two workgroups fit a CU
+  if (splits > LG_MAX_DELTA + 1) splits = LG_MAX_DELTA + 1;
+  while (splits > 1 && K / splits < 512) --splits;
+  if (splits < 1 || M > c->map.lg_delta_rows || N != c->cfg.d_model) splits = 1;
+  a.k_per = ((K + splits - 1) / splits + LG_BK - 1) / LG_BK * LG_BK;
+  splits = (K + a.k_per - 1) / a.k_per;
+  a.delta = (float*)(c->ws + c->map.delta);
+  a.delta_stride = c->map.lg_delta_stride;
+  *n_delta = splits - 1;
+  return lg_launch<LG_RESID>(s, a, true, splits);
+}
+
+// q32[M,dq], k32[M,dkv] (float) and v[M,dkv] (bfloat16) = A[M,K] times the three projections, one launch
+hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
+                           float* k32, void* v, int M, int dq, int dkv, int K) {
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
+  a.C = q32; a.C2 = k32; a.C3 = v;
+  a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
+  return lg_launch<LG_QKV>(s, a, false);
 }
 
 // h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
