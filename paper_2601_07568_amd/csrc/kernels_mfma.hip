@@ -1123,6 +1123,7 @@ struct LgArgs {
   void* C3;                // QKV: bfloat16 values
   int N2, tiles_n1, tiles_n2;   // QKV: width of the key/value projections, column tiles of q and of k
   int k_per;               // RESID: K range of one split (multiple of LG_BK); gridDim.y splits
+  int k_splits;            // 256-row kernel: number of K splits (its grid is flat)
   float* delta;            // RESID: products of splits 1.. go to delta[(split - 1) * delta_stride + m * N + n]
   int64_t delta_stride;
   const int32_t* m_dev;    // optional device row count
@@ -1366,6 +1367,276 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same products for at least 256 token rows, arranged for one wave per SIMD: a workgroup of 4
+// waves owns a 256 x 256 tile, each wave 128 x 128 of it as 4 x 4 instructions of 32 x 32 x 16 with
+// the 256 accumulator registers in the accumulation file.  Both operands stay row-major in memory
+// and are copied straight into LDS (no register pass) in 32-deep K stages of a 4-stage ring, 16 rows
+// x 64 bytes per wave instruction, the 16-byte pieces of a row xor-ed with bits 2..3 of the row so
+// that a fragment read (32 rows x one piece) touches every bank once.  Per stage a wave issues its
+// share of the copies for three stages ahead and reads the next operands between the products of
+// the current ones; the only wait on memory is "the stage after this one has landed", once per
+// stage, in the middle of the products.
+constexpr int T2_NS = 4, T2_STAGE = 32768, T2_LDS = T2_NS * T2_STAGE;
+#define T2_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void t2_copy16(const void* g, void* l) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)l, 16, 0, 0);
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char t2_smem[];
+  unsigned char* smem = t2_smem;
+  constexpr int TILE_N = (EPI == LG_SWIGLU) ? 128 : 256;      // output features of a tile
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  int M = a.M;
+  if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
+  const int N = a.N, K = a.K;
+  const int wm = w & 1, wn = w >> 1;
+  const int r = lane & 31, h = lane >> 5;
+  // Persistent workgroups, one per CU: the work items (K split, column tile, row tile - row tile
+  // fastest, only row tiles that hold rows) are dealt in contiguous runs to the 8 XCDs (workgroups
+  // go round-robin to XCDs), inside an XCD round-robin to its workgroups, so the row tiles that
+  // share a weight tile run at the same time next to the same L2.
+  const int tiles_m = (M + 255) / 256;
+  const int n_tiles = tiles_m * a.tiles_n;
+  const int n_items = n_tiles * a.k_splits;
+  const int per_xcd = (n_items + 7) / 8;
+  for (int iw = blockIdx.x >> 3; iw < per_xcd; iw += gridDim.x >> 3) {
+  const int item = (blockIdx.x & 7) * per_xcd + iw;
+  if (item >= n_items) break;
+  const int split = item / n_tiles, tile = item - split * n_tiles;
+  const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+  const int m0 = tm * 256, n0 = tn * TILE_N;
+  int k_begin = 0, k_end = K;
+  if constexpr (EPI == LG_RESID) {
+    k_begin = split * a.k_per;
+    k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
+  }
+  // the ring is free once every wave has read the previous item's last operands
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  // copies: instruction q of this wave covers rows (w*4 + q%4)*16 .. +15 of the token part (q < 4) or of
+  // the weight part; lane p: row p/4, LDS piece p%4 holds source piece (p%4) ^ ((row>>2)&3)
+  const bf16_t* gsrc[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int r = (w * 4 + (q & 3)) * 16 + (lane >> 2);
+    const int piece = (lane & 3) ^ ((r >> 2) & 3);
+    if (q < 4) {
+      int row = m0 + r; row = row < M ? row : M - 1;
+      gsrc[q] = a.A + (int64_t)row * K + piece * 8;
+    } else if constexpr (EPI == LG_SWIGLU) {
+      // a wave's four weight tiles are gate, gate, up, up of the same 64 features
+      int row = n0 + (r >> 7) * 64 + ((r >> 5) & 1) * 32 + (r & 31); row = row < N ? row : N - 1;
+      gsrc[q] = (((r >> 6) & 1) ? a.W2 : a.W) + (int64_t)row * K + piece * 8;
+    } else {
+      int row = n0 + r; row = row < N ? row : N - 1;
+      gsrc[q] = a.W + (int64_t)row * K + piece * 8;
+    }
+  }
+  // fragment reads: lane (r = l%32, h = l/32), k-step s of a stage: piece 2s + h
+  int offA[2], offW[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int slotp = ((2 * ks + h) ^ ((r >> 2) & 3)) * 16;
+    offA[ks] = (wm * 128 + r) * 64 + slotp;
+    offW[ks] = 16384 + (wn * 128 + r) * 64 + slotp;
+  }
+  f32x16 acc[4][4];   // [weight tile][token tile]
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int ns = (k_end - k_begin) / 32;      // K ranges are multiples of 32 (checked on the host)
+#define T2_MMA(ks, i, j)                                                                                          \
+  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[ks][i]),                    \
+                                                      __builtin_bit_cast(bf16x8, fa[ks][j]), acc[i][j], 0, 0, 0)
+  u32x4 fa[2][4], fw[2][4];
+#pragma unroll
+  for (int st = 0; st < T2_NS - 1; ++st) {
+    const int kd = k_begin + (st < ns ? st : ns - 1) * 32;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t2_copy16(gsrc[q] + kd, smem + st * T2_STAGE + (q >> 2) * 16384 + (w * 4 + (q & 3)) * 1024);
+  }
+  __builtin_amdgcn_s_waitcnt(T2_VMCNT(8 * (T2_NS - 2)));
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    fa[0][j] = *(const u32x4*)(smem + offA[0] + j * 2048);
+    fw[0][j] = *(const u32x4*)(smem + offW[0] + j * 2048);
+  }
+  for (int st = 0; st < ns; ++st) {
+    const unsigned char* base = smem + (st % T2_NS) * T2_STAGE;
+    const unsigned char* nbase = smem + ((st + 1) % T2_NS) * T2_STAGE;
+    unsigned char* dbase = smem + ((st + T2_NS - 1) % T2_NS) * T2_STAGE;   // freed by the barrier of the stage before
+    const int sn = st + T2_NS - 1;
+    const int kd = k_begin + (sn < ns ? sn : ns - 1) * 32;                  // past the end: a repeat into a free slot
+    // k-step 0: in the shadow of its products request the ring's next stage and read k-step 1's operands
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+      T2_MMA(0, i, 0); T2_MMA(0, i, 1); T2_MMA(0, i, 2); T2_MMA(0, i, 3);
+      t2_copy16(gsrc[2 * i] + kd, dbase + ((2 * i) >> 2) * 16384 + (w * 4 + ((2 * i) & 3)) * 1024);
+      t2_copy16(gsrc[2 * i + 1] + kd, dbase + ((2 * i + 1) >> 2) * 16384 + (w * 4 + ((2 * i + 1) & 3)) * 1024);
+      fa[1][i] = *(const u32x4*)(base + offA[1] + i * 2048);
+      fw[1][i] = *(const u32x4*)(base + offW[1] + i * 2048);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // k-step 1: wait until every wave's copies of the next stage have landed (all but the two
+    // youngest stages of this wave's own), then read that stage's first operands
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+      T2_MMA(1, i, 0); T2_MMA(1, i, 1); T2_MMA(1, i, 2); T2_MMA(1, i, 3);
+      if (i == 0) {
+        __builtin_amdgcn_s_waitcnt(T2_VMCNT(8 * (T2_NS - 2)));
+        __builtin_amdgcn_s_barrier();
+      }
+      if (i == 1) { fa[0][0] = *(const u32x4*)(nbase + offA[0]); fa[0][1] = *(const u32x4*)(nbase + offA[0] + 2048); fa[0][2] = *(const u32x4*)(nbase + offA[0] + 4096); }
+      if (i == 2) { fa[0][3] = *(const u32x4*)(nbase + offA[0] + 6144); fw[0][0] = *(const u32x4*)(nbase + offW[0]); fw[0][1] = *(const u32x4*)(nbase + offW[0] + 2048); }
+      if (i == 3) { fw[0][2] = *(const u32x4*)(nbase + offW[0] + 4096); fw[0][3] = *(const u32x4*)(nbase + offW[0] + 6144); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#undef T2_MMA
+  __builtin_amdgcn_s_waitcnt(T2_VMCNT(0));   // the ring's trailing repeats must not outlive the workgroup
+
+  // lane holds token column l%32 of token tile j; features (e/4)*8 + (l/32)*4 + e%4 of weight tile i
+  if constexpr (EPI == LG_LMSTATS) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + wm * 128 + j * 32 + r;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {      // 64 columns per partial
+        // the lane's 32 logits of this partial: maximum first (columns ascend, so the first of equal
+        // maxima is the lowest), then the two sums against it
+        float mx = -DEV_INF;
+        int ix = 0x7fffffff;
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int i = half * 2 + ii;
+            const int n = n0 + wn * 128 + i * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+            const float z = acc[i][j][e];
+            if (n < N && n != a.mask_id && z > mx) { mx = z; ix = n; }
+          }
+        RowStat st;
+        st.init();
+        if (ix != 0x7fffffff) {
+          float se = 0.f, sz = 0.f;
+#pragma unroll
+          for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int i = half * 2 + ii;
+              const int n = n0 + wn * 128 + i * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+              const float z = acc[i][j][e];
+              const float ex = (n < N && n != a.mask_id) ? __builtin_amdgcn_exp2f((z - mx) * 1.4426950408889634f) : 0.f;
+              se += ex;
+              sz = fmaf(ex, z, sz);
+            }
+          st.m = mx; st.idx = ix; st.s = se; st.t = sz;
+        }
+        const float m2 = __shfl_xor(st.m, 32, 64), s2 = __shfl_xor(st.s, 32, 64), t2 = __shfl_xor(st.t, 32, 64);
+        const int i2 = __shfl_xor(st.idx, 32, 64);
+        st.merge(m2, i2, s2, t2);
+        const int nb = n0 + wn * 128 + half * 64;
+        if (h == 0 && m < M && nb < N) {
+          float* o = a.part + ((int64_t)m * a.n_parts + nb / 64) * 4;
+          *(f32x4*)o = f32x4{st.m, __int_as_float(st.idx), st.s, st.t};
+        }
+      }
+    }
+  } else {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int m = m0 + wm * 128 + j * 32 + r;
+    if (m >= M) continue;
+    if constexpr (EPI == LG_SWIGLU) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int n = n0 + wn * 64 + i * 32 + e4 * 8 + h * 4;
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float gt = acc[i][j][e4 * 4 + e];
+            v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[i + 2][j][e4 * 4 + e];
+          }
+          if (n + 4 <= N) {
+            *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          } else {
+            for (int e = 0; e < 4 && n + e < N; ++e) ((bf16_t*)a.C)[(int64_t)m * N + n + e] = f32_to_bf16(v[e]);
+          }
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int n = n0 + wn * 128 + i * 32 + e4 * 8 + h * 4;
+          const f32x4 v = f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+          const int64_t at = (int64_t)m * N + n;
+          if (n + 4 <= N) {
+            if (split == 0) { f32x4* p = (f32x4*)((float*)a.C + at); *p = *p + v; }
+            else *(f32x4*)(a.delta + (int64_t)(split - 1) * a.delta_stride + at) = v;
+          } else {
+            for (int e = 0; e < 4 && n + e < N; ++e) {
+              if (split == 0) ((float*)a.C)[at + e] += v[e];
+              else a.delta[(int64_t)(split - 1) * a.delta_stride + at + e] = v[e];
+            }
+          }
+        }
+    }
+  }
+  }   // store epilogues
+  }   // work items
+}
+
+// the 256 x 256 form needs the whole ring in LDS: more than the default limit of a kernel
+static bool t2_ready = false;
+static int t2_cus = 256;
+hipError_t init_gemm_t256() {
+  if (t2_ready) return hipSuccess;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        cus >= 8)
+      t2_cus = cus / 8 * 8;
+  }
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_LMSTATS>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
+  t2_ready = e == hipSuccess;
+  return e;
+}
+
+template <int EPI>
+static hipError_t t2_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
+  constexpr int tile_n = EPI == LG_SWIGLU ? 128 : 256;
+  a.tiles_m = (a.M + 255) / 256;
+  a.tiles_n = (a.N + tile_n - 1) / tile_n;
+  a.k_splits = k_splits;
+  if (EPI != LG_RESID) a.k_per = a.K;
+  const int items = a.tiles_m * a.tiles_n * k_splits;
+  const int grid = items < t2_cus ? (items + 7) / 8 * 8 : t2_cus;   // one persistent workgroup per CU
+  k_gemm_t256<EPI><<<grid, 256, T2_LDS, s>>>(a);
+  return hipGetLastError();
+}
+static bool t2_usable(int M, int K) {
+  static const int off = getenv("DLLM_NO_T256") ? 1 : 0;   // tuning aid
+  return t2_ready && !off && M >= 256 && K % 32 == 0 && K >= 128;
+}
+
 template <int EPI>
 static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256, int k_splits = 1) {
   // Two 128-row workgroups per CU measure 2.3x faster than one 256-row workgroup (LM head, 512 rows):
@@ -1407,8 +1678,9 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = x; a.M = M; a.N = N; a.K = K;
-  const int tiles = ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
-  int splits = 512 / tiles;                                   // two workgroups fit a CU
+  const bool t2 = t2_usable(M, K) && K >= 8192;   // short sums: the 128-row tiles fill the chip better
+  const int tiles = t2 ? ((M + 255) / 256) * ((N + 255) / 256) : ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
+  int splits = (t2 ? 256 : 512) / tiles;                      // one 256-row workgroup or two 128-row ones fit a CU
   if (splits > LG_MAX_DELTA + 1) splits = LG_MAX_DELTA + 1;
   while (splits > 1 && K / splits < 512) --splits;
   if (splits < 1 || M > c->map.lg_delta_rows || N != c->cfg.d_model) splits = 1;
@@ -1417,6 +1689,7 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   a.delta = (float*)(c->ws + c->map.delta);
   a.delta_stride = c->map.lg_delta_stride;
   *n_delta = splits - 1;
+  if (t2) return t2_launch<LG_RESID>(s, a, splits);
   return lg_launch<LG_RESID>(s, a, true, splits);
 }
 
@@ -1437,6 +1710,7 @@ hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, cons
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
+  if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
   return lg_launch<LG_SWIGLU>(s, a, false);
 }
 
@@ -1451,6 +1725,7 @@ hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_
   a.n_parts = (f.vocab + 63) / 64;
   a.mask_id = f.mask_id;
   *n_parts_out = a.n_parts;
+  if (t2_usable(max_rows, a.K)) return t2_launch<LG_LMSTATS>(s, a);
   return lg_launch<LG_LMSTATS>(s, a, true);
 }
 
