@@ -599,6 +599,44 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
 }
 
 // x[T, d] += delta_0 + delta_1 + ..  (open residual sums; used where no RMSNorm follows)
+// row-major bfloat16 output, four elements per thread and pass (d % 4 == 0)
+__global__ __launch_bounds__(256) void k_rmsnorm_row4(int d, float eps, float* x, const bf16_t* gain, bf16_t* out,
+                                                      const int32_t* rows, const int32_t* n_rows_dev, const float* delta,
+                                                      int n_delta, int64_t delta_stride) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  int src = r;
+  if (rows) {
+    if (r >= *n_rows_dev) return;
+    src = rows[r];
+  }
+  float4* xr = (float4*)(x + (int64_t)src * d);
+  const int n4 = d >> 2;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 v = xr[i];
+    if (n_delta > 0) {      // open K splits of the last residual projection, added in split order
+      for (int sd = 0; sd < n_delta; ++sd) {
+        const float4 dv = ((const float4*)(delta + sd * delta_stride + (int64_t)src * d))[i];
+        v.x += dv.x; v.y += dv.y; v.z += dv.z; v.w += dv.w;
+      }
+      xr[i] = v;
+    }
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum(ss, red);
+  const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+  uint2* orow = (uint2*)(out + (int64_t)r * d);
+  for (int i = threadIdx.x; i < n4; i += 256) {   // a thread re-reads only what it wrote itself
+    const float4 v = xr[i];
+    const uint2 gq = ((const uint2*)gain)[i];
+    const float g0 = bf16_to_f32((bf16_t)(gq.x & 0xffff)), g1 = bf16_to_f32((bf16_t)(gq.x >> 16));
+    const float g2 = bf16_to_f32((bf16_t)(gq.y & 0xffff)), g3 = bf16_to_f32((bf16_t)(gq.y >> 16));
+    orow[i] = make_uint2((uint32_t)f32_to_bf16(v.x * rinv * g0) | ((uint32_t)f32_to_bf16(v.y * rinv * g1) << 16),
+                         (uint32_t)f32_to_bf16(v.z * rinv * g2) | ((uint32_t)f32_to_bf16(v.w * rinv * g3) << 16));
+  }
+}
+
 __global__ void k_fold_delta(int64_t n, float* x, const float* delta, int n_delta, int64_t delta_stride) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
@@ -620,6 +658,9 @@ hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, c
   if (IS_BF16(c) && frag_mt > 0 && f.d_model <= 16384)
     k_rmsnorm_frag<<<T, 512, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t),
                                      rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta, c->map.delta_stride);
+  else if (IS_BF16(c) && frag_mt == 0 && f.d_model % 4 == 0)
+    k_rmsnorm_row4<<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t), rows,
+                                     n_rows_dev, WS(c, delta, float), n_delta, c->map.lg_delta_stride);
   else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
                                         WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta,

@@ -16,10 +16,9 @@ SMALL = synth.ModelShape(2, 512, 8, 2, 128, 1408, 5000, 4999, dtype="bf16", lm_h
 SMALL64 = synth.ModelShape(1, 384, 6, 3, 64, 1000, 3000, 2999, dtype="bf16", lm_head_scale=8.0, name="small-dh64")
 
 
-def run_small(ms, lens, Q, n_masked, mode, seed=7):
+def run_small(ms, lens, Q, n_masked, mode, seed=7, mp=8):
     w = synth.Weights(ms, seed)
     Bn = len(lens)
-    mp = 8
     eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
                         max_tokens=sum(lens) + Bn * Q)
     eng.set_kernel_mode(mode)
@@ -75,6 +74,12 @@ def test_small_gqa_model(mode):
 @pytest.mark.parametrize("mode", [0, 1])
 def test_small_head_dim_64_model(mode):
     run_small(SMALL64, [45, 130, 64], 64, 40, mode)
+
+
+def test_small_model_256_query_rows_and_long_prefill():
+    """Four sequences x 64 query rows and a 539-token prefill: the 256-row tiles of the large GEMM path with
+    ragged feature counts (1000 MLP features, 3000 vocabulary entries) and a ragged last row tile."""
+    run_small(SMALL64, [45, 130, 64, 300], 64, 40, 0, mp=12)
 
 
 def test_llada_shaped_layer_and_head_full_size():
