@@ -51,8 +51,9 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->q = take(t_max * dq * es);
   m->tpad = c->max_tokens > 0 ? (int64_t)c->max_tokens + 32 * (int64_t)c->max_batch : 0;
   m->v = take(t_max * dkv * es);
-  m->kpack = take((size_t)m->tpad * dkv * es);
-  m->vpack = take((size_t)m->tpad * dkv * es);
+  // 64 rows / 64 keys of slack: the staged attention reads whole 64-key blocks, also a sequence's last one
+  m->kpack = take(((size_t)m->tpad + 64) * dkv * es);
+  m->vpack = take(((size_t)m->tpad * dkv + 64) * es);
   m->cu_pad = take(((size_t)c->max_batch + 1) * 4);
   m->o = take((t_max + 16) * (dq + 128) * es);
   m->g = take(t_max * c->d_ff * 4);

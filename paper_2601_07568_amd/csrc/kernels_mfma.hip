@@ -791,7 +791,7 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const
 // loader's consecutive lanes, which walk along a row, hit different banks); two LDS buffers, the
 // next block in flight in registers while the current one is multiplied.  Arithmetic, masking and
 // outputs are those of k_attn_step.
-template <int DH, int NW, bool PAGED>
+template <int DH, int NW, bool PAGED, bool FAST>
 __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   constexpr int KK = DH / 32, DT = DH / 16, QT = 2;
   constexpr int KP = DH / 8;                 // 16-byte pieces of a K row
@@ -849,8 +849,23 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
     const int key = (kb64 << 6) + ((p - KPB) & 7) * 8;
     return key < kv_len ? key : (kv_len - 1) & ~7;              // zeroed when it is put into LDS
   };
+  // FAST: a 64-key block lies inside one page (page size a multiple of 64) or in the packed scratch, so
+  // its K rows are 64 * DH contiguous elements and its V^T rows 64 contiguous keys per channel: one
+  // base per block (wave-uniform) plus a per-thread constant.  Rows past the sequence end are read
+  // as they are (inside the page, or inside the workspace) and masked or zeroed later.
+  int koff[MAXP];
+#pragma unroll
+  for (int i = 0; i < MAXP; ++i) {
+    const int p = tid + i * nthr;
+    if (i * nthr < KPB) koff[i] = p * 8;
+    else koff[i] = ((p - KPB) >> 3) * (PAGED ? pt : kv.tpad) + ((p - KPB) & 7) * 8;
+  }
   auto fetch_pages = [&](int (&pg)[MAXP], int kb64) {
-    if constexpr (PAGED) {
+    if constexpr (PAGED && FAST) {
+      const int pi = (kb64 << 6) >> sh;
+      const int v = table[pi < kv.max_pages ? pi : kv.max_pages - 1];
+      pg[0] = pi < kv.max_pages ? v : -1;
+    } else if constexpr (PAGED) {
 #pragma unroll
       for (int i = 0; i < MAXP; ++i) {
         const int pi = piece_key(i, kb64) >> sh;
@@ -861,6 +876,27 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   };
   auto issue = [&](u32x4 (&reg)[MAXP], const int (&pg)[MAXP], int kb64, uint32_t& vbad) {
     vbad = 0;
+    if constexpr (FAST) {
+      const int k0 = kb64 << 6;
+      int64_t kb, vb;
+      if constexpr (PAGED) {
+        const int page = __builtin_amdgcn_readfirstlane(pg[0]);
+        const bool ok = (uint32_t)page < (uint32_t)kv.n_pages;
+        bad |= !ok;
+        vbad = ok ? 0u : 0xffffffffu;
+        const int64_t rows = (((int64_t)(ok ? page : 0) * kv.n_kv_heads + kvh) << sh);
+        kb = (rows + (k0 & (pt - 1))) * DH;
+        vb = rows * DH + (k0 & (pt - 1));
+      } else {
+        kb = ((int64_t)kvh * kv.tpad + pcol + k0) * DH;
+        vb = (int64_t)kvh * DH * kv.tpad + pcol + k0;
+      }
+      const bf16_t* kp = kslab + kb;
+      const bf16_t* vp = vslab + vb;
+#pragma unroll
+      for (int i = 0; i < MAXP; ++i) reg[i] = *(const u32x4*)((i * nthr < KPB ? kp : vp) + koff[i]);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < MAXP; ++i) {
       const int p = tid + i * nthr;
@@ -895,6 +931,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   auto commit = [&](const u32x4 (&reg)[MAXP], int buf, int kb64, uint32_t vbad) {
     u32x4* dk = &sk[buf][0][0][0][0];
     u32x4* dv = &sv[buf][0][0][0];
+    const bool fix = (kb64 << 6) + 64 > kv_len || __builtin_amdgcn_ballot_w64(vbad != 0) != 0;
 #pragma unroll
     for (int i = 0; i < MAXP; ++i) {
       const int p = tid + i * nthr;
@@ -905,15 +942,17 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
         dk[(((half * 2 + tt) * KK + (pc >> 2)) * 64) + (pc & 3) * 16 + (cc ^ (4 * (pc & 3)) ^ (pc >> 2))] = reg[i];
       } else {
         const int q = p - KPB, ch = q >> 3, kg = q & 7;
-        int valid = kv_len - ((kb64 << 6) + kg * 8);            // elements of this piece inside the sequence
-        if (vbad & (1u << i)) valid = 0;
         u32x4 v = reg[i];
+        if (fix) {                                              // only a sequence's last block, or a bad page
+          int valid = kv_len - ((kb64 << 6) + kg * 8);          // elements of this piece inside the sequence
+          if (vbad & (1u << i)) valid = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          uint32_t x = v[e];
-          x = valid > 2 * e + 1 ? x : (x & 0x0000ffffu);
-          x = valid > 2 * e ? x : 0u;
-          v[e] = x;
+          for (int e = 0; e < 4; ++e) {
+            uint32_t x = v[e];
+            x = valid > 2 * e + 1 ? x : (x & 0x0000ffffu);
+            x = valid > 2 * e ? x : 0u;
+            v[e] = x;
+          }
         }
         dv[(((kg >> 2) * DT + (ch >> 4)) * 64) + (kg & 3) * 16 + ((ch & 15) ^ (4 * (kg & 3)) ^ (2 * (kg >> 2)))] = v;
       }
@@ -1074,13 +1113,19 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   if (n_rg >= 4 && !no_lds && a.pt_shift >= 0) {
     // many rows per kv head: K/V staged once per workgroup in LDS (at least 4 waves load)
     const bool paged = g.Q > 0;
+    const bool fast = !paged || a.pt_shift >= 6;     // a 64-key block never straddles pages
+#define ATTN_LDS(DHV, NWV)                                                                                 \
+  do {                                                                                                     \
+    if (!paged) k_attn_lds<DHV, NWV, false, true><<<grid, NWV * 64, 0, s>>>(a);                            \
+    else if (fast) k_attn_lds<DHV, NWV, true, true><<<grid, NWV * 64, 0, s>>>(a);                          \
+    else k_attn_lds<DHV, NWV, true, false><<<grid, NWV * 64, 0, s>>>(a);                                   \
+  } while (0)
     if (f.head_dim == 128) {
-      if (n_rg_wg <= 4) { if (paged) k_attn_lds<128, 4, true><<<grid, 256, 0, s>>>(a); else k_attn_lds<128, 4, false><<<grid, 256, 0, s>>>(a); }
-      else { if (paged) k_attn_lds<128, 8, true><<<grid, 512, 0, s>>>(a); else k_attn_lds<128, 8, false><<<grid, 512, 0, s>>>(a); }
+      if (n_rg_wg <= 4) ATTN_LDS(128, 4); else ATTN_LDS(128, 8);
     } else {
-      if (n_rg_wg <= 4) { if (paged) k_attn_lds<64, 4, true><<<grid, 256, 0, s>>>(a); else k_attn_lds<64, 4, false><<<grid, 256, 0, s>>>(a); }
-      else { if (paged) k_attn_lds<64, 8, true><<<grid, 512, 0, s>>>(a); else k_attn_lds<64, 8, false><<<grid, 512, 0, s>>>(a); }
+      if (n_rg_wg <= 4) ATTN_LDS(64, 4); else ATTN_LDS(64, 8);
     }
+#undef ATTN_LDS
   } else if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
   else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
   hipError_t e = hipGetLastError();
