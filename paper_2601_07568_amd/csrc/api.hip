@@ -76,6 +76,8 @@ static bool build_map(const dllm_config* c, Workspace* m) {
     size_t sk_floats = (size_t)SK_MAX_DELTA * m->delta_stride, lg_floats = (size_t)LG_MAX_DELTA * m->lg_delta_stride;
     m->delta = take(c->dtype == DLLM_BF16 ? (sk_floats > lg_floats ? sk_floats : lg_floats) * 4 : 0);
   }
+  m->qkvp_stride = m->lg_delta_rows * (int64_t)(dq + 2 * dkv);
+  m->qkvp = take(c->dtype == DLLM_BF16 ? (size_t)LG_QKV_SPLITS * m->qkvp_stride * 4 : 0);
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
   m->total = off;
@@ -307,7 +309,11 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
     } else {
       ProfScope p(c, s, 0, 2.0 * T * (dq + 2.0 * dkv) * f.d_model);   // large path: work recorded in flops
-      if (big_mfma && f.d_model % 8 == 0 && dq % 4 == 0 && dkv % 4 == 0) {
+      int n_part = 0;
+      if (big_mfma) TRY(launch_gemm_qkv_split(c, s, c->ws + c->map.xn, L.wq, L.wk, L.wv, T, dq, dkv, f.d_model, &n_part), "wqkv");
+      if (n_part > 0) {
+        // q | k | v left as partial sums over K; the rotary kernel adds them
+      } else if (big_mfma && f.d_model % 8 == 0 && dq % 4 == 0 && dkv % 4 == 0) {
         TRY(launch_gemm_qkv(s, c->ws + c->map.xn, L.wq, L.wk, L.wv, WSP(c, q32, float), WSP(c, k32, float),
                             c->ws + c->map.v, T, dq, dkv, f.d_model), "wqkv");
       } else {
@@ -315,7 +321,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
       }
-      TRY(launch_rope_kv(c, s, g, l), "rope_kv");
+      TRY(launch_rope_kv(c, s, g, l, n_part), "rope_kv");
     }
     {
       ProfScope p(c, s, 5, 2.0 * 2.0 * dkv * (double)g.max_kv * g.B);

@@ -148,6 +148,8 @@ struct Workspace {
   size_t delta;        // float open residual sums: [SK_MAX_DELTA][64, d] (skinny path) or [LG_MAX_DELTA][lg_delta_rows, d]
   int64_t delta_stride;
   int64_t lg_delta_rows, lg_delta_stride;   // large path: rows the buffer covers (0 = none), floats per split
+  size_t qkvp;         // float [LG_QKV_SPLITS][lg_delta_rows, dq + 2 dkv]: K-split partial sums of the fused q/k/v product
+  int64_t qkvp_stride;
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
   int64_t t_max, r_max, t_step, tpad;
@@ -207,6 +209,7 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
                           const int32_t* n_rows_dev, int frag_mt, int n_delta);
 hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta, bool frag_path);
+constexpr int LG_QKV_SPLITS = 3;       // large path: most K splits of the fused q/k/v product
 constexpr int LG_MAX_DELTA = 3;        // large path: a residual projection is split over K at most 4 ways
 constexpr int LG_DELTA_ROWS = 2048;    // ... and only when the token count leaves the chip underfilled
 constexpr int SK_MAX_DELTA = 8;   // most K splits of a residual projection
@@ -216,7 +219,7 @@ enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
 // C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,
                                int M, int N, int K, Epi epi);
-hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer);
+hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, int n_part = 0);
 hipError_t launch_swiglu(dllm_ctx* c, hipStream_t s, int T);
 hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer);
 hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32_t* cand, float* conf,
@@ -244,6 +247,8 @@ hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C
 hipError_t init_gemm_t256();   // once per process, before the first large GEMM (raises a kernel's LDS limit)
 hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
                                    int* n_delta);
+hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
+                                 int M, int dq, int dkv, int K, int* n_part);
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
                            float* k32, void* v, int M, int dq, int dkv, int K);
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,

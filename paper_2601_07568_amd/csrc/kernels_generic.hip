@@ -235,26 +235,34 @@ template <typename T>
 __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float* kf, T* q, const T* v,
                           const float* cs, const float* sn, const int32_t* tok_seq, const int32_t* tok_pos,
                           const int32_t* n_cache, T* pool_k, T* pool_v, KVView pool, T* pack_k, T* pack_v,
-                          KVView pack, bool to_pack, int32_t* status) {
+                          KVView pack, bool to_pack, int32_t* status, const float* part, int n_part,
+                          int64_t part_stride) {
   const int t = blockIdx.x;
   const int half = dh >> 1;
   const float* c = cs + (int64_t)t * half;
   const float* s = sn + (int64_t)t * half;
-  const float* qs = qf + (int64_t)t * Hq * dh;
+  // n_part > 0: q, k, v arrive as n_part partial sums over K of one [T, Hq*dh + 2*Hkv*dh] float
+  // matrix each (q | k | v); they are added in split order
+  const int np = n_part > 0 ? n_part : 1;
+  const int64_t ps = n_part > 0 ? part_stride : 0;
+  const float* qs = n_part > 0 ? part + (int64_t)t * (Hq + 2 * Hkv) * dh : qf + (int64_t)t * Hq * dh;
   T* qt = q + (int64_t)t * Hq * dh;
   for (int i = threadIdx.x; i < Hq * half; i += blockDim.x) {
     int h = i / half, j = i - h * half;
-    float a = qs[h * dh + j], b = qs[h * dh + j + half];
+    float a = 0.f, b = 0.f;
+    for (int sp = 0; sp < np; ++sp) { a += qs[sp * ps + h * dh + j]; b += qs[sp * ps + h * dh + j + half]; }
     Elem<T>::store(qt + h * dh + j, a * c[j] - b * s[j]);
     Elem<T>::store(qt + h * dh + j + half, b * c[j] + a * s[j]);
   }
   const int b = tok_seq[t], pos = tok_pos[t];
   const bool cached = (n_cache == nullptr) || (pos < n_cache[b]);
-  const float* ks = kf + (int64_t)t * Hkv * dh;
+  const float* ks = n_part > 0 ? qs + Hq * dh : kf + (int64_t)t * Hkv * dh;
   const T* vt = v + (int64_t)t * Hkv * dh;
+  const float* vparts = qs + (Hq + Hkv) * dh;
   for (int i = threadIdx.x; i < Hkv * half; i += blockDim.x) {
     int h = i / half, j = i - h * half;
-    float a = ks[h * dh + j], bb = ks[h * dh + j + half];
+    float a = 0.f, bb = 0.f;
+    for (int sp = 0; sp < np; ++sp) { a += ks[sp * ps + h * dh + j]; bb += ks[sp * ps + h * dh + j + half]; }
     float r0 = a * c[j] - bb * s[j], r1 = bb * c[j] + a * s[j];
     int64_t ko, vo;
     int vs;
@@ -274,10 +282,18 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
     int h = i / dh, j = i - h * dh;
     int64_t ko, vo;
     int vs;
-    if (cached && kv_locate(pool, b, pos, h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = vt[h * dh + j];
+    T val;
+    if (n_part > 0) {
+      float acc = 0.f;
+      for (int sp = 0; sp < np; ++sp) acc += vparts[sp * ps + h * dh + j];
+      Elem<T>::store(&val, acc);
+    } else {
+      val = vt[h * dh + j];
+    }
+    if (cached && kv_locate(pool, b, pos, h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = val;
     if (to_pack) {
       kv_locate(pack, b, pos, h, ko, vo, vs);
-      pack_v[vo + (int64_t)j * vs] = vt[h * dh + j];
+      pack_v[vo + (int64_t)j * vs] = val;
     }
   }
 }
@@ -725,7 +741,7 @@ KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer) {
   return g.Q > 0 ? pool_view(c, g, layer) : pack_view(c);
 }
 
-hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer) {
+hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, int n_part) {
   const dllm_config& f = c->cfg;
   KVView pool = pool_view(c, g, layer), pack = pack_view(c);
   const bool to_pack = g.Q == 0;
@@ -735,13 +751,14 @@ hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int lay
                                           WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
                                           WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
                                           n_cache, (bf16_t*)pool.k, (bf16_t*)pool.v, pool, (bf16_t*)pack.k,
-                                          (bf16_t*)pack.v, pack, to_pack, WS(c, status, int32_t));
+                                          (bf16_t*)pack.v, pack, to_pack, WS(c, status, int32_t), WS(c, qkvp, float),
+                                          n_part, c->map.qkvp_stride);
   else
     k_rope_kv<float><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
                                          WS(c, q, float), WS(c, v, float), WS(c, rope_cos, float),
                                          WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
                                          n_cache, (float*)pool.k, (float*)pool.v, pool, (float*)pack.k,
-                                         (float*)pack.v, pack, to_pack, WS(c, status, int32_t));
+                                         (float*)pack.v, pack, to_pack, WS(c, status, int32_t), nullptr, 0, 0);
   return hipGetLastError();
 }
 

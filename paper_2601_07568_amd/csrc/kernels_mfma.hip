@@ -1457,7 +1457,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
   const int m0 = tm * 256, n0 = tn * TILE_N;
   int k_begin = 0, k_end = K;
-  if constexpr (EPI == LG_RESID) {
+  if constexpr (EPI == LG_RESID || EPI == LG_QKV) {
     k_begin = split * a.k_per;
     k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
   }
@@ -1478,6 +1478,13 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
       // a wave's four weight tiles are gate, gate, up, up of the same 64 features
       int row = n0 + (r >> 7) * 64 + ((r >> 5) & 1) * 32 + (r & 31); row = row < N ? row : N - 1;
       gsrc[q] = (((r >> 6) & 1) ? a.W2 : a.W) + (int64_t)row * K + piece * 8;
+    } else if constexpr (EPI == LG_QKV) {
+      // three projections stacked along the features: q rows [0, N), then k and v with N2 rows each
+      // (all multiples of 256, so a tile belongs to one of them)
+      const int row = n0 + r;
+      const bf16_t* wsel = row < N ? a.W : (row < N + a.N2 ? a.W2 : a.W3);
+      const int lrow = row < N ? row : (row < N + a.N2 ? row - N : row - N - a.N2);
+      gsrc[q] = wsel + (int64_t)lrow * K + piece * 8;
     } else {
       int row = n0 + r; row = row < N ? row : N - 1;
       gsrc[q] = a.W + (int64_t)row * K + piece * 8;
@@ -1623,6 +1630,17 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
             for (int e = 0; e < 4 && n + e < N; ++e) ((bf16_t*)a.C)[(int64_t)m * N + n + e] = f32_to_bf16(v[e]);
           }
         }
+    } else if constexpr (EPI == LG_QKV) {
+      // every split stores its partial sums: [split][row][q | k | v] floats
+      const int nt = N + 2 * a.N2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int n = n0 + wn * 128 + i * 32 + e4 * 8 + h * 4;
+          *(f32x4*)(a.delta + (int64_t)split * a.delta_stride + (int64_t)m * nt + n) =
+              f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+        }
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -1661,6 +1679,7 @@ hipError_t init_gemm_t256() {
   hipError_t e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_LMSTATS>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_gemm_t256<LG_QKV>, hipFuncAttributeMaxDynamicSharedMemorySize, T2_LDS);
   t2_ready = e == hipSuccess;
   return e;
 }
@@ -1670,8 +1689,9 @@ static hipError_t t2_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
   constexpr int tile_n = EPI == LG_SWIGLU ? 128 : 256;
   a.tiles_m = (a.M + 255) / 256;
   a.tiles_n = (a.N + tile_n - 1) / tile_n;
+  if (EPI == LG_QKV) a.tiles_n = (a.N + 2 * a.N2) / 256;
   a.k_splits = k_splits;
-  if (EPI != LG_RESID) a.k_per = a.K;
+  if (EPI != LG_RESID && EPI != LG_QKV) a.k_per = a.K;
   const int items = a.tiles_m * a.tiles_n * k_splits;
   const int grid = items < t2_cus ? (items + 7) / 8 * 8 : t2_cus;   // one persistent workgroup per CU
   k_gemm_t256<EPI><<<grid, 256, T2_LDS, s>>>(a);
@@ -1736,6 +1756,31 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   *n_delta = splits - 1;
   if (t2) return t2_launch<LG_RESID>(s, a, splits);
   return lg_launch<LG_RESID>(s, a, true, splits);
+}
+
+// The fused q/k/v product on 256-row tiles, its sum over K split to fill the chip: every split leaves
+// [M, dq + 2 dkv] float partial sums (q | k | v) for the rotary kernel to add.  *n_part = 0: not taken.
+hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
+                                 int M, int dq, int dkv, int K, int* n_part) {
+  *n_part = 0;
+  if (!t2_usable(M, K) || M > c->map.lg_delta_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
+    return hipSuccess;
+  LgArgs a;
+  memset(&a, 0, sizeof(a));
+  a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
+  a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
+  const int tiles = ((M + 255) / 256) * ((dq + 2 * dkv) / 256);
+  int splits = 256 / tiles;
+  if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
+  while (splits > 1 && K / splits < 1024) --splits;
+  if (splits < 1) splits = 1;
+  if (tiles * splits < 128) return hipSuccess;            // too few work items: the 128-row tiles do better
+  a.k_per = ((K + splits - 1) / splits + 31) / 32 * 32;
+  splits = (K + a.k_per - 1) / a.k_per;
+  a.delta = (float*)(c->ws + c->map.qkvp);
+  a.delta_stride = c->map.qkvp_stride;
+  *n_part = splits;
+  return t2_launch<LG_QKV>(s, a, splits);
 }
 
 // q32[M,dq], k32[M,dkv] (float) and v[M,dkv] (bfloat16) = A[M,K] times the three projections, one launch
