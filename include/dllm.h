@@ -156,10 +156,22 @@ int dllm_denoise_step(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_
  * descending, index ascending (NaN confidences come last).  Unmasking position i sets
  * q_tokens[i] = cand_token[i]; other positions are left untouched.
  *   q_tokens dev int32 [B, Q] in/out    n_unmasked, n_remaining dev int32 [B, Q / block_len] or NULL
- *   Requires Q % block_len == 0, 1 <= block_len <= 1024, min_unmask >= 1. */
+ *   Requires Q % block_len == 0, 1 <= block_len <= 1024, min_unmask >= 0 (0 = threshold only, the
+ *   conservative strategy Section 3.2 gives a newly activated block). */
 int dllm_unmask(dllm_ctx *ctx, void *stream, int B, int Q, int block_len, int32_t *q_tokens,
                 const int32_t *cand_token, const float *conf, float threshold, int min_unmask,
                 int32_t *n_unmasked, int32_t *n_remaining);
+
+/* The same selection on the entropy of the predictive distribution (Section 3.2, "Entropy-Based
+ * Multi-Block Parallel Decoding": positions that meet the entropy threshold are decoded, lower
+ * entropy first; Appendix, inference settings: thresholds of 0.4 to 0.5).  Within a block every
+ * masked position with entropy <= theta is unmasked, and so are the min(min_unmask, #masked)
+ * masked positions that come first when ordered by entropy ascending, index ascending (NaN
+ * entropies come last).  entropy is the array dllm_denoise_step / dllm_refresh_cache write (nats).
+ * Arguments, layouts and limits as for dllm_unmask. */
+int dllm_unmask_entropy(dllm_ctx *ctx, void *stream, int B, int Q, int block_len, int32_t *q_tokens,
+                        const int32_t *cand_token, const float *entropy, float theta, int min_unmask,
+                        int32_t *n_unmasked, int32_t *n_remaining);
 
 /* KV refresh (Section 3.2, "KV-Refresh"; the forward passes of the "Completed but Stabilizing"
  * state): the same no-cache forward as dllm_prefill_kv over the committed tokens, optionally

@@ -213,11 +213,27 @@ def unmask(tokens, cand, conf, mask_id, tau, m):
     return tokens, sorted(chosen)
 
 
+def unmask_entropy(tokens, cand, entropy, mask_id, theta, m):
+    """Entropy-threshold selection on one block (Section 3.2, entropy-based decoding; Appendix,
+    inference settings: theta between 0.4 and 0.5 nats).  Masked positions with entropy <= theta
+    are unmasked, and so are the m' = min(m, #masked) masked positions of lowest entropy (lowest
+    index first among equals).  m = 0 is the threshold-only strategy of an "Activated" block,
+    m >= 1 the strategy of a "Fully-Activated" one.  Returns (new tokens, chosen indices)."""
+    tokens = np.array(tokens, copy=True)
+    masked = [i for i in range(len(tokens)) if tokens[i] == mask_id]
+    chosen = {i for i in masked if entropy[i] <= theta}
+    order = sorted(masked, key=lambda i: (entropy[i], i))
+    chosen.update(order[:min(m, len(masked))])
+    for i in chosen:
+        tokens[i] = cand[i]
+    return tokens, sorted(chosen)
+
+
 def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, widen=None,
-                 n_layers=None, store=None):
+                 n_layers=None, store=None, rule="prob"):
     """One whole step on a window of one or more blocks: forward, confidence of the masked
-    rows, selection per block.  Returns dict with new tokens, cand, conf, entropy, chosen,
-    logits."""
+    rows, selection per block (rule "prob": max-probability >= tau; rule "entropy": entropy <=
+    tau).  Returns dict with new tokens, cand, conf, entropy, chosen, logits."""
     ms = model.ms
     block_tokens = np.asarray(block_tokens)
     Q = len(block_tokens)
@@ -228,14 +244,17 @@ def denoise_step(model, block_tokens, cache_k, cache_v, tau, m, block_len=None, 
     chosen_all = []
     for b0 in range(0, Q, bl):
         sl = slice(b0, b0 + bl)
-        new[sl], ch = unmask(block_tokens[sl], cand[sl], conf[sl], ms.mask_id, tau, m)
+        if rule == "entropy":
+            new[sl], ch = unmask_entropy(block_tokens[sl], cand[sl], ent[sl], ms.mask_id, tau, m)
+        else:
+            new[sl], ch = unmask(block_tokens[sl], cand[sl], conf[sl], ms.mask_id, tau, m)
         chosen_all += [b0 + i for i in ch]
     return {"tokens": new, "cand": cand, "conf": conf, "entropy": ent, "chosen": chosen_all,
             "logits": logits}
 
 
 def decode(model, prompt, n_blocks, block_len, tau, m, widen=None, n_layers=None,
-           record=None, store=None):
+           record=None, store=None, rule="prob"):
     """Sequential-block decoding: cache the prompt, then for each block append block_len mask
     ids, run denoise steps until none is left, refresh the cache with a no-cache forward over
     everything decoded so far, go on.  Returns (all tokens, number of forwards with cache)."""
@@ -246,7 +265,7 @@ def decode(model, prompt, n_blocks, block_len, tau, m, widen=None, n_layers=None
     for _ in range(n_blocks):
         blk = np.full(block_len, ms.mask_id, dtype=np.int64)
         while (blk == ms.mask_id).any():
-            r = denoise_step(model, blk, ck, cv, tau, m, None, widen, n_layers, store)
+            r = denoise_step(model, blk, ck, cv, tau, m, None, widen, n_layers, store, rule)
             if record is not None:
                 record.append({"before": blk.copy(), **r})
             blk = r["tokens"]

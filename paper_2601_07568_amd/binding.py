@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         "dllm_prefill_kv": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
+        "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_refresh_cache": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "dllm_debug_logits": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_debug_hidden": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp]),
@@ -197,6 +198,13 @@ class Engine:
         B, Q = q_tokens.shape
         self._check(lib().dllm_unmask(self.ctx, self._stream(), B, Q, block_len or Q, _ptr(q_tokens), _ptr(cand),
                                       _ptr(conf), threshold, min_unmask, _ptr(n_unmasked), _ptr(n_remaining)))
+
+    def unmask_entropy(self, q_tokens, cand, entropy, theta, min_unmask, block_len=None, n_unmasked=None,
+                       n_remaining=None):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_unmask_entropy(self.ctx, self._stream(), B, Q, block_len or Q, _ptr(q_tokens),
+                                              _ptr(cand), _ptr(entropy), theta, min_unmask, _ptr(n_unmasked),
+                                              _ptr(n_remaining)))
 
     def refresh_cache(self, tokens, cu_seqlens, block_table, n_commit=None, cand=None, conf=None, entropy=None,
                       *, total_tokens, max_seqlen):

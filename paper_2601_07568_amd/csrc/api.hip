@@ -477,11 +477,23 @@ extern "C" int dllm_unmask(dllm_ctx* c, void* stream, int B, int Q, int block_le
                            const int32_t* cand_token, const float* conf, float threshold, int min_unmask,
                            int32_t* n_unmasked, int32_t* n_remaining) {
   if (!c || !q_tokens || !cand_token || !conf) return DLLM_EINVAL;
-  if (B < 1 || Q < 1 || block_len < 1 || min_unmask < 1 || Q % block_len != 0) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || block_len < 1 || min_unmask < 0 || Q % block_len != 0) return DLLM_EINVAL;
   if (threshold != threshold) return DLLM_EINVAL;
   if (block_len > 1024 || (int64_t)B * (Q / block_len) > (1 << 24)) return DLLM_ESHAPE;
   TRY(launch_unmask((hipStream_t)stream, B, Q, block_len, q_tokens, cand_token, conf, threshold, min_unmask,
                     c->cfg.mask_id, n_unmasked, n_remaining), "unmask");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_unmask_entropy(dllm_ctx* c, void* stream, int B, int Q, int block_len, int32_t* q_tokens,
+                                   const int32_t* cand_token, const float* entropy, float theta, int min_unmask,
+                                   int32_t* n_unmasked, int32_t* n_remaining) {
+  if (!c || !q_tokens || !cand_token || !entropy) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || block_len < 1 || min_unmask < 0 || Q % block_len != 0) return DLLM_EINVAL;
+  if (theta != theta) return DLLM_EINVAL;
+  if (block_len > 1024 || (int64_t)B * (Q / block_len) > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_unmask((hipStream_t)stream, B, Q, block_len, q_tokens, cand_token, entropy, theta, min_unmask,
+                    c->cfg.mask_id, n_unmasked, n_remaining, true), "unmask_entropy");
   return DLLM_OK;
 }
 

@@ -229,7 +229,7 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
                            float* entropy);
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
-                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining);
+                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
 
 // ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------

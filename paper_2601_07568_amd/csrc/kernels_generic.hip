@@ -533,7 +533,9 @@ __device__ inline bool conf_before(float a, int ia, float b, int ib) {
 }
 __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                                                const float* conf, float thr, int min_unmask, int32_t mask_id,
-                                               int32_t* n_unmasked, int32_t* n_remaining) {
+                                               int32_t* n_unmasked, int32_t* n_remaining, int low_first) {
+  // low_first: the statistic is an entropy - low values pass the threshold and come first; the
+  // selection runs on its negation
   __shared__ float cf[1024];
   __shared__ unsigned char msk[1024];
   const int nblk = Q / block_len;
@@ -544,7 +546,7 @@ __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_
   for (int i = lane; i < block_len; i += 64) {
     bool mk = q_tokens[base + i] == mask_id;
     msk[i] = mk;
-    cf[i] = conf[base + i];
+    cf[i] = low_first ? -conf[base + i] : conf[base + i];
     n_masked += mk;
   }
   for (int o = 32; o > 0; o >>= 1) n_masked += __shfl_xor(n_masked, o, 64);
@@ -816,9 +818,9 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
 
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                          const float* conf, float thr, int min_unmask, int32_t mask_id, int32_t* n_unmasked,
-                         int32_t* n_remaining) {
-  k_unmask<<<B * (Q / block_len), 64, 0, s>>>(Q, block_len, q_tokens, cand, conf, thr, min_unmask, mask_id,
-                                              n_unmasked, n_remaining);
+                         int32_t* n_remaining, bool low_first) {
+  k_unmask<<<B * (Q / block_len), 64, 0, s>>>(Q, block_len, q_tokens, cand, conf, low_first ? -thr : thr, min_unmask,
+                                              mask_id, n_unmasked, n_remaining, low_first ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -99,7 +99,12 @@ def test_calls_validate_before_launching():
     assert L.dllm_refresh_cache(ctx, None, 1, 64, 64, p, p, None, p, p, p, None) == E   # outputs need n_commit
     assert L.dllm_refresh_cache(ctx, None, 1, 64, 64, p, p, p, p, p, None, None) == E
     # unmask
-    assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, 0.9, 0, None, None) == E        # floor must be >= 1
+    assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, 0.9, -1, None, None) == E       # floor must be >= 0
+    assert L.dllm_unmask_entropy(ctx, None, 1, 32, 32, p, p, p, 0.45, -1, None, None) == E
+    assert L.dllm_unmask_entropy(ctx, None, 1, 32, 5, p, p, p, 0.45, 1, None, None) == E
+    assert L.dllm_unmask_entropy(ctx, None, 1, 32, 32, p, p, None, 0.45, 1, None, None) == E
+    assert L.dllm_unmask_entropy(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E
+    assert L.dllm_unmask_entropy(ctx, None, 1, 4096, 2048, p, p, p, 0.45, 1, None, None) == S
     assert L.dllm_unmask(ctx, None, 1, 32, 5, p, p, p, 0.9, 1, None, None) == E         # Q % block_len
     assert L.dllm_unmask(ctx, None, 1, 32, 32, None, p, p, 0.9, 1, None, None) == E
     assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E

@@ -76,6 +76,43 @@ def test_teacher_forced_steps_logits_conf_and_unmask(world):
     assert eng.read_status() == 0
 
 
+def test_teacher_forced_steps_entropy_rule(world):
+    """The paper's own selection rule (entropy <= theta, floor by lowest entropy) through dllm_unmask_entropy,
+    on the oracle's trajectory under that rule.  Entropies agree to ~1e-5 here, so a step is exempt only if the
+    oracle's own selection is within 1e-3 nats of changing."""
+    eng, w = world["eng"], world["w"]
+    table = H.identity_table(eng, 1)
+    gpu_prefill(eng, [world["prompt"]], table)
+    prefix = eng.i32([P]); tab = eng.i32(table)
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    # the tiny random model is far from peaked (entropies 5.44 .. 5.47 nats on the first step): theta = 2 leaves
+    # the floor to decide every step, theta = 5.443 sits in a gap of the first step's entropies and passes several rows
+    for theta, need in ((2.0, 16), (5.443, 1)):
+      rec = []
+      O.decode(w, world["prompt"], 1, Q, theta, 1, record=rec, rule="entropy")
+      assert 1 <= len(rec) <= 32
+      checked = multi = 0
+      for r in rec:
+        qt = eng.i32(r["before"][None, :])
+        eng.denoise_step(qt, prefix, tab, cand, conf, ent, max_prefix_len=P)
+        masked = r["before"] == TINY.mask_id
+        np.testing.assert_allclose(ent.cpu().numpy()[0][masked], r["entropy"][masked], rtol=0, atol=2e-4)
+        eng.unmask_entropy(qt, cand, ent, theta, 1)
+        # decided: no masked entropy within the margin of theta, floor boundary not a near-tie
+        if H.selection_is_decided(-np.asarray(r["entropy"]), masked, -theta, 1):
+            after = qt.cpu().numpy()[0]
+            assert np.nonzero(after != r["before"])[0].tolist() == r["chosen"]
+            assert (after[r["chosen"]] == r["cand"][r["chosen"]]).all()
+            checked += 1
+            multi += len(r["chosen"]) > 1
+      assert checked >= need
+      if theta > 5:
+          assert multi >= 1
+    assert eng.read_status() == 0
+
+
 def test_free_running_decode_matches_oracle(world):
     """The GPU carries its own state from step to step; it is put back on the oracle's trajectory
     only after a step whose selection the oracle itself leaves within 1e-3 of a tie."""

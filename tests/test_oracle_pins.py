@@ -289,6 +289,60 @@ def sort_reference_unmask(tokens, cand, conf, mask_id, tau, m):
     return tokens, sorted(take)
 
 
+def sort_reference_unmask_entropy(tokens, cand, ent, mask_id, theta, m):
+    tokens = np.array(tokens, copy=True)
+    idx = np.nonzero(tokens == mask_id)[0]
+    if len(idx) == 0:
+        return tokens, []
+    order = idx[np.lexsort((idx, ent[idx]))]                  # primary: entropy asc, secondary: index asc
+    take = set(order[:min(m, len(idx))].tolist()) | set(idx[ent[idx] <= theta].tolist())
+    for i in take:
+        tokens[i] = cand[i]
+    return tokens, sorted(take)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_unmask_entropy_against_sort_reference_with_ties(seed):
+    rng = np.random.default_rng(100 + seed)
+    n, mask_id = 32, 999
+    tokens = np.where(rng.random(n) < 0.6, mask_id, rng.integers(0, 900, n))
+    ent = rng.choice([0.0, 0.2, 0.4, 0.45, 0.5, 3.0], size=n) if seed % 2 else rng.random(n) * 2
+    cand = rng.integers(0, 900, n)
+    nm = int((tokens == mask_id).sum())
+    for theta in (-1.0, 0.0, 0.4, 0.45, 0.5, 100.0):
+        for m in (0, 1, 2, 5, 40):
+            a, ca = O.unmask_entropy(tokens, cand, ent, mask_id, theta, m)
+            b, cb = sort_reference_unmask_entropy(tokens, cand, ent, mask_id, theta, m)
+            np.testing.assert_array_equal(a, b)
+            assert ca == cb
+            assert len(ca) >= min(m, nm)
+            assert (a[tokens != mask_id] == tokens[tokens != mask_id]).all()         # never touched
+    # the two ends: a threshold nothing meets leaves exactly the floor, one everything meets takes all
+    assert len(O.unmask_entropy(tokens, cand, ent, mask_id, -1.0, 3)[1]) == min(3, nm)
+    assert len(O.unmask_entropy(tokens, cand, ent, mask_id, -1.0, 0)[1]) == 0
+    assert len(O.unmask_entropy(tokens, cand, ent, mask_id, 1e9, 0)[1]) == nm
+
+
+def test_entropy_rule_is_the_probability_rule_on_two_point_distributions():
+    """On rows whose mass sits on two tokens, entropy is a decreasing function of the max-probability, so
+    'H <= h(p0)' and 'conf >= p0' must select the same rows and order the floor the same way."""
+    rng = np.random.default_rng(5)
+    n, V, mask_id = 24, 50, 49
+    p = 0.5 + 0.5 * rng.random(n)                                # max-probability of each row
+    logits = np.full((n, V), -1e30)
+    logits[np.arange(n), 3] = np.log(p)
+    logits[np.arange(n), 7] = np.log1p(-p)
+    cand, conf, ent, _ = O.confidence(logits, mask_id)
+    h = lambda q: -(q * np.log(q) + (1 - q) * np.log1p(-q))
+    np.testing.assert_allclose(ent, h(p), rtol=1e-9, atol=1e-12)
+    tokens = np.full(n, mask_id)
+    for p0, m in ((0.9, 1), (0.75, 3), (0.999, 2), (0.5, 0)):
+        a, ca = O.unmask(tokens, cand, conf, mask_id, p0, m)
+        b, cb = O.unmask_entropy(tokens, cand, ent, mask_id, h(p0), m)
+        assert ca == cb
+        np.testing.assert_array_equal(a, b)
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_unmask_against_sort_reference_with_ties(seed):
     rng = np.random.default_rng(seed)
