@@ -579,7 +579,7 @@ __device__ __forceinline__ void attn_softmax_block(f32x4 (&s)[2][QT], int k0, in
 }
 
 template <int DH, int QT>
-__global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
+__global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
   constexpr int KK = DH / 32;   // k-steps of Q K^T
   constexpr int DT = DH / 16;   // 16-row tiles of O^T
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -628,60 +628,80 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
   for (int t = 0; t < QT; ++t) { m_run[t] = -DEV_INF; l_run[t] = 0.f; }
   bool bad = false;
 
-  const int nkb = (kv_len + 31) >> 5;
-  for (int kb = unit; kb < nkb; kb += a.n_units) {
+  // A wave takes its 32-key blocks two at a time: the page ids of both, then the K and V^T
+  // fragments of both are requested before the first is multiplied, so the second block's two
+  // memory round trips hide behind the first block's arithmetic (at batch 1 a wave owns about
+  // two blocks and the kernel is a chain of latencies).
+  struct Blk {
+    u32x4 kf[2][KK];   // K fragments (A operand): tile tt row c <-> key k0 + 8*(c/4) + c%4 + 4*tt
+    u32x4 vf[DT];      // V^T fragments (A operand of the second product): row = channel d*16 + c, keys k0+8g..+7
+    bool pbad;         // the V page is not addressable
+  };
+  auto key_of = [&](int kb, int which) -> int {     // which: 0, 1 = K tiles, 2 = V; clamped into the sequence
     const int k0 = kb << 5;
-    // ---- K fragments (A operand): tile tt row c <-> key k0 + 8*(c/4) + c%4 + 4*tt
-    u32x4 kf[2][KK];
+    if (which < 2) {
+      const int key = k0 + 8 * (c >> 2) + (c & 3) + 4 * which;
+      return key < kv_len ? key : kv_len - 1;       // masked at the scores; keeps the load in bounds
+    }
+    const int key = k0 + 8 * g;
+    return key < kv_len ? key : (kv_len - 1) & ~7;  // zeroed before use
+  };
+  auto pages = [&](int kb, int (&pg)[3]) {
+    if (paged) {
+#pragma unroll
+      for (int x = 0; x < 3; ++x) {
+        const int pi = key_of(kb, x) / pt;
+        const int v = table[pi < kv.max_pages ? pi : kv.max_pages - 1];
+        pg[x] = pi < kv.max_pages ? v : -1;
+      }
+    }
+  };
+  auto issue = [&](int kb, const int (&pg)[3], Blk& blk) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      int key = k0 + 8 * (c >> 2) + (c & 3) + 4 * tt;
-      if (key >= kv_len) key = kv_len - 1;                     // masked below; keeps the load in bounds
+      const int key = key_of(kb, tt);
       const bf16_t* kp;
       if (paged) {
-        const int pi = key / pt;
-        int page = pi < kv.max_pages ? table[pi] : -1;
-        if (page < 0 || page >= kv.n_pages) { page = 0; bad = true; }
-        kp = kslab + (((int64_t)page * kv.n_kv_heads + kvh) * pt + (key - pi * pt)) * DH + g * 8;
+        const bool ok = (uint32_t)pg[tt] < (uint32_t)kv.n_pages;
+        bad |= !ok;
+        kp = kslab + (((int64_t)(ok ? pg[tt] : 0) * kv.n_kv_heads + kvh) * pt + (key - key / pt * pt)) * DH + g * 8;
       } else {
         kp = kslab + ((int64_t)kvh * kv.tpad + pcol + key) * DH + g * 8;
       }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kf[tt][kk] = *(const u32x4*)(kp + kk * 32);
+      for (int kk = 0; kk < KK; ++kk) blk.kf[tt][kk] = *(const u32x4*)(kp + kk * 32);
     }
-    // ---- V^T fragments (A operand of the second product): row = channel d*16 + c, keys k0+8g..+7
-    u32x4 vf[DT];
-    {
-      int key = k0 + 8 * g;
-      if (key >= kv_len) key = (kv_len - 1) & ~7;
-      bool pbad = false;
-      const bf16_t* vp;
-      int64_t vstep;                                           // elements between channels d*16 and (d+1)*16
-      if (paged) {
-        const int pi = key / pt;
-        int page = pi < kv.max_pages ? table[pi] : -1;
-        if (page < 0 || page >= kv.n_pages) { page = 0; pbad = true; }
-        vp = vslab + (((int64_t)page * kv.n_kv_heads + kvh) * DH + c) * pt + (key - pi * pt);
-        vstep = (int64_t)16 * pt;
-      } else {
-        vp = vslab + ((int64_t)kvh * DH + c) * kv.tpad + pcol + key;
-        vstep = (int64_t)16 * kv.tpad;
-      }
+    const int key = key_of(kb, 2);
+    const bf16_t* vp;
+    int64_t vstep;                                           // elements between channels d*16 and (d+1)*16
+    blk.pbad = false;
+    if (paged) {
+      const bool ok = (uint32_t)pg[2] < (uint32_t)kv.n_pages;
+      bad |= !ok;
+      blk.pbad = !ok;
+      vp = vslab + (((int64_t)(ok ? pg[2] : 0) * kv.n_kv_heads + kvh) * DH + c) * pt + (key - key / pt * pt);
+      vstep = (int64_t)16 * pt;
+    } else {
+      vp = vslab + ((int64_t)kvh * DH + c) * kv.tpad + pcol + key;
+      vstep = (int64_t)16 * kv.tpad;
+    }
 #pragma unroll
-      for (int d = 0; d < DT; ++d) vf[d] = *(const u32x4*)(vp + d * vstep);
-      if (pbad || k0 + 32 > kv_len) {
-        // zero what lies beyond the sequence (or in a page that is not addressable): the slots may
-        // hold anything, and 0 * NaN would poison the row
+    for (int d = 0; d < DT; ++d) blk.vf[d] = *(const u32x4*)(vp + d * vstep);
+  };
+  auto compute = [&](int kb, Blk& blk) {
+    const int k0 = kb << 5;
+    if (__builtin_amdgcn_ballot_w64(blk.pbad) != 0 || k0 + 32 > kv_len) {
+      // zero what lies beyond the sequence (or in a page that is not addressable): the slots may
+      // hold anything, and 0 * NaN would poison the row
 #pragma unroll
-        for (int d = 0; d < DT; ++d) {
+      for (int d = 0; d < DT; ++d) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            uint32_t v = vf[d][e];
-            const int ke = k0 + 8 * g + 2 * e;
-            if (pbad || ke >= kv_len) v &= 0xffff0000u;
-            if (pbad || ke + 1 >= kv_len) v &= 0x0000ffffu;
-            vf[d][e] = v;
-          }
+        for (int e = 0; e < 4; ++e) {
+          uint32_t v = blk.vf[d][e];
+          const int ke = k0 + 8 * g + 2 * e;
+          if (blk.pbad || ke >= kv_len) v &= 0xffff0000u;
+          if (blk.pbad || ke + 1 >= kv_len) v &= 0x0000ffffu;
+          blk.vf[d][e] = v;
         }
       }
     }
@@ -693,7 +713,7 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
       for (int t = 0; t < QT; ++t) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) acc = mfma16(kf[tt][kk], qf[t][kk], acc);
+        for (int kk = 0; kk < KK; ++kk) acc = mfma16(blk.kf[tt][kk], qf[t][kk], acc);
         s[tt][t] = acc;
       }
     // ---- online softmax per query column
@@ -704,9 +724,24 @@ __global__ __launch_bounds__(512) void k_attn_step(const AttnArgs a) {
     for (int d = 0; d < DT; ++d)
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
-        oacc[d][t] = mfma16(vf[d], pf[t], oacc[d][t]);
-        oacc[d][t] = mfma16(vf[d], pl[t], oacc[d][t]);
+        oacc[d][t] = mfma16(blk.vf[d], pf[t], oacc[d][t]);
+        oacc[d][t] = mfma16(blk.vf[d], pl[t], oacc[d][t]);
       }
+  };
+
+  const int nkb = (kv_len + 31) >> 5;
+  for (int kb = unit; kb < nkb; kb += 2 * a.n_units) {
+    const int kb2 = kb + a.n_units;
+    const bool two = kb2 < nkb;
+    const int kbb = two ? kb2 : kb;               // a repeat of the first block's loads: no branch around a load
+    int pga[3], pgb[3];
+    pages(kb, pga);
+    pages(kbb, pgb);
+    Blk ba, bb;
+    issue(kb, pga, ba);
+    issue(kbb, pgb, bb);
+    compute(kb, ba);
+    if (two) compute(kb2, bb);
   }
 
   // ---- write the unit's partial: lane holds query column c, channels d*16 + 4g + i
@@ -1074,14 +1109,22 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   const int R = max_q * G;
   constexpr int QT = 2;
   const int n_rg = (R + 16 * QT - 1) / (16 * QT);
-  const int n_rg_wg = n_rg < 8 ? n_rg : 8;
+  static const int no_lds = getenv("DLLM_NO_ATTN_LDS") ? 1 : 0;   // tuning aid
+  int pt_shift = 0;
+  if (g.Q > 0) {
+    pt_shift = -1;
+    for (int sft = 3; sft < 31; ++sft) if (f.page_tokens == (1 << sft)) pt_shift = sft;
+  }
+  const bool staged = n_rg >= 4 && !no_lds && pt_shift >= 0;   // K/V staged in LDS, up to 8 row groups per workgroup
+  const int rg_cap = staged ? 8 : 4;                           // the register-direct kernel runs at most 4 waves
+  const int n_rg_wg = n_rg < rg_cap ? n_rg : rg_cap;
   const int n_chunks = (n_rg + n_rg_wg - 1) / n_rg_wg;
   const int nkb = (g.max_kv + 31) / 32;
   // units along the keys: short dependent chains matter more than partial traffic here (a step's
   // attention is a few MB), so give every unit about two 32-key blocks, within the partial buffer
   int64_t want = 2048 / ((int64_t)g.B * f.n_kv_heads * n_rg);
   if (want < 1) want = 1;
-  int64_t by_work = n_rg >= 4 ? (nkb + 7) / 8 : (nkb + 1) / 2;   // staged kernel: at least four 64-key blocks per unit
+  int64_t by_work = staged ? (nkb + 7) / 8 : (nkb + 1) / 2;   // staged kernel: at least four 64-key blocks per unit
   int64_t by_space = c->map.attn_rows / ((int64_t)g.T * f.n_q_heads);
   int64_t units = want < by_work ? want : by_work;
   if (units > by_space) units = by_space;
@@ -1098,19 +1141,14 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   a.kv = kv;
   a.Q = g.Q; a.Hq = f.n_q_heads; a.Hkv = f.n_kv_heads; a.B = g.B;
   a.n_units = (int)units; a.kspl = kspl; a.n_rg_wg = n_rg_wg;
-  a.pt_shift = 0;
-  if (g.Q > 0) {
-    a.pt_shift = -1;
-    for (int sft = 3; sft < 31; ++sft) if (f.page_tokens == (1 << sft)) a.pt_shift = sft;
-  }
+  a.pt_shift = pt_shift;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)f.head_dim);
   a.part_o = WSM(c, attn_part, float);
   a.part_ml = a.part_o + (size_t)c->map.attn_rows * f.head_dim;
   a.status = WSM(c, status, int32_t);
   dim3 grid((unsigned)(units / kspl), n_chunks, g.B * f.n_kv_heads);
   const int threads = 64 * n_rg_wg * kspl;
-  static const int no_lds = getenv("DLLM_NO_ATTN_LDS") ? 1 : 0;   // tuning aid
-  if (n_rg >= 4 && !no_lds && a.pt_shift >= 0) {
+  if (staged) {
     // many rows per kv head: K/V staged once per workgroup in LDS (at least 4 waves load)
     const bool paged = g.Q > 0;
     const bool fast = !paged || a.pt_shift >= 6;     // a 64-key block never straddles pages
