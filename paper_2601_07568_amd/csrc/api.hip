@@ -133,7 +133,10 @@ extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_we
   c->ws = (char*)workspace;
   c->map = m;
   c->kernel_mode = 0;
-  if (cfg->dtype == DLLM_BF16) (void)init_gemm_t256();   // without it the 128-row kernels serve every size
+  if (cfg->dtype == DLLM_BF16) {
+    (void)init_gemm_t256();      // without it the 128-row kernels serve every size
+    (void)init_attn_kernels();   // without it every wave of the batch-1 attention writes its own partial
+  }
   *out = c;
   return DLLM_OK;
 }

@@ -238,12 +238,12 @@ size_t packed_weight_bytes(int N, int K);
 hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int K);
 constexpr int SK_MAX_ROWS = 64;   // the skinny (weight-streaming) kernels take at most this many rows
 KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer);
-hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K);
 hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K);
 hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool);
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
 hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi);
+hipError_t init_attn_kernels();   // once per process (raises a kernel's LDS limit)
 hipError_t init_gemm_t256();   // once per process, before the first large GEMM (raises a kernel's LDS limit)
 hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
                                    int* n_delta);

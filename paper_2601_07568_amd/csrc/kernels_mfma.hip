@@ -28,7 +28,7 @@ __device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
                                                  0, 0);
 }
 
-enum SkEpi { SK_RESID = 0, SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4, SK_DELTA = 5 };
+enum SkEpi { SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4, SK_DELTA = 5 };
 
 struct SkArgs {
   const bf16_t* X;          // activations [M, K]
@@ -239,14 +239,13 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
       val[t] = s;
     }
     const bool tok_ok = tok < M;
-    if constexpr (EPI == SK_RESID || EPI == SK_F32 || EPI == SK_DELTA) {
+    if constexpr (EPI == SK_F32 || EPI == SK_DELTA) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = row0[t] + fr;
         if (tok_ok && n < a.N0) {
           float* p = a.out_f32 + (int64_t)tok * a.N0 + n;
           if (EPI == SK_DELTA) p[(int64_t)blockIdx.y * a.delta_stride] = val[t];
-          else if (EPI == SK_RESID) *p += val[t];
           else *p = val[t];
         }
       }
@@ -386,15 +385,6 @@ static SkArgs sk_base(const void* X, int M, int K) {
   return a;
 }
 
-// x[M,N] += A[M,K] * W[N,K]^T        (A in fragment order, see frag_offset)
-hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K) {
-  SkArgs a = sk_base(A, M, K);
-  a.W0 = (const bf16_t*)W;   // packed
-  a.N0 = N;
-  a.out_f32 = x;
-  return sk_launch_mt<1, SK_NW, SK_RESID>(s, a, (N + 15) / 16);
-}
-
 // Residual projection with the sum over K left open: split y of K writes A*W^T restricted to its
 // K range into delta + y*delta_stride ([M, N] float); the next RMSNorm adds x + delta_0 + delta_1 ..
 // in that order.  With K split across workgroups a workgroup can own 64 weight rows instead of 16
@@ -510,7 +500,8 @@ struct AttnArgs {
   KVView kv;
   int Q, Hq, Hkv, B;
   int n_units;              // key-splitting units per row group (gridDim.x * waves along keys)
-  int kspl;                 // units inside a workgroup
+  int kspl;                 // units (waves along the keys) inside a workgroup; their partials are merged in LDS
+  int n_parts;              // partials per row = workgroups along the keys
   int n_rg_wg;              // row groups per workgroup
   int pt_shift;             // log2(page_tokens) if that is a power of two (0 for the packed scratch), else -1
   float scale_log2;         // log2(e) / sqrt(DH)
@@ -586,6 +577,7 @@ __global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
   const int c = lane & 15, g = lane >> 4;
   const int rg = blockIdx.y * a.n_rg_wg + (w % a.n_rg_wg);
   const int unit = blockIdx.x * a.kspl + (w / a.n_rg_wg);
+  extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
   const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
   const int G = a.Hq / a.Hkv;
   const bool paged = a.Q > 0;
@@ -744,33 +736,78 @@ __global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
     if (two) compute(kb2, bb);
   }
 
-  // ---- write the unit's partial: lane holds query column c, channels d*16 + 4g + i
+  // ---- results: lane holds query column c, channels d*16 + 4g + i
+  float l_red[QT];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     float l = l_run[t];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    if (row_out[t] < 0) continue;
-    if (a.n_units == 1) {
-      // the only unit of its rows: normalise and store the output itself
-      const float inv = l > 0.f ? 1.0f / l : 0.f;
-      const int64_t ro = row_out[t];
-      const int tok = (int)(ro / a.Hq), head = (int)(ro - (int64_t)tok * a.Hq);
+    l_red[t] = l;
+  }
+  auto store_out = [&](int d, int t, f32x4 v, float l) {       // normalised output, the row's only partial
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const int64_t ro = row_out[t];
+    const int tok = (int)(ro / a.Hq), head = (int)(ro - (int64_t)tok * a.Hq);
+    const int ch = d * 16 + 4 * g;
+    const int64_t at = a.out_mt > 0 ? frag_offset(tok, head * DH + ch, a.out_mt) : ro * DH + ch;
+    *(uint2*)(a.o + at) = make_uint2(pack_bf16x2(v[0] * inv, v[1] * inv), pack_bf16x2(v[2] * inv, v[3] * inv));
+  };
+  if (a.kspl > 1) {
+    // The workgroup's waves hold partial results of the same rows over different keys (launched only
+    // with one row group per workgroup, so every wave is here): bring them to a common maximum,
+    // park them in LDS and let each wave add up a slice of the channels, in wave order.
+    const int KS = a.kspl;
+    float* sm_m = (float*)attn_smem;                           // [KS][QT][16]
+    float* sm_l = sm_m + KS * QT * 16;                         // [KS][QT][16]
+    f32x4* sm_o = (f32x4*)(attn_smem + 2 * KS * QT * 16 * sizeof(float));   // [KS][DT*QT][64]
+    if (g == 0) {
 #pragma unroll
-      for (int d = 0; d < DT; ++d) {
-        const int ch = d * 16 + 4 * g;
-        const int64_t at = a.out_mt > 0 ? frag_offset(tok, head * DH + ch, a.out_mt) : ro * DH + ch;
-        *(uint2*)(a.o + at) = make_uint2(
-            (uint32_t)f32_to_bf16(oacc[d][t][0] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][1] * inv) << 16),
-            (uint32_t)f32_to_bf16(oacc[d][t][2] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][3] * inv) << 16));
-      }
-      continue;
+      for (int t = 0; t < QT; ++t) { sm_m[(w * QT + t) * 16 + c] = m_run[t]; sm_l[(w * QT + t) * 16 + c] = l_red[t]; }
     }
-    const int64_t slot = row_out[t] * a.n_units + unit;
-    float* po = a.part_o + slot * DH + 4 * g;
+    __syncthreads();
+    float m_all[QT], l_all[QT];
 #pragma unroll
-    for (int d = 0; d < DT; ++d) *(f32x4*)(po + d * 16) = oacc[d][t];
-    if (g == 0) { a.part_ml[slot * 2] = m_run[t]; a.part_ml[slot * 2 + 1] = l; }
+    for (int t = 0; t < QT; ++t) {
+      float mx = -DEV_INF;
+      for (int ww = 0; ww < KS; ++ww) mx = fmaxf(mx, sm_m[(ww * QT + t) * 16 + c]);
+      float ls = 0.f;
+      for (int ww = 0; ww < KS; ++ww) {
+        const float mw = sm_m[(ww * QT + t) * 16 + c];
+        ls += mw > -DEV_INF ? sm_l[(ww * QT + t) * 16 + c] * exp2f(mw - mx) : 0.f;
+      }
+      m_all[t] = mx;
+      l_all[t] = ls;
+      const float f = m_run[t] > -DEV_INF ? exp2f(m_run[t] - mx) : 0.f;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) sm_o[(w * DT * QT + d * QT + t) * 64 + lane] = oacc[d][t] * f;
+    }
+    __syncthreads();
+    for (int u = w; u < DT * QT; u += KS) {
+      const int d = u / QT, t = u - d * QT;
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int ww = 0; ww < KS; ++ww) acc = acc + sm_o[(ww * DT * QT + u) * 64 + lane];
+      if (row_out[t] < 0) continue;
+      if (a.n_parts == 1) { store_out(d, t, acc, l_all[t]); continue; }
+      const int64_t slot = row_out[t] * a.n_parts + blockIdx.x;
+      *(f32x4*)(a.part_o + slot * DH + d * 16 + 4 * g) = acc;
+      if (d == 0 && g == 0) { a.part_ml[slot * 2] = m_all[t]; a.part_ml[slot * 2 + 1] = l_all[t]; }
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      if (row_out[t] < 0) continue;
+      if (a.n_parts == 1) {
+#pragma unroll
+        for (int d = 0; d < DT; ++d) store_out(d, t, oacc[d][t], l_red[t]);
+        continue;
+      }
+      const int64_t slot = row_out[t] * a.n_parts + unit;
+      float* po = a.part_o + slot * DH + 4 * g;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) *(f32x4*)(po + d * 16) = oacc[d][t];
+      if (g == 0) { a.part_ml[slot * 2] = m_run[t]; a.part_ml[slot * 2 + 1] = l_red[t]; }
+    }
   }
   if (bad) atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
 }
@@ -1102,6 +1139,16 @@ bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
 }
 
 // Attention of a denoise step (paged pool) or of a no-cache forward (packed scratch).
+// merging four waves' partial results takes a little more LDS than a kernel gets by default
+static bool attn_merge_ready = false;
+hipError_t init_attn_kernels() {
+  if (attn_merge_ready) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)k_attn_step<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_attn_step<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+  attn_merge_ready = e == hipSuccess;
+  return e;
+}
+
 hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out) {
   const dllm_config& f = c->cfg;
   const int G = f.n_q_heads / f.n_kv_heads;
@@ -1130,8 +1177,17 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   if (units > by_space) units = by_space;
   if (units > ATTN_MAX_SPLITS) units = ATTN_MAX_SPLITS;
   if (units < 1) units = 1;                                   // a single unit needs no partial buffer
-  if (const char* e = getenv("DLLM_ATTN_UNITS")) { int v = atoi(e); if (v >= 1 && v <= by_space && v <= ATTN_MAX_SPLITS) units = v; }
-  const int kspl = 1;
+  // one row group per KV head (a batch-1 block on a multi-head model): four units share a workgroup and
+  // merge their partial results in LDS, which leaves a quarter of the partials to write and re-read
+  int kspl = 1;
+  if (!staged && n_rg == 1 && attn_merge_ready && units >= 4) {
+    kspl = 4;
+    int64_t parts = (nkb + 2 * kspl - 1) / (2 * kspl);
+    if (parts * kspl > want) parts = want / kspl;
+    if (parts > by_space) parts = by_space;
+    if (parts < 1) parts = 1;
+    units = parts * kspl;
+  }
   AttnArgs a;
   a.q = WSM(c, q, bf16_t);
   a.prefix_len = g.prefix_len;
@@ -1141,6 +1197,7 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   a.kv = kv;
   a.Q = g.Q; a.Hq = f.n_q_heads; a.Hkv = f.n_kv_heads; a.B = g.B;
   a.n_units = (int)units; a.kspl = kspl; a.n_rg_wg = n_rg_wg;
+  a.n_parts = (int)(units / kspl);
   a.pt_shift = pt_shift;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)f.head_dim);
   a.part_o = WSM(c, attn_part, float);
@@ -1164,15 +1221,18 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
       if (n_rg_wg <= 4) ATTN_LDS(64, 4); else ATTN_LDS(64, 8);
     }
 #undef ATTN_LDS
-  } else if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, 0, s>>>(a);
-  else k_attn_step<64, QT><<<grid, threads, 0, s>>>(a);
+  } else {
+    const size_t lds = kspl > 1 ? (size_t)kspl * (2 * QT * 16 * sizeof(float) + (size_t)(f.head_dim / 16) * QT * 64 * 16) : 0;
+    if (f.head_dim == 128) k_attn_step<128, QT><<<grid, threads, lds, s>>>(a);
+    else k_attn_step<64, QT><<<grid, threads, lds, s>>>(a);
+  }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || units == 1) return e;
+  if (e != hipSuccess || a.n_parts == 1) return e;
   const int rows = g.T * f.n_q_heads;
   if (f.head_dim == 128)
-    k_attn_combine<128><<<(rows + 3) / 4, 512, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt, rows);
+    k_attn_combine<128><<<(rows + 3) / 4, 512, 0, s>>>(a.part_o, a.part_ml, a.n_parts, a.o, f.n_q_heads, a.out_mt, rows);
   else
-    k_attn_combine<64><<<(rows + 7) / 8, 512, 0, s>>>(a.part_o, a.part_ml, a.n_units, a.o, f.n_q_heads, a.out_mt, rows);
+    k_attn_combine<64><<<(rows + 7) / 8, 512, 0, s>>>(a.part_o, a.part_ml, a.n_parts, a.o, f.n_q_heads, a.out_mt, rows);
   return hipGetLastError();
 }
 
@@ -1741,15 +1801,10 @@ static bool t2_usable(int M, int K) {
 }
 
 template <int EPI>
-static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256, int k_splits = 1) {
-  // Two 128-row workgroups per CU measure 2.3x faster than one 256-row workgroup (LM head, 512 rows):
-  // with a single wave per SIMD nothing covers the LDS and barrier waits.  The 256-row form stays
-  // selectable for tuning.
-  static const int force256 = getenv("DLLM_LG_256") ? 1 : 0;
-  const int t256 = ((a.M + 255) / 256) * ((a.N + LG_BN - 1) / LG_BN);
-  const bool big = allow_256 && t256 >= 256 && force256;
-  const int bm = big ? 256 : 128;
-  a.tiles_m = (a.M + bm - 1) / bm;
+static hipError_t lg_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
+  // 128-row tiles, two workgroups per CU (a 256-row form of this kernel, one workgroup per CU, measured
+  // 2.3x slower: with a single wave per SIMD nothing covers its LDS and barrier waits)
+  a.tiles_m = (a.M + 127) / 128;
   constexpr int tile_n = EPI == LG_SWIGLU ? LG_BN / 2 : LG_BN;
   a.tiles_n = (a.N + tile_n - 1) / tile_n;
   if constexpr (EPI == LG_QKV) {
@@ -1758,7 +1813,6 @@ static hipError_t lg_launch(hipStream_t s, LgArgs a, bool allow_256, int k_split
     a.tiles_n = a.tiles_n1 + 2 * a.tiles_n2;
   }
   const dim3 grid((a.tiles_m * a.tiles_n + 7) / 8 * 8, k_splits);
-  if (big) { k_gemm_mfma<256, EPI><<<grid, 256, 0, s>>>(a); return hipGetLastError(); }
   k_gemm_mfma<128, EPI><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
@@ -1768,10 +1822,10 @@ hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = C; a.M = M; a.N = N; a.K = K;
-  if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a, true);
-  if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a, true);
+  if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a);
+  if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a);
   a.k_per = (K + LG_BK - 1) / LG_BK * LG_BK;
-  return lg_launch<LG_RESID>(s, a, true);
+  return lg_launch<LG_RESID>(s, a);
 }
 
 // x[M,N] += A[M,K] W[N,K]^T with the sum over K split while that fills the chip better: split 0 adds
@@ -1793,7 +1847,7 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   a.delta_stride = c->map.lg_delta_stride;
   *n_delta = splits - 1;
   if (t2) return t2_launch<LG_RESID>(s, a, splits);
-  return lg_launch<LG_RESID>(s, a, true, splits);
+  return lg_launch<LG_RESID>(s, a, splits);
 }
 
 // The fused q/k/v product on 256-row tiles, its sum over K split to fill the chip: every split leaves
@@ -1829,7 +1883,7 @@ hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const v
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
   a.C = q32; a.C2 = k32; a.C3 = v;
   a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
-  return lg_launch<LG_QKV>(s, a, false);
+  return lg_launch<LG_QKV>(s, a);
 }
 
 // h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
@@ -1839,7 +1893,7 @@ hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, cons
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
   if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
-  return lg_launch<LG_SWIGLU>(s, a, false);
+  return lg_launch<LG_SWIGLU>(s, a);
 }
 
 // LM head on the compacted rows (row-major ws.xn) -> softmax statistics per 64 columns
@@ -1854,7 +1908,7 @@ hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_
   a.mask_id = f.mask_id;
   *n_parts_out = a.n_parts;
   if (t2_usable(max_rows, a.K)) return t2_launch<LG_LMSTATS>(s, a);
-  return lg_launch<LG_LMSTATS>(s, a, true);
+  return lg_launch<LG_LMSTATS>(s, a);
 }
 
 }  // namespace dllm
