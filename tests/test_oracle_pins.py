@@ -452,3 +452,28 @@ def test_round_bf16_is_nearest_even():
     want = torch.from_numpy(x).float().to(torch.bfloat16).double().numpy()
     np.testing.assert_array_equal(got, want)
     assert got[3] == 1.0 and got[4] == 1.0 + 2.0 ** -6               # ties go to the even mantissa
+
+
+# ------------------------------------------------------------------ stored trajectory
+
+def test_oracle_reproduces_the_stored_tiny_trajectory():
+    """tests/golden/tiny_decode_trajectory.json was written by tests/golden/make_golden.py from the oracle alone
+    (the paper prints no value for this path); the oracle must still produce it: unmask order and token ids
+    exactly, confidences and entropies to the stored rounding."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "golden", "tiny_decode_trajectory.json")) as f:
+        stored = json.load(f)
+    now = mod.build()
+    assert now["workload"] == stored["workload"] and len(now["runs"]) == len(stored["runs"])
+    for a, b in zip(now["runs"], stored["runs"]):
+        assert a["steps"] == b["steps"] and a["final_block"] == b["final_block"]
+        for x, y in zip(a["trajectory"], b["trajectory"]):
+            assert x["chosen"] == y["chosen"] and x["tokens"] == y["tokens"]
+            np.testing.assert_allclose(x["conf"], y["conf"], rtol=0, atol=2e-6)
+            np.testing.assert_allclose(x["entropy"], y["entropy"], rtol=0, atol=2e-5)
