@@ -88,6 +88,71 @@ def cpu_baseline(ms, P, Q, n_masked, budget_s=20.0):
 MFMA_PEAK_TFLOPS = 2500.0
 
 
+def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev, theta=0.45, add_at=0.1, full_at=0.95,
+                          delay=1):
+    """One generation with the multi-block decoding of Section 3.2 (entropy threshold 0.45 nats, block-add at 10 %,
+    fully-activate at 95 %, one stabilizing round): the block states live on the device (dllm_fsm_update), the host
+    reads four integers per round to pick the window and the kind of forward.  With random weights the entropies
+    stay near ln(V), so the floors of the fully activated blocks drive the decode; the leg measures the machinery
+    (windows of more than one block, forwards without cache, per-block floors), not the paper's parallelism."""
+    NB = n_blocks
+    gen = torch.full((1, NB * Q), ms.mask_id, dtype=torch.int32, device=dev)
+    state = torch.zeros(1, NB, dtype=torch.int32, device=dev)
+    state[0, 0] = 2
+    counter = torch.zeros(1, NB, dtype=torch.int32, device=dev)
+    floor = torch.full((1, NB), -1, dtype=torch.int32, device=dev)
+    floor[0, 0] = 1
+    summary = torch.zeros(1, 4, dtype=torch.int32, device=dev)
+    Qmax = 4 * Q
+    cand = torch.zeros(1, Qmax, dtype=torch.int32, device=dev)
+    conf = torch.zeros(1, Qmax, dtype=torch.float32, device=dev)
+    ent = torch.zeros(1, Qmax, dtype=torch.float32, device=dev)
+    n_max = P + NB * Q
+    c2 = torch.zeros(n_max, dtype=torch.int32, device=dev)
+    f2 = torch.zeros(n_max, dtype=torch.float32, device=dev)
+    e2 = torch.zeros(n_max, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.prefill_kv(prompt, eng.i32([0, P]), table, None, total_tokens=P, max_seqlen=P)
+    lo, hi, stab = 0, 0, 0
+    rounds = nocache_rounds = wide_rounds = 0
+    while lo >= 0:
+        if hi - lo + 1 > 4:
+            hi = lo + 3                                            # the window this engine was sized for
+        nw = hi - lo + 1
+        window = gen[:, lo * Q:(hi + 1) * Q]
+        fl = floor[:, lo:hi + 1]
+        if stab:
+            st, ct = state[0].tolist(), counter[0].tolist()
+            for b in range(NB):                                    # blocks this round will complete (host mirror)
+                if st[b] == 3 and ct[b] - 1 <= 0 and (b == 0 or st[b - 1] == 4):
+                    st[b] = 4
+            n_tok = P + (hi + 1) * Q
+            seq = torch.cat([prompt, gen[0, :(hi + 1) * Q]])
+            eng.refresh_cache(seq, eng.i32([0, n_tok]), table, eng.i32([P + st.count(4) * Q]), c2, f2, e2,
+                              total_tokens=n_tok, max_seqlen=n_tok)
+            s0 = P + lo * Q
+            eng.unmask_blocks(window, c2[s0:n_tok][None], e2[s0:n_tok][None], theta, fl, True, Q)
+            nocache_rounds += 1
+        else:
+            eng.denoise_step(window, eng.i32([P + lo * Q]), table, cand[:, :nw * Q], conf[:, :nw * Q], ent[:, :nw * Q],
+                             max_prefix_len=P + lo * Q)
+            eng.unmask_blocks(window, cand[:, :nw * Q], ent[:, :nw * Q], theta, fl, True, Q)
+        eng.fsm_update(gen, state, counter, Q, add_at, full_at, delay, bool(stab), floor, summary)
+        lo, hi, stab, _ = summary[0].tolist()
+        rounds += 1
+        wide_rounds += nw > 1
+        if rounds > 8 * NB * Q:
+            raise RuntimeError("multi-block decode does not terminate")
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    assert int((gen == ms.mask_id).sum()) == 0
+    return {"tokens": NB * Q, "forwards": rounds, "forwards_without_cache": nocache_rounds,
+            "forwards_with_more_than_one_block": wide_rounds, "seconds": sec, "tokens_per_s": NB * Q / sec,
+            "tokens_per_forward": NB * Q / rounds, "rule": f"entropy <= {theta}", "block_add": add_at,
+            "fully_activate": full_at, "stabilizing_rounds": delay}
+
+
 def large_batch(args, torch, np, synth, Engine, dev):
     """Long-context large-batch step (not the default workload): Dream-7B-shaped model, batch 32, prefix KV of
     8192 tokens per sequence drawn directly on the device, one block of 32 per sequence with 16 masked:
@@ -206,7 +271,7 @@ def main():
     pt = 64
     max_len = P + n_blocks * Q
     mp = (max_len + pt - 1) // pt
-    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=mp, max_batch=1, max_q=Q,
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=mp, max_batch=1, max_q=4 * Q,
                  max_tokens=max_len, device_weights=device_weights(ms, torch, dev, 1))
     table = eng.i32(np.arange(mp)[None])
     prompt = eng.i32(synth.random_tokens(ms, 3, P))
@@ -325,6 +390,11 @@ def main():
         gen = {"tokens": n_blocks * Q, "forwards": forwards, "seconds": gsec, "tokens_per_s": n_blocks * Q / gsec,
                "steps_per_s": forwards / gsec, "tokens_per_forward": n_blocks * Q / forwards}
 
+    # ---- the same generation with multi-block decoding (entropy rule, block state machine on the device)
+    gen_mb = None
+    if not args.no_generation and n_blocks > 1:
+        gen_mb = multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev)
+
     out = {
         "metric": "denoise_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -332,7 +402,7 @@ def main():
         "config": {"workload": name, "layers": ms.n_layers, "prefix": P, "block": Q, "page_tokens": pt,
                    "launch": "eager" if graph is None else "hip graph of one step, replayed"},
         "step_algorithmic_GB": step_bytes / 1e9, "step_GBps": step_gbs, "step_frac_of_hbm_peak": step_gbs / HBM_PEAK_GBS,
-        "roofline": roofline, "kernels": kern, "generation": gen,
+        "roofline": roofline, "kernels": kern, "generation": gen, "generation_multiblock": gen_mb,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ms, P, Q, n_masked0)

@@ -173,6 +173,46 @@ int dllm_unmask_entropy(dllm_ctx *ctx, void *stream, int B, int Q, int block_len
                         const int32_t *cand_token, const float *entropy, float theta, int min_unmask,
                         int32_t *n_unmasked, int32_t *n_remaining);
 
+/* The selection with a floor per block (Section 3.2: a newly activated block decodes only what meets
+ * the threshold, a fully activated one at least one position per forward).  stat is the confidence
+ * (by_entropy = 0: positions with stat >= threshold pass, highest first) or the entropy (by_entropy
+ * != 0: positions with stat <= threshold pass, lowest first).  floor[b, k] >= 0 is the floor of block k
+ * of sequence b; a negative entry leaves that block untouched (its counts are still reported).
+ *   floor dev int32 [B, Q / block_len]; everything else as for dllm_unmask. */
+int dllm_unmask_blocks(dllm_ctx *ctx, void *stream, int B, int Q, int block_len, int32_t *q_tokens,
+                       const int32_t *cand_token, const float *stat, float threshold, int by_entropy,
+                       const int32_t *floor, int32_t *n_unmasked, int32_t *n_remaining);
+
+/* Block states of multi-block decoding (Section 3.2: Inactive, Activated, Fully-Activated, Completed
+ * but Stabilizing, Completed) and their transitions after a round, evaluated on the device from the
+ * generation tokens themselves.  In block order, with filled = unmasked positions of a block and
+ * prev = filled of the block before it (the first block's predecessor counts as complete):
+ *   Stabilizing: counter -= 1 if the round's forward did not use the cache (nocache_round != 0);
+ *                becomes Completed once counter <= 0 and the block before it is Completed;
+ *   Activated / Fully-Activated: becomes Stabilizing with counter = delay when filled == block_len;
+ *                an Activated block becomes Fully-Activated when prev / block_len >= full_at;
+ *   the first Inactive block: becomes Activated when the block before it is not Inactive and
+ *                prev / block_len >= add_at (Fully-Activated at once if also >= full_at).
+ * Appendix, inference settings: add_at 0.1, full_at 0.95, delay 1 or 2.  The ratios are compared in
+ * double precision on the host side of the call (converted to counts).
+ *   gen_tokens dev int32 [B, n_blocks * block_len]   the generation part of each sequence
+ *   state, counter dev int32 [B, n_blocks] in/out    state values DLLM_BLOCK_*
+ *   floor_next dev int32 [B, n_blocks] or NULL       floors for dllm_unmask_blocks in the next round:
+ *                                                    1 Fully-Activated, 0 Activated, -1 otherwise
+ *   summary dev int32 [B, 4] or NULL                 first and last active block (-1 if none), whether a
+ *                                                    block is Stabilizing (the next forward must not use
+ *                                                    the cache), number of Completed blocks
+ *   Requires 1 <= n_blocks <= DLLM_FSM_MAX_BLOCKS, delay >= 0. */
+#define DLLM_BLOCK_INACTIVE 0
+#define DLLM_BLOCK_ACTIVATED 1
+#define DLLM_BLOCK_FULLY_ACTIVATED 2
+#define DLLM_BLOCK_STABILIZING 3
+#define DLLM_BLOCK_COMPLETED 4
+#define DLLM_FSM_MAX_BLOCKS 256
+int dllm_fsm_update(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, const int32_t *gen_tokens,
+                    int32_t *state, int32_t *counter, double add_at, double full_at, int delay, int nocache_round,
+                    int32_t *floor_next, int32_t *summary);
+
 /* KV refresh (Section 3.2, "KV-Refresh"; the forward passes of the "Completed but Stabilizing"
  * state): the same no-cache forward as dllm_prefill_kv over the committed tokens, optionally
  * followed by in-flight ones, overwriting the cached K/V of positions [0, n_commit[b]) (all if

@@ -273,3 +273,108 @@ def decode(model, prompt, n_blocks, block_len, tau, m, widen=None, n_layers=None
         seq = np.concatenate([seq, blk])
         ck, cv = prefill(model, seq, None, n_layers, widen, store)      # refresh at the block boundary
     return seq, steps
+
+
+# ---------------------------------------------------------------------------------------------
+# Multi-block decoding (Section 3.2, "Entropy-Based Multi-Block Parallel Decoding"; thresholds from
+# the appendix, "Inference Settings": block-add 0.1, decoded-token 0.95, cache delay 1-2 rounds).
+#
+# The paper gives the five block states and the transition rules in one paragraph.  What it leaves
+# open is fixed here (and listed with the other readings in the design notes):
+#   * the first block starts Fully-Activated (its "preceding block" is the prompt, which is complete);
+#   * "X % completion" = unmasked positions / block length >= X;
+#   * a round's forward does not use the cache iff some block is Stabilizing at the start of the
+#     round; otherwise it uses the cache of the prompt and the Completed blocks;
+#   * transitions are evaluated after the round's unmasking, in block order, on the new tokens;
+#     a newly added block whose predecessor is already >= 95 % complete starts Fully-Activated;
+#   * a Stabilizing block counts the no-cache rounds since it filled up and becomes Completed after
+#     `delay` of them, but not before its predecessor is Completed (the cache grows in order);
+#   * decoding ends when no [MASK] is left.
+INACTIVE, ACTIVATED, FULLY_ACTIVATED, STABILIZING, COMPLETED = 0, 1, 2, 3, 4
+
+
+def fsm_update(state, counter, filled, block_len, add_at, full_at, delay, nocache_round):
+    """State transitions of one sequence after a round.  state, counter: per-block lists; filled[b] =
+    unmasked positions of block b after the round's unmasking; nocache_round: the round's forward
+    did not use the cache.  Returns (new state, new counter) as lists."""
+    nb = len(state)
+    st, ct = list(state), list(counter)
+    for b in range(nb):
+        done_prev = 1.0 if b == 0 else filled[b - 1] / block_len
+        if st[b] == STABILIZING:
+            if nocache_round:
+                ct[b] -= 1
+            if ct[b] <= 0 and (b == 0 or st[b - 1] == COMPLETED):
+                st[b] = COMPLETED
+        elif st[b] in (ACTIVATED, FULLY_ACTIVATED):
+            if filled[b] == block_len:
+                st[b], ct[b] = STABILIZING, delay
+            elif st[b] == ACTIVATED and done_prev >= full_at:
+                st[b] = FULLY_ACTIVATED
+        elif st[b] == INACTIVE:
+            if b > 0 and st[b - 1] != INACTIVE and done_prev >= add_at:
+                st[b] = FULLY_ACTIVATED if done_prev >= full_at else ACTIVATED
+            break                                   # only the first inactive block can be added
+    return st, ct
+
+
+def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", add_at=0.1, full_at=0.95,
+                      delay=1, widen=None, n_layers=None, store=None, record=None, max_rounds=None):
+    """Multi-block decoding of n_blocks blocks after the prompt.  Every round: one forward over the
+    window of Activated / Fully-Activated blocks (against the cache, or without it while a block is
+    Stabilizing, in which case the cache is rewritten from that forward), selection per block with
+    a floor of 0 (Activated) or 1 (Fully-Activated), then the state transitions.
+    Returns (tokens of prompt + generation, number of forwards)."""
+    ms = model.ms
+    prompt = np.asarray(prompt, dtype=np.int64)
+    P = len(prompt)
+    gen = np.full(n_blocks * block_len, ms.mask_id, dtype=np.int64)
+    state = [INACTIVE] * n_blocks
+    counter = [0] * n_blocks
+    state[0] = FULLY_ACTIVATED
+    ck, cv = prefill(model, prompt, None, n_layers, widen, store)       # cache of the prompt
+    n_done = 0                                                          # Completed blocks (in the cache)
+    rounds = 0
+    limit = max_rounds if max_rounds is not None else 4 * n_blocks * block_len + 8 * n_blocks
+    while (gen == ms.mask_id).any():
+        assert rounds < limit, "multi-block decoding does not terminate"
+        active = [b for b in range(n_blocks) if state[b] in (ACTIVATED, FULLY_ACTIVATED)]
+        lo, hi = active[0], active[-1]
+        nocache = any(s == STABILIZING for s in state)
+        if nocache:
+            seq = np.concatenate([prompt, gen[:(hi + 1) * block_len]])
+            logits_all, Ks, Vs, _ = forward_full(model, seq, n_layers, widen, store=store)
+            logits = logits_all[P + lo * block_len:]
+        else:
+            assert lo == n_done
+            window = gen[lo * block_len:(hi + 1) * block_len]
+            logits, _ = forward_cached(model, window, ck, cv, n_layers, widen, store=store)
+        cand, conf, ent, _ = confidence(logits, ms.mask_id)
+        before = gen.copy()
+        chosen = []
+        for b in active:
+            off = (b - lo) * block_len
+            sl = slice(b * block_len, (b + 1) * block_len)
+            floor = 1 if state[b] == FULLY_ACTIVATED else 0
+            if rule == "entropy":
+                gen[sl], ch = unmask_entropy(gen[sl], cand[off:off + block_len], ent[off:off + block_len],
+                                             ms.mask_id, thr, floor)
+            else:
+                gen[sl], ch = unmask(gen[sl], cand[off:off + block_len], conf[off:off + block_len],
+                                     ms.mask_id, thr, floor)
+            chosen += [b * block_len + i for i in ch]
+        filled = [int((gen[b * block_len:(b + 1) * block_len] != ms.mask_id).sum()) for b in range(n_blocks)]
+        new_state, counter = fsm_update(state, counter, filled, block_len, add_at, full_at, delay, nocache)
+        n_done_new = sum(1 for s in new_state if s == COMPLETED)
+        if nocache and n_done_new > n_done:
+            # the blocks that became Completed take their K/V from this round's no-cache forward, which
+            # also rewrites the cache of everything before them
+            n = P + n_done_new * block_len
+            ck, cv = [k[:n] for k in Ks], [v[:n] for v in Vs]
+        if record is not None:
+            record.append({"before": before, "lo": lo, "hi": hi, "nocache": nocache, "state": list(state),
+                           "cand": cand, "conf": conf, "entropy": ent, "chosen": chosen,
+                           "state_after": list(new_state), "counter_after": list(counter)})
+        state, n_done = new_state, n_done_new
+        rounds += 1
+    return np.concatenate([prompt, gen]), rounds

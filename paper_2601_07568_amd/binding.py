@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
+        "dllm_unmask_blocks": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp, vp]),
+        "dllm_fsm_update": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, C.c_double, C.c_double, i32, i32, vp, vp]),
         "dllm_refresh_cache": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "dllm_debug_logits": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_debug_hidden": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp]),
@@ -205,6 +207,20 @@ class Engine:
         self._check(lib().dllm_unmask_entropy(self.ctx, self._stream(), B, Q, block_len or Q, _ptr(q_tokens),
                                               _ptr(cand), _ptr(entropy), theta, min_unmask, _ptr(n_unmasked),
                                               _ptr(n_remaining)))
+
+    def unmask_blocks(self, q_tokens, cand, stat, threshold, floor, by_entropy, block_len, n_unmasked=None,
+                      n_remaining=None):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_unmask_blocks(self.ctx, self._stream(), B, Q, block_len, _ptr(q_tokens), _ptr(cand),
+                                             _ptr(stat), threshold, 1 if by_entropy else 0, _ptr(floor),
+                                             _ptr(n_unmasked), _ptr(n_remaining)))
+
+    def fsm_update(self, gen_tokens, state, counter, block_len, add_at, full_at, delay, nocache_round,
+                   floor_next=None, summary=None):
+        B, NB = state.shape
+        self._check(lib().dllm_fsm_update(self.ctx, self._stream(), B, NB, block_len, _ptr(gen_tokens), _ptr(state),
+                                          _ptr(counter), add_at, full_at, delay, 1 if nocache_round else 0,
+                                          _ptr(floor_next), _ptr(summary)))
 
     def refresh_cache(self, tokens, cu_seqlens, block_table, n_commit=None, cand=None, conf=None, entropy=None,
                       *, total_tokens, max_seqlen):

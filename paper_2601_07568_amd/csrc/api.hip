@@ -500,6 +500,34 @@ extern "C" int dllm_unmask_entropy(dllm_ctx* c, void* stream, int B, int Q, int 
   return DLLM_OK;
 }
 
+extern "C" int dllm_unmask_blocks(dllm_ctx* c, void* stream, int B, int Q, int block_len, int32_t* q_tokens,
+                                  const int32_t* cand_token, const float* stat, float threshold, int by_entropy,
+                                  const int32_t* floor, int32_t* n_unmasked, int32_t* n_remaining) {
+  if (!c || !q_tokens || !cand_token || !stat || !floor) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || block_len < 1 || Q % block_len != 0) return DLLM_EINVAL;
+  if (threshold != threshold) return DLLM_EINVAL;
+  if (block_len > 1024 || (int64_t)B * (Q / block_len) > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_unmask((hipStream_t)stream, B, Q, block_len, q_tokens, cand_token, stat, threshold, 0, c->cfg.mask_id,
+                    n_unmasked, n_remaining, by_entropy != 0, floor), "unmask_blocks");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_update(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, const int32_t* gen_tokens,
+                               int32_t* state, int32_t* counter, double add_at, double full_at, int delay,
+                               int nocache_round, int32_t* floor_next, int32_t* summary) {
+  if (!c || !gen_tokens || !state || !counter) return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || delay < 0) return DLLM_EINVAL;
+  if (!(add_at >= 0.0) || !(full_at >= 0.0)) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || block_len > (1 << 20)) return DLLM_ESHAPE;
+  // the counts of unmasked positions from which "filled / block_len >= threshold" holds, in double
+  int need_add = 0, need_full = 0;
+  while (need_add <= block_len && (double)need_add / (double)block_len < add_at) ++need_add;
+  while (need_full <= block_len && (double)need_full / (double)block_len < full_at) ++need_full;
+  TRY(launch_fsm_update((hipStream_t)stream, B, n_blocks, block_len, gen_tokens, c->cfg.mask_id, state, counter,
+                        need_add, need_full, delay, nocache_round != 0, floor_next, summary), "fsm_update");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_reset_status(dllm_ctx* c, void* stream) {
   if (!c) return DLLM_EINVAL;
   TRY(launch_set_i32((hipStream_t)stream, WSP(c, status, int32_t), 16, 0), "reset_status");

@@ -229,7 +229,10 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
                            float* entropy);
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
-                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false);
+                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false, const int32_t* floors = nullptr);
+hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,
+                             int32_t* state, int32_t* counter, int need_add, int need_full, int delay, int nocache_round,
+                             int32_t* floor_next, int32_t* summary);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
 
 // ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------

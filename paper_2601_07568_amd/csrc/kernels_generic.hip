@@ -533,9 +533,11 @@ __device__ inline bool conf_before(float a, int ia, float b, int ib) {
 }
 __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                                                const float* conf, float thr, int min_unmask, int32_t mask_id,
-                                               int32_t* n_unmasked, int32_t* n_remaining, int low_first) {
+                                               int32_t* n_unmasked, int32_t* n_remaining, int low_first,
+                                               const int32_t* floors) {
   // low_first: the statistic is an entropy - low values pass the threshold and come first; the
-  // selection runs on its negation
+  // selection runs on its negation.  floors: optional floor per (sequence, block) instead of
+  // min_unmask; a negative entry leaves the block untouched.
   __shared__ float cf[1024];
   __shared__ unsigned char msk[1024];
   const int nblk = Q / block_len;
@@ -551,10 +553,11 @@ __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_
   }
   for (int o = 32; o > 0; o >>= 1) n_masked += __shfl_xor(n_masked, o, 64);
   __syncthreads();
-  const int floor_n = min(min_unmask, n_masked);
+  const int floor_in = floors ? floors[blockIdx.x] : min_unmask;
+  const int floor_n = min(floor_in, n_masked);
   int n_un = 0;
   for (int i = lane; i < block_len; i += 64) {
-    if (!msk[i]) continue;
+    if (!msk[i] || floor_in < 0) continue;
     const float c = cf[i];
     bool take = (c >= thr);
     if (!take) {
@@ -818,9 +821,66 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
 
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                          const float* conf, float thr, int min_unmask, int32_t mask_id, int32_t* n_unmasked,
-                         int32_t* n_remaining, bool low_first) {
+                         int32_t* n_remaining, bool low_first, const int32_t* floors) {
   k_unmask<<<B * (Q / block_len), 64, 0, s>>>(Q, block_len, q_tokens, cand, conf, low_first ? -thr : thr, min_unmask,
-                                              mask_id, n_unmasked, n_remaining, low_first ? 1 : 0);
+                                              mask_id, n_unmasked, n_remaining, low_first ? 1 : 0, floors);
+  return hipGetLastError();
+}
+
+// Block states of multi-block decoding, one wave per sequence: count the unmasked positions of every
+// block, then lane 0 walks the blocks in order and applies the transitions.  need_add / need_full are
+// the unmasked counts that mean "10 %" and "95 %" complete (computed on the host in double).
+__global__ __launch_bounds__(64) void k_fsm_update(int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,
+                                                   int32_t* state, int32_t* counter, int need_add, int need_full,
+                                                   int delay, int nocache_round, int32_t* floor_next,
+                                                   int32_t* summary) {
+  __shared__ int filled[DLLM_FSM_MAX_BLOCKS];
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int32_t* g = gen + (int64_t)b * n_blocks * block_len;
+  for (int k = 0; k < n_blocks; ++k) {
+    int n = 0;
+    for (int i = lane; i < block_len; i += 64) n += g[(int64_t)k * block_len + i] != mask_id;
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_xor(n, o, 64);
+    if (lane == 0) filled[k] = n;
+  }
+  __syncthreads();
+  if (lane != 0) return;
+  int32_t* st = state + (int64_t)b * n_blocks;
+  int32_t* ct = counter + (int64_t)b * n_blocks;
+  for (int k = 0; k < n_blocks; ++k) {
+    const int prev = k == 0 ? block_len : filled[k - 1];
+    const int sk = st[k];
+    if (sk == DLLM_BLOCK_STABILIZING) {
+      if (nocache_round) ct[k] -= 1;
+      if (ct[k] <= 0 && (k == 0 || st[k - 1] == DLLM_BLOCK_COMPLETED)) st[k] = DLLM_BLOCK_COMPLETED;
+    } else if (sk == DLLM_BLOCK_ACTIVATED || sk == DLLM_BLOCK_FULLY_ACTIVATED) {
+      if (filled[k] == block_len) { st[k] = DLLM_BLOCK_STABILIZING; ct[k] = delay; }
+      else if (sk == DLLM_BLOCK_ACTIVATED && prev >= need_full) st[k] = DLLM_BLOCK_FULLY_ACTIVATED;
+    } else if (sk == DLLM_BLOCK_INACTIVE) {
+      if (k > 0 && st[k - 1] != DLLM_BLOCK_INACTIVE && prev >= need_add)
+        st[k] = prev >= need_full ? DLLM_BLOCK_FULLY_ACTIVATED : DLLM_BLOCK_ACTIVATED;
+      break;                                       // only the first inactive block can be added
+    }
+  }
+  int lo = -1, hi = -1, stab = 0, done = 0;
+  for (int k = 0; k < n_blocks; ++k) {
+    const int sk = st[k];
+    const bool act = sk == DLLM_BLOCK_ACTIVATED || sk == DLLM_BLOCK_FULLY_ACTIVATED;
+    if (act) { if (lo < 0) lo = k; hi = k; }
+    stab |= sk == DLLM_BLOCK_STABILIZING;
+    done += sk == DLLM_BLOCK_COMPLETED;
+    if (floor_next) floor_next[(int64_t)b * n_blocks + k] = sk == DLLM_BLOCK_FULLY_ACTIVATED ? 1 : (sk == DLLM_BLOCK_ACTIVATED ? 0 : -1);
+  }
+  if (summary) {
+    summary[b * 4 + 0] = lo; summary[b * 4 + 1] = hi; summary[b * 4 + 2] = stab; summary[b * 4 + 3] = done;
+  }
+}
+
+hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,
+                             int32_t* state, int32_t* counter, int need_add, int need_full, int delay, int nocache_round,
+                             int32_t* floor_next, int32_t* summary) {
+  k_fsm_update<<<B, 64, 0, s>>>(n_blocks, block_len, gen, mask_id, state, counter, need_add, need_full, delay,
+                                nocache_round, floor_next, summary);
   return hipGetLastError();
 }
 

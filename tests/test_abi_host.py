@@ -105,6 +105,14 @@ def test_calls_validate_before_launching():
     assert L.dllm_unmask_entropy(ctx, None, 1, 32, 32, p, p, None, 0.45, 1, None, None) == E
     assert L.dllm_unmask_entropy(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E
     assert L.dllm_unmask_entropy(ctx, None, 1, 4096, 2048, p, p, p, 0.45, 1, None, None) == S
+    # per-block floors and the block state machine
+    assert L.dllm_unmask_blocks(ctx, None, 1, 64, 32, p, p, p, 0.45, 1, None, None, None) == E    # floors are required
+    assert L.dllm_unmask_blocks(ctx, None, 1, 64, 48, p, p, p, 0.45, 1, p, None, None) == E
+    assert L.dllm_fsm_update(ctx, None, 1, 8, 32, None, p, p, 0.1, 0.95, 1, 0, None, None) == E
+    assert L.dllm_fsm_update(ctx, None, 1, 0, 32, p, p, p, 0.1, 0.95, 1, 0, None, None) == E
+    assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, float("nan"), 0.95, 1, 0, None, None) == E
+    assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, 0.1, 0.95, -1, 0, None, None) == E
+    assert L.dllm_fsm_update(ctx, None, 1, 257, 32, p, p, p, 0.1, 0.95, 1, 0, None, None) == S
     assert L.dllm_unmask(ctx, None, 1, 32, 5, p, p, p, 0.9, 1, None, None) == E         # Q % block_len
     assert L.dllm_unmask(ctx, None, 1, 32, 32, None, p, p, 0.9, 1, None, None) == E
     assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E

@@ -454,6 +454,109 @@ def test_round_bf16_is_nearest_even():
     assert got[3] == 1.0 and got[4] == 1.0 + 2.0 ** -6               # ties go to the even mantissa
 
 
+# ------------------------------------------------------------------ multi-block state machine
+
+def test_fsm_transitions_follow_the_stated_rules():
+    """Block-add at 10 %, fully-activate at 95 %, Stabilizing when full, Completed after `delay` no-cache rounds
+    and never before the predecessor (Section 3.2; appendix thresholds), on hand-made situations."""
+    I, A, F, S, C = O.INACTIVE, O.ACTIVATED, O.FULLY_ACTIVATED, O.STABILIZING, O.COMPLETED
+    up = lambda st, ct, filled, nocache=False, delay=1: O.fsm_update(st, ct, filled, 32, 0.1, 0.95, delay, nocache)
+    # 3 of 32 unmasked is 9.4 %: nothing is added; 4 of 32 is 12.5 %: the next block is added, Activated
+    assert up([F, I, I], [0, 0, 0], [3, 0, 0])[0] == [F, I, I]
+    assert up([F, I, I], [0, 0, 0], [4, 0, 0])[0] == [F, A, I]
+    # only the first inactive block is ever added, however far the first block is
+    assert up([F, I, I], [0, 0, 0], [20, 0, 0])[0] == [F, A, I]
+    # 30 of 32 is 93.75 %: still Activated; 31 of 32 is 96.9 %: Fully-Activated
+    assert up([F, A, I], [0, 0, 0], [30, 2, 0])[0] == [F, A, I]
+    assert up([F, A, I], [0, 0, 0], [31, 2, 0])[0] == [F, F, I]
+    # a block that fills up starts Stabilizing with the delay as its counter; its successor follows the 95 % rule
+    st, ct = up([F, A, I], [0, 0, 0], [32, 5, 0], delay=2)
+    assert st == [S, F, A] and ct[0] == 2
+    # Stabilizing counts only rounds whose forward did not use the cache
+    assert up([S, F, A], [2, 0, 0], [32, 9, 0], nocache=False, delay=2) == ([S, F, A], [2, 0, 0])
+    assert up([S, F, A], [2, 0, 0], [32, 9, 0], nocache=True, delay=2) == ([S, F, A], [1, 0, 0])
+    assert up([S, F, A], [1, 0, 0], [32, 9, 0], nocache=True, delay=2)[0] == [C, F, A]
+    # a later block may fill first, but it is not Completed before its predecessor
+    st, ct = up([F, S], [0, 1], [31, 32], nocache=True)
+    assert st == [F, S] and ct[1] == 0
+    st, ct = up([S, S], [1, 0], [32, 32], nocache=True)
+    assert st == [C, C]                                      # in block order: block 0 first, then block 1 may follow
+    # a block added when its predecessor is already past 95 % starts Fully-Activated
+    assert up([F, I], [0, 0], [31, 0])[0] == [F, F]
+
+
+def sequential_schedule_reference(model, prompt, n_blocks, block_len, theta):
+    """What multi-block decoding must reduce to when a block is only added once its predecessor is complete
+    (add_at = full_at = 1, delay = 1): one block at a time with a floor of 1; the round after a block fills up
+    is a no-cache forward over everything including the next block's masks, which both decides that block's
+    first unmasking and supplies the cache (prompt + filled blocks) for its remaining rounds."""
+    ms = model.ms
+    seq = np.array(prompt, dtype=np.int64)
+    ck, cv = O.prefill(model, seq)
+    rounds = 0
+    for b in range(n_blocks):
+        blk = np.full(block_len, ms.mask_id, dtype=np.int64)
+        first = b > 0
+        while (blk == ms.mask_id).any():
+            if first:
+                full = np.concatenate([seq, blk])
+                logits_all, Ks, Vs, _ = O.forward_full(model, full)
+                logits = logits_all[len(seq):]
+                ck, cv = [k[:len(seq)] for k in Ks], [v[:len(seq)] for v in Vs]
+                first = False
+            else:
+                logits, _ = O.forward_cached(model, blk, ck, cv)
+            cand, conf, ent, _ = O.confidence(logits, ms.mask_id)
+            blk, _ = O.unmask_entropy(blk, cand, ent, ms.mask_id, theta, 1)
+            rounds += 1
+        seq = np.concatenate([seq, blk])
+    return seq, rounds
+
+
+def test_multiblock_reduces_to_one_block_at_a_time():
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 11, 16)
+    a, ra = O.decode_multiblock(model, toks[:9], 3, 4, 2.5, "entropy", add_at=1.0, full_at=1.0, delay=1)
+    b, rb = sequential_schedule_reference(model, toks[:9], 3, 4, 2.5)
+    np.testing.assert_array_equal(a, b)
+    assert ra == rb
+
+
+@pytest.mark.parametrize("theta,delay", [(0.5, 1), (3.0, 2), (100.0, 1)])
+def test_multiblock_invariants(theta, delay):
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 12, 16)
+    ms = model.ms
+    rec = []
+    seq, rounds = O.decode_multiblock(model, toks[:7], 4, 4, theta, "entropy", add_at=0.25, full_at=0.75, delay=delay,
+                                      record=rec)
+    assert len(seq) == 7 + 16 and (seq != ms.mask_id).all() and rounds == len(rec)
+    prev_state = None
+    for r in rec:
+        st = r["state"]
+        # a forward without the cache exactly when a block is stabilizing
+        assert r["nocache"] == (O.STABILIZING in st)
+        # the window is the run of active blocks; Completed blocks precede it in order
+        assert all(s in (O.ACTIVATED, O.FULLY_ACTIVATED) for s in st[r["lo"]:r["hi"] + 1] if s != O.STABILIZING)
+        comp = [i for i, s in enumerate(st) if s == O.COMPLETED]
+        assert comp == list(range(len(comp)))
+        # states only move forward, never re-mask, a fully activated block always makes progress
+        if prev_state is not None:
+            assert all(x >= y for x, y in zip(st, prev_state))
+        prev_state = st
+        before = r["before"]
+        for b, s in enumerate(st):
+            n = sum(1 for i in r["chosen"] if i // 4 == b)
+            if s == O.FULLY_ACTIVATED:
+                assert n >= 1
+            if s not in (O.ACTIVATED, O.FULLY_ACTIVATED):
+                assert n == 0
+        assert all(before[i] == ms.mask_id for i in r["chosen"])
+    # theta above every entropy: each block is filled in the round it is first seen, so few rounds
+    if theta >= 100:
+        assert rounds <= 4 + 1
+
+
 # ------------------------------------------------------------------ stored trajectory
 
 def test_oracle_reproduces_the_stored_tiny_trajectory():
