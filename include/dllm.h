@@ -213,6 +213,36 @@ int dllm_fsm_update(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_
                     int32_t *state, int32_t *counter, double add_at, double full_at, int delay, int nocache_round,
                     int32_t *floor_next, int32_t *summary);
 
+/* The selection of dllm_unmask / dllm_unmask_entropy that also records the decoding order (Section 3.1:
+ * the teacher's pseudo-trajectory is the order in which its tokens are decoded, one per step, for the
+ * full output length): order[b, i] = step_index for every position this call unmasks, other entries are
+ * left as they are.  With threshold above 1 (by_entropy = 0) and min_unmask = 1 exactly one position per
+ * block is decoded per call; trajectory state T_j then has position i decoded iff order[b, i] <= j.
+ *   order dev int32 [B, Q] in/out; other arguments as for dllm_unmask_blocks / dllm_unmask. */
+int dllm_unmask_traced(dllm_ctx *ctx, void *stream, int B, int Q, int block_len, int32_t *q_tokens,
+                       const int32_t *cand_token, const float *stat, float threshold, int by_entropy, int min_unmask,
+                       int32_t step_index, int32_t *order, int32_t *n_unmasked, int32_t *n_remaining);
+
+/* Noisy sequence of pseudo-trajectory distillation (Section 3.1, the displayed case formula): given the
+ * ground-truth response y, the teacher's decoding order, a decoding window {s, ..., s + k} and a ratio t,
+ * position i (1-based, as in the paper; array index i - 1) of the output is y_i if i <= s, [MASK] if
+ * i > s + k, and inside the window y_i iff order_i <= s + ceil(k t) (decoded in trajectory state
+ * T_{s + ceil(k t)}), else [MASK].  Where the two printed cases overlap the window bounds decide.
+ *   y, order dev int32 [B, n]; window_start dev int32 [B] (s per sequence); out dev int32 [B, n]
+ *   Requires 0 <= t <= 1, k >= 0, B <= 65535. */
+int dllm_noisy_sequence(dllm_ctx *ctx, void *stream, int B, int n, const int32_t *y, const int32_t *order,
+                        const int32_t *window_start, int k, double t, int32_t *out);
+
+/* Early stopping (Section 3.2, "Early Stopping on EOS Token"): a sequence is finished once an
+ * end-of-sequence token has been decoded and no [MASK] is left before it; the caller stops issuing
+ * forwards for it.  finished[b] = 1/0, first_eos[b] = index of that token or -1.  active_index lists,
+ * in order, the sequences that are not finished (entries past n_active[0] are -1), for the caller to
+ * gather the next call's batch from.
+ *   gen_tokens dev int32 [B, n]; finished dev int32 [B]; first_eos dev int32 [B] or NULL;
+ *   active_index dev int32 [B] and n_active dev int32 [1], both or neither. */
+int dllm_eos_scan(dllm_ctx *ctx, void *stream, int B, int n, const int32_t *gen_tokens, int32_t eos_id,
+                  int32_t *finished, int32_t *first_eos, int32_t *active_index, int32_t *n_active);
+
 /* KV refresh (Section 3.2, "KV-Refresh"; the forward passes of the "Completed but Stabilizing"
  * state): the same no-cache forward as dllm_prefill_kv over the committed tokens, optionally
  * followed by in-flight ones, overwriting the cached K/V of positions [0, n_commit[b]) (all if

@@ -378,3 +378,54 @@ def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", a
         state, n_done = new_state, n_done_new
         rounds += 1
     return np.concatenate([prompt, gen]), rounds
+
+
+# ---------------------------------------------------------------------------------------------
+# Teacher pseudo-trajectory (Section 3.1; appendix "Extracting Pseudo Trajectory of the Teacher
+# dLLM") and early stopping (Section 3.2, "Early Stopping on EOS Token").
+
+def teacher_trajectory(model, prompt, n_blocks, block_len, widen=None, n_layers=None, store=None):
+    """The teacher's decoding order: exactly one token is unmasked per step (the most confident
+    masked position of the current block; threshold above 1, floor 1), generation runs for the
+    full length n = n_blocks * block_len whatever is decoded (no stop at an end-of-sequence token).
+    Returns (tokens [n], order [n]) with order[i] = the step (1 .. n) that unmasked position i, so
+    that trajectory state T_j has position i decoded iff order[i] <= j."""
+    rec = []
+    seq, steps = decode(model, prompt, n_blocks, block_len, 2.0, 1, widen, n_layers, rec, store)
+    n = n_blocks * block_len
+    assert steps == n
+    order = np.zeros(n, dtype=np.int64)
+    for j, r in enumerate(rec):
+        (i,) = r["chosen"]
+        order[(j // block_len) * block_len + i] = j + 1
+    return seq[len(prompt):], order
+
+
+def noisy_sequence(y, order, s, k, t, mask_id):
+    """Noisy training sequence of Section 3.1 (the displayed case formula): with the decoding window
+    {s, ..., s + k} and ratio t, position i (1-based in the paper) keeps the ground truth y_i if
+    i <= s, is [MASK] if i > s + k, and inside the window keeps y_i iff the teacher's trajectory
+    state T_{s + ceil(k t)} has it decoded.  Where the two printed cases overlap, the window bounds
+    decide.  Indices here are 0-based: position j is the paper's i = j + 1."""
+    y = np.asarray(y)
+    m = s + int(np.ceil(k * t))
+    out = np.array(y, copy=True)
+    for j in range(len(y)):
+        i = j + 1
+        if i <= s:
+            continue
+        if i > s + k or order[j] > m:
+            out[j] = mask_id
+    return out
+
+
+def eos_state(gen, eos_id, mask_id):
+    """Early stop: a sequence is finished once an end-of-sequence token has been decoded with no
+    [MASK] left before it (so everything up to it is final).  Returns (finished, index of that token
+    or -1)."""
+    for p, tok in enumerate(gen):
+        if tok == mask_id:
+            return False, -1
+        if tok == eos_id:
+            return True, p
+    return False, -1

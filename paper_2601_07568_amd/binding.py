@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
+        "dllm_unmask_traced": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]),
+        "dllm_noisy_sequence": (i32, [vp, vp, i32, i32, vp, vp, vp, i32, C.c_double, vp]),
+        "dllm_eos_scan": (i32, [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]),
         "dllm_unmask_blocks": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp, vp]),
         "dllm_fsm_update": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, C.c_double, C.c_double, i32, i32, vp, vp]),
         "dllm_refresh_cache": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
@@ -214,6 +217,23 @@ class Engine:
         self._check(lib().dllm_unmask_blocks(self.ctx, self._stream(), B, Q, block_len, _ptr(q_tokens), _ptr(cand),
                                              _ptr(stat), threshold, 1 if by_entropy else 0, _ptr(floor),
                                              _ptr(n_unmasked), _ptr(n_remaining)))
+
+    def unmask_traced(self, q_tokens, cand, stat, threshold, min_unmask, step_index, order, by_entropy=False,
+                      block_len=None, n_unmasked=None, n_remaining=None):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_unmask_traced(self.ctx, self._stream(), B, Q, block_len or Q, _ptr(q_tokens),
+                                             _ptr(cand), _ptr(stat), threshold, 1 if by_entropy else 0, min_unmask,
+                                             step_index, _ptr(order), _ptr(n_unmasked), _ptr(n_remaining)))
+
+    def noisy_sequence(self, y, order, window_start, k, t, out):
+        B, n = y.shape
+        self._check(lib().dllm_noisy_sequence(self.ctx, self._stream(), B, n, _ptr(y), _ptr(order),
+                                              _ptr(window_start), k, t, _ptr(out)))
+
+    def eos_scan(self, gen_tokens, eos_id, finished, first_eos=None, active_index=None, n_active=None):
+        B, n = gen_tokens.shape
+        self._check(lib().dllm_eos_scan(self.ctx, self._stream(), B, n, _ptr(gen_tokens), eos_id, _ptr(finished),
+                                        _ptr(first_eos), _ptr(active_index), _ptr(n_active)))
 
     def fsm_update(self, gen_tokens, state, counter, block_len, add_at, full_at, delay, nocache_round,
                    floor_next=None, summary=None):

@@ -528,6 +528,42 @@ extern "C" int dllm_fsm_update(dllm_ctx* c, void* stream, int B, int n_blocks, i
   return DLLM_OK;
 }
 
+extern "C" int dllm_unmask_traced(dllm_ctx* c, void* stream, int B, int Q, int block_len, int32_t* q_tokens,
+                                  const int32_t* cand_token, const float* stat, float threshold, int by_entropy,
+                                  int min_unmask, int32_t step_index, int32_t* order, int32_t* n_unmasked,
+                                  int32_t* n_remaining) {
+  if (!c || !q_tokens || !cand_token || !stat || !order) return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || block_len < 1 || min_unmask < 0 || Q % block_len != 0) return DLLM_EINVAL;
+  if (threshold != threshold) return DLLM_EINVAL;
+  if (block_len > 1024 || (int64_t)B * (Q / block_len) > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_unmask((hipStream_t)stream, B, Q, block_len, q_tokens, cand_token, stat, threshold, min_unmask,
+                    c->cfg.mask_id, n_unmasked, n_remaining, by_entropy != 0, nullptr, order, step_index),
+      "unmask_traced");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_noisy_sequence(dllm_ctx* c, void* stream, int B, int n, const int32_t* y, const int32_t* order,
+                                   const int32_t* window_start, int k, double t, int32_t* out) {
+  if (!c || !y || !order || !window_start || !out) return DLLM_EINVAL;
+  if (B < 1 || n < 1 || k < 0 || !(t >= 0.0) || !(t <= 1.0)) return DLLM_EINVAL;
+  if (B > 65535 || n > (1 << 28)) return DLLM_ESHAPE;
+  const int kt = (int)ceil((double)k * t);
+  TRY(launch_noisy_sequence((hipStream_t)stream, B, n, y, order, window_start, k, kt, c->cfg.mask_id, out),
+      "noisy_sequence");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_eos_scan(dllm_ctx* c, void* stream, int B, int n, const int32_t* gen_tokens, int32_t eos_id,
+                             int32_t* finished, int32_t* first_eos, int32_t* active_index, int32_t* n_active) {
+  if (!c || !gen_tokens || !finished) return DLLM_EINVAL;
+  if (B < 1 || n < 1 || (active_index == nullptr) != (n_active == nullptr)) return DLLM_EINVAL;
+  if (eos_id < 0 || eos_id >= c->cfg.vocab || eos_id == c->cfg.mask_id) return DLLM_EINVAL;
+  if (B > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_eos_scan((hipStream_t)stream, B, n, gen_tokens, eos_id, c->cfg.mask_id, finished, first_eos, active_index,
+                      n_active), "eos_scan");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_reset_status(dllm_ctx* c, void* stream) {
   if (!c) return DLLM_EINVAL;
   TRY(launch_set_i32((hipStream_t)stream, WSP(c, status, int32_t), 16, 0), "reset_status");

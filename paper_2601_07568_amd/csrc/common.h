@@ -229,7 +229,12 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
                            float* entropy);
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
-                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false, const int32_t* floors = nullptr);
+                         int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false, const int32_t* floors = nullptr,
+                         int32_t* order = nullptr, int32_t step_index = 0);
+hipError_t launch_noisy_sequence(hipStream_t s, int B, int n, const int32_t* y, const int32_t* order, const int32_t* s_dev,
+                                 int k, int kt, int32_t mask_id, int32_t* out);
+hipError_t launch_eos_scan(hipStream_t s, int B, int n, const int32_t* gen, int32_t eos_id, int32_t mask_id,
+                           int32_t* finished, int32_t* first_eos, int32_t* active_index, int32_t* n_active);
 hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,
                              int32_t* state, int32_t* counter, int need_add, int need_full, int delay, int nocache_round,
                              int32_t* floor_next, int32_t* summary);

@@ -534,7 +534,7 @@ __device__ inline bool conf_before(float a, int ia, float b, int ib) {
 __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                                                const float* conf, float thr, int min_unmask, int32_t mask_id,
                                                int32_t* n_unmasked, int32_t* n_remaining, int low_first,
-                                               const int32_t* floors) {
+                                               const int32_t* floors, int32_t* order, int32_t step_index) {
   // low_first: the statistic is an entropy - low values pass the threshold and come first; the
   // selection runs on its negation.  floors: optional floor per (sequence, block) instead of
   // min_unmask; a negative entry leaves the block untouched.
@@ -568,6 +568,7 @@ __global__ __launch_bounds__(64) void k_unmask(int Q, int block_len, int32_t* q_
     }
     if (take) {
       q_tokens[base + i] = cand[base + i];
+      if (order) order[base + i] = step_index;      // the decoding order of the trajectory being recorded
       ++n_un;
     }
   }
@@ -821,9 +822,11 @@ hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts
 
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens, const int32_t* cand,
                          const float* conf, float thr, int min_unmask, int32_t mask_id, int32_t* n_unmasked,
-                         int32_t* n_remaining, bool low_first, const int32_t* floors) {
+                         int32_t* n_remaining, bool low_first, const int32_t* floors, int32_t* order,
+                         int32_t step_index) {
   k_unmask<<<B * (Q / block_len), 64, 0, s>>>(Q, block_len, q_tokens, cand, conf, low_first ? -thr : thr, min_unmask,
-                                              mask_id, n_unmasked, n_remaining, low_first ? 1 : 0, floors);
+                                              mask_id, n_unmasked, n_remaining, low_first ? 1 : 0, floors, order,
+                                              step_index);
   return hipGetLastError();
 }
 
@@ -881,6 +884,71 @@ hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, 
                              int32_t* floor_next, int32_t* summary) {
   k_fsm_update<<<B, 64, 0, s>>>(n_blocks, block_len, gen, mask_id, state, counter, need_add, need_full, delay,
                                 nocache_round, floor_next, summary);
+  return hipGetLastError();
+}
+
+// noisy sequence from a recorded decoding order: position j (0-based) keeps y if j < s, is masked if
+// j >= s + k, and inside the window keeps y iff it was decoded by step s + kt
+__global__ void k_noisy_sequence(int n, const int32_t* y, const int32_t* order, const int32_t* s_dev, int k, int kt,
+                                 int32_t mask_id, int32_t* out) {
+  const int b = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int s = s_dev[b];
+  const int64_t at = (int64_t)b * n + j;
+  const int i = j + 1;
+  int32_t v = y[at];
+  if (i > s && (i > s + k || order[at] > s + kt)) v = mask_id;
+  out[at] = v;
+}
+
+hipError_t launch_noisy_sequence(hipStream_t s, int B, int n, const int32_t* y, const int32_t* order, const int32_t* s_dev,
+                                 int k, int kt, int32_t mask_id, int32_t* out) {
+  dim3 grid((n + 255) / 256, B);
+  k_noisy_sequence<<<grid, 256, 0, s>>>(n, y, order, s_dev, k, kt, mask_id, out);
+  return hipGetLastError();
+}
+
+// early stop: one wave per sequence finds the first [MASK] and the first end-of-sequence token; the
+// sequence is finished if the latter comes first.  A second, single-wave kernel lists the sequences
+// that are not finished, in order.
+__global__ __launch_bounds__(64) void k_eos_scan(int n, const int32_t* gen, int32_t eos_id, int32_t mask_id,
+                                                 int32_t* finished, int32_t* first_eos) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int32_t* g = gen + (int64_t)b * n;
+  int fm = n, fe = n;
+  for (int i = lane; i < n; i += 64) {
+    const int32_t t = g[i];
+    if (t == mask_id && i < fm) fm = i;
+    if (t == eos_id && i < fe) fe = i;
+  }
+  for (int o = 32; o > 0; o >>= 1) { fm = min(fm, __shfl_xor(fm, o, 64)); fe = min(fe, __shfl_xor(fe, o, 64)); }
+  if (lane == 0) {
+    const bool fin = fe < n && fe < fm;
+    finished[b] = fin ? 1 : 0;
+    if (first_eos) first_eos[b] = fin ? fe : -1;
+  }
+}
+__global__ __launch_bounds__(64) void k_list_active(int B, const int32_t* finished, int32_t* active_index, int32_t* n_active) {
+  const int lane = threadIdx.x;
+  int count = 0;
+  for (int b0 = 0; b0 < B; b0 += 64) {
+    const int b = b0 + lane;
+    const bool act = b < B && finished[b] == 0;
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(act);
+    if (act) active_index[count + __popcll(m & ((1ull << lane) - 1ull))] = b;
+    count += __popcll(m);
+  }
+  for (int b = count + lane; b < B; b += 64) active_index[b] = -1;
+  if (lane == 0) n_active[0] = count;
+}
+
+hipError_t launch_eos_scan(hipStream_t s, int B, int n, const int32_t* gen, int32_t eos_id, int32_t mask_id,
+                           int32_t* finished, int32_t* first_eos, int32_t* active_index, int32_t* n_active) {
+  k_eos_scan<<<B, 64, 0, s>>>(n, gen, eos_id, mask_id, finished, first_eos);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !active_index || !n_active) return e;
+  k_list_active<<<1, 64, 0, s>>>(B, finished, active_index, n_active);
   return hipGetLastError();
 }
 

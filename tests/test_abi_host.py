@@ -113,6 +113,12 @@ def test_calls_validate_before_launching():
     assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, float("nan"), 0.95, 1, 0, None, None) == E
     assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, 0.1, 0.95, -1, 0, None, None) == E
     assert L.dllm_fsm_update(ctx, None, 1, 257, 32, p, p, p, 0.1, 0.95, 1, 0, None, None) == S
+    # trajectory recording, noisy sequences, early stop
+    assert L.dllm_unmask_traced(ctx, None, 1, 32, 32, p, p, p, 2.0, 0, 1, 1, None, None, None) == E   # order is required
+    assert L.dllm_noisy_sequence(ctx, None, 1, 32, p, p, p, 8, 1.5, p) == E                         # 0 <= t <= 1
+    assert L.dllm_noisy_sequence(ctx, None, 1, 32, p, p, None, 8, 0.5, p) == E
+    assert L.dllm_eos_scan(ctx, None, 1, 32, p, -1, p, None, None, None) == E
+    assert L.dllm_eos_scan(ctx, None, 1, 32, p, 5, p, None, p, None) == E                            # both or neither
     assert L.dllm_unmask(ctx, None, 1, 32, 5, p, p, p, 0.9, 1, None, None) == E         # Q % block_len
     assert L.dllm_unmask(ctx, None, 1, 32, 32, None, p, p, 0.9, 1, None, None) == E
     assert L.dllm_unmask(ctx, None, 1, 32, 32, p, p, p, float("nan"), 1, None, None) == E

@@ -170,3 +170,69 @@ def test_multiblock_decode_round_by_round(eng, thr, rule, delay, n_blocks):
     # the tiny random model's confidences sit within 1e-3 of each other far more often than its entropies
     assert checked >= max(1, len(rec) // (2 if rule == "entropy" else 8))
     assert eng.read_status() == 0
+
+
+def test_unmask_traced_records_the_teacher_order(eng):
+    """One token per step through dllm_unmask_traced on synthetic confidences: the recorded order equals the oracle's
+    replay of the same selections, and noisy sequences built from it on the device equal the oracle's."""
+    ms = eng.ms
+    rng = np.random.default_rng(77)
+    Bn, nblk, bl = 2, 3, 8
+    n = nblk * bl
+    order = torch.zeros(Bn, n, dtype=torch.int32, device=eng.device)
+    ref_order = np.zeros((Bn, n), dtype=np.int64)
+    tokens = np.full((Bn, n), ms.mask_id, dtype=np.int32)
+    qt = eng.i32(tokens)
+    step = 0
+    for blk in range(nblk):                                     # blocks in sequence, one position per step
+        for _ in range(bl):
+            step += 1
+            conf = rng.random((Bn, n)).astype(np.float32)
+            cand = rng.integers(0, 4000, (Bn, n)).astype(np.int32)
+            sl = slice(blk * bl, (blk + 1) * bl)
+            view = qt[:, sl].contiguous()
+            ov = order[:, sl].contiguous()
+            eng.unmask_traced(view, eng.i32(cand[:, sl]), torch.from_numpy(conf[:, sl].copy()).to(eng.device), 2.0, 1,
+                              step, ov)
+            qt[:, sl] = view
+            order[:, sl] = ov
+            for b in range(Bn):
+                new, ch = O.unmask(tokens[b, sl], cand[b, sl], conf[b, sl], ms.mask_id, np.float32(2.0), 1)
+                tokens[b, sl] = new
+                (i,) = ch
+                ref_order[b, blk * bl + i] = step
+    assert (qt.cpu().numpy() == tokens).all()
+    got_order = order.cpu().numpy()
+    assert (got_order == ref_order).all()
+    for b in range(Bn):
+        assert sorted(got_order[b].tolist()) == list(range(1, n + 1))
+    y = rng.integers(0, 4000, (Bn, n)).astype(np.int32)
+    out = torch.zeros(Bn, n, dtype=torch.int32, device=eng.device)
+    for s_list, k, t in (([4, 9], 8, 0.5), ([0, 0], n, 0.25), ([8, 16], 8, 1.0), ([3, 20], 5, 0.0), ([0, 23], 1, 0.7)):
+        eng.noisy_sequence(eng.i32(y), order, eng.i32(s_list), k, t, out)
+        got = out.cpu().numpy()
+        for b in range(Bn):
+            assert (got[b] == O.noisy_sequence(y[b], ref_order[b], s_list[b], k, t, ms.mask_id)).all()
+
+
+def test_eos_scan_and_active_list(eng):
+    ms = eng.ms
+    rng = np.random.default_rng(5)
+    eos = 17
+    for Bn, n in ((1, 32), (7, 100), (130, 64), (64, 1)):
+        gen = rng.integers(0, 40, (Bn, n)).astype(np.int32)          # small alphabet: EOS shows up often
+        gen[rng.random((Bn, n)) < 0.1] = ms.mask_id
+        if Bn > 3:
+            gen[2, :] = 3                                             # no EOS, no mask
+            gen[3, 0] = eos
+        fin = torch.zeros(Bn, dtype=torch.int32, device=eng.device)
+        first = torch.zeros(Bn, dtype=torch.int32, device=eng.device)
+        act = torch.zeros(Bn, dtype=torch.int32, device=eng.device)
+        nact = torch.zeros(1, dtype=torch.int32, device=eng.device)
+        eng.eos_scan(eng.i32(gen), eos, fin, first, act, nact)
+        ref = [O.eos_state(gen[b].tolist(), eos, ms.mask_id) for b in range(Bn)]
+        assert fin.cpu().numpy().tolist() == [int(f) for f, _ in ref]
+        assert first.cpu().numpy().tolist() == [p for _, p in ref]
+        alive = [b for b in range(Bn) if not ref[b][0]]
+        assert int(nact) == len(alive)
+        assert act.cpu().numpy().tolist() == alive + [-1] * (Bn - len(alive))

@@ -557,6 +557,60 @@ def test_multiblock_invariants(theta, delay):
         assert rounds <= 4 + 1
 
 
+# ------------------------------------------------------------------ teacher trajectory, noisy sequence, early stop
+
+def test_teacher_trajectory_is_a_one_token_per_step_order():
+    model = small_model()
+    toks = synth.random_tokens(model.ms, 13, 16)
+    n_blocks, bl = 3, 4
+    y, order = O.teacher_trajectory(model, toks[:6], n_blocks, bl)
+    n = n_blocks * bl
+    # one position per step, every step once, blocks in sequence (block b holds steps b*bl+1 .. (b+1)*bl)
+    assert sorted(order.tolist()) == list(range(1, n + 1))
+    for b in range(n_blocks):
+        assert sorted(order[b * bl:(b + 1) * bl].tolist()) == list(range(b * bl + 1, (b + 1) * bl + 1))
+    # replaying the order on the same model reproduces the tokens: state T_j has exactly j positions decoded
+    rec = []
+    O.decode(model, toks[:6], n_blocks, bl, 2.0, 1, record=rec)
+    for j, r in enumerate(rec):
+        decoded_before = set(np.nonzero(order <= j)[0].tolist())
+        blk0 = (j // bl) * bl
+        assert {blk0 + i for i in np.nonzero(r["before"] != model.ms.mask_id)[0]} == {i for i in decoded_before if i >= blk0}
+    assert (y != model.ms.mask_id).all()
+
+
+def test_noisy_sequence_cases_of_the_formula():
+    mask = 99
+    y = np.arange(10, 22)                                     # n = 12
+    order = np.array([3, 1, 2, 4, 8, 5, 7, 6, 9, 12, 10, 11])
+    # window {s, ..., s+k} = {4, ..., 8}, t = 0.5: trajectory state T_{4 + 2} = T_6
+    out = O.noisy_sequence(y, order, 4, 4, 0.5, mask)
+    # i <= 4 keep; i in 5..8 keep iff order <= 6: orders (8, 5, 7, 6) -> mask, keep, mask, keep; i > 8 mask
+    assert out.tolist() == [10, 11, 12, 13, mask, 15, mask, 17, mask, mask, mask, mask]
+    # t = 0: T_s; in a left-to-right-by-block trajectory nothing inside the window is decoded yet
+    assert O.noisy_sequence(y, order, 4, 4, 0.0, mask).tolist() == [10, 11, 12, 13] + [mask] * 8
+    # t = 1: T_{s+k}: the whole window is decided by steps <= 8
+    assert O.noisy_sequence(y, order, 4, 4, 1.0, mask).tolist() == [10, 11, 12, 13, 14, 15, 16, 17] + [mask] * 4
+    # s = 0, k = n: the trajectory alone decides; the number kept is the number of steps taken
+    for t in (0.0, 0.25, 0.5, 1.0):
+        o = O.noisy_sequence(y, order, 0, 12, t, mask)
+        assert int((o != mask).sum()) == int(np.ceil(12 * t))
+        assert ((o != mask) == (order <= np.ceil(12 * t))).all()
+    # a position the window bound keeps is kept even if the trajectory has not reached it (bounds decide)
+    late = np.array([12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1])
+    assert O.noisy_sequence(y, late, 4, 4, 0.5, mask)[:4].tolist() == [10, 11, 12, 13]
+    assert (O.noisy_sequence(y, late, 4, 4, 0.5, mask)[8:] == mask).all()
+
+
+def test_eos_state():
+    mask, eos = 99, 7
+    assert O.eos_state([1, 2, 7, 99, 5], eos, mask) == (True, 2)           # masks after the EOS do not matter
+    assert O.eos_state([1, 99, 7, 3], eos, mask) == (False, -1)            # a mask before it: not final yet
+    assert O.eos_state([1, 2, 3], eos, mask) == (False, -1)
+    assert O.eos_state([7], eos, mask) == (True, 0)
+    assert O.eos_state([1, 7, 7], eos, mask) == (True, 1)                  # the first one counts
+
+
 # ------------------------------------------------------------------ stored trajectory
 
 def test_oracle_reproduces_the_stored_tiny_trajectory():
