@@ -231,12 +231,93 @@ def large_batch(args, torch, np, synth, Engine, dev):
     print(json.dumps(out))
 
 
+def prefill_batch(args, torch, np, synth, Engine, dev):
+    """Workload c4 (not the default): Dream-7B-shaped model, 16 prompts of 2048 random tokens prefilled in one call
+    (32768 rows through every GEMM, bidirectional attention inside each prompt), then denoise steps with two blocks
+    of 32 in flight per sequence (64 query rows each, 1024 in all) against the 2048-token caches, tau 0.85, floor 1
+    per block.  Reports both: the prefill in TFLOP/s and the step in steps/s."""
+    ms = synth.DREAM_7B if args.layers is None else synth.DREAM_7B.with_layers(args.layers)
+    Bn, S, Q, bl, pt = 16, 2048, 64, 32, 64
+    mp = (S + Q + pt - 1) // pt
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+                 max_tokens=Bn * S, device_weights=device_weights(ms, torch, dev, 4), pack=False)
+    table = eng.i32(np.arange(Bn * mp).reshape(Bn, mp))
+    toks = eng.i32(np.concatenate([synth.random_tokens(ms, 40 + b, S) for b in range(Bn)]))
+    cu = eng.i32(np.arange(Bn + 1) * S)
+    d, dq, dkv, F, G = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff, ms.n_q_heads // ms.n_kv_heads
+    gemm_per_row = 2 * (d * (dq + 2 * dkv) + dq * d + 3 * d * F)
+
+    def prefill():
+        eng.prefill_kv(toks, cu, table, None, total_tokens=Bn * S, max_seqlen=S)
+
+    prefill()
+    torch.cuda.synchronize()
+    n_pre = 2
+    t0 = time.perf_counter()
+    for _ in range(n_pre):
+        prefill()
+    torch.cuda.synchronize()
+    pre_s = (time.perf_counter() - t0) / n_pre
+    pre_flops = ms.n_layers * (Bn * S * gemm_per_row + 4 * Bn * ms.n_q_heads * S * S * ms.head_dim)
+    eng.profile_enable(True)
+    prefill()
+    pk = {}
+    for cls, nm in KCLASS.items():
+        n, tms, work = eng.profile_read(cls)
+        if n:
+            pk[nm] = {"launches": n, "avg_us": tms / n * 1e3}
+    eng.profile_enable(False)
+
+    prefix = eng.i32([S] * Bn)
+    fresh = eng.i32(np.stack([np.concatenate([synth.masked_block(ms, 5, bl, 24, stream=2 * b),
+                                              synth.masked_block(ms, 5, bl, 32, stream=2 * b + 1)]) for b in range(Bn)]))
+    qt = fresh.clone()
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+
+    def one_step(i):
+        if i % 16 == 0:
+            qt.copy_(fresh)
+        eng.denoise_step(qt, prefix, table, cand, conf, None, max_prefix_len=S)
+        eng.unmask(qt, cand, conf, 0.85, 1, block_len=bl)
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert eng.read_status() == 0
+    T = Bn * Q
+    step_flops = ms.n_layers * (T * gemm_per_row + 4 * (Q * G) * (S + Q) * ms.head_dim * ms.n_kv_heads * Bn) \
+        + 2 * (Bn * 56) * ms.vocab * d
+    ms_per_step = elapsed / args.steps * 1e3
+    out = {"metric": "denoise_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "Dream-7B-shaped %d layers, bf16, batch 16, prompts 2048 prefilled, 2 blocks of 32 in "
+                                  "flight per sequence, tau 0.85, min 1 per block" % ms.n_layers, "layers": ms.n_layers,
+                      "prefix": S, "block": bl, "blocks_in_flight": 2, "batch": Bn, "page_tokens": pt},
+           "query_tokens_per_s": T * args.steps / elapsed, "step_algorithmic_TFLOP": step_flops / 1e12,
+           "step_TFLOPs": step_flops / (ms_per_step * 1e-3) / 1e12,
+           "step_frac_of_mfma_peak": step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+           "prefill": {"tokens": Bn * S, "seconds": pre_s, "tokens_per_s": Bn * S / pre_s,
+                       "algorithmic_TFLOP": pre_flops / 1e12, "TFLOPs": pre_flops / pre_s / 1e12,
+                       "frac_of_mfma_peak": pre_flops / pre_s / 1e12 / MFMA_PEAK_TFLOPS, "kernels": pk},
+           "roofline": {"bound": "mfma", "kernel": "prefill (all kernels)", "achieved": pre_flops / pre_s / 1e12,
+                        "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": pre_flops / pre_s / 1e12 / MFMA_PEAK_TFLOPS,
+                        "traffic": None}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--workload", default="c3", choices=["c3", "c2", "c5"])
+    ap.add_argument("--workload", default="c3", choices=["c3", "c2", "c4", "c5"])
     ap.add_argument("--layers", type=int, default=None, help="override depth (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-generation", action="store_true")
@@ -259,6 +340,9 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "c5":
         large_batch(args, torch, np, synth, Engine, dev)
+        return
+    if args.workload == "c4":
+        prefill_batch(args, torch, np, synth, Engine, dev)
         return
     if args.workload == "c3":
         ms, P, Q, n_blocks, tau, m_floor, n_masked0 = synth.LLADA_8B, 1024, 32, 8, 0.9, 2, 32

@@ -77,7 +77,9 @@ static bool build_map(const dllm_config* c, Workspace* m) {
     m->delta = take(c->dtype == DLLM_BF16 ? (sk_floats > lg_floats ? sk_floats : lg_floats) * 4 : 0);
   }
   m->qkvp_stride = m->lg_delta_rows * (int64_t)(dq + 2 * dkv);
-  m->qkvp = take(c->dtype == DLLM_BF16 ? (size_t)LG_QKV_SPLITS * m->qkvp_stride * 4 : 0);
+  m->qkvp_rows = (int64_t)LG_QKV_SPLITS * m->lg_delta_rows > (int64_t)t_max ? (int64_t)LG_QKV_SPLITS * m->lg_delta_rows : (int64_t)t_max;
+  if (c->dtype != DLLM_BF16) m->qkvp_rows = 0;
+  m->qkvp = take((size_t)m->qkvp_rows * (dq + 2 * dkv) * 4);
   m->scratch_bytes = 0;
   m->scratch = take(m->scratch_bytes);
   m->total = off;

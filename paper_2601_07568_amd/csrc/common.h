@@ -150,6 +150,7 @@ struct Workspace {
   int64_t lg_delta_rows, lg_delta_stride;   // large path: rows the buffer covers (0 = none), floats per split
   size_t qkvp;         // float [LG_QKV_SPLITS][lg_delta_rows, dq + 2 dkv]: K-split partial sums of the fused q/k/v product
   int64_t qkvp_stride;
+  int64_t qkvp_rows;   // rows a single (unsplit) product may have
   size_t scratch;      // general scratch for fast kernels (split-K partials)
   size_t total;
   int64_t t_max, r_max, t_step, tpad;

@@ -298,6 +298,135 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
   }
 }
 
+// The same for bfloat16 storage, eight token rows per workgroup: q and k are rotated four channel
+// pairs per thread (vector loads and stores), and when the eight rows are eight consecutive, 8-aligned
+// positions of one sequence their V values go out as one 16-byte store per channel (V is stored with the
+// keys of a channel contiguous); otherwise row by row as above.
+__global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh, const float* qf, const float* kf, bf16_t* q,
+                                                  const bf16_t* v, const float* cs, const float* sn,
+                                                  const int32_t* tok_seq, const int32_t* tok_pos, const int32_t* n_cache,
+                                                  bf16_t* pool_k, bf16_t* pool_v, KVView pool, bf16_t* pack_k,
+                                                  bf16_t* pack_v, KVView pack, bool to_pack, int32_t* status,
+                                                  const float* part, int n_part, int64_t part_stride) {
+  const int t0 = blockIdx.x * 8;
+  const int half = dh >> 1, hq4 = half >> 2;          // dh % 8 == 0
+  const int np = n_part > 0 ? n_part : 1;
+  const int64_t ps = n_part > 0 ? part_stride : 0;
+  const int dq = Hq * dh, dkv = Hkv * dh, nt = dq + 2 * dkv;
+  bool bad = false;
+  __shared__ int s_b[8], s_pos[8], s_cached[8];
+  if (threadIdx.x < 8) {
+    const int t = t0 + threadIdx.x;
+    int b = -1, pos = 0, cached = 0;
+    if (t < T) {
+      b = tok_seq[t]; pos = tok_pos[t];
+      cached = (n_cache == nullptr) || (pos < n_cache[b]);
+    }
+    s_b[threadIdx.x] = b; s_pos[threadIdx.x] = pos; s_cached[threadIdx.x] = cached;
+  }
+  __syncthreads();
+  for (int e = 0; e < 8; ++e) {
+    const int t = t0 + e;
+    if (t >= T) break;
+    const int b = s_b[e], pos = s_pos[e];
+    const bool cached = s_cached[e] != 0;
+    const float4* c4 = (const float4*)(cs + (int64_t)t * half);
+    const float4* s4 = (const float4*)(sn + (int64_t)t * half);
+    const float* qs = n_part > 0 ? part + (int64_t)t * nt : qf + (int64_t)t * dq;
+    bf16_t* qt = q + (int64_t)t * dq;
+    for (int i = threadIdx.x; i < Hq * hq4; i += 256) {
+      const int h = i / hq4, j4 = i - h * hq4;
+      float4 a = {0.f, 0.f, 0.f, 0.f}, bb = {0.f, 0.f, 0.f, 0.f};
+      for (int sp = 0; sp < np; ++sp) {
+        const float4 x = *(const float4*)(qs + sp * ps + h * dh + j4 * 4), y = *(const float4*)(qs + sp * ps + h * dh + half + j4 * 4);
+        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; bb.x += y.x; bb.y += y.y; bb.z += y.z; bb.w += y.w;
+      }
+      const float4 c = c4[j4], sn4 = s4[j4];
+      *(uint2*)(qt + h * dh + j4 * 4) = make_uint2(
+          (uint32_t)f32_to_bf16(a.x * c.x - bb.x * sn4.x) | ((uint32_t)f32_to_bf16(a.y * c.y - bb.y * sn4.y) << 16),
+          (uint32_t)f32_to_bf16(a.z * c.z - bb.z * sn4.z) | ((uint32_t)f32_to_bf16(a.w * c.w - bb.w * sn4.w) << 16));
+      *(uint2*)(qt + h * dh + half + j4 * 4) = make_uint2(
+          (uint32_t)f32_to_bf16(bb.x * c.x + a.x * sn4.x) | ((uint32_t)f32_to_bf16(bb.y * c.y + a.y * sn4.y) << 16),
+          (uint32_t)f32_to_bf16(bb.z * c.z + a.z * sn4.z) | ((uint32_t)f32_to_bf16(bb.w * c.w + a.w * sn4.w) << 16));
+    }
+    const float* ks = n_part > 0 ? qs + dq : kf + (int64_t)t * dkv;
+    for (int i = threadIdx.x; i < Hkv * hq4; i += 256) {
+      const int h = i / hq4, j4 = i - h * hq4;
+      float4 a = {0.f, 0.f, 0.f, 0.f}, bb = {0.f, 0.f, 0.f, 0.f};
+      for (int sp = 0; sp < np; ++sp) {
+        const float4 x = *(const float4*)(ks + sp * ps + h * dh + j4 * 4), y = *(const float4*)(ks + sp * ps + h * dh + half + j4 * 4);
+        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; bb.x += y.x; bb.y += y.y; bb.z += y.z; bb.w += y.w;
+      }
+      const float4 c = c4[j4], sn4 = s4[j4];
+      const uint2 lo = make_uint2(
+          (uint32_t)f32_to_bf16(a.x * c.x - bb.x * sn4.x) | ((uint32_t)f32_to_bf16(a.y * c.y - bb.y * sn4.y) << 16),
+          (uint32_t)f32_to_bf16(a.z * c.z - bb.z * sn4.z) | ((uint32_t)f32_to_bf16(a.w * c.w - bb.w * sn4.w) << 16));
+      const uint2 hi = make_uint2(
+          (uint32_t)f32_to_bf16(bb.x * c.x + a.x * sn4.x) | ((uint32_t)f32_to_bf16(bb.y * c.y + a.y * sn4.y) << 16),
+          (uint32_t)f32_to_bf16(bb.z * c.z + a.z * sn4.z) | ((uint32_t)f32_to_bf16(bb.w * c.w + a.w * sn4.w) << 16));
+      int64_t ko, vo;
+      int vs;
+      if (cached) {
+        if (kv_locate(pool, b, pos, h, ko, vo, vs)) {
+          *(uint2*)(pool_k + ko + j4 * 4) = lo;
+          *(uint2*)(pool_k + ko + half + j4 * 4) = hi;
+        } else bad = true;
+      }
+      if (to_pack) {
+        kv_locate(pack, b, pos, h, ko, vo, vs);
+        *(uint2*)(pack_k + ko + j4 * 4) = lo;
+        *(uint2*)(pack_k + ko + half + j4 * 4) = hi;
+      }
+    }
+  }
+  // ---- V: eight rows of a channel at once where they are eight consecutive aligned positions
+  bool group = t0 + 8 <= T && (s_pos[0] & 7) == 0;
+  for (int e = 1; e < 8 && group; ++e) group = s_b[e] == s_b[0] && s_pos[e] == s_pos[0] + e && s_cached[e] == s_cached[0];
+  for (int i = threadIdx.x; i < dkv; i += 256) {
+    const int h = i / dh, j = i - h * dh;
+    bf16_t val[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int t = t0 + e;
+      val[e] = 0;
+      if (t >= T) continue;
+      if (n_part > 0) {
+        float acc = 0.f;
+        for (int sp = 0; sp < np; ++sp) acc += part[(int64_t)t * nt + sp * ps + dq + dkv + i];
+        val[e] = f32_to_bf16(acc);
+      } else {
+        val[e] = v[(int64_t)t * dkv + i];
+      }
+    }
+    int64_t ko, vo;
+    int vs;
+    if (group) {
+      const uint4 pk = make_uint4((uint32_t)val[0] | ((uint32_t)val[1] << 16), (uint32_t)val[2] | ((uint32_t)val[3] << 16),
+                                  (uint32_t)val[4] | ((uint32_t)val[5] << 16), (uint32_t)val[6] | ((uint32_t)val[7] << 16));
+      if (s_cached[0]) {
+        if (kv_locate(pool, s_b[0], s_pos[0], h, ko, vo, vs)) *(uint4*)(pool_v + vo + (int64_t)j * vs) = pk;
+        else bad = true;
+      }
+      if (to_pack) {
+        kv_locate(pack, s_b[0], s_pos[0], h, ko, vo, vs);
+        *(uint4*)(pack_v + vo + (int64_t)j * vs) = pk;
+      }
+    } else {
+      for (int e = 0; e < 8 && t0 + e < T; ++e) {
+        if (s_cached[e]) {
+          if (kv_locate(pool, s_b[e], s_pos[e], h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = val[e];
+          else bad = true;
+        }
+        if (to_pack) {
+          kv_locate(pack, s_b[e], s_pos[e], h, ko, vo, vs);
+          pack_v[vo + (int64_t)j * vs] = val[e];
+        }
+      }
+    }
+  }
+  if (bad) atomicOr(status, DLLM_STATUS_BAD_PAGE);
+}
+
 template <typename T>
 __global__ void k_swiglu(int64_t n, const float* g, const float* u, T* h) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -752,7 +881,14 @@ hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int lay
   KVView pool = pool_view(c, g, layer), pack = pack_view(c);
   const bool to_pack = g.Q == 0;
   const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
-  if (IS_BF16(c))
+  if (IS_BF16(c) && f.head_dim % 8 == 0 && f.page_tokens % 8 == 0)
+    k_rope_kv8<<<(g.T + 7) / 8, 256, 0, s>>>(g.T, f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
+                                            WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
+                                            WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
+                                            n_cache, (bf16_t*)pool.k, (bf16_t*)pool.v, pool, (bf16_t*)pack.k,
+                                            (bf16_t*)pack.v, pack, to_pack, WS(c, status, int32_t), WS(c, qkvp, float),
+                                            n_part, c->map.qkvp_stride);
+  else if (IS_BF16(c))
     k_rope_kv<bf16_t><<<g.T, 256, 0, s>>>(f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
                                           WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
                                           WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),

@@ -1835,7 +1835,8 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = x; a.M = M; a.N = N; a.K = K;
-  const bool t2 = t2_usable(M, K) && K >= 8192;   // short sums: the 128-row tiles fill the chip better
+  // short sums over few rows: the 128-row tiles fill the chip better
+  const bool t2 = t2_usable(M, K) && (K >= 8192 || ((M + 255) / 256) * ((N + 255) / 256) >= 192);
   const int tiles = t2 ? ((M + 255) / 256) * ((N + 255) / 256) : ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
   int splits = (t2 ? 256 : 512) / tiles;                      // one 256-row workgroup or two 128-row ones fit a CU
   if (splits > LG_MAX_DELTA + 1) splits = LG_MAX_DELTA + 1;
@@ -1855,7 +1856,7 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
 hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
                                  int M, int dq, int dkv, int K, int* n_part) {
   *n_part = 0;
-  if (!t2_usable(M, K) || M > c->map.lg_delta_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
+  if (!t2_usable(M, K) || M > c->map.qkvp_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
     return hipSuccess;
   LgArgs a;
   memset(&a, 0, sizeof(a));
@@ -1865,7 +1866,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
   int splits = 256 / tiles;
   if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
   while (splits > 1 && K / splits < 1024) --splits;
-  if (splits < 1) splits = 1;
+  if (splits < 1 || M > c->map.lg_delta_rows) splits = 1;   // the split buffers cover lg_delta_rows rows
   if (tiles * splits < 128) return hipSuccess;            // too few work items: the 128-row tiles do better
   a.k_per = ((K + splits - 1) / splits + 31) / 32 * 32;
   splits = (K + a.k_per - 1) / a.k_per;
