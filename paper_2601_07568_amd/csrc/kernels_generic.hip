@@ -309,6 +309,7 @@ __global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh
                                                   bf16_t* pack_v, KVView pack, bool to_pack, int32_t* status,
                                                   const float* part, int n_part, int64_t part_stride) {
   const int t0 = blockIdx.x * 8;
+  const int tid = threadIdx.x + 256 * blockIdx.y, nthr = 256 * gridDim.y;   // gridDim.y workgroups share the eight rows' channels
   const int half = dh >> 1, hq4 = half >> 2;          // dh % 8 == 0
   const int np = n_part > 0 ? n_part : 1;
   const int64_t ps = n_part > 0 ? part_stride : 0;
@@ -325,64 +326,53 @@ __global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh
     s_b[threadIdx.x] = b; s_pos[threadIdx.x] = pos; s_cached[threadIdx.x] = cached;
   }
   __syncthreads();
-  for (int e = 0; e < 8; ++e) {
+  // q and k: all (row, head, 4-pair chunk) items of the eight rows in one flat loop, so that every
+  // thread's loads are in flight together
+  const int rows = T - t0 < 8 ? T - t0 : 8;
+  const int nq = Hq * hq4, nk = Hkv * hq4;
+  for (int idx = tid; idx < rows * (nq + nk); idx += nthr) {
+    const int e = idx / (nq + nk), i = idx - e * (nq + nk);
     const int t = t0 + e;
-    if (t >= T) break;
-    const int b = s_b[e], pos = s_pos[e];
-    const bool cached = s_cached[e] != 0;
-    const float4* c4 = (const float4*)(cs + (int64_t)t * half);
-    const float4* s4 = (const float4*)(sn + (int64_t)t * half);
-    const float* qs = n_part > 0 ? part + (int64_t)t * nt : qf + (int64_t)t * dq;
-    bf16_t* qt = q + (int64_t)t * dq;
-    for (int i = threadIdx.x; i < Hq * hq4; i += 256) {
-      const int h = i / hq4, j4 = i - h * hq4;
-      float4 a = {0.f, 0.f, 0.f, 0.f}, bb = {0.f, 0.f, 0.f, 0.f};
-      for (int sp = 0; sp < np; ++sp) {
-        const float4 x = *(const float4*)(qs + sp * ps + h * dh + j4 * 4), y = *(const float4*)(qs + sp * ps + h * dh + half + j4 * 4);
-        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; bb.x += y.x; bb.y += y.y; bb.z += y.z; bb.w += y.w;
-      }
-      const float4 c = c4[j4], sn4 = s4[j4];
-      *(uint2*)(qt + h * dh + j4 * 4) = make_uint2(
-          (uint32_t)f32_to_bf16(a.x * c.x - bb.x * sn4.x) | ((uint32_t)f32_to_bf16(a.y * c.y - bb.y * sn4.y) << 16),
-          (uint32_t)f32_to_bf16(a.z * c.z - bb.z * sn4.z) | ((uint32_t)f32_to_bf16(a.w * c.w - bb.w * sn4.w) << 16));
-      *(uint2*)(qt + h * dh + half + j4 * 4) = make_uint2(
-          (uint32_t)f32_to_bf16(bb.x * c.x + a.x * sn4.x) | ((uint32_t)f32_to_bf16(bb.y * c.y + a.y * sn4.y) << 16),
-          (uint32_t)f32_to_bf16(bb.z * c.z + a.z * sn4.z) | ((uint32_t)f32_to_bf16(bb.w * c.w + a.w * sn4.w) << 16));
+    const bool is_q = i < nq;
+    const int ii = is_q ? i : i - nq;
+    const int h = ii / hq4, j4 = ii - h * hq4;
+    const float4 c = ((const float4*)(cs + (int64_t)t * half))[j4], sn4 = ((const float4*)(sn + (int64_t)t * half))[j4];
+    const float* src = n_part > 0 ? part + (int64_t)t * nt + (is_q ? 0 : dq) : (is_q ? qf + (int64_t)t * dq : kf + (int64_t)t * dkv);
+    float4 a = {0.f, 0.f, 0.f, 0.f}, bb = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < np; ++sp) {
+      const float4 x = *(const float4*)(src + sp * ps + h * dh + j4 * 4), y = *(const float4*)(src + sp * ps + h * dh + half + j4 * 4);
+      a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; bb.x += y.x; bb.y += y.y; bb.z += y.z; bb.w += y.w;
     }
-    const float* ks = n_part > 0 ? qs + dq : kf + (int64_t)t * dkv;
-    for (int i = threadIdx.x; i < Hkv * hq4; i += 256) {
-      const int h = i / hq4, j4 = i - h * hq4;
-      float4 a = {0.f, 0.f, 0.f, 0.f}, bb = {0.f, 0.f, 0.f, 0.f};
-      for (int sp = 0; sp < np; ++sp) {
-        const float4 x = *(const float4*)(ks + sp * ps + h * dh + j4 * 4), y = *(const float4*)(ks + sp * ps + h * dh + half + j4 * 4);
-        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; bb.x += y.x; bb.y += y.y; bb.z += y.z; bb.w += y.w;
-      }
-      const float4 c = c4[j4], sn4 = s4[j4];
-      const uint2 lo = make_uint2(
-          (uint32_t)f32_to_bf16(a.x * c.x - bb.x * sn4.x) | ((uint32_t)f32_to_bf16(a.y * c.y - bb.y * sn4.y) << 16),
-          (uint32_t)f32_to_bf16(a.z * c.z - bb.z * sn4.z) | ((uint32_t)f32_to_bf16(a.w * c.w - bb.w * sn4.w) << 16));
-      const uint2 hi = make_uint2(
-          (uint32_t)f32_to_bf16(bb.x * c.x + a.x * sn4.x) | ((uint32_t)f32_to_bf16(bb.y * c.y + a.y * sn4.y) << 16),
-          (uint32_t)f32_to_bf16(bb.z * c.z + a.z * sn4.z) | ((uint32_t)f32_to_bf16(bb.w * c.w + a.w * sn4.w) << 16));
-      int64_t ko, vo;
-      int vs;
-      if (cached) {
-        if (kv_locate(pool, b, pos, h, ko, vo, vs)) {
-          *(uint2*)(pool_k + ko + j4 * 4) = lo;
-          *(uint2*)(pool_k + ko + half + j4 * 4) = hi;
-        } else bad = true;
-      }
-      if (to_pack) {
-        kv_locate(pack, b, pos, h, ko, vo, vs);
-        *(uint2*)(pack_k + ko + j4 * 4) = lo;
-        *(uint2*)(pack_k + ko + half + j4 * 4) = hi;
-      }
+    const uint2 lo = make_uint2(
+        (uint32_t)f32_to_bf16(a.x * c.x - bb.x * sn4.x) | ((uint32_t)f32_to_bf16(a.y * c.y - bb.y * sn4.y) << 16),
+        (uint32_t)f32_to_bf16(a.z * c.z - bb.z * sn4.z) | ((uint32_t)f32_to_bf16(a.w * c.w - bb.w * sn4.w) << 16));
+    const uint2 hi = make_uint2(
+        (uint32_t)f32_to_bf16(bb.x * c.x + a.x * sn4.x) | ((uint32_t)f32_to_bf16(bb.y * c.y + a.y * sn4.y) << 16),
+        (uint32_t)f32_to_bf16(bb.z * c.z + a.z * sn4.z) | ((uint32_t)f32_to_bf16(bb.w * c.w + a.w * sn4.w) << 16));
+    if (is_q) {
+      bf16_t* qt = q + (int64_t)t * dq + h * dh;
+      *(uint2*)(qt + j4 * 4) = lo;
+      *(uint2*)(qt + half + j4 * 4) = hi;
+      continue;
+    }
+    int64_t ko, vo;
+    int vs;
+    if (s_cached[e]) {
+      if (kv_locate(pool, s_b[e], s_pos[e], h, ko, vo, vs)) {
+        *(uint2*)(pool_k + ko + j4 * 4) = lo;
+        *(uint2*)(pool_k + ko + half + j4 * 4) = hi;
+      } else bad = true;
+    }
+    if (to_pack) {
+      kv_locate(pack, s_b[e], s_pos[e], h, ko, vo, vs);
+      *(uint2*)(pack_k + ko + j4 * 4) = lo;
+      *(uint2*)(pack_k + ko + half + j4 * 4) = hi;
     }
   }
   // ---- V: eight rows of a channel at once where they are eight consecutive aligned positions
   bool group = t0 + 8 <= T && (s_pos[0] & 7) == 0;
   for (int e = 1; e < 8 && group; ++e) group = s_b[e] == s_b[0] && s_pos[e] == s_pos[0] + e && s_cached[e] == s_cached[0];
-  for (int i = threadIdx.x; i < dkv; i += 256) {
+  for (int i = tid; i < dkv; i += nthr) {
     const int h = i / dh, j = i - h * dh;
     bf16_t val[8];
 #pragma unroll
@@ -881,8 +871,12 @@ hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int lay
   KVView pool = pool_view(c, g, layer), pack = pack_view(c);
   const bool to_pack = g.Q == 0;
   const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
+  // eight rows per workgroup; with few rows their channels are spread over up to eight workgroups
+  const int groups8 = (g.T + 7) / 8;
+  int slices8 = groups8 >= 1024 ? 1 : (1024 + groups8 - 1) / groups8;
+  if (slices8 > 8) slices8 = 8;
   if (IS_BF16(c) && f.head_dim % 8 == 0 && f.page_tokens % 8 == 0)
-    k_rope_kv8<<<(g.T + 7) / 8, 256, 0, s>>>(g.T, f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
+    k_rope_kv8<<<dim3(groups8, slices8), 256, 0, s>>>(g.T, f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
                                             WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
                                             WS(c, rope_sin, float), WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
                                             n_cache, (bf16_t*)pool.k, (bf16_t*)pool.v, pool, (bf16_t*)pack.k,
