@@ -53,7 +53,7 @@ def gather_cache(eng, table_row, n, layer, which):
 STORE = {"f32": None, "bf16": synth.round_bf16}     # storage precision of the decisions, per dtype
 
 
-def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, gpu_logits=None):
+def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, gpu_logits=None, eps=None):
     """GPU cand/conf/entropy of the masked rows against an oracle step record r (r comes from the
     oracle run in the model's storage precision, so that both sides decide in the same precision).
 
@@ -67,7 +67,7 @@ def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, gpu_logits=None):
     z = np.asarray(r["logits"], dtype=np.float64)
     _, oconf, oent, p = O.confidence(z, ms.mask_id)
     margin = top2_margin(p)
-    eps = LOGIT_TOL[dtype]
+    eps = LOGIT_TOL[dtype] if eps is None else eps
     zz = np.delete(z, ms.mask_id, axis=1)
     pp = np.delete(p, ms.mask_id, axis=1)
     delta = eps * np.abs(z).max(axis=-1)
