@@ -50,6 +50,17 @@ def gather_cache(eng, table_row, n, layer, which):
     return out
 
 
+def gather_cache_rows(eng, table_row, n, layer, which):
+    """As gather_cache, page by page on the device (for long prefixes)."""
+    import torch
+    slab = eng.kv_slab(layer, which)                            # [pages, Hkv, pt, dh] view
+    pt = eng.cfg.page_tokens
+    n_pages = (n + pt - 1) // pt
+    idx = torch.as_tensor(np.asarray(table_row[:n_pages]), device=slab.device, dtype=torch.long)
+    rows = slab[idx].permute(0, 2, 1, 3).reshape(n_pages * pt, slab.shape[1], slab.shape[3])[:n]
+    return rows.float().cpu().numpy()
+
+
 STORE = {"f32": None, "bf16": synth.round_bf16}     # storage precision of the decisions, per dtype
 
 

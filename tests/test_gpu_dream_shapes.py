@@ -112,3 +112,74 @@ def test_two_blocks_in_flight_on_prefilled_prompts(weights):
         blks.append(synth.masked_block(MS, 60 + b, Q, 40))
     check_step(eng, w, 2, Q, blks, caches, lens, table, 0.85, 1, 32)
     eng.close()
+
+
+def test_full_depth_batch_32_prefix_8192_sampled_sequences():
+    """The long-context large-batch workload in the launch configuration bench.py times (Dream-7B-shaped, 28 layers,
+    batch 32, prefix KV of 8192 tokens per sequence drawn on the device, one block of 32 with 16 masked): the
+    library runs the whole batch, the oracle recomputes two of its sequences layer by layer from host copies of
+    the device-drawn weights and of those sequences' cache pages."""
+    import bench
+    from paper_2601_07568_amd.binding import Engine
+    ms = synth.DREAM_7B
+    Bn, P, Q, pt = 32, 8192, 32, 64
+    dev = torch.device("cuda:0")
+    mp = (P + Q + pt - 1) // pt
+    g, layers = bench.device_weights(ms, torch, dev, 5)
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q, max_tokens=0,
+                 device_weights=(g, layers), pack=False)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    pool = eng.kv_pool.view(torch.bfloat16)
+    for i in range(0, pool.numel(), 1 << 28):
+        n = min(1 << 28, pool.numel() - i)
+        pool[i:i + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    table_np = np.arange(Bn * mp).reshape(Bn, mp)
+    table = eng.i32(table_np)
+    blks = np.stack([synth.masked_block(ms, 5, Q, 16, stream=b) for b in range(Bn)])
+    sample = [3, 29]
+    # host copies of the sampled sequences' caches, taken before the step writes its own rows behind them
+    caches = {b: [(H.gather_cache_rows(eng, table_np[b], P, l, 0).astype(np.float64),
+                   H.gather_cache_rows(eng, table_np[b], P, l, 1).astype(np.float64)) for l in range(ms.n_layers)]
+              for b in sample}
+    qt = eng.i32(blks)
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    ent = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    prefix = eng.i32([P] * Bn)
+    eng.denoise_step(qt, prefix, table, cand, conf, ent, max_prefix_len=P)
+    assert eng.read_status() == 0
+    host = lambda t: t.float().cpu().numpy().astype(np.float64)
+    ident = lambda a: a
+    pos = np.arange(Q) + P
+    xs = {(b, w): host(g["tok_emb"][torch.from_numpy(blks[b]).to(dev)]) for b in sample for w in (0, 1)}
+    for l in range(ms.n_layers):
+        lw = {n: host(t) for n, t in layers[l].items()}
+        for b in sample:
+            ck, cv = caches[b][l]
+            for w in (0, 1):
+                st = ST if w else None
+                x = xs[(b, w)]
+                q, k, v = O.layer_qkv(ms, lw, x, pos, ident, st)
+                xs[(b, w)] = O.layer_finish(ms, lw, x, O.attention(q, np.concatenate([ck, k]), np.concatenate([cv, v])),
+                                            ident, st)
+        del lw
+
+    class Head:
+        pass
+    head = Head()
+    head.ms = ms
+    hw = {"final_norm": host(g["final_norm"]), "lm_head": host(g["lm_head"])}
+    Head.__getitem__ = lambda self, k: hw[k]
+    for b in sample:
+        stored = O.head_logits(head, xs[(b, 1)], ident, ST)
+        masked = blks[b] == ms.mask_id
+        ocand, oconf, oent, _ = O.confidence(stored, ms.mask_id)
+        r = {"logits": stored, "cand": ocand, "conf": oconf, "entropy": oent}
+        # outputs only (the batch's logits are never materialised): decisions and statistics of the masked rows, with
+        # the tolerance the full-depth bfloat16 storage meets (1.5x the slice tolerance, see the 32-layer test)
+        n_exact = H.check_step_outputs(ms, r, masked, cand.cpu().numpy()[b], conf.cpu().numpy()[b],
+                                       ent.cpu().numpy()[b], "bf16", eps=1.5 * H.LOGIT_TOL["bf16"])
+        print(f"seq {b}: {n_exact} of {int(masked.sum())} masked rows decided by margin and equal")
+        assert (cand.cpu().numpy()[b][~masked] == blks[b][~masked]).all()
+    eng.close()
