@@ -455,6 +455,9 @@ def main():
         g0 = time.perf_counter()
         seq = prompt.clone()
         eng.prefill_kv(seq, cu, table, None, total_tokens=P, max_seqlen=P)
+        torch.cuda.synchronize()
+        prefill_s = time.perf_counter() - g0
+        refresh_s = 0.0
         forwards = 0
         cur = P
         for b in range(n_blocks):
@@ -468,11 +471,22 @@ def main():
                     break
             seq = torch.cat([seq, blk[0]])
             cur += Q
+            torch.cuda.synchronize()
+            r0 = time.perf_counter()
             eng.refresh_cache(seq, eng.i32([0, cur]), table, None, total_tokens=cur, max_seqlen=cur)
+            torch.cuda.synchronize()
+            refresh_s += time.perf_counter() - r0
         torch.cuda.synchronize()
         gsec = time.perf_counter() - g0
+        per_tok = ms.n_layers * 2 * (d * (dq + 2 * dkv) + dq * d + 3 * d * F)          # GEMM flops per row
+        attn_fl = lambda S: ms.n_layers * 4 * ms.n_q_heads * S * S * ms.head_dim       # QK^T and PV once each
+        refresh_lens = [P + (b + 1) * Q for b in range(n_blocks)]
+        refresh_flops = sum(S * per_tok + attn_fl(S) for S in refresh_lens)
         gen = {"tokens": n_blocks * Q, "forwards": forwards, "seconds": gsec, "tokens_per_s": n_blocks * Q / gsec,
-               "steps_per_s": forwards / gsec, "tokens_per_forward": n_blocks * Q / forwards}
+               "steps_per_s": forwards / gsec, "tokens_per_forward": n_blocks * Q / forwards,
+               "prefill": {"tokens": P, "ms": prefill_s * 1e3, "TFLOPs": (P * per_tok + attn_fl(P)) / prefill_s / 1e12},
+               "refresh": {"calls": n_blocks, "tokens": refresh_lens, "ms_total": refresh_s * 1e3,
+                           "TFLOPs": refresh_flops / refresh_s / 1e12}}
 
     # ---- the same generation with multi-block decoding (entropy rule, block state machine on the device)
     gen_mb = None
