@@ -16,10 +16,10 @@ SMALL = synth.ModelShape(2, 512, 8, 2, 128, 1408, 5000, 4999, dtype="bf16", lm_h
 SMALL64 = synth.ModelShape(1, 384, 6, 3, 64, 1000, 3000, 2999, dtype="bf16", lm_head_scale=8.0, name="small-dh64")
 
 
-def run_small(ms, lens, Q, n_masked, mode, seed=7, mp=8):
+def run_small(ms, lens, Q, n_masked, mode, seed=7, mp=8, pt=32):
     w = synth.Weights(ms, seed)
     Bn = len(lens)
-    eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+    eng = H.make_engine(ms, w, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
                         max_tokens=sum(lens) + Bn * Q)
     eng.set_kernel_mode(mode)
     seqs = [synth.random_tokens(ms, seed + i, n) for i, n in enumerate(lens)]
@@ -80,6 +80,13 @@ def test_small_model_256_query_rows_and_long_prefill():
     """Four sequences x 64 query rows and a 539-token prefill: the 256-row tiles of the large GEMM path with
     ragged feature counts (1000 MLP features, 3000 vocabulary entries) and a ragged last row tile."""
     run_small(SMALL64, [45, 130, 64, 300], 64, 40, 0, mp=12)
+
+
+@pytest.mark.parametrize("pt,mp", [(24, 8), (8, 24), (128, 2)])
+def test_small_gqa_model_other_page_sizes(pt, mp):
+    """Page sizes that are not a power of two (the staged attention does not take them), the smallest one (a
+    64-key block spans eight pages) and one larger than a block."""
+    run_small(SMALL, [100, 77], 32, 20, 0, mp=mp, pt=pt)
 
 
 def test_llada_shaped_layer_and_head_full_size():
