@@ -121,3 +121,35 @@ def test_llada_shaped_layer_and_head_full_size():
         assert np.nonzero(qt.cpu().numpy()[0] != blk)[0].tolist() == r["chosen"]
     assert eng.read_status() == 0
     eng.close()
+
+
+@pytest.mark.parametrize("Bn,Q", [(1, 32), (4, 64)])
+def test_degenerate_steps_nothing_masked_and_empty_prefix(Bn, Q):
+    """A step whose block holds no [MASK] (the LM head has no rows to do) and a step over an empty prefix (the block
+    attends to itself only), on the small-row and on the 256-row path."""
+    ms = SMALL64
+    w = synth.Weights(ms, 9)
+    eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=4, n_pages=4 * Bn, max_batch=Bn, max_q=Q,
+                        max_tokens=Bn * Q)
+    table = H.identity_table(eng, Bn)
+    tab = eng.i32(table)
+    cand = torch.full((Bn, Q), -7, dtype=torch.int32, device=eng.device)
+    conf = torch.full((Bn, Q), -7.0, dtype=torch.float32, device=eng.device)
+    ent = torch.full((Bn, Q), -7.0, dtype=torch.float32, device=eng.device)
+    # empty prefix, nothing masked
+    blk = np.stack([synth.random_tokens(ms, 20 + b, Q) for b in range(Bn)]).astype(np.int32)
+    eng.denoise_step(eng.i32(blk), eng.i32([0] * Bn), tab, cand, conf, ent, max_prefix_len=0)
+    assert (cand.cpu().numpy() == blk).all() and (conf.cpu().numpy() == 1).all()
+    # empty prefix, some masked: equals the oracle's no-cache forward over the block alone
+    blks = np.stack([synth.masked_block(ms, 30 + b, Q, Q // 2) for b in range(Bn)]).astype(np.int32)
+    eng.denoise_step(eng.i32(blks), eng.i32([0] * Bn), tab, cand, conf, ent, max_prefix_len=0)
+    logits = eng.debug_logits(eng.i32(blks), eng.i32([0] * Bn), tab, max_prefix_len=0).cpu().numpy()
+    for b in range(Bn):
+        exact, _, _, _ = O.forward_full(w, blks[b], widen=W)
+        assert H.rel_err_rows(logits[b], exact).max() <= H.LOGIT_TOL["bf16"]
+        full, _, _, _ = O.forward_full(w, blks[b], widen=W, store=ST)
+        r = {"logits": full, "cand": O.confidence(full, ms.mask_id)[0]}
+        H.check_step_outputs(ms, r, blks[b] == ms.mask_id, cand.cpu().numpy()[b], conf.cpu().numpy()[b],
+                             ent.cpu().numpy()[b], "bf16", gpu_logits=logits[b])
+    assert eng.read_status() == 0
+    eng.close()
