@@ -212,6 +212,34 @@ int dllm_unmask_blocks(dllm_ctx *ctx, void *stream, int B, int Q, int block_len,
 int dllm_fsm_update(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, const int32_t *gen_tokens,
                     int32_t *state, int32_t *counter, double add_at, double full_at, int delay, int nocache_round,
                     int32_t *floor_next, int32_t *summary);
+/* nocache_round < 0: derived per sequence - the round skipped the cache iff one of the sequence's blocks was
+ * Stabilizing in the incoming state (the rule by which the forward of a round is chosen). */
+
+/* A denoise step whose sequences have different numbers of query rows (multi-block decoding: the windows of
+ * the sequences of a batch differ): as dllm_denoise_step, but rows j >= q_valid[b] of sequence b are padding.
+ * Padding rows are no keys for the other rows (sequence b attends to prefix_len[b] + q_valid[b] keys), get no
+ * LM-head row, report their own token with confidence 1 and write nothing to the cache (only positions up
+ * to prefix_len[b] + q_valid[b] - 1 need to be mapped by the block table).
+ *   q_valid dev int32 [B], 0 <= q_valid[b] <= Q (clamped) */
+int dllm_denoise_step_var(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len, const int32_t *q_tokens,
+                          const int32_t *prefix_len, const int32_t *q_valid, const int32_t *block_table,
+                          int32_t *cand_token, float *conf, float *entropy);
+
+/* The window of a cached round of multi-block decoding, per sequence, from the block states: the run of
+ * Activated / Fully-Activated blocks, at most W of them, copied out of the generation tokens into
+ * win_tokens (padded with pad_token), with the floors of those blocks (-1 for padding blocks), the prefix
+ * length base_len[b] + first_block * block_len and the valid-row count - the arguments of
+ * dllm_denoise_step_var (Q = W * block_len) and dllm_unmask_blocks.  A sequence with a Stabilizing block
+ * (its round must not use the cache) or without an active block gets an empty window (q_valid 0, floors
+ * -1).  dllm_fsm_scatter writes the valid rows of the windows back into the generation tokens.
+ *   gen_tokens dev int32 [B, n_blocks * block_len]; state dev int32 [B, n_blocks]; base_len dev int32 [B]
+ *   win_tokens dev int32 [B, W * block_len]; win_floor dev int32 [B, W]; prefix_len, q_valid, win_lo dev int32 [B]
+ *   pad_token: any token id other than the mask id. */
+int dllm_fsm_window(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, int W, const int32_t *gen_tokens,
+                    const int32_t *state, const int32_t *base_len, int32_t pad_token, int32_t *win_tokens,
+                    int32_t *win_floor, int32_t *prefix_len, int32_t *q_valid, int32_t *win_lo);
+int dllm_fsm_scatter(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, int W, const int32_t *win_tokens,
+                     const int32_t *win_lo, const int32_t *q_valid, int32_t *gen_tokens);
 
 /* The selection of dllm_unmask / dllm_unmask_entropy that also records the decoding order (Section 3.1:
  * the teacher's pseudo-trajectory is the order in which its tokens are decoded, one per step, for the

@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
+        "dllm_denoise_step_var": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "dllm_fsm_window": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "dllm_fsm_scatter": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_unmask_traced": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]),
         "dllm_noisy_sequence": (i32, [vp, vp, i32, i32, vp, vp, vp, i32, C.c_double, vp]),
         "dllm_eos_scan": (i32, [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]),
@@ -235,11 +238,30 @@ class Engine:
         self._check(lib().dllm_eos_scan(self.ctx, self._stream(), B, n, _ptr(gen_tokens), eos_id, _ptr(finished),
                                         _ptr(first_eos), _ptr(active_index), _ptr(n_active)))
 
+    def denoise_step_var(self, q_tokens, prefix_len, q_valid, block_table, cand, conf, entropy=None, *, max_prefix_len):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_denoise_step_var(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                                _ptr(prefix_len), _ptr(q_valid), _ptr(block_table), _ptr(cand),
+                                                _ptr(conf), _ptr(entropy)))
+
+    def fsm_window(self, gen_tokens, state, base_len, block_len, W, pad_token, win_tokens, win_floor, prefix_len,
+                   q_valid, win_lo):
+        B, NB = state.shape
+        self._check(lib().dllm_fsm_window(self.ctx, self._stream(), B, NB, block_len, W, _ptr(gen_tokens), _ptr(state),
+                                          _ptr(base_len), pad_token, _ptr(win_tokens), _ptr(win_floor),
+                                          _ptr(prefix_len), _ptr(q_valid), _ptr(win_lo)))
+
+    def fsm_scatter(self, win_tokens, win_lo, q_valid, gen_tokens, n_blocks, block_len, W):
+        B = win_lo.numel()
+        self._check(lib().dllm_fsm_scatter(self.ctx, self._stream(), B, n_blocks, block_len, W, _ptr(win_tokens),
+                                           _ptr(win_lo), _ptr(q_valid), _ptr(gen_tokens)))
+
     def fsm_update(self, gen_tokens, state, counter, block_len, add_at, full_at, delay, nocache_round,
                    floor_next=None, summary=None):
         B, NB = state.shape
         self._check(lib().dllm_fsm_update(self.ctx, self._stream(), B, NB, block_len, _ptr(gen_tokens), _ptr(state),
-                                          _ptr(counter), add_at, full_at, delay, 1 if nocache_round else 0,
+                                          _ptr(counter), add_at, full_at, delay,
+                                          -1 if nocache_round is None else (1 if nocache_round else 0),
                                           _ptr(floor_next), _ptr(summary)))
 
     def refresh_cache(self, tokens, cu_seqlens, block_table, n_commit=None, cand=None, conf=None, entropy=None,

@@ -399,11 +399,13 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
 }
 
 static int check_step_args(dllm_ctx* c, int B, int Q, int max_prefix_len, const void* q_tokens,
-                           const void* prefix_len, const void* block_table) {
+                           const void* prefix_len, const void* block_table, bool padded = false) {
   if (!c || !q_tokens || !prefix_len || !block_table) return DLLM_EINVAL;
   if (B < 1 || Q < 1 || max_prefix_len < 0) return DLLM_EINVAL;
   if (B > c->cfg.max_batch || Q > c->cfg.max_q) return DLLM_ESHAPE;
-  if ((int64_t)max_prefix_len + Q > (int64_t)c->cfg.max_pages_per_seq * c->cfg.page_tokens) return DLLM_ESHAPE;
+  // with padding rows only the valid rows need pages (checked on the device, row by row)
+  const int64_t reach = (int64_t)max_prefix_len + (padded ? 0 : Q);
+  if (reach > (int64_t)c->cfg.max_pages_per_seq * c->cfg.page_tokens) return DLLM_ESHAPE;
   return DLLM_OK;
 }
 
@@ -412,6 +414,7 @@ static StepGeom step_geom(int B, int Q, int max_prefix_len, const int32_t* q_tok
   StepGeom g;
   g.B = B; g.T = B * Q; g.Q = Q; g.max_kv = max_prefix_len + Q;
   g.tokens = q_tokens; g.prefix_len = prefix_len; g.cu_seqlens = nullptr; g.n_cache = nullptr;
+  g.q_valid = nullptr;
   g.block_table = block_table;
   return g;
 }
@@ -423,6 +426,18 @@ extern "C" int dllm_denoise_step(dllm_ctx* c, void* stream, int B, int Q, int ma
   if (rc != DLLM_OK) return rc;
   if (!cand_token || !conf) return DLLM_EINVAL;
   StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  HeadOut h{cand_token, conf, entropy};
+  return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, &h, nullptr, nullptr);
+}
+
+extern "C" int dllm_denoise_step_var(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                     const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* q_valid,
+                                     const int32_t* block_table, int32_t* cand_token, float* conf, float* entropy) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table, true);
+  if (rc != DLLM_OK) return rc;
+  if (!cand_token || !conf || !q_valid) return DLLM_EINVAL;
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  g.q_valid = q_valid;
   HeadOut h{cand_token, conf, entropy};
   return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, &h, nullptr, nullptr);
 }
@@ -458,6 +473,7 @@ static int packed_forward(dllm_ctx* c, void* stream, int B, int total_tokens, in
   StepGeom g;
   g.B = B; g.T = total_tokens; g.Q = 0; g.max_kv = max_seqlen;
   g.tokens = tokens; g.prefix_len = nullptr; g.cu_seqlens = cu_seqlens; g.n_cache = n_cache;
+  g.q_valid = nullptr;
   g.block_table = block_table;
   return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, head, nullptr, nullptr);
 }
@@ -526,7 +542,33 @@ extern "C" int dllm_fsm_update(dllm_ctx* c, void* stream, int B, int n_blocks, i
   while (need_add <= block_len && (double)need_add / (double)block_len < add_at) ++need_add;
   while (need_full <= block_len && (double)need_full / (double)block_len < full_at) ++need_full;
   TRY(launch_fsm_update((hipStream_t)stream, B, n_blocks, block_len, gen_tokens, c->cfg.mask_id, state, counter,
-                        need_add, need_full, delay, nocache_round != 0, floor_next, summary), "fsm_update");
+                        need_add, need_full, delay, nocache_round < 0 ? -1 : (nocache_round != 0), floor_next, summary),
+      "fsm_update");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_window(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, int W,
+                               const int32_t* gen_tokens, const int32_t* state, const int32_t* base_len,
+                               int32_t pad_token, int32_t* win_tokens, int32_t* win_floor, int32_t* prefix_len,
+                               int32_t* q_valid, int32_t* win_lo) {
+  if (!c || !gen_tokens || !state || !base_len || !win_tokens || !win_floor || !prefix_len || !q_valid || !win_lo)
+    return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || W < 1) return DLLM_EINVAL;
+  if (pad_token < 0 || pad_token >= c->cfg.vocab || pad_token == c->cfg.mask_id) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || (int64_t)W * block_len > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_fsm_window((hipStream_t)stream, B, n_blocks, block_len, W, gen_tokens, state, base_len, pad_token,
+                        win_tokens, win_floor, prefix_len, q_valid, win_lo), "fsm_window");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_scatter(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, int W,
+                                const int32_t* win_tokens, const int32_t* win_lo, const int32_t* q_valid,
+                                int32_t* gen_tokens) {
+  if (!c || !win_tokens || !win_lo || !q_valid || !gen_tokens) return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || W < 1) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || (int64_t)W * block_len > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_fsm_scatter((hipStream_t)stream, B, n_blocks, block_len, W, win_tokens, win_lo, q_valid, gen_tokens),
+      "fsm_scatter");
   return DLLM_OK;
 }
 

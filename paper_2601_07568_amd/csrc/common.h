@@ -196,6 +196,8 @@ struct StepGeom {           // which tokens a forward runs over
   int max_kv;               // upper bound of keys any row attends to (launch sizing)
   const int32_t* tokens;    // dev [T]
   const int32_t* prefix_len;   // dev [B] (step) or nullptr
+  const int32_t* q_valid;      // dev [B] or nullptr (step): rows of a sequence past q_valid[b] are padding - they are
+                               // no keys for the other rows and get no LM-head row
   const int32_t* cu_seqlens;   // dev [B+1] (packed) or nullptr
   const int32_t* n_cache;      // dev [B] or nullptr (packed: how many positions go to the pool)
   const int32_t* block_table;  // dev [B, max_pages]
@@ -232,6 +234,11 @@ hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
                          int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false, const int32_t* floors = nullptr,
                          int32_t* order = nullptr, int32_t step_index = 0);
+hipError_t launch_fsm_window(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* gen,
+                             const int32_t* state, const int32_t* base_len, int32_t pad_token, int32_t* win_tokens,
+                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo);
+hipError_t launch_fsm_scatter(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* win_tokens,
+                              const int32_t* win_lo, const int32_t* q_valid, int32_t* gen);
 hipError_t launch_noisy_sequence(hipStream_t s, int B, int n, const int32_t* y, const int32_t* order, const int32_t* s_dev,
                                  int k, int kt, int32_t mask_id, int32_t* out);
 hipError_t launch_eos_scan(hipStream_t s, int B, int n, const int32_t* gen, int32_t eos_id, int32_t mask_id,

@@ -41,7 +41,7 @@ __device__ inline float block_max(float v, float* red) {
 // ------------------------------------------------------------------------------------------
 // token map: sequence and position of every row of the forward
 __global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, const int32_t* cu,
-                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad) {
+                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad, const int32_t* q_valid) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t == 0 && Q == 0) {   // padded column offsets of the packed K/V scratch
     int acc = 0;
@@ -52,7 +52,8 @@ __global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, cons
   if (Q > 0) {
     int b = t / Q;
     tok_seq[t] = b;
-    tok_pos[t] = prefix_len[b] + (t - b * Q);
+    // padding rows of a step (past q_valid of their sequence) have no position: nothing of theirs is cached
+    tok_pos[t] = (q_valid && (t - b * Q) >= q_valid[b]) ? -1 : prefix_len[b] + (t - b * Q);
   } else {
     int lo = 0, hi = B;  // largest b with cu[b] <= t
     while (hi - lo > 1) {
@@ -255,7 +256,7 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
     Elem<T>::store(qt + h * dh + j + half, b * c[j] + a * s[j]);
   }
   const int b = tok_seq[t], pos = tok_pos[t];
-  const bool cached = (n_cache == nullptr) || (pos < n_cache[b]);
+  const bool cached = pos >= 0 && ((n_cache == nullptr) || (pos < n_cache[b]));   // pos < 0: a padding row
   const float* ks = n_part > 0 ? qs + Hq * dh : kf + (int64_t)t * Hkv * dh;
   const T* vt = v + (int64_t)t * Hkv * dh;
   const float* vparts = qs + (Hq + Hkv) * dh;
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh
     int b = -1, pos = 0, cached = 0;
     if (t < T) {
       b = tok_seq[t]; pos = tok_pos[t];
-      cached = (n_cache == nullptr) || (pos < n_cache[b]);
+      cached = pos >= 0 && ((n_cache == nullptr) || (pos < n_cache[b]));            // pos < 0: a padding row
     }
     s_b[threadIdx.x] = b; s_pos[threadIdx.x] = pos; s_cached[threadIdx.x] = cached;
   }
@@ -432,7 +433,8 @@ constexpr int ATT_CHUNK = 1024;
 template <typename T>
 __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const T* q, T* o,
                                                    const int32_t* tok_seq, const int32_t* prefix_len,
-                                                   const int32_t* cu, KVView kv, int32_t* status) {
+                                                   const int32_t* cu, KVView kv, int32_t* status,
+                                                   const int32_t* q_valid) {
   __shared__ float qs[128];
   __shared__ float sc[ATT_CHUNK];
   __shared__ int64_t offs[ATT_CHUNK];   // V offset of each key of the chunk, -1 = not addressable
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
   __shared__ float osum[256];
   const int t = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
   const int b = tok_seq[t];
-  const int kv_len = (Q > 0) ? prefix_len[b] + Q : cu[b + 1] - cu[b];
+  const int kv_len = (Q > 0) ? prefix_len[b] + (q_valid ? min(max(q_valid[b], 0), Q) : Q) : cu[b + 1] - cu[b];
   const int kvh = h / (Hq / kv.n_kv_heads);
   const T* kbase = (const T*)kv.k;
   const T* vbase = (const T*)kv.v;
@@ -507,7 +509,8 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
 __global__ __launch_bounds__(1024) void k_mask_rows(int T, int32_t mask_id, int cap, const int32_t* tokens,
                                                     const int32_t* tok_seq, const int32_t* tok_pos,
                                                     const int32_t* n_commit, int32_t* rows, int32_t* status,
-                                                    int32_t* cand, float* conf, float* entropy) {
+                                                    int32_t* cand, float* conf, float* entropy, int Q,
+                                                    const int32_t* q_valid) {
   __shared__ int wcount[16];
   __shared__ int base_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -518,7 +521,9 @@ __global__ __launch_bounds__(1024) void k_mask_rows(int T, int32_t mask_id, int 
     bool eligible = false, flag = false;
     if (t < T) {
       eligible = (n_commit == nullptr) || (tok_pos[t] >= n_commit[tok_seq[t]]);
-      flag = eligible && tokens[t] == mask_id;
+      // padding rows of a step (past q_valid of their sequence) report their own token, whatever it is
+      const bool pad = q_valid != nullptr && (t - tok_seq[t] * Q) >= q_valid[tok_seq[t]];
+      flag = eligible && !pad && tokens[t] == mask_id;
       if (eligible && !flag) {
         cand[t] = tokens[t];
         conf[t] = 1.0f;
@@ -715,7 +720,7 @@ __global__ void k_set_i32(int32_t* p, int n, int32_t v) {
 hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
   k_token_map<<<(g.T + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
                                                 WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
-                                                WS(c, cu_pad, int32_t));
+                                                WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr);
   return hipGetLastError();
 }
 
@@ -913,11 +918,11 @@ hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& 
   if (IS_BF16(c))
     k_attention<bf16_t><<<grid, 256, 0, s>>>(f.n_q_heads, f.head_dim, g.Q, WS(c, q, bf16_t), WS(c, o, bf16_t),
                                              WS(c, tok_seq, int32_t), g.prefix_len, g.cu_seqlens, kv,
-                                             WS(c, status, int32_t));
+                                             WS(c, status, int32_t), g.q_valid);
   else
     k_attention<float><<<grid, 256, 0, s>>>(f.n_q_heads, f.head_dim, g.Q, WS(c, q, float), WS(c, o, float),
                                             WS(c, tok_seq, int32_t), g.prefix_len, g.cu_seqlens, kv,
-                                            WS(c, status, int32_t));
+                                            WS(c, status, int32_t), g.q_valid);
   return hipGetLastError();
 }
 
@@ -926,7 +931,7 @@ hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32
   const int32_t* n_commit = (g.Q > 0) ? nullptr : g.n_cache;
   k_mask_rows<<<1, 1024, 0, s>>>(g.T, c->cfg.mask_id, (int)c->map.r_max, g.tokens, WS(c, tok_seq, int32_t),
                                  WS(c, tok_pos, int32_t), n_commit, WS(c, rows, int32_t),
-                                 WS(c, status, int32_t), cand, conf, entropy);
+                                 WS(c, status, int32_t), cand, conf, entropy, g.Q, g.Q > 0 ? g.q_valid : nullptr);
   return hipGetLastError();
 }
 
@@ -980,6 +985,10 @@ __global__ __launch_bounds__(64) void k_fsm_update(int n_blocks, int block_len, 
   if (lane != 0) return;
   int32_t* st = state + (int64_t)b * n_blocks;
   int32_t* ct = counter + (int64_t)b * n_blocks;
+  if (nocache_round < 0) {      // derived: the round skipped the cache iff a block was stabilizing when it began
+    nocache_round = 0;
+    for (int k = 0; k < n_blocks; ++k) nocache_round |= st[k] == DLLM_BLOCK_STABILIZING;
+  }
   for (int k = 0; k < n_blocks; ++k) {
     const int prev = k == 0 ? block_len : filled[k - 1];
     const int sk = st[k];
@@ -1007,6 +1016,58 @@ __global__ __launch_bounds__(64) void k_fsm_update(int n_blocks, int block_len, 
   if (summary) {
     summary[b * 4 + 0] = lo; summary[b * 4 + 1] = hi; summary[b * 4 + 2] = stab; summary[b * 4 + 3] = done;
   }
+}
+
+// Window of a cached round, per sequence: the run of active blocks (at most W), as the tokens, floors,
+// prefix length and valid-row count that dllm_denoise_step_var / dllm_unmask_blocks take.  A sequence that
+// has a stabilizing block (its round must not use the cache) or no active block gets an empty window.
+__global__ void k_fsm_window(int n_blocks, int block_len, int W, const int32_t* gen, const int32_t* state,
+                             const int32_t* base_len, int32_t pad_token, int32_t* win_tokens, int32_t* win_floor,
+                             int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo) {
+  const int b = blockIdx.x;
+  const int32_t* st = state + (int64_t)b * n_blocks;
+  int lo = -1, hi = -1, stab = 0, done = 0;
+  for (int k = 0; k < n_blocks; ++k) {
+    const int sk = st[k];
+    if (sk == DLLM_BLOCK_ACTIVATED || sk == DLLM_BLOCK_FULLY_ACTIVATED) { if (lo < 0) lo = k; hi = k; }
+    stab |= sk == DLLM_BLOCK_STABILIZING;
+    done += sk == DLLM_BLOCK_COMPLETED;
+  }
+  int nw = (lo < 0 || stab) ? 0 : hi - lo + 1;
+  if (nw > W) nw = W;
+  if (nw == 0) lo = done;                              // an empty window sits right behind the cached blocks
+  if (threadIdx.x == 0) {
+    prefix_len[b] = base_len[b] + lo * block_len;
+    q_valid[b] = nw * block_len;
+    win_lo[b] = lo;
+  }
+  for (int k = threadIdx.x; k < W; k += blockDim.x) {
+    const int sk = k < nw ? st[lo + k] : DLLM_BLOCK_INACTIVE;
+    win_floor[(int64_t)b * W + k] = k < nw ? (sk == DLLM_BLOCK_FULLY_ACTIVATED ? 1 : (sk == DLLM_BLOCK_ACTIVATED ? 0 : -1)) : -1;
+  }
+  for (int j = threadIdx.x; j < W * block_len; j += blockDim.x)
+    win_tokens[(int64_t)b * W * block_len + j] =
+        j < nw * block_len ? gen[(int64_t)b * n_blocks * block_len + (int64_t)lo * block_len + j] : pad_token;
+}
+__global__ void k_fsm_scatter(int n_blocks, int block_len, int W, const int32_t* win_tokens, const int32_t* win_lo,
+                              const int32_t* q_valid, int32_t* gen) {
+  const int b = blockIdx.x;
+  const int lo = win_lo[b], nv = q_valid[b];
+  for (int j = threadIdx.x; j < nv; j += blockDim.x)
+    gen[(int64_t)b * n_blocks * block_len + (int64_t)lo * block_len + j] = win_tokens[(int64_t)b * W * block_len + j];
+}
+
+hipError_t launch_fsm_window(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* gen,
+                             const int32_t* state, const int32_t* base_len, int32_t pad_token, int32_t* win_tokens,
+                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo) {
+  k_fsm_window<<<B, 256, 0, s>>>(n_blocks, block_len, W, gen, state, base_len, pad_token, win_tokens, win_floor,
+                                 prefix_len, q_valid, win_lo);
+  return hipGetLastError();
+}
+hipError_t launch_fsm_scatter(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* win_tokens,
+                              const int32_t* win_lo, const int32_t* q_valid, int32_t* gen) {
+  k_fsm_scatter<<<B, 256, 0, s>>>(n_blocks, block_len, W, win_tokens, win_lo, q_valid, gen);
+  return hipGetLastError();
 }
 
 hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,

@@ -274,7 +274,9 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
           } else {
             int64_t ko, vo;
             int vs;
-            if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs)) {
+            if (a.tok_pos[tok] < 0) {
+              // a padding row: nothing of it is cached
+            } else if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs)) {
               a.pool_k[ko + j] = r0;
               a.pool_k[ko + j + half] = r1;
             } else atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_
           const int h = n / a.dh, ch = n - h * a.dh;
           int64_t ko, vo;
           int vs;
-          if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs))
+          if (a.tok_pos[tok] >= 0 && kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs))
             a.pool_v[vo + (int64_t)ch * vs] = f32_to_bf16(val[NT - 1]);
         }
       }
@@ -493,7 +495,8 @@ hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_pa
 // k_attn_combine merges them.
 struct AttnArgs {
   const bf16_t* q;          // [T, Hq, DH] rotated
-  const int32_t* prefix_len;  // denoise step: keys = prefix_len[b] + Q
+  const int32_t* prefix_len;  // denoise step: keys = prefix_len[b] + Q (or + q_valid[b])
+  const int32_t* q_valid;     // denoise step, optional: rows past q_valid[b] are padding and no keys
   const int32_t* cu;          // no-cache forward (Q == 0): sequence b is rows cu[b] .. cu[b+1], keys = its length
   bf16_t* o;                // output when n_units == 1 (row-major, or fragment order if out_mt > 0)
   int out_mt;
@@ -585,7 +588,7 @@ __global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
   const int n_q = paged ? a.Q : a.cu[b + 1] - a.cu[b];          // its query rows
   const int R = n_q * G;
   if (rg * 16 * QT >= R) return;
-  const int kv_len = paged ? a.prefix_len[b] + a.Q : n_q;
+  const int kv_len = paged ? a.prefix_len[b] + (a.q_valid ? min(max(a.q_valid[b], 0), a.Q) : a.Q) : n_q;
   const KVView& kv = a.kv;
   const int pt = paged ? kv.page_tokens : 1;
   const bf16_t* kslab = (const bf16_t*)kv.k;
@@ -882,7 +885,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   const int row_base = PAGED ? b * a.Q : a.cu[b];
   const int n_q = PAGED ? a.Q : a.cu[b + 1] - a.cu[b];
   const int R = n_q * G;
-  const int kv_len = PAGED ? a.prefix_len[b] + a.Q : n_q;
+  const int kv_len = PAGED ? a.prefix_len[b] + (a.q_valid ? min(max(a.q_valid[b], 0), a.Q) : a.Q) : n_q;
   const bool active = w < a.n_rg_wg && rg * 16 * QT < R;     // waves beyond the rows only help loading
   if (blockIdx.y * a.n_rg_wg * 16 * QT >= R) return;         // whole workgroup beyond this sequence's rows
   const KVView& kv = a.kv;
@@ -1191,6 +1194,7 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   AttnArgs a;
   a.q = WSM(c, q, bf16_t);
   a.prefix_len = g.prefix_len;
+  a.q_valid = g.Q > 0 ? g.q_valid : nullptr;
   a.cu = g.cu_seqlens;
   a.o = WSM(c, o, bf16_t);
   a.out_mt = frag_out ? (g.T + 15) / 16 : 0;

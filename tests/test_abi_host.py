@@ -113,6 +113,12 @@ def test_calls_validate_before_launching():
     assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, float("nan"), 0.95, 1, 0, None, None) == E
     assert L.dllm_fsm_update(ctx, None, 1, 8, 32, p, p, p, 0.1, 0.95, -1, 0, None, None) == E
     assert L.dllm_fsm_update(ctx, None, 1, 257, 32, p, p, p, 0.1, 0.95, 1, 0, None, None) == S
+    # steps with padding rows, windows of the block state machine
+    assert L.dllm_denoise_step_var(ctx, None, 1, 32, 64, p, p, None, p, p, p, None) == E           # q_valid is required
+    assert L.dllm_fsm_window(ctx, None, 1, 8, 32, 0, p, p, p, 0, p, p, p, p, p) == E                # W >= 1
+    assert L.dllm_fsm_window(ctx, None, 1, 8, 32, 2, p, p, p, -1, p, p, p, p, p) == E               # pad token in the vocabulary
+    assert L.dllm_fsm_window(ctx, None, 1, 8, 32, 2, p, p, None, 0, p, p, p, p, p) == E
+    assert L.dllm_fsm_scatter(ctx, None, 1, 8, 32, 2, p, p, None, p) == E
     # trajectory recording, noisy sequences, early stop
     assert L.dllm_unmask_traced(ctx, None, 1, 32, 32, p, p, p, 2.0, 0, 1, 1, None, None, None) == E   # order is required
     assert L.dllm_noisy_sequence(ctx, None, 1, 32, p, p, p, 8, 1.5, p) == E                         # 0 <= t <= 1

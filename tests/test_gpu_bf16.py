@@ -153,3 +153,50 @@ def test_degenerate_steps_nothing_masked_and_empty_prefix(Bn, Q):
                              ent.cpu().numpy()[b], "bf16", gpu_logits=logits[b])
     assert eng.read_status() == 0
     eng.close()
+
+
+@pytest.mark.parametrize("lens,qvalid", [([70], [32]), ([100, 77, 45, 130], [64, 32, 0, 33])])
+def test_step_with_padding_rows(lens, qvalid):
+    """dllm_denoise_step_var: rows past q_valid[b] are padding.  The valid rows must equal the oracle's step over the
+    valid rows alone, padding rows report their own token, and nothing is written to the cache behind the valid rows
+    (one sequence on the <= 64-row kernels, four on the large path)."""
+    ms, Q = SMALL, 64
+    w = synth.Weights(ms, 7)
+    Bn = len(lens)
+    eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=8, n_pages=8 * Bn, max_batch=Bn, max_q=Q,
+                        max_tokens=sum(lens) + Bn * Q)
+    seqs = [synth.random_tokens(ms, 40 + i, n) for i, n in enumerate(lens)]
+    table = H.identity_table(eng, Bn)
+    tab = eng.i32(table)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(seqs)), eng.i32(cu), tab, None, total_tokens=int(cu[-1]), max_seqlen=max(lens))
+    blks = np.stack([synth.masked_block(ms, 60 + b, Q, 30) for b in range(Bn)]).astype(np.int32)
+    for b in range(Bn):
+        blks[b, qvalid[b]:] = ms.mask_id if b % 2 else 11          # padding content must not matter, masks included
+    # sentinel K/V behind every sequence's valid rows
+    for l in range(ms.n_layers):
+        for which in (0, 1):
+            slab = eng.kv_slab(l, which)
+            for b in range(Bn):
+                for p in range(lens[b] + qvalid[b], lens[b] + Q):
+                    slab[int(table[b][p // 32]), :, p % 32, :] = 3.0
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(Bn, Q, dtype=torch.float32, device=eng.device)
+    eng.denoise_step_var(eng.i32(blks), eng.i32(lens), eng.i32(qvalid), tab, cand, conf, ent, max_prefix_len=max(lens))
+    assert eng.read_status() == 0
+    c, f, e = cand.cpu().numpy(), conf.cpu().numpy(), ent.cpu().numpy()
+    for b in range(Bn):
+        nv = qvalid[b]
+        assert (c[b, nv:] == blks[b, nv:]).all() and (f[b, nv:] == 1).all()
+        for l in range(ms.n_layers):
+            for which in (0, 1):
+                got = H.gather_cache(eng, table[b], lens[b] + Q, l, which)
+                assert (got[lens[b] + nv:] == 3.0).all()              # nothing written behind the valid rows
+        if nv == 0:
+            continue
+        ck, cv = O.prefill(w, seqs[b], widen=W, store=ST)
+        r = O.denoise_step(w, blks[b, :nv], ck, cv, 0.9, 1, widen=W, store=ST)
+        n_exact = H.check_step_outputs(ms, r, blks[b, :nv] == ms.mask_id, c[b, :nv], f[b, :nv], e[b, :nv], "bf16")
+        assert n_exact >= 1
+    eng.close()

@@ -236,3 +236,99 @@ def test_eos_scan_and_active_list(eng):
         alive = [b for b in range(Bn) if not ref[b][0]]
         assert int(nact) == len(alive)
         assert act.cpu().numpy().tolist() == alive + [-1] * (Bn - len(alive))
+
+
+def test_batched_multiblock_rounds_with_ragged_windows():
+    """Three sequences (different prompts and prompt lengths) decoded with the state machine at once: every cached
+    round is ONE dllm_denoise_step_var call over per-sequence windows built on the device (dllm_fsm_window), one
+    dllm_unmask_blocks, one dllm_fsm_scatter and one dllm_fsm_update (forward type derived per sequence); sequences
+    whose round must not use the cache get an empty window there and their own refresh call.  Every round starts from
+    the oracle's per-sequence state and is compared with it."""
+    ms = TINY
+    w = synth.Weights(ms, 0)
+    NB, Wn, thr, delay = 3, 3, 5.443, 1
+    lens = [64, 40, 57]
+    Bn = len(lens)
+    eng = H.make_engine(ms, w, page_tokens=16, max_pages_per_seq=12, n_pages=12 * Bn, max_batch=Bn, max_q=Wn * BL,
+                        max_tokens=512)
+    prompts = [synth.random_tokens(ms, 50 + b, lens[b]) for b in range(Bn)]
+    recs = []
+    for b in range(Bn):
+        rec = []
+        O.decode_multiblock(w, prompts[b], NB, BL, thr, "entropy", delay=delay, record=rec)
+        recs.append(rec)
+    table = H.identity_table(eng, Bn)
+    tab = eng.i32(table)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), tab, None, total_tokens=int(cu[-1]), max_seqlen=max(lens))
+    dev = eng.device
+    Q = Wn * BL
+    win = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    wfl = torch.zeros(Bn, Wn, dtype=torch.int32, device=dev)
+    pre = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    qv = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    wlo = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    ent = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    base = eng.i32(lens)
+    done_state = [O.COMPLETED] * NB
+    checked = batched_wide = 0
+    for rnd in range(max(len(r) for r in recs)):
+        live = [b for b in range(Bn) if rnd < len(recs[b])]
+        gen_np = np.zeros((Bn, NB * BL), dtype=np.int32)
+        st_np = np.zeros((Bn, NB), dtype=np.int32)
+        ct_np = np.zeros((Bn, NB), dtype=np.int32)
+        for b in range(Bn):
+            if b in live:
+                r = recs[b][rnd]
+                gen_np[b], st_np[b] = r["before"], r["state"]
+                ct_np[b] = recs[b][rnd - 1]["counter_after"] if rnd else [0] * NB
+            else:                                               # finished: whatever it ended with, all blocks done
+                gen_np[b], st_np[b] = recs[b][-1]["before"], done_state
+        gen, state, counter = eng.i32(gen_np), eng.i32(st_np), eng.i32(ct_np)
+        eng.fsm_window(gen, state, base, BL, Wn, 0, win, wfl, pre, qv, wlo)
+        qv_np, pre_np, lo_np = qv.cpu().numpy(), pre.cpu().numpy(), wlo.cpu().numpy()
+        for b in range(Bn):
+            cached = b in live and not recs[b][rnd]["nocache"]
+            if cached:
+                r = recs[b][rnd]
+                assert qv_np[b] == (r["hi"] - r["lo"] + 1) * BL and lo_np[b] == r["lo"] and pre_np[b] == lens[b] + r["lo"] * BL
+            else:
+                assert qv_np[b] == 0 and (wfl.cpu().numpy()[b] == -1).all()
+        # sequences whose round does not use the cache: their own forward (keeps their caches on the oracle's schedule)
+        for b in live:
+            r = recs[b][rnd]
+            if not r["nocache"]:
+                continue
+            n_tok = lens[b] + (r["hi"] + 1) * BL
+            full = np.concatenate([prompts[b], r["before"][:(r["hi"] + 1) * BL]])
+            done_after = sum(s == O.COMPLETED for s in r["state_after"])
+            eng.refresh_cache(eng.i32(full), eng.i32([0, n_tok]), eng.i32(table[b:b + 1]),
+                              eng.i32([lens[b] + done_after * BL]), None, None, None, total_tokens=n_tok, max_seqlen=n_tok)
+        if int(qv_np.max()) > 0:
+            eng.denoise_step_var(win, pre, qv, tab, cand, conf, ent, max_prefix_len=int(pre_np.max()))
+            eng.unmask_blocks(win, cand, ent, thr, wfl, True, BL)
+            eng.fsm_scatter(win, wlo, qv, gen, NB, BL, Wn)
+            batched_wide += int((qv_np > 0).sum()) > 1
+        eng.fsm_update(gen, state, counter, BL, 0.1, 0.95, delay, None, None, None)
+        got_gen, got_state, got_ct = gen.cpu().numpy(), state.cpu().numpy(), counter.cpu().numpy()
+        for b in range(Bn):
+            if b not in live:
+                assert (got_gen[b] == gen_np[b]).all() and got_state[b].tolist() == done_state
+                continue
+            r = recs[b][rnd]
+            if r["nocache"]:
+                assert (got_gen[b] == gen_np[b]).all()          # untouched by the batched calls
+                continue
+            masked = r["before"][r["lo"] * BL:(r["hi"] + 1) * BL] == ms.mask_id
+            np.testing.assert_allclose(ent.cpu().numpy()[b][:len(masked)][masked], r["entropy"][masked], rtol=0, atol=5e-4,
+                                       err_msg=f"round {rnd} seq {b} window {r['lo']}..{r['hi']} qv {qv_np.tolist()} pre {pre_np.tolist()}")
+            if not decided(r, thr, "entropy", BL):
+                continue
+            assert np.nonzero(got_gen[b] != gen_np[b])[0].tolist() == r["chosen"]
+            assert got_state[b].tolist() == r["state_after"] and got_ct[b].tolist() == r["counter_after"]
+            checked += 1
+    assert checked >= 6 and batched_wide >= 2
+    assert eng.read_status() == 0
+    eng.close()
