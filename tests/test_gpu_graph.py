@@ -53,3 +53,65 @@ def test_graph_replay_equals_eager(ms):
         assert int(nrem) == Q - 2 * (replay + 1)
     assert eng.read_status() == 0
     eng.close()
+
+
+@pytest.mark.parametrize("ms", [synth.TINY, SMALL], ids=["tiny-f32", "small-bf16"])
+def test_cached_multiblock_round_as_one_graph(ms):
+    """A whole cached round of multi-block decoding for a batch - windows built on the device, the step with padding
+    rows, the selection with a floor per block, the write-back and the state transitions - captured once and replayed
+    round after round: every replay must leave the tokens, states and counters the eager calls leave."""
+    Bn, NB, BL, Wn = 3, 3, 32, 2
+    lens = [48, 33, 64]
+    thr = 100.0 if ms is SMALL else 5.46            # an entropy threshold that lets a few positions through per round
+    w = synth.Weights(ms, 12)
+    eng = H.make_engine(ms, w, page_tokens=16, max_pages_per_seq=12, n_pages=12 * Bn, max_batch=Bn, max_q=Wn * BL,
+                        max_tokens=sum(lens) + Bn * Wn * BL)
+    dev = eng.device
+    table = eng.i32(H.identity_table(eng, Bn))
+    prompts = [synth.random_tokens(ms, 70 + b, lens[b]) for b in range(Bn)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), table, None, total_tokens=int(cu[-1]), max_seqlen=max(lens))
+    Q = Wn * BL
+    base = eng.i32(lens)
+    max_prefix = max(lens) + NB * BL
+
+    def buffers():
+        return dict(win=torch.zeros(Bn, Q, dtype=torch.int32, device=dev), wfl=torch.zeros(Bn, Wn, dtype=torch.int32, device=dev),
+                    pre=torch.zeros(Bn, dtype=torch.int32, device=dev), qv=torch.zeros(Bn, dtype=torch.int32, device=dev),
+                    wlo=torch.zeros(Bn, dtype=torch.int32, device=dev), cand=torch.zeros(Bn, Q, dtype=torch.int32, device=dev),
+                    conf=torch.zeros(Bn, Q, dtype=torch.float32, device=dev), ent=torch.zeros(Bn, Q, dtype=torch.float32, device=dev))
+
+    def one_round(gen, state, counter, b):
+        eng.fsm_window(gen, state, base, BL, Wn, 0, b["win"], b["wfl"], b["pre"], b["qv"], b["wlo"])
+        eng.denoise_step_var(b["win"], b["pre"], b["qv"], table, b["cand"], b["conf"], b["ent"], max_prefix_len=max_prefix)
+        eng.unmask_blocks(b["win"], b["cand"], b["ent"], thr, b["wfl"], True, BL)
+        eng.fsm_scatter(b["win"], b["wlo"], b["qv"], gen, NB, BL, Wn)
+        eng.fsm_update(gen, state, counter, BL, 0.1, 0.95, 1, None, None, None)
+
+    def fresh():
+        gen = torch.full((Bn, NB * BL), ms.mask_id, dtype=torch.int32, device=dev)
+        state = torch.zeros(Bn, NB, dtype=torch.int32, device=dev)
+        state[:, 0] = 2
+        return gen, state, torch.zeros(Bn, NB, dtype=torch.int32, device=dev)
+
+    gen, state, counter = fresh()
+    gb = buffers()
+    one_round(*[t.clone() for t in (gen, state, counter)], buffers())          # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_round(gen, state, counter, gb)
+    torch.cuda.synchronize()
+    g0, s0, c0 = fresh()
+    gen.copy_(g0); state.copy_(s0); counter.copy_(c0)
+    progressed = 0
+    for replay in range(6):
+        eg, es, ec = gen.clone(), state.clone(), counter.clone()
+        one_round(eg, es, ec, buffers())                                       # eager, on a copy of the same state
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(gen, eg) and torch.equal(state, es) and torch.equal(counter, ec), replay
+        progressed += int((gen != ms.mask_id).sum())
+    assert progressed > 0 and eng.read_status() == 0
+    eng.close()
