@@ -213,7 +213,9 @@ int dllm_fsm_update(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_
                     int32_t *state, int32_t *counter, double add_at, double full_at, int delay, int nocache_round,
                     int32_t *floor_next, int32_t *summary);
 /* nocache_round < 0: derived per sequence - the round skipped the cache iff one of the sequence's blocks was
- * Stabilizing in the incoming state (the rule by which the forward of a round is chosen). */
+ * Stabilizing in the incoming state (the rule by which the forward of a round is chosen).  The library only
+ * counts: running that forward (dllm_refresh_cache with the step outputs) for those sequences before this call
+ * is the caller's part. */
 
 /* A denoise step whose sequences have different numbers of query rows (multi-block decoding: the windows of
  * the sequences of a batch differ): as dllm_denoise_step, but rows j >= q_valid[b] of sequence b are padding.
