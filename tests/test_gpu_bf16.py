@@ -89,6 +89,15 @@ def test_small_gqa_model_other_page_sizes(pt, mp):
     run_small(SMALL, [100, 77], 32, 20, 0, mp=mp, pt=pt)
 
 
+WIDE_MLP = synth.ModelShape(1, 320, 5, 5, 64, 8192, 2000, 1999, dtype="bf16", lm_head_scale=8.0, name="wide-mlp")
+
+
+def test_wide_mlp_narrow_model_on_256_row_tiles():
+    """d_model 320 with an 8192-wide MLP and a 300-token prefill: the down projection takes the 256-row tiles with a
+    long K and a ragged feature count (320 = one and a quarter tiles), its K sum split and folded by the next norm."""
+    run_small(WIDE_MLP, [300, 41], 32, 20, 0, mp=12)
+
+
 def test_llada_shaped_layer_and_head_full_size():
     """Workload: one LLaDA-8B-shaped layer + LM head over vocab 126464, batch 1, prefix 512, block 32
     (24 masked), threshold 0.9, floor 1 -- all rows checked against the oracle."""
