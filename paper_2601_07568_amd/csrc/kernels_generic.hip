@@ -621,24 +621,39 @@ __global__ __launch_bounds__(256) void k_lm_head(const T* __restrict__ A, const 
 }
 
 // one wavefront per compacted row: merge the per-tile statistics and emit the outputs
-__global__ __launch_bounds__(64) void k_lm_merge(const float* part, int n_vtiles, const int32_t* rows,
-                                                 const int32_t* n_rows_dev, int32_t* cand, float* conf,
-                                                 float* entropy) {
+__global__ __launch_bounds__(256) void k_lm_merge(const float* part, int n_vtiles, const int32_t* rows,
+                                                  const int32_t* n_rows_dev, int32_t* cand, float* conf,
+                                                  float* entropy) {
+  // 256 threads per row; a thread's partials are fetched eight at a time before they are merged, so the
+  // loads of a batch are in flight together; lanes, then waves, merge in a fixed order
+  __shared__ float4 wst[4];
   const int r = blockIdx.x;
   if (r >= *n_rows_dev) return;
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float4* prow = (const float4*)part + (int64_t)r * n_vtiles;
   RowStat st;
   st.init();
-  for (int v = lane; v < n_vtiles; v += 64) {
-    const float* p = part + ((int64_t)r * n_vtiles + v) * 4;
-    st.merge(p[0], __float_as_int(p[1]), p[2], p[3]);
+  for (int v0 = tid; v0 < n_vtiles; v0 += 256 * 8) {
+    float4 p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = v0 + u * 256;
+      p[u] = prow[v < n_vtiles ? v : n_vtiles - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (v0 + u * 256 < n_vtiles) st.merge(p[u].x, __float_as_int(p[u].y), p[u].z, p[u].w);
   }
   for (int o = 1; o < 64; o <<= 1) {
     float m2 = __shfl_xor(st.m, o, 64), s2 = __shfl_xor(st.s, o, 64), t2 = __shfl_xor(st.t, o, 64);
     int i2 = __shfl_xor(st.idx, o, 64);
     st.merge(m2, i2, s2, t2);
   }
-  if (lane == 0) {
+  if (lane == 0) wst[wave] = make_float4(st.m, __int_as_float(st.idx), st.s, st.t);
+  __syncthreads();
+  if (tid == 0) {
+    st.init();
+    for (int w = 0; w < 4; ++w) st.merge(wst[w].x, __float_as_int(wst[w].y), wst[w].z, wst[w].w);
     const int t = rows[r];
     cand[t] = st.idx;
     conf[t] = 1.0f / st.s;
@@ -950,7 +965,7 @@ hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows) {
 
 hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts, int32_t* cand, float* conf,
                            float* entropy) {
-  k_lm_merge<<<max_rows, 64, 0, s>>>(WS(c, lm_part, float), n_parts, WS(c, rows, int32_t),
+  k_lm_merge<<<max_rows, 256, 0, s>>>(WS(c, lm_part, float), n_parts, WS(c, rows, int32_t),
                                      WS(c, status, int32_t) + 1, cand, conf, entropy);
   return hipGetLastError();
 }
