@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdllm.so")
 HEADER = os.path.join(os.path.dirname(HERE), "include", "dllm.h")
-SOURCES = ["api.hip", "kernels_generic.hip", "kernels_mfma.hip"]
+SOURCES = ["api.hip", "kernels_generic.hip", "kernels_skinny.hip", "kernels_attention.hip", "kernels_gemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-sanitize",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -248,7 +248,7 @@ hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, 
                              int32_t* floor_next, int32_t* summary);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
 
-// ---- launchers implemented in kernels_mfma.hip (bf16, gfx950 matrix cores) --------------------
+// ---- launchers implemented in kernels_skinny.hip / kernels_attention.hip / kernels_gemm.hip (bf16, matrix cores) --
 bool mfma_supported(const dllm_ctx* c);
 size_t packed_weight_bytes(int N, int K);
 hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int K);
