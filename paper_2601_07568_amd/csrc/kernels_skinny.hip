@@ -127,7 +127,9 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
 // workgroup's prologue and reduction overlap the other's streaming)
 template <int NT, int MT, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_skinny(const SkArgs a) {
-  constexpr int JB = (NT == 1) ? 4 : 2;   // weight bytes in flight per wave: two stages of NT*JB KiB
+  // weight bytes in flight per wave: two stages of NT*JB KiB; with three or four activation tiles the
+  // shorter stage keeps the kernel at two workgroups per CU
+  constexpr int JB = (NT == 1) ? 4 : ((MT >= 3 || EPI == SK_DELTA) ? 1 : 2);
   __shared__ float red[NW][NT][MT][4][64];
   __shared__ float lmst[EPI == SK_LMSTATS ? MT : 1][4][16][4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
