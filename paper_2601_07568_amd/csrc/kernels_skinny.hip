@@ -385,7 +385,7 @@ hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void
   a.out_f32 = delta;
   a.delta_stride = delta_stride;
   const int groups = (N + 63) / 64;
-  const int n_full = K / 64;                       // stages of JB = 2 steps
+  const int n_full = K / 32;                       // the kernel's stages: one 32-element step each (JB = 1)
   int ks = (256 + groups - 1) / groups;
   if (ks > max_splits) ks = max_splits;
   if (ks > n_full / (2 * SK_NW)) ks = n_full / (2 * SK_NW);   // at least two stages per wave
