@@ -525,6 +525,164 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   }   // work items
 }
 
+// ------------------------------------------------------------------------------------------
+// 65 .. 255 token rows (a few blocks in flight at small batch): the weights still have to stream from
+// memory once and the products are few, so what counts is bytes in flight and how often the activations
+// are re-read.  A workgroup of 4 waves owns 128 token rows x 64 weight rows; both operands are copied
+// straight into a 4-stage LDS ring of 32-deep K stages (12 KiB each: three workgroups fit a CU), the
+// activations are shared by the waves through LDS, the products are 32 x 32 x 16 ones (wave tile 64 x 32).
+// Row swizzle and operand layout are those of the 256 x 256 kernel.  A wave's 32 weight rows are 16 gate
+// rows followed by the 16 up rows of the same features for SiLU(gate)*up: both land in one lane.
+constexpr int TS_NS = 4, TS_STAGE = 12288, TS_LDS = TS_NS * TS_STAGE;
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[TS_LDS];
+  constexpr int TILE_N = (EPI == LG_SWIGLU) ? 32 : 64;        // output features of a tile
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  int M = a.M;
+  if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
+  const int N = a.N, K = a.K;
+  const int tile = blockIdx.x;
+  const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
+  const int m0 = tm * 128, n0 = tn * TILE_N;
+  if (m0 >= M) return;
+  const int wm = w & 1, wn = w >> 1;
+  const int r = lane & 31, h = lane >> 5;
+  int k_begin = 0, k_end = K;
+  if constexpr (EPI == LG_RESID || EPI == LG_QKV) {
+    k_begin = blockIdx.y * a.k_per;
+    k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
+  }
+  // copies: this wave moves token blocks 2w, 2w+1 (16 rows each) and weight block w of a stage
+  const bf16_t* gsrc[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int rr = (q < 2 ? (2 * w + q) : w) * 16 + (lane >> 2);
+    const int piece = (lane & 3) ^ ((rr >> 2) & 3);
+    if (q < 2) {
+      int row = m0 + rr; row = row < M ? row : M - 1;
+      gsrc[q] = a.A + (int64_t)row * K + piece * 8;
+    } else if constexpr (EPI == LG_SWIGLU) {
+      int row = n0 + (rr >> 5) * 16 + (rr & 15); row = row < N ? row : N - 1;
+      gsrc[q] = (((rr >> 4) & 1) ? a.W2 : a.W) + (int64_t)row * K + piece * 8;
+    } else if constexpr (EPI == LG_QKV) {
+      const int row = n0 + rr;                       // q | k | v stacked, each a multiple of 64 rows
+      const bf16_t* wsel = row < N ? a.W : (row < N + a.N2 ? a.W2 : a.W3);
+      const int lrow = row < N ? row : (row < N + a.N2 ? row - N : row - N - a.N2);
+      gsrc[q] = wsel + (int64_t)lrow * K + piece * 8;
+    } else {
+      int row = n0 + rr; row = row < N ? row : N - 1;
+      gsrc[q] = a.W + (int64_t)row * K + piece * 8;
+    }
+  }
+  auto copy_stage = [&](int slot, int kd) {
+    unsigned char* base = smem + slot * TS_STAGE;
+    t2_copy16(gsrc[0] + kd, base + (2 * w) * 1024);
+    t2_copy16(gsrc[1] + kd, base + (2 * w + 1) * 1024);
+    t2_copy16(gsrc[2] + kd, base + 8192 + w * 1024);
+  };
+  int offA[2], offW[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int slotp = ((2 * ks + h) ^ ((r >> 2) & 3)) * 16;
+    offA[ks] = (wm * 64 + r) * 64 + slotp;
+    offW[ks] = 8192 + (wn * 32 + r) * 64 + slotp;
+  }
+  f32x16 acc[2];   // token tiles j = 0, 1 of this wave against its weight tile
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+  const int ns = (k_end - k_begin) / 32;      // K ranges are multiples of 32 (checked on the host)
+#pragma unroll
+  for (int st = 0; st < TS_NS - 1; ++st) copy_stage(st, k_begin + (st < ns ? st : ns - 1) * 32);
+  for (int st = 0; st < ns; ++st) {
+    // this wave's copies of stage st are the oldest of its 3 * (NS - 1) outstanding ones
+    __builtin_amdgcn_s_waitcnt(T2_VMCNT(3 * (TS_NS - 2)));
+    __builtin_amdgcn_s_barrier();               // every wave's part of stage st is in; stage st - 1 is free
+    {
+      const int sn = st + TS_NS - 1;
+      copy_stage(sn % TS_NS, k_begin + (sn < ns ? sn : ns - 1) * 32);   // past the end: a repeat into a free slot
+    }
+    const unsigned char* base = smem + (st % TS_NS) * TS_STAGE;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const u32x4 fw = *(const u32x4*)(base + offW[ks]);
+      const u32x4 fa0 = *(const u32x4*)(base + offA[ks]), fa1 = *(const u32x4*)(base + offA[ks] + 2048);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa0), acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa1), acc[1], 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(T2_VMCNT(0));   // the ring's trailing repeats must not outlive the workgroup
+
+  // lane holds token column l%32 of token tile j; weight rows (e/4)*8 + (l/32)*4 + e%4 of the wave's tile
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int m = m0 + wm * 64 + j * 32 + r;
+    if (m >= M) continue;
+    if constexpr (EPI == LG_SWIGLU) {
+#pragma unroll
+      for (int e4 = 0; e4 < 2; ++e4) {
+        const int n = n0 + wn * 16 + e4 * 8 + h * 4;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gt = acc[j][e4 * 4 + e];
+          v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[j][8 + e4 * 4 + e];
+        }
+        if (n + 4 <= N) {
+          *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        } else {
+          for (int e = 0; e < 4 && n + e < N; ++e) ((bf16_t*)a.C)[(int64_t)m * N + n + e] = f32_to_bf16(v[e]);
+        }
+      }
+    } else if constexpr (EPI == LG_QKV) {
+      const int nt = N + 2 * a.N2;
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int n = n0 + wn * 32 + e4 * 8 + h * 4;
+        *(f32x4*)(a.delta + (int64_t)blockIdx.y * a.delta_stride + (int64_t)m * nt + n) =
+            f32x4{acc[j][e4 * 4], acc[j][e4 * 4 + 1], acc[j][e4 * 4 + 2], acc[j][e4 * 4 + 3]};
+      }
+    } else {
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int n = n0 + wn * 32 + e4 * 8 + h * 4;
+        const f32x4 v = f32x4{acc[j][e4 * 4], acc[j][e4 * 4 + 1], acc[j][e4 * 4 + 2], acc[j][e4 * 4 + 3]};
+        const int64_t at = (int64_t)m * N + n;
+        if (n + 4 <= N) {
+          if (blockIdx.y == 0) { f32x4* p = (f32x4*)((float*)a.C + at); *p = *p + v; }
+          else *(f32x4*)(a.delta + (int64_t)(blockIdx.y - 1) * a.delta_stride + at) = v;
+        } else {
+          for (int e = 0; e < 4 && n + e < N; ++e) {
+            if (blockIdx.y == 0) ((float*)a.C)[at + e] += v[e];
+            else a.delta[(int64_t)(blockIdx.y - 1) * a.delta_stride + at + e] = v[e];
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+static hipError_t ts_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
+  constexpr int tile_n = EPI == LG_SWIGLU ? 32 : 64;
+  a.tiles_m = (a.M + 127) / 128;
+  a.tiles_n = EPI == LG_QKV ? (a.N + 2 * a.N2) / 64 : (a.N + tile_n - 1) / tile_n;
+  if (EPI != LG_RESID && EPI != LG_QKV) a.k_per = a.K;
+  const dim3 grid(a.tiles_m * a.tiles_n, k_splits);
+  k_gemm_ts<EPI><<<grid, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+// rows for which the streaming tiles are the better form: more than the weight-streaming kernels take, fewer
+// than fill 256-row tiles
+static bool ts_usable(int M, int K) {
+  static const int off = getenv("DLLM_NO_TS") ? 1 : 0;   // tuning aid
+  return !off && M > 64 && M < 256 && K % 32 == 0 && K >= 128;
+}
+
 // the 256 x 256 form needs the whole ring in LDS: more than the default limit of a kernel
 static bool t2_ready = false;
 static int t2_cus = 256;
@@ -597,6 +755,20 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = x; a.M = M; a.N = N; a.K = K;
+  if (ts_usable(M, K) && M <= c->map.lg_delta_rows && N == c->cfg.d_model) {
+    // streaming tiles: K split until about three workgroups per CU are in flight
+    const int tiles = ((M + 127) / 128) * ((N + 63) / 64);
+    int splits = 768 / tiles;
+    if (splits > LG_MAX_DELTA + 1) splits = LG_MAX_DELTA + 1;
+    while (splits > 1 && K / splits < 512) --splits;
+    if (splits < 1) splits = 1;
+    a.k_per = ((K + splits - 1) / splits + 31) / 32 * 32;
+    splits = (K + a.k_per - 1) / a.k_per;
+    a.delta = (float*)(c->ws + c->map.delta);
+    a.delta_stride = c->map.lg_delta_stride;
+    *n_delta = splits - 1;
+    return ts_launch<LG_RESID>(s, a, splits);
+  }
   // short sums over few rows: the 128-row tiles fill the chip better
   const bool t2 = t2_usable(M, K) && (K >= 8192 || ((M + 255) / 256) * ((N + 255) / 256) >= 192);
   const int tiles = t2 ? ((M + 255) / 256) * ((N + 255) / 256) : ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
@@ -618,6 +790,23 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
 hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
                                  int M, int dq, int dkv, int K, int* n_part) {
   *n_part = 0;
+  if (ts_usable(M, K) && M <= c->map.lg_delta_rows && dq % 64 == 0 && dkv % 64 == 0 && c->map.qkvp_stride > 0) {
+    LgArgs a;
+    memset(&a, 0, sizeof(a));
+    a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
+    a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
+    const int tiles = ((M + 127) / 128) * ((dq + 2 * dkv) / 64);
+    int splits = 768 / tiles;
+    if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
+    while (splits > 1 && K / splits < 512) --splits;
+    if (splits < 1) splits = 1;
+    a.k_per = ((K + splits - 1) / splits + 31) / 32 * 32;
+    splits = (K + a.k_per - 1) / a.k_per;
+    a.delta = (float*)(c->ws + c->map.qkvp);
+    a.delta_stride = c->map.qkvp_stride;
+    *n_part = splits;
+    return ts_launch<LG_QKV>(s, a, splits);
+  }
   if (!t2_usable(M, K) || M > c->map.qkvp_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
     return hipSuccess;
   LgArgs a;
@@ -655,6 +844,7 @@ hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, cons
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
+  if (ts_usable(M, K)) return ts_launch<LG_SWIGLU>(s, a);
   if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
   return lg_launch<LG_SWIGLU>(s, a);
 }
@@ -670,6 +860,8 @@ hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_
   a.n_parts = (f.vocab + 63) / 64;
   a.mask_id = f.mask_id;
   *n_parts_out = a.n_parts;
+  // (65 .. 255 rows stay on the 128 x 128 tiles: 4.3 TB/s at 128 rows, against 2.8 TB/s for the 128 x 64
+  // streaming tiles, whose activation re-reads double the bytes the LM head moves)
   if (t2_usable(max_rows, a.K)) return t2_launch<LG_LMSTATS>(s, a);
   return lg_launch<LG_LMSTATS>(s, a);
 }
