@@ -126,7 +126,7 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
 // (second launch bound: at least 4 waves per SIMD, i.e. two 8-wave workgroups per CU, so that one
 // workgroup's prologue and reduction overlap the other's streaming)
 template <int NT, int MT, int NW, int EPI>
-__global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : 1) void k_skinny(const SkArgs a) {
+__global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 && MT >= 3) ? 2 : 1)) void k_skinny(const SkArgs a) {
   // weight bytes in flight per wave: two stages of NT*JB KiB; with three or four activation tiles the
   // shorter stage keeps the kernel at two workgroups per CU
   constexpr int JB = (NT == 1) ? 4 : ((MT >= 3 || EPI == SK_DELTA) ? 1 : 2);
