@@ -98,15 +98,18 @@ def test_wide_mlp_narrow_model_on_256_row_tiles():
     run_small(WIDE_MLP, [300, 41], 32, 20, 0, mp=12)
 
 
-def test_llada_shaped_layer_and_head_full_size():
+@pytest.mark.parametrize("Q,n_masked", [(32, 24), (48, 30), (64, 40), (128, 70)])
+def test_llada_shaped_layer_and_head_full_size(Q, n_masked):
     """Workload: one LLaDA-8B-shaped layer + LM head over vocab 126464, batch 1, prefix 512, block 32
-    (24 masked), threshold 0.9, floor 1 -- all rows checked against the oracle."""
+    (24 masked), threshold 0.9, floor 1 -- all rows checked against the oracle.  Also with 48, 64 and 128 query
+    rows (more blocks in flight): the weight-streaming kernels with three and four row tiles, and the streaming
+    tiles that take over above 64 rows."""
     ms = synth.LLADA_8B.with_layers(1)
-    P, Q = 512, 32
+    P = 512
     w = synth.Weights(ms, 2)
-    eng = H.make_engine(ms, w, page_tokens=64, max_pages_per_seq=9, n_pages=9, max_batch=1, max_q=Q, max_tokens=P)
+    eng = H.make_engine(ms, w, page_tokens=64, max_pages_per_seq=10, n_pages=10, max_batch=1, max_q=Q, max_tokens=P)
     prompt = synth.random_tokens(ms, 2, P)
-    blk = synth.masked_block(ms, 2, Q, 24)
+    blk = synth.masked_block(ms, 2, Q, n_masked)
     table = H.identity_table(eng, 1)
     eng.prefill_kv(eng.i32(prompt), eng.i32([0, P]), eng.i32(table), None, total_tokens=P, max_seqlen=P)
     qt = eng.i32(blk[None])
