@@ -532,13 +532,15 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
 // straight into a 4-stage LDS ring of 32-deep K stages (12 KiB each: three workgroups fit a CU), the
 // activations are shared by the waves through LDS, the products are 32 x 32 x 16 ones (wave tile 64 x 32).
 // Row swizzle and operand layout are those of the 256 x 256 kernel.  A wave's 32 weight rows are 16 gate
-// rows followed by the 16 up rows of the same features for SiLU(gate)*up: both land in one lane.
-constexpr int TS_NS = 4, TS_STAGE = 12288, TS_LDS = TS_NS * TS_STAGE;
+// rows followed by the 16 up rows of the same features for SiLU(gate)*up: both land in one lane.  The tile is
+// 128 x 128 where the matrix is wide enough to still fill the chip (gate/up): fewer activation re-reads.
+constexpr int TS_NS = 4;
 
-template <int EPI>
+template <int EPI, int WT>      // WT: 32-row weight tiles per wave (the workgroup's tile is 128 x 64*WT)
 __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[TS_LDS];
-  constexpr int TILE_N = (EPI == LG_SWIGLU) ? 32 : 64;        // output features of a tile
+  constexpr int BN = 64 * WT, TS_STAGE = 8192 + BN * 64;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[TS_NS * TS_STAGE];
+  constexpr int TILE_N = (EPI == LG_SWIGLU) ? BN / 2 : BN;    // output features of a tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int M = a.M;
   if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
@@ -554,17 +556,18 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
     k_begin = blockIdx.y * a.k_per;
     k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
   }
-  // copies: this wave moves token blocks 2w, 2w+1 (16 rows each) and weight block w of a stage
-  const bf16_t* gsrc[3];
+  // copies: this wave moves token blocks 2w, 2w+1 (16 rows each) and weight blocks w*WT .. of a stage
+  constexpr int NC = 2 + WT;
+  const bf16_t* gsrc[NC];
 #pragma unroll
-  for (int q = 0; q < 3; ++q) {
-    const int rr = (q < 2 ? (2 * w + q) : w) * 16 + (lane >> 2);
+  for (int q = 0; q < NC; ++q) {
+    const int rr = (q < 2 ? (2 * w + q) : (w * WT + q - 2)) * 16 + (lane >> 2);
     const int piece = (lane & 3) ^ ((rr >> 2) & 3);
     if (q < 2) {
       int row = m0 + rr; row = row < M ? row : M - 1;
       gsrc[q] = a.A + (int64_t)row * K + piece * 8;
     } else if constexpr (EPI == LG_SWIGLU) {
-      int row = n0 + (rr >> 5) * 16 + (rr & 15); row = row < N ? row : N - 1;
+      int row = n0 + (rr >> 5) * 16 + (rr & 15); row = row < N ? row : N - 1;     // every 32 rows: 16 gate, 16 up
       gsrc[q] = (((rr >> 4) & 1) ? a.W2 : a.W) + (int64_t)row * K + piece * 8;
     } else if constexpr (EPI == LG_QKV) {
       const int row = n0 + rr;                       // q | k | v stacked, each a multiple of 64 rows
@@ -580,27 +583,30 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
     unsigned char* base = smem + slot * TS_STAGE;
     t2_copy16(gsrc[0] + kd, base + (2 * w) * 1024);
     t2_copy16(gsrc[1] + kd, base + (2 * w + 1) * 1024);
-    t2_copy16(gsrc[2] + kd, base + 8192 + w * 1024);
+#pragma unroll
+    for (int q = 0; q < WT; ++q) t2_copy16(gsrc[2 + q] + kd, base + 8192 + (w * WT + q) * 1024);
   };
   int offA[2], offW[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int slotp = ((2 * ks + h) ^ ((r >> 2) & 3)) * 16;
     offA[ks] = (wm * 64 + r) * 64 + slotp;
-    offW[ks] = 8192 + (wn * 32 + r) * 64 + slotp;
+    offW[ks] = 8192 + (wn * 32 * WT + r) * 64 + slotp;
   }
-  f32x16 acc[2];   // token tiles j = 0, 1 of this wave against its weight tile
+  f32x16 acc[WT][2];   // [weight tile][token tile]
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int i = 0; i < WT; ++i)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int ns = (k_end - k_begin) / 32;      // K ranges are multiples of 32 (checked on the host)
 #pragma unroll
   for (int st = 0; st < TS_NS - 1; ++st) copy_stage(st, k_begin + (st < ns ? st : ns - 1) * 32);
   for (int st = 0; st < ns; ++st) {
-    // this wave's copies of stage st are the oldest of its 3 * (NS - 1) outstanding ones
-    __builtin_amdgcn_s_waitcnt(T2_VMCNT(3 * (TS_NS - 2)));
+    // this wave's copies of stage st are the oldest of its NC * (NS - 1) outstanding ones
+    __builtin_amdgcn_s_waitcnt(T2_VMCNT(NC * (TS_NS - 2)));
     __builtin_amdgcn_s_barrier();               // every wave's part of stage st is in; stage st - 1 is free
     {
       const int sn = st + TS_NS - 1;
@@ -609,10 +615,13 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
     const unsigned char* base = smem + (st % TS_NS) * TS_STAGE;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const u32x4 fw = *(const u32x4*)(base + offW[ks]);
       const u32x4 fa0 = *(const u32x4*)(base + offA[ks]), fa1 = *(const u32x4*)(base + offA[ks] + 2048);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa0), acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa1), acc[1], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < WT; ++i) {
+        const u32x4 fw = *(const u32x4*)(base + offW[ks] + i * 2048);
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa0), acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw), __builtin_bit_cast(bf16x8, fa1), acc[i][1], 0, 0, 0);
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(T2_VMCNT(0));   // the ring's trailing repeats must not outlive the workgroup
@@ -624,13 +633,15 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
     if (m >= M) continue;
     if constexpr (EPI == LG_SWIGLU) {
 #pragma unroll
+      for (int i = 0; i < WT; ++i)
+#pragma unroll
       for (int e4 = 0; e4 < 2; ++e4) {
-        const int n = n0 + wn * 16 + e4 * 8 + h * 4;
+        const int n = n0 + (wn * WT + i) * 16 + e4 * 8 + h * 4;
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float gt = acc[j][e4 * 4 + e];
-          v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[j][8 + e4 * 4 + e];
+          const float gt = acc[i][j][e4 * 4 + e];
+          v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[i][j][8 + e4 * 4 + e];
         }
         if (n + 4 <= N) {
           *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
@@ -641,16 +652,20 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
     } else if constexpr (EPI == LG_QKV) {
       const int nt = N + 2 * a.N2;
 #pragma unroll
+      for (int i = 0; i < WT; ++i)
+#pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        const int n = n0 + wn * 32 + e4 * 8 + h * 4;
+        const int n = n0 + (wn * WT + i) * 32 + e4 * 8 + h * 4;
         *(f32x4*)(a.delta + (int64_t)blockIdx.y * a.delta_stride + (int64_t)m * nt + n) =
-            f32x4{acc[j][e4 * 4], acc[j][e4 * 4 + 1], acc[j][e4 * 4 + 2], acc[j][e4 * 4 + 3]};
+            f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
       }
     } else {
 #pragma unroll
+      for (int i = 0; i < WT; ++i)
+#pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        const int n = n0 + wn * 32 + e4 * 8 + h * 4;
-        const f32x4 v = f32x4{acc[j][e4 * 4], acc[j][e4 * 4 + 1], acc[j][e4 * 4 + 2], acc[j][e4 * 4 + 3]};
+        const int n = n0 + (wn * WT + i) * 32 + e4 * 8 + h * 4;
+        const f32x4 v = f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
         const int64_t at = (int64_t)m * N + n;
         if (n + 4 <= N) {
           if (blockIdx.y == 0) { f32x4* p = (f32x4*)((float*)a.C + at); *p = *p + v; }
@@ -666,14 +681,14 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
   }
 }
 
-template <int EPI>
+template <int EPI, int WT>
 static hipError_t ts_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
-  constexpr int tile_n = EPI == LG_SWIGLU ? 32 : 64;
+  constexpr int bn = 64 * WT, tile_n = EPI == LG_SWIGLU ? bn / 2 : bn;
   a.tiles_m = (a.M + 127) / 128;
-  a.tiles_n = EPI == LG_QKV ? (a.N + 2 * a.N2) / 64 : (a.N + tile_n - 1) / tile_n;
+  a.tiles_n = EPI == LG_QKV ? (a.N + 2 * a.N2) / bn : (a.N + tile_n - 1) / tile_n;
   if (EPI != LG_RESID && EPI != LG_QKV) a.k_per = a.K;
   const dim3 grid(a.tiles_m * a.tiles_n, k_splits);
-  k_gemm_ts<EPI><<<grid, 256, 0, s>>>(a);
+  k_gemm_ts<EPI, WT><<<grid, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 // rows for which the streaming tiles are the better form: more than the weight-streaming kernels take, fewer
@@ -767,7 +782,7 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
     a.delta = (float*)(c->ws + c->map.delta);
     a.delta_stride = c->map.lg_delta_stride;
     *n_delta = splits - 1;
-    return ts_launch<LG_RESID>(s, a, splits);
+    return ts_launch<LG_RESID, 1>(s, a, splits);
   }
   // short sums over few rows: the 128-row tiles fill the chip better
   const bool t2 = t2_usable(M, K) && (K >= 8192 || ((M + 255) / 256) * ((N + 255) / 256) >= 192);
@@ -805,7 +820,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
     a.delta = (float*)(c->ws + c->map.qkvp);
     a.delta_stride = c->map.qkvp_stride;
     *n_part = splits;
-    return ts_launch<LG_QKV>(s, a, splits);
+    return ts_launch<LG_QKV, 1>(s, a, splits);
   }
   if (!t2_usable(M, K) || M > c->map.qkvp_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
     return hipSuccess;
@@ -844,7 +859,7 @@ hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, cons
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
-  if (ts_usable(M, K)) return ts_launch<LG_SWIGLU>(s, a);
+  if (ts_usable(M, K)) return ts_launch<LG_SWIGLU, 2>(s, a);
   if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
   return lg_launch<LG_SWIGLU>(s, a);
 }
