@@ -810,7 +810,8 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
     memset(&a, 0, sizeof(a));
     a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
     a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
-    const int tiles = ((M + 127) / 128) * ((dq + 2 * dkv) / 64);
+    const bool wide = dq % 128 == 0 && dkv % 128 == 0 && (dq + 2 * dkv) / 128 >= 64;   // 128 x 128 tiles still fill the chip
+    const int tiles = ((M + 127) / 128) * ((dq + 2 * dkv) / (wide ? 128 : 64));
     int splits = 768 / tiles;
     if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
     while (splits > 1 && K / splits < 512) --splits;
@@ -820,6 +821,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
     a.delta = (float*)(c->ws + c->map.qkvp);
     a.delta_stride = c->map.qkvp_stride;
     *n_part = splits;
+    if (wide) return ts_launch<LG_QKV, 2>(s, a, splits);
     return ts_launch<LG_QKV, 1>(s, a, splits);
   }
   if (!t2_usable(M, K) || M > c->map.qkvp_rows || dq % 256 != 0 || dkv % 256 != 0 || c->map.qkvp_stride == 0)
