@@ -43,9 +43,15 @@ def test_four_full_width_layers_two_blocks_against_oracle():
             eng.denoise_step(qt, eng.i32([cur]), tab, cand, conf, ent, max_prefix_len=cur)
             logits = eng.debug_logits(qt, eng.i32([cur]), tab, max_prefix_len=cur).cpu().numpy()[0]
             err = H.rel_err_rows(logits, exact).max()
+            err_store = H.rel_err_rows(logits, r["logits"]).max()
+            inherent = H.rel_err_rows(r["logits"], exact).max()      # what bf16 storage alone costs at this depth
             print(f"block {blk_no} step {step}: logit rel err vs exact oracle {err:.3e}, "
-                  f"vs bf16-storage oracle {H.rel_err_rows(logits, r['logits']).max():.3e}")
-            assert err <= H.LOGIT_TOL["bf16"]
+                  f"vs bf16-storage oracle {err_store:.3e}; bf16-storage oracle vs exact {inherent:.3e}")
+            # four layers deep the storage rounding itself uses up most of the tolerance (1.6e-2 .. 2e-2 here): the
+            # library must stay within the tolerance of the oracle that rounds where it rounds, and no farther
+            # from the exact one than that oracle is, give or take a quarter
+            assert err_store <= H.LOGIT_TOL["bf16"]
+            assert err <= max(H.LOGIT_TOL["bf16"], 1.25 * inherent)
             masked = blk == ms.mask_id
             H.check_step_outputs(ms, r, masked, cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0],
                                  "bf16", gpu_logits=logits)
