@@ -891,10 +891,10 @@ hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int lay
   KVView pool = pool_view(c, g, layer), pack = pack_view(c);
   const bool to_pack = g.Q == 0;
   const int32_t* n_cache = (g.Q > 0) ? nullptr : g.n_cache;
-  // eight rows per workgroup; with few rows their channels are spread over up to eight workgroups
+  // eight rows per workgroup; with few rows their channels are spread over up to 32 workgroups
   const int groups8 = (g.T + 7) / 8;
-  int slices8 = groups8 >= 1024 ? 1 : (1024 + groups8 - 1) / groups8;
-  if (slices8 > 8) slices8 = 8;
+  int slices8 = groups8 >= 2048 ? 1 : (2048 + groups8 - 1) / groups8;
+  if (slices8 > 32) slices8 = 32;
   if (IS_BF16(c) && f.head_dim % 8 == 0 && f.page_tokens % 8 == 0)
     k_rope_kv8<<<dim3(groups8, slices8), 256, 0, s>>>(g.T, f.n_q_heads, f.n_kv_heads, f.head_dim, WS(c, q32, float), WS(c, k32, float),
                                             WS(c, q, bf16_t), WS(c, v, bf16_t), WS(c, rope_cos, float),
