@@ -216,8 +216,16 @@ def large_batch(args, torch, np, synth, Engine, dev):
     roofline = None
     if dom:
         a = kern[dom]["TFLOPs"]
+        traffic = None
+        # HBM bytes per launch of this kernel from the committed rocprofv3 --pmc summary (measured offline with the
+        # commands that file lists, not in this run)
+        pmc = os.path.join(ROOT, "profiles", "denoise_step_c5_hbm_traffic_pmc.txt")
+        if args.layers is None and os.path.exists(pmc):
+            for line in open(pmc):
+                if line.startswith(f"traffic_bytes_per_launch k_gemm_t256({dom}):"):
+                    traffic = float(line.split(":")[1])
         roofline = {"bound": "mfma", "kernel": f"k_gemm_t256 ({dom})", "achieved": a, "peak": MFMA_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": a / MFMA_PEAK_TFLOPS, "traffic": None, "avg_us": kern[dom]["avg_us"]}
+                    "unit": "TFLOP/s", "frac": a / MFMA_PEAK_TFLOPS, "traffic": traffic, "avg_us": kern[dom]["avg_us"]}
     out = {"metric": "denoise_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
