@@ -342,6 +342,17 @@ __global__ __launch_bounds__(512) void k_attn_combine(const float* part_o, const
   // eight units at a time: their loads are independent and issued together, the running
   // (max, numerator, denominator) is rescaled between chunks
   float M = -DEV_INF, num = 0.f, den = 0.f;
+  if (n_units == 2) {                                   // the common case at large batch: no padded chunk of eight
+    const int64_t slot = row * 2;
+    const float4 ml = *(const float4*)(part_ml + slot * 2);            // (m0, l0, m1, l1)
+    const float o0 = part_o[slot * DH + d], o1 = part_o[(slot + 1) * DH + d];
+    const float Mn = fmaxf(ml.x, ml.z);
+    if (Mn > -DEV_INF) {
+      const float s0 = exp2f(ml.x - Mn), s1 = exp2f(ml.z - Mn);
+      den = fmaf(ml.w, s1, ml.y * s0);
+      num = fmaf(o1, s1, o0 * s0);
+    }
+  } else
   for (int u0 = 0; u0 < n_units; u0 += 8) {
     float mu[8], lu[8], ou[8];
 #pragma unroll
