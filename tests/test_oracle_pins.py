@@ -412,6 +412,45 @@ def test_decode_invariants(tau, m):
         assert steps == 16                       # one token per forward: the teacher-trajectory mode
 
 
+def test_denoise_step_applies_the_floor_to_each_block_of_the_window():
+    """A window of two blocks with different masked counts (Section 3.2: at least one position per forward is a
+    rule of a block, not of the window).  The expected sets are written by hand from the confidences of the one
+    joint forward: with a threshold that cannot fire every block gives up its min(m, #masked) most confident
+    masked positions, so a floor taken over the window as a whole, a floor applied to the first block only, or
+    block offsets that are not added to the chosen indices each give a different set."""
+    model = small_model()
+    ms = model.ms
+    prompt = synth.random_tokens(ms, 4, 6)
+    ck, cv = O.prefill(model, prompt)
+    bl = 8
+    win = synth.random_tokens(ms, 5, 2 * bl)
+    masked_a, masked_b = [1, 6], [0, 2, 3, 4, 5, 7]            # block 0: 2 masked, block 1: 6 masked
+    for i in masked_a:
+        win[i] = ms.mask_id
+    for i in masked_b:
+        win[bl + i] = ms.mask_id
+    logits, _ = O.forward_cached(model, win, ck, cv)
+    _, conf, ent, _ = O.confidence(logits, ms.mask_id)
+    for m in (1, 3):
+        want = sorted(masked_a, key=lambda i: (-conf[i], i))[:min(m, 2)] + \
+            [bl + i for i in sorted(masked_b, key=lambda i: (-conf[bl + i], i))[:min(m, 6)]]
+        r = O.denoise_step(model, win, ck, cv, tau=2.0, m=m, block_len=bl)
+        assert r["chosen"] == sorted(want) and len(want) == min(m, 2) + min(m, 6)
+        changed = np.nonzero(r["tokens"] != win)[0].tolist()
+        assert changed == sorted(want) and (r["tokens"][changed] == r["cand"][changed]).all()
+        # one block over the whole window: the floor is taken once
+        whole = O.denoise_step(model, win, ck, cv, tau=2.0, m=m)
+        assert len(whole["chosen"]) == m
+        # entropy rule, same split: lowest entropy first, per block
+        want_e = sorted(masked_a, key=lambda i: (ent[i], i))[:min(m, 2)] + \
+            [bl + i for i in sorted(masked_b, key=lambda i: (ent[bl + i], i))[:min(m, 6)]]
+        re_ = O.denoise_step(model, win, ck, cv, tau=-1.0, m=m, block_len=bl, rule="entropy")
+        assert re_["chosen"] == sorted(want_e)
+    # a threshold that every row passes empties both blocks at once, whatever the floor
+    r = O.denoise_step(model, win, ck, cv, tau=0.0, m=1, block_len=bl)
+    assert r["chosen"] == sorted(masked_a + [bl + i for i in masked_b])
+
+
 def test_threshold_branch_fires_on_tiny_config():
     # recorded expectation: with the x8 head some rows of the tiny model do cross 0.2
     w = synth.Weights(TINY, 0)
