@@ -28,26 +28,6 @@ HBM_PEAK_GBS = 8000.0
 KCLASS = {0: "qkv", 1: "wo", 2: "gate_up", 3: "down", 4: "lm_head", 5: "attention"}
 
 
-def device_weights(ms, torch, device, seed):
-    """Random-init weights of the architecture, drawn on the device (never aliased between layers)."""
-    gen = torch.Generator(device=device)
-    gen.manual_seed(seed)
-    dt = torch.bfloat16 if ms.dtype == "bf16" else torch.float32
-
-    def mat(rows, cols, std=0.02):
-        return (torch.randn(rows, cols, generator=gen, device=device, dtype=torch.float32) * std).to(dt)
-
-    d, dq, dkv, F = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff
-    ones = lambda: torch.ones(d, device=device, dtype=dt)
-    g = {"tok_emb": mat(ms.vocab, d), "lm_head": mat(ms.vocab, d, 0.02 * ms.lm_head_scale), "final_norm": ones()}
-    layers = []
-    for _ in range(ms.n_layers):
-        layers.append({"attn_norm": ones(), "wq": mat(dq, d), "wk": mat(dkv, d), "wv": mat(dkv, d),
-                       "wo": mat(d, dq), "mlp_norm": ones(), "w_gate": mat(F, d), "w_up": mat(F, d),
-                       "w_down": mat(d, F)})
-    return g, layers
-
-
 def cpu_baseline(ms, P, Q, n_masked, budget_s=24.0):
     """The CPU oracle as it stands, timed on the host: denoise steps (one layer + LM head at full
     shape, then extrapolated to the model's depth) on the same workload shape."""
@@ -161,7 +141,7 @@ def large_batch(args, torch, np, synth, Engine, dev):
     Bn, P, Q, pt = 32, 8192, 32, 64
     mp = (P + Q + pt - 1) // pt
     eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
-                 max_tokens=0, device_weights=device_weights(ms, torch, dev, 5), pack=False)
+                 max_tokens=0, device_weights=synth.device_weights(ms, torch, dev, 5), pack=False)
     gen = torch.Generator(device=dev)
     gen.manual_seed(7)
     pool = eng.kv_pool.view(torch.bfloat16)
@@ -248,7 +228,7 @@ def prefill_batch(args, torch, np, synth, Engine, dev):
     Bn, S, Q, bl, pt = 16, 2048, 64, 32, 64
     mp = (S + Q + pt - 1) // pt
     eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
-                 max_tokens=Bn * S, device_weights=device_weights(ms, torch, dev, 4), pack=False)
+                 max_tokens=Bn * S, device_weights=synth.device_weights(ms, torch, dev, 4), pack=False)
     table = eng.i32(np.arange(Bn * mp).reshape(Bn, mp))
     toks = eng.i32(np.concatenate([synth.random_tokens(ms, 40 + b, S) for b in range(Bn)]))
     cu = eng.i32(np.arange(Bn + 1) * S)
@@ -364,7 +344,7 @@ def main():
     max_len = P + n_blocks * Q
     mp = (max_len + pt - 1) // pt
     eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=mp, max_batch=1, max_q=4 * Q,
-                 max_tokens=max_len, device_weights=device_weights(ms, torch, dev, 1))
+                 max_tokens=max_len, device_weights=synth.device_weights(ms, torch, dev, 1))
     table = eng.i32(np.arange(mp)[None])
     prompt = eng.i32(synth.random_tokens(ms, 3, P))
     cu = eng.i32([0, P])

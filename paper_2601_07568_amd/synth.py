@@ -193,3 +193,23 @@ def random_kv(ms: ModelShape, seed: int, layer: int, seq: int, n_tokens: int) ->
         a = np.random.Generator(np.random.Philox(key=key)).standard_normal(shape, dtype=np.float32)
         out.append(_to_store(a, ms.dtype))
     return out[0], out[1]
+
+
+def device_weights(ms, torch, device, seed):
+    """Random-init weights of the architecture, drawn on the device (never aliased between layers)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    dt = torch.bfloat16 if ms.dtype == "bf16" else torch.float32
+
+    def mat(rows, cols, std=0.02):
+        return (torch.randn(rows, cols, generator=gen, device=device, dtype=torch.float32) * std).to(dt)
+
+    d, dq, dkv, F = ms.d_model, ms.n_q_heads * ms.head_dim, ms.n_kv_heads * ms.head_dim, ms.d_ff
+    ones = lambda: torch.ones(d, device=device, dtype=dt)
+    g = {"tok_emb": mat(ms.vocab, d), "lm_head": mat(ms.vocab, d, 0.02 * ms.lm_head_scale), "final_norm": ones()}
+    layers = []
+    for _ in range(ms.n_layers):
+        layers.append({"attn_norm": ones(), "wq": mat(dq, d), "wk": mat(dkv, d), "wv": mat(dkv, d),
+                       "wo": mat(d, dq), "mlp_norm": ones(), "w_gate": mat(F, d), "w_up": mat(F, d),
+                       "w_down": mat(d, F)})
+    return g, layers
