@@ -147,6 +147,23 @@ int dllm_denoise_step(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_
                       const int32_t *block_table, int32_t *cand_token, float *conf,
                       float *entropy);
 
+/* dllm_denoise_step for callers that cannot allocate device memory or bring a workspace of their own
+ * into the call: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and same results as dllm_denoise_step, but every intermediate of the
+ * step lives in a device array inside the library (DLLM_STATIC_SCRATCH_BYTES = 64 MiB, held by every GPU
+ * the library runs on until the process ends) instead of the context's workspace; the call allocates
+ * nothing and frees nothing.  The context must be one whose dllm_workspace_bytes fits the array
+ * (a batch-1 step of 32 rows at the 8B shape needs 54 MiB), otherwise DLLM_ENOSPACE is returned and
+ * nothing is enqueued.  Status bits raised by the step are merged into the context's status word.
+ * All calls on one GPU share the one array, whatever their context: calls that overlap in time on
+ * a GPU race.  The array keeps the last call's contents; the call clears what it needs cleared. */
+#define DLLM_STATIC_SCRATCH_BYTES (64u << 20)
+size_t dllm_static_scratch_bytes(void);
+int dllm_denoise_step_static(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len,
+                             const int32_t *q_tokens, const int32_t *prefix_len,
+                             const int32_t *block_table, int32_t *cand_token, float *conf,
+                             float *entropy);
+
 /* Threshold-based parallel unmasking with a floor (Section 3.2: tokens that pass the threshold
  * are decoded, and at least a minimum number per forward regardless of the threshold; with
  * threshold > 1 and min_unmask = 1 this is the one-token-per-step rule of Section 3.1).

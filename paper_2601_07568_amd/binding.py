@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         "dllm_pack_weights": (i32, [vp, vp, vp, sz]),
         "dllm_prefill_kv": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_denoise_step": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "dllm_denoise_step_static": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]),
+        "dllm_static_scratch_bytes": (sz, []),
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_denoise_step_var": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
@@ -200,6 +202,12 @@ class Engine:
         self._check(lib().dllm_denoise_step(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
                                             _ptr(prefix_len), _ptr(block_table), _ptr(cand), _ptr(conf),
                                             _ptr(entropy)))
+
+    def denoise_step_static(self, q_tokens, prefix_len, block_table, cand, conf, entropy=None, *, max_prefix_len):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_denoise_step_static(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                                   _ptr(prefix_len), _ptr(block_table), _ptr(cand), _ptr(conf),
+                                                   _ptr(entropy)))
 
     def unmask(self, q_tokens, cand, conf, threshold, min_unmask, block_len=None, n_unmasked=None,
                n_remaining=None):

@@ -442,6 +442,63 @@ extern "C" int dllm_denoise_step_var(dllm_ctx* c, void* stream, int B, int Q, in
   return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, &h, nullptr, nullptr);
 }
 
+// ---- the denoise step for callers that cannot allocate ---------------------------------------------
+// The intermediates of the step (everything the workspace of dllm_create holds) live in a file-scope
+// device array instead.  Each GPU has its own copy of the array at its own address; the address is looked
+// up once per device, with that device current, and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[DLLM_STATIC_SCRATCH_BYTES];
+static constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];   // per device, nullptr until looked up
+
+__global__ void k_or_status(int32_t* dst, const int32_t* src) {
+  const int32_t v = src[0];
+  if (v != 0) atomicOr(dst, v);
+}
+
+static int static_scratch(dllm_ctx* c, char** out) {
+  int dev = -1;
+  TRY(hipGetDevice(&dev), "hipGetDevice");
+  if (dev < 0 || dev >= MAX_DEVICES) return DLLM_ESHAPE;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (!p || ((uintptr_t)p & 255) != 0) return DLLM_EINVAL;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return DLLM_OK;
+}
+
+extern "C" size_t dllm_static_scratch_bytes(void) { return (size_t)DLLM_STATIC_SCRATCH_BYTES; }
+
+extern "C" int dllm_denoise_step_static(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                        const int32_t* q_tokens, const int32_t* prefix_len,
+                                        const int32_t* block_table, int32_t* cand_token, float* conf,
+                                        float* entropy) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  if (rc != DLLM_OK) return rc;
+  if (!cand_token || !conf) return DLLM_EINVAL;
+  if (c->map.total > (size_t)DLLM_STATIC_SCRATCH_BYTES) return DLLM_ENOSPACE;
+  char* sp = nullptr;
+  rc = static_scratch(c, &sp);
+  if (rc != DLLM_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* const own = c->ws;
+  int32_t* const own_status = WSP(c, status, int32_t);
+  // the array keeps the previous call's contents: the status words are the only part a step reads before writing
+  // (a fill kernel, not a memset node, so that the call can be captured into a graph)
+  TRY(launch_set_i32(s, (int32_t*)(sp + c->map.status), 16, 0), "clear scratch status");
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  HeadOut h{cand_token, conf, entropy};
+  c->ws = sp;
+  rc = run_forward(c, s, g, c->cfg.n_layers, &h, nullptr, nullptr);
+  c->ws = own;
+  if (rc != DLLM_OK) return rc;
+  k_or_status<<<1, 1, 0, s>>>(own_status, (const int32_t*)(sp + c->map.status));
+  TRY(hipGetLastError(), "merge status");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_debug_logits(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
                                  const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* block_table,
                                  float* logits) {

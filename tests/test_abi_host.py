@@ -89,6 +89,15 @@ def test_calls_validate_before_launching():
     assert L.dllm_denoise_step(ctx, None, 1, 32, 64, p, p, p, None, p, None) == E
     assert L.dllm_denoise_step(None, None, 1, 32, 64, p, p, p, p, p, None) == E
     assert L.dllm_debug_logits(ctx, None, 1, 32, 64, p, p, p, None) == E
+    # the step that allocates nothing: same argument rules, and the context must fit the library's array
+    assert L.dllm_denoise_step_static(ctx, None, 0, 32, 64, p, p, p, p, p, None) == E
+    assert L.dllm_denoise_step_static(ctx, None, 1, 33, 64, p, p, p, p, p, None) == S
+    assert L.dllm_denoise_step_static(ctx, None, 1, 32, 64, p, p, p, p, None, None) == E
+    assert L.dllm_denoise_step_static(None, None, 1, 32, 64, p, p, p, p, p, None) == E
+    rc_big, big, keep_big, ws_big, _ = fake_ctx(cfg_for(synth.TINY, max_tokens=16384))
+    assert rc_big == B.DLLM_OK and ws_big > L.dllm_static_scratch_bytes()
+    assert L.dllm_denoise_step_static(big, None, 1, 32, 64, p, p, p, p, p, None) == B.DLLM_ENOSPACE
+    L.dllm_destroy(big)
     assert L.dllm_debug_hidden(ctx, None, 1, 32, 64, p, p, p, 3, p) == E                # only 2 layers
     # prefill / refresh
     assert L.dllm_prefill_kv(ctx, None, 1, 129, 129, p, p, None, p) == S                # > max_tokens
