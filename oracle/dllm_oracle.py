@@ -37,9 +37,11 @@ Storage precision.  All arithmetic is float64.  A model whose activations are ha
 to kernel in a narrower type decides its arg max and its unmask set on values that went through
 that type, so those decisions have to be taken in the same precision here: every forward takes
 an optional `store` function (e.g. round-to-bfloat16) that is applied exactly where the data
-layout of the library stores an activation -- the normalised GEMM input, q and k after the
-rotary embedding, v, the attention output, and silu(gate)*up -- and nowhere else (the residual
-stream, scores, probabilities and logits are never rounded).  store=None is the exact definition.
+layout of the library stores an activation -- the GEMM input of a normalised layer (x * gain is
+what is stored; the row's factor rsqrt(mean(x^2) + eps) is a scalar that stays in full precision
+and multiplies the product), q and k after the rotary embedding, v, the attention output, and
+silu(gate)*up -- and nowhere else (the residual stream, scores, probabilities and logits are never
+rounded).  store=None is the exact definition.
 """
 from __future__ import annotations
 
@@ -100,10 +102,19 @@ def _st(a, store):
     return a if store is None else np.asarray(store(a), dtype=np.float64)
 
 
+def norm_input(x, gain, eps, store=None):
+    """RMSNorm as the input of a linear layer.  Exactly rmsnorm(x, gain, eps); with a storage function the stored
+    activation is x * gain and the row factor is applied in full precision (it commutes with the linear layer)."""
+    if store is None:
+        return rmsnorm(x, gain, eps)
+    x = np.asarray(x, dtype=np.float64)
+    return _st(x * gain, store) / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+
+
 def layer_qkv(ms, lw, x, pos, widen=None, store=None):
     """Normalised input -> rotated q, rotated k, v for the rows of x at absolute positions pos."""
     S = x.shape[0]
-    h = _st(rmsnorm(x, _f64(lw["attn_norm"], widen), ms.rms_eps), store)
+    h = norm_input(x, _f64(lw["attn_norm"], widen), ms.rms_eps, store)
     q = (h @ _f64(lw["wq"], widen).T).reshape(S, ms.n_q_heads, ms.head_dim)
     k = (h @ _f64(lw["wk"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
     v = (h @ _f64(lw["wv"], widen).T).reshape(S, ms.n_kv_heads, ms.head_dim)
@@ -114,7 +125,7 @@ def layer_finish(ms, lw, x, o, widen=None, store=None):
     """Output projection + residual, then SwiGLU MLP + residual."""
     S = x.shape[0]
     x = x + _st(o, store).reshape(S, -1) @ _f64(lw["wo"], widen).T
-    h = _st(rmsnorm(x, _f64(lw["mlp_norm"], widen), ms.rms_eps), store)
+    h = norm_input(x, _f64(lw["mlp_norm"], widen), ms.rms_eps, store)
     g = h @ _f64(lw["w_gate"], widen).T
     u = h @ _f64(lw["w_up"], widen).T
     return x + _st(silu(g) * u, store) @ _f64(lw["w_down"], widen).T
@@ -123,7 +134,7 @@ def layer_finish(ms, lw, x, o, widen=None, store=None):
 def head_logits(model, x, widen=None, store=None):
     """Final norm and LM head: raw logits [rows, vocab] (row i predicts position i, no shift)."""
     ms = model.ms
-    h = _st(rmsnorm(x, _f64(model["final_norm"], widen), ms.rms_eps), store)
+    h = norm_input(x, _f64(model["final_norm"], widen), ms.rms_eps, store)
     return h @ _f64(model["lm_head"], widen).T
 
 

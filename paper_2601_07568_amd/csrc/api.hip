@@ -69,12 +69,14 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   if (m->attn_rows < 65536) m->attn_rows = 65536;
   m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
   if (c->dtype != DLLM_BF16) m->attn_rows = 0;
+  m->rscale = take(t_max * 4);
+  m->ss = take((size_t)64 * ((((size_t)c->d_model + 15) / 16 + 3) / 4 * 4) * 4);
   m->delta_stride = (int64_t)SK_MAX_ROWS * c->d_model;
   m->lg_delta_rows = c->dtype == DLLM_BF16 ? (int64_t)(t_max < (size_t)LG_DELTA_ROWS ? t_max : (size_t)LG_DELTA_ROWS) : 0;
   m->lg_delta_stride = m->lg_delta_rows * c->d_model;
   {
-    size_t sk_floats = (size_t)SK_MAX_DELTA * m->delta_stride, lg_floats = (size_t)LG_MAX_DELTA * m->lg_delta_stride;
-    m->delta = take(c->dtype == DLLM_BF16 ? (sk_floats > lg_floats ? sk_floats : lg_floats) * 4 : 0);
+    size_t lg_floats = (size_t)LG_MAX_DELTA * m->lg_delta_stride;
+    m->delta = take(c->dtype == DLLM_BF16 ? lg_floats * 4 : 0);
   }
   m->qkvp_stride = m->lg_delta_rows * (int64_t)(dq + 2 * dkv);
   m->qkvp_rows = (int64_t)LG_QKV_SPLITS * m->lg_delta_rows > (int64_t)t_max ? (int64_t)LG_QKV_SPLITS * m->lg_delta_rows : (int64_t)t_max;
@@ -277,11 +279,13 @@ struct ProfScope {
 };
 
 // plain GEMM of the non-skinny path: matrix cores for bfloat16 (any M), scalar FMA otherwise
+// norm_in: A is the output of an RMSNorm (bfloat16 models: x * gain, with the row factors in ws.rscale)
 static hipError_t gemm_any(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K,
-                           Epi epi) {
+                           Epi epi, bool norm_in = false) {
+  const float* rs = (norm_in && c->cfg.dtype == DLLM_BF16) ? (const float*)(c->ws + c->map.rscale) : nullptr;
   if (c->cfg.dtype == DLLM_BF16 && c->kernel_mode == 0 && N % 4 == 0 && K % 8 == 0)
-    return launch_gemm_mfma(s, A, W, C, M, N, K, epi);
-  return launch_gemm_generic(c, s, A, W, C, M, N, K, epi);
+    return launch_gemm_mfma(s, A, W, C, M, N, K, epi, rs);
+  return launch_gemm_generic(c, s, A, W, C, M, N, K, epi, rs);
 }
 
 struct HeadOut {
@@ -298,20 +302,26 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
   const int T = g.T;
   const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
   TRY(launch_token_map(c, s, g), "token_map");
-  TRY(launch_embed(c, s, g), "embed");
-  TRY(launch_rope_table(c, s, g), "rope_table");
   // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
-  // (their activation operands are kept in fragment order, which only these kernels write)
+  // (their activation operands are kept in fragment order, which only these kernels write).  On this path no
+  // RMSNorm is launched: the producer of the residual stream (embedding, output projection, down projection)
+  // leaves x * gain of the next norm in fragment order plus partial sums of squares per row, and the consuming
+  // GEMM applies the row's normalisation factor to its float accumulators.
   const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS && attn_step_supported(c, g);
   const bool big_mfma = f.dtype == DLLM_BF16 && c->kernel_mode == 0 && f.d_ff % 4 == 0 && f.vocab % 4 == 0;
+  const int ss_groups = (f.d_model + 15) / 16;
+  int n_ss = 1;      // partial sums of squares the current skinny-path GEMM input comes with
+  if (sk) TRY(launch_sk_embed(c, s, g, n_layers_run > 0 ? c->layers[0].attn_norm : c->final_norm), "embed");
+  else TRY(launch_embed(c, s, g), "embed");
+  TRY(launch_rope_table(c, s, g), "rope_table");
   int pending = 0;   // open residual sums (K splits of the last residual projection) not yet added to x
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
-    TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
+    if (!sk) TRY(launch_rmsnorm(c, s, L.attn_norm, T, nullptr, nullptr, 0, pending), "rmsnorm");
     pending = 0;
     if (sk) {
       ProfScope p(c, s, 0, 2.0 * (dq + 2.0 * dkv) * f.d_model);
-      TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l)), "qkv");
+      TRY(launch_sk_qkv(c, s, g, l, attention_view(c, g, l), n_ss), "qkv");
     } else {
       ProfScope p(c, s, 0, 2.0 * T * (dq + 2.0 * dkv) * f.d_model);   // large path: work recorded in flops
       int n_part = 0;
@@ -320,11 +330,11 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
         // q | k | v left as partial sums over K; the rotary kernel adds them
       } else if (big_mfma && f.d_model % 8 == 0 && dq % 4 == 0 && dkv % 4 == 0) {
         TRY(launch_gemm_qkv(s, c->ws + c->map.xn, L.wq, L.wk, L.wv, WSP(c, q32, float), WSP(c, k32, float),
-                            c->ws + c->map.v, T, dq, dkv, f.d_model), "wqkv");
+                            c->ws + c->map.v, T, dq, dkv, f.d_model, WSP(c, rscale, float)), "wqkv");
       } else {
-        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32), "wq");
-        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32), "wk");
-        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE), "wv");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32, true), "wq");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32, true), "wk");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.wv, c->ws + c->map.v, T, dkv, f.d_model, EPI_STORE, true), "wv");
       }
       TRY(launch_rope_kv(c, s, g, l, n_part), "rope_kv");
     }
@@ -335,31 +345,34 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     }
     if (sk) {
       ProfScope p(c, s, 1, 2.0 * dq * f.d_model);
-      TRY(launch_sk_delta(c, s, c->ws + c->map.o, c->packed_layers[l].wo, WSP(c, delta, float), c->map.delta_stride,
-                          SK_MAX_DELTA, T, f.d_model, dq, &pending), "wo");
+      TRY(launch_sk_resid(c, s, c->ws + c->map.o, c->packed_layers[l].wo, T, f.d_model, dq, L.mlp_norm), "wo");
+      n_ss = ss_groups;
     } else {
       ProfScope p(c, s, 1, 2.0 * T * (double)dq * f.d_model);
       if (big_mfma && f.d_model % 4 == 0 && dq % 8 == 0)
         TRY(launch_gemm_resid_split(c, s, c->ws + c->map.o, L.wo, WSP(c, x, float), T, f.d_model, dq, &pending), "wo");
       else TRY(gemm_any(c, s, c->ws + c->map.o, L.wo, c->ws + c->map.x, T, f.d_model, dq, EPI_RESID), "wo");
     }
-    TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "rmsnorm");
+    if (!sk) TRY(launch_rmsnorm(c, s, L.mlp_norm, T, nullptr, nullptr, 0, pending), "rmsnorm");
     pending = 0;
     if (sk) {
       {
         ProfScope p(c, s, 2, 2.0 * 2.0 * f.d_ff * f.d_model);
-        TRY(launch_sk_swiglu(c, s, l, T), "swiglu");
+        TRY(launch_sk_swiglu(c, s, l, T, n_ss), "swiglu");
       }
       ProfScope p(c, s, 3, 2.0 * f.d_ff * f.d_model);
-      TRY(launch_sk_delta(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, WSP(c, delta, float),
-                          c->map.delta_stride, SK_MAX_DELTA, T, f.d_model, f.d_ff, &pending), "w_down");
+      // the down projection prepares the input of whatever reads the residual stream next
+      const void* gain_next = l + 1 < n_layers_run ? c->layers[l + 1].attn_norm : c->final_norm;
+      TRY(launch_sk_resid(c, s, c->ws + c->map.h, c->packed_layers[l].w_down, T, f.d_model, f.d_ff, gain_next),
+          "w_down");
     } else {
       if (big_mfma) {
         ProfScope p(c, s, 2, 2.0 * T * 2.0 * f.d_ff * f.d_model);
-        TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model), "gate_up");
+        TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model,
+                               WSP(c, rscale, float)), "gate_up");
       } else {
-        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_gate");
-        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32), "w_up");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_gate");
+        TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_up");
         TRY(launch_swiglu(c, s, T), "swiglu");
       }
       ProfScope p(c, s, 3, 2.0 * T * (double)f.d_ff * f.d_model);
@@ -370,30 +383,35 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
     }
   }
   if (hidden_out) {
-    if (pending) { TRY(launch_fold_delta(c, s, T, pending, sk), "fold_delta"); pending = 0; }
+    if (pending) { TRY(launch_fold_delta(c, s, T, pending, false), "fold_delta"); pending = 0; }
     TRY(launch_copy_f32(s, WSP(c, x, float), hidden_out, (size_t)T * f.d_model), "copy_hidden");
   }
   if (logits_out) {
-    TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, sk ? (T + 15) / 16 : 0, pending), "final_norm");
-    pending = 0;
-    if (sk) TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->packed_lm_head, logits_out, T, f.vocab, f.d_model), "lm_head");
-    else TRY(gemm_any(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32), "lm_head");
+    if (sk) {
+      TRY(launch_sk_f32(c, s, c->ws + c->map.xn, c->packed_lm_head, logits_out, T, f.vocab, f.d_model, n_ss), "lm_head");
+    } else {
+      TRY(launch_rmsnorm(c, s, c->final_norm, T, nullptr, nullptr, 0, pending), "final_norm");
+      pending = 0;
+      TRY(gemm_any(c, s, c->ws + c->map.xn, c->lm_head, logits_out, T, f.vocab, f.d_model, EPI_STORE_F32, true), "lm_head");
+    }
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
     TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
-    TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1,
-                       sk ? (max_rows + 15) / 16 : 0, pending), "final_norm");
-    pending = 0;
+    if (!sk) {
+      TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1, 0, pending),
+          "final_norm");
+      pending = 0;
+    }
     int n_parts = c->map.n_vtiles;
     if (sk) {
       ProfScope p(c, s, 4, 2.0 * f.vocab * f.d_model);
-      TRY(launch_sk_lmstats(c, s, max_rows, &n_parts), "lm_head");
+      TRY(launch_sk_lmstats(c, s, T, n_ss, &n_parts), "lm_head");
     } else if (big_mfma) {
       ProfScope p(c, s, 4, 2.0 * max_rows * (double)f.vocab * f.d_model);   // upper bound: max_rows rows
       TRY(launch_gemm_lmstats(c, s, max_rows, &n_parts), "lm_head");
     } else TRY(launch_lm_head_generic(c, s, max_rows), "lm_head");
-    TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy), "lm_merge");
+    TRY(launch_lm_merge(c, s, max_rows, n_parts, head->cand, head->conf, head->entropy, sk), "lm_merge");
   }
   return DLLM_OK;
 }

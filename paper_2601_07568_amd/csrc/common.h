@@ -145,7 +145,9 @@ struct Workspace {
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
   size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
   int64_t attn_rows;   // capacity in (token, head, unit) rows
-  size_t delta;        // float open residual sums: [SK_MAX_DELTA][64, d] (skinny path) or [LG_MAX_DELTA][lg_delta_rows, d]
+  size_t rscale;       // float [Tmax]                  row normalisation factors of the current GEMM input (bfloat16 models)
+  size_t ss;           // float [64][d/16 rounded up to 4]   partial sums of squares of the rows of the skinny path's GEMM input
+  size_t delta;        // float open residual sums of K-split residual projections: [LG_MAX_DELTA][lg_delta_rows, d]
   int64_t delta_stride;
   int64_t lg_delta_rows, lg_delta_stride;   // large path: rows the buffer covers (0 = none), floats per split
   size_t qkvp;         // float [LG_QKV_SPLITS][lg_delta_rows, dq + 2 dkv]: K-split partial sums of the fused q/k/v product
@@ -215,21 +217,22 @@ hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta, boo
 constexpr int LG_QKV_SPLITS = 3;       // large path: most K splits of the fused q/k/v product
 constexpr int LG_MAX_DELTA = 3;        // large path: a residual projection is split over K at most 4 ways
 constexpr int LG_DELTA_ROWS = 2048;    // ... and only when the token count leaves the chip underfilled
-constexpr int SK_MAX_DELTA = 8;   // most K splits of a residual projection
-hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* delta,
-                           int64_t delta_stride, int max_splits, int M, int N, int K, int* n_splits);
+hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, int M, int N, int K,
+                           const void* gain_next);
+hipError_t launch_sk_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain);
 enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
 // C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,
-                               int M, int N, int K, Epi epi);
+                               int M, int N, int K, Epi epi, const float* rscale = nullptr);
 hipError_t launch_rope_kv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, int n_part = 0);
 hipError_t launch_swiglu(dllm_ctx* c, hipStream_t s, int T);
 hipError_t launch_attention_generic(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer);
 hipError_t launch_mask_rows(dllm_ctx* c, hipStream_t s, const StepGeom& g, int32_t* cand, float* conf,
                             float* entropy);
 hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows);
+// by_token: the partial statistics of compacted row r are stored at row rows[r] (the LM head ran on every row)
 hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts, int32_t* cand, float* conf,
-                           float* entropy);
+                           float* entropy, bool by_token = false);
 hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_tokens,
                          const int32_t* cand, const float* conf, float thr, int min_unmask,
                          int32_t mask_id, int32_t* n_unmasked, int32_t* n_remaining, bool low_first = false, const int32_t* floors = nullptr,
@@ -254,11 +257,15 @@ size_t packed_weight_bytes(int N, int K);
 hipError_t launch_pack_weight(hipStream_t s, const void* W, void* P, int N, int K);
 constexpr int SK_MAX_ROWS = 64;   // the skinny (weight-streaming) kernels take at most this many rows
 KVView attention_view(dllm_ctx* c, const StepGeom& g, int layer);
-hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K);
-hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool);
-hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M);
-hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
-hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi);
+// n_ss: partial sums of squares per row the GEMM input comes with (1 after the embedding, d_model / 64 after a
+// residual projection)
+hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K,
+                         int n_ss);
+hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool, int n_ss);
+hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M, int n_ss);
+hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int T, int n_ss, int* n_parts_out);
+hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi,
+                            const float* rscale = nullptr);
 hipError_t init_attn_kernels();   // once per process (raises a kernel's LDS limit)
 hipError_t init_gemm_t256();   // once per process, before the first large GEMM (raises a kernel's LDS limit)
 hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
@@ -266,9 +273,9 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
 hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
                                  int M, int dq, int dkv, int K, int* n_part);
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
-                           float* k32, void* v, int M, int dq, int dkv, int K);
+                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale);
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K);
+                              int K, const float* rscale);
 hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g);
 hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out);

@@ -33,6 +33,8 @@ struct LgArgs {
   float* delta;            // RESID: products of splits 1.. go to delta[(split - 1) * delta_stride + m * N + n]
   int64_t delta_stride;
   const int32_t* m_dev;    // optional device row count
+  const float* rscale;     // optional [M]: A holds x * gain rounded to bfloat16; the row's normalisation factor
+                           // multiplies the float accumulators (every epilogue but RESID, whose input is not a norm's)
   int M, N, K, tiles_m, tiles_n;
   float* part;             // LMSTATS: [rows, n_parts, 4]
   int n_parts;
@@ -192,12 +194,13 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
     for (int j = 0; j < WT; ++j) {
       const int m = m0 + wm + j * 16 + c;
       if (m >= M) continue;
+      const float rs = a.rscale ? a.rscale[m] : 1.0f;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int n = n0 + (wn >> 1) + i * 16 + 4 * g;
-        f32x4 v = acc[0][i][j];
+        f32x4 v = acc[0][i][j] * rs;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * acc[0][i + 2][j][e];
+        for (int e = 0; e < 4; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * (acc[0][i + 2][j][e] * rs);
         if (n + 4 <= N) {
           *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) =
               make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
@@ -213,6 +216,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
 #pragma unroll
     for (int j = 0; j < WT; ++j) {
       const int m = m0 + wm + j * 16 + c;
+      const float rs = (a.rscale && m < M) ? a.rscale[m] : 1.0f;
       RowStat st;
       st.init();
 #pragma unroll
@@ -220,7 +224,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int n = n0 + wn + i * 16 + 4 * g + e;
-          if (n < N && n != a.mask_id) st.merge(acc[0][i][j][e], n, 1.0f, acc[0][i][j][e]);
+          const float z = acc[0][i][j][e] * rs;
+          if (n < N && n != a.mask_id) st.merge(z, n, 1.0f, z);
         }
 #pragma unroll
       for (int o = 16; o < 64; o <<= 1) {
@@ -239,10 +244,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const LgArgs a) {
   for (int j = 0; j < WT; ++j) {
     const int m = m0 + wm + j * 16 + c;
     if (m >= M) continue;
+    const float rs = (EPI != LG_RESID && a.rscale) ? a.rscale[m] : 1.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int n = n0 + wn + i * 16 + 4 * g;
-      f32x4 v = acc[0][i][j];
+      f32x4 v = acc[0][i][j] * rs;
       if (n + 4 <= N) {
         const int64_t at = (int64_t)m * N + n;
         if (EPI == LG_RESID) {
@@ -425,6 +431,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int m = m0 + wm * 128 + j * 32 + r;
+      const float rs = (a.rscale && m < M) ? a.rscale[m] : 1.0f;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {      // 64 columns per partial
         // the lane's 32 logits of this partial: maximum first (columns ascend, so the first of equal
@@ -437,7 +444,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
           for (int e = 0; e < 16; ++e) {
             const int i = half * 2 + ii;
             const int n = n0 + wn * 128 + i * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-            const float z = acc[i][j][e];
+            const float z = acc[i][j][e] * rs;
             if (n < N && n != a.mask_id && z > mx) { mx = z; ix = n; }
           }
         RowStat st;
@@ -450,7 +457,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
             for (int e = 0; e < 16; ++e) {
               const int i = half * 2 + ii;
               const int n = n0 + wn * 128 + i * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-              const float z = acc[i][j][e];
+              const float z = acc[i][j][e] * rs;
               const float ex = (n < N && n != a.mask_id) ? __builtin_amdgcn_exp2f((z - mx) * 1.4426950408889634f) : 0.f;
               se += ex;
               sz = fmaf(ex, z, sz);
@@ -472,6 +479,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   for (int j = 0; j < 4; ++j) {
     const int m = m0 + wm * 128 + j * 32 + r;
     if (m >= M) continue;
+    const float rs = (EPI != LG_RESID && a.rscale) ? a.rscale[m] : 1.0f;
     if constexpr (EPI == LG_SWIGLU) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -481,8 +489,8 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float gt = acc[i][j][e4 * 4 + e];
-            v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[i + 2][j][e4 * 4 + e];
+            const float gt = acc[i][j][e4 * 4 + e] * rs;
+            v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * (acc[i + 2][j][e4 * 4 + e] * rs);
           }
           if (n + 4 <= N) {
             *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
@@ -499,7 +507,7 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
         for (int e4 = 0; e4 < 4; ++e4) {
           const int n = n0 + wn * 128 + i * 32 + e4 * 8 + h * 4;
           *(f32x4*)(a.delta + (int64_t)split * a.delta_stride + (int64_t)m * nt + n) =
-              f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+              f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]} * rs;
         }
     } else {
 #pragma unroll
@@ -631,6 +639,7 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
   for (int j = 0; j < 2; ++j) {
     const int m = m0 + wm * 64 + j * 32 + r;
     if (m >= M) continue;
+    const float rs = (EPI != LG_RESID && a.rscale) ? a.rscale[m] : 1.0f;
     if constexpr (EPI == LG_SWIGLU) {
 #pragma unroll
       for (int i = 0; i < WT; ++i)
@@ -640,8 +649,8 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float gt = acc[i][j][e4 * 4 + e];
-          v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * acc[i][j][8 + e4 * 4 + e];
+          const float gt = acc[i][j][e4 * 4 + e] * rs;
+          v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * (acc[i][j][8 + e4 * 4 + e] * rs);
         }
         if (n + 4 <= N) {
           *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
@@ -657,7 +666,7 @@ __global__ __launch_bounds__(256) void k_gemm_ts(const LgArgs a) {
       for (int e4 = 0; e4 < 4; ++e4) {
         const int n = n0 + (wn * WT + i) * 32 + e4 * 8 + h * 4;
         *(f32x4*)(a.delta + (int64_t)blockIdx.y * a.delta_stride + (int64_t)m * nt + n) =
-            f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+            f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]} * rs;
       }
     } else {
 #pragma unroll
@@ -753,10 +762,12 @@ static hipError_t lg_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
 }
 
 // C[M,N] (=, +=) A[M,K] W[N,K]^T for bfloat16 operands; N % 4 == 0 and K % 8 == 0
-hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi) {
+hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi,
+                            const float* rscale) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = C; a.M = M; a.N = N; a.K = K;
+  a.rscale = epi == EPI_RESID ? nullptr : rscale;
   if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a);
   if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a);
   a.k_per = (K + LG_BK - 1) / LG_BK * LG_BK;
@@ -810,6 +821,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
     memset(&a, 0, sizeof(a));
     a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
     a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
+    a.rscale = WSM(c, rscale, float);
     const bool wide = dq % 128 == 0 && dkv % 128 == 0 && (dq + 2 * dkv) / 128 >= 64;   // 128 x 128 tiles still fill the chip
     const int tiles = ((M + 127) / 128) * ((dq + 2 * dkv) / (wide ? 128 : 64));
     int splits = 768 / tiles;
@@ -830,6 +842,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
   a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
+  a.rscale = WSM(c, rscale, float);
   const int tiles = ((M + 255) / 256) * ((dq + 2 * dkv) / 256);
   int splits = 256 / tiles;
   if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
@@ -846,9 +859,10 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
 
 // q32[M,dq], k32[M,dkv] (float) and v[M,dkv] (bfloat16) = A[M,K] times the three projections, one launch
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
-                           float* k32, void* v, int M, int dq, int dkv, int K) {
+                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
+  a.rscale = rscale;
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
   a.C = q32; a.C2 = k32; a.C3 = v;
   a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
@@ -857,9 +871,10 @@ hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const v
 
 // h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K) {
+                              int K, const float* rscale) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
+  a.rscale = rscale;
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
   if (ts_usable(M, K)) return ts_launch<LG_SWIGLU, 2>(s, a);
   if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
@@ -873,6 +888,7 @@ hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_
   memset(&a, 0, sizeof(a));
   a.A = WSM(c, xn, bf16_t); a.W = (const bf16_t*)c->lm_head; a.M = max_rows; a.N = f.vocab; a.K = f.d_model;
   a.m_dev = WSM(c, status, int32_t) + 1;
+  a.rscale = WSM(c, rscale, float);
   a.part = WSM(c, lm_part, float);
   a.n_parts = (f.vocab + 63) / 64;
   a.mask_id = f.mask_id;

@@ -93,7 +93,8 @@ __global__ void k_rope_table(int T, int half, double log2_base, const int32_t* t
 
 template <typename T>
 __global__ void k_rmsnorm(int d, float eps, float* x, const T* gain, T* out, const int32_t* rows,
-                          const int32_t* n_rows_dev, int frag_mt, const float* delta, int n_delta, int64_t delta_stride) {
+                          const int32_t* n_rows_dev, int frag_mt, const float* delta, int n_delta, int64_t delta_stride,
+                          float* rscale) {
   __shared__ float red[16];
   int r = blockIdx.x;
   int src = r;
@@ -113,68 +114,15 @@ __global__ void k_rmsnorm(int d, float eps, float* x, const T* gain, T* out, con
   }
   ss = block_sum(ss, red);
   float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+  // rscale: the output is x * gain and the row factor goes to rscale[r] (the consuming GEMM multiplies its
+  // accumulators by it); otherwise the output is the normalised row
+  if (rscale) {
+    if (threadIdx.x == 0) rscale[r] = rinv;
+    rinv = 1.0f;
+  }
   for (int i = threadIdx.x; i < d; i += blockDim.x) {   // a thread re-reads only what it wrote itself
     const int64_t at = frag_mt > 0 ? frag_offset(r, i, frag_mt) : (int64_t)r * d + i;
     Elem<T>::store(out + at, xr[i] * rinv * Elem<T>::load(gain + i));
-  }
-}
-
-// RMSNorm of one row per workgroup into fragment order: each thread owns whole 16-byte units (8
-// consecutive channels), two float4 loads in, one 16-byte store out.  d % 8 == 0.
-// If n_delta > 0 the row first takes up the open residual sums: x += delta_0 + delta_1 + .. (in that
-// order), and the updated row is written back.
-__global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, float* x, const bf16_t* gain,
-                                                      bf16_t* out, const int32_t* rows, const int32_t* n_rows_dev,
-                                                      int frag_mt, const float* delta, int n_delta,
-                                                      int64_t delta_stride) {
-  __shared__ float red[16];
-  const int r = blockIdx.x;
-  int src = r;
-  if (rows) {
-    if (r >= *n_rows_dev) return;
-    src = rows[r];
-  }
-  float4* xr = (float4*)(x + (int64_t)src * d);
-  const int n_units = d >> 3;
-  float4 v[4][2];          // up to 4 units per thread (d <= 16384)
-  float ss = 0.f;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int u = threadIdx.x + q * 512;
-    if (u < n_units) {
-      v[q][0] = xr[2 * u];
-      v[q][1] = xr[2 * u + 1];
-      if (n_delta > 0) {
-        for (int sd = 0; sd < n_delta; ++sd) {
-          const float4* dr = (const float4*)(delta + sd * delta_stride + (int64_t)src * d);
-          const float4 d0 = dr[2 * u], d1 = dr[2 * u + 1];
-          v[q][0].x += d0.x; v[q][0].y += d0.y; v[q][0].z += d0.z; v[q][0].w += d0.w;
-          v[q][1].x += d1.x; v[q][1].y += d1.y; v[q][1].z += d1.z; v[q][1].w += d1.w;
-        }
-        xr[2 * u] = v[q][0];
-        xr[2 * u + 1] = v[q][1];
-      }
-      ss += v[q][0].x * v[q][0].x + v[q][0].y * v[q][0].y + v[q][0].z * v[q][0].z + v[q][0].w * v[q][0].w +
-            v[q][1].x * v[q][1].x + v[q][1].y * v[q][1].y + v[q][1].z * v[q][1].z + v[q][1].w * v[q][1].w;
-    }
-  }
-  ss = block_sum(ss, red);
-  const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int u = threadIdx.x + q * 512;
-    if (u < n_units) {
-      const uint4 gv = *(const uint4*)(gain + 8 * u);
-      const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
-      const float xv[8] = {v[q][0].x, v[q][0].y, v[q][0].z, v[q][0].w, v[q][1].x, v[q][1].y, v[q][1].z, v[q][1].w};
-      uint32_t o[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float g0 = bf16_to_f32((bf16_t)(gw[e] & 0xffffu)), g1 = bf16_to_f32((bf16_t)(gw[e] >> 16));
-        o[e] = (uint32_t)f32_to_bf16(xv[2 * e] * rinv * g0) | ((uint32_t)f32_to_bf16(xv[2 * e + 1] * rinv * g1) << 16);
-      }
-      *(uint4*)(out + frag_offset(r, 8 * u, frag_mt)) = make_uint4(o[0], o[1], o[2], o[3]);
-    }
   }
 }
 
@@ -182,7 +130,7 @@ __global__ __launch_bounds__(512) void k_rmsnorm_frag(int d, float eps, float* x
 // C[M,N] = A[M,K] * W[N,K]^T, 64x64 tile, 16-deep slices through LDS, 4x4 per thread
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void k_gemm(const T* __restrict__ A, const T* __restrict__ W, void* Cv,
-                                              int M, int N, int K) {
+                                              int M, int N, int K, const float* rscale) {
   __shared__ float As[16][68];
   __shared__ float Ws[16][68];
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
@@ -217,13 +165,14 @@ __global__ __launch_bounds__(256) void k_gemm(const T* __restrict__ A, const T* 
   for (int i = 0; i < 4; ++i) {
     int m = m0 + ty * 4 + i;
     if (m >= M) continue;
+    const float rs = (EPI != EPI_RESID && rscale) ? rscale[m] : 1.0f;   // row factor of a normalised input
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int n = n0 + tx * 4 + j;
       if (n >= N) continue;
       int64_t idx = (int64_t)m * N + n;
-      if (EPI == EPI_STORE) Elem<T>::store((T*)Cv + idx, acc[i][j]);
-      else if (EPI == EPI_STORE_F32) ((float*)Cv)[idx] = acc[i][j];
+      if (EPI == EPI_STORE) Elem<T>::store((T*)Cv + idx, acc[i][j] * rs);
+      else if (EPI == EPI_STORE_F32) ((float*)Cv)[idx] = acc[i][j] * rs;
       else ((float*)Cv)[idx] += acc[i][j];
     }
   }
@@ -558,7 +507,7 @@ __global__ __launch_bounds__(1024) void k_mask_rows(int T, int32_t mask_id, int 
 template <typename T>
 __global__ __launch_bounds__(256) void k_lm_head(const T* __restrict__ A, const T* __restrict__ W, int V, int K,
                                                  int32_t mask_id, const int32_t* n_rows_dev, float* part,
-                                                 int n_vtiles) {
+                                                 int n_vtiles, const float* rscale) {
   __shared__ float As[16][68];
   __shared__ float Ws[16][68];
   __shared__ float Cs[64][65];
@@ -604,9 +553,10 @@ __global__ __launch_bounds__(256) void k_lm_head(const T* __restrict__ A, const 
       for (int j = 0; j < 4; ++j) Cs[ty * 4 + i][tx * 4 + j] = acc[i][j];
     __syncthreads();
     if (tid < 64 && m0 + tid < M) {
+      const float rs = rscale ? rscale[m0 + tid] : 1.0f;      // row factor of the normalised input
       for (int j = 0; j < 64; ++j) {
         int col = n0 + j;
-        if (col < V && col != mask_id) st.push(Cs[tid][j], col);
+        if (col < V && col != mask_id) st.push(Cs[tid][j] * rs, col);
       }
     }
     __syncthreads();
@@ -623,14 +573,14 @@ __global__ __launch_bounds__(256) void k_lm_head(const T* __restrict__ A, const 
 // one wavefront per compacted row: merge the per-tile statistics and emit the outputs
 __global__ __launch_bounds__(256) void k_lm_merge(const float* part, int n_vtiles, const int32_t* rows,
                                                   const int32_t* n_rows_dev, int32_t* cand, float* conf,
-                                                  float* entropy) {
+                                                  float* entropy, int by_token) {
   // 256 threads per row; a thread's partials are fetched eight at a time before they are merged, so the
   // loads of a batch are in flight together; lanes, then waves, merge in a fixed order
   __shared__ float4 wst[4];
   const int r = blockIdx.x;
   if (r >= *n_rows_dev) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float4* prow = (const float4*)part + (int64_t)r * n_vtiles;
+  const float4* prow = (const float4*)part + (int64_t)(by_token ? rows[r] : r) * n_vtiles;
   RowStat st;
   st.init();
   for (int v0 = tid; v0 < n_vtiles; v0 += 256 * 8) {
@@ -759,11 +709,10 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
   return hipGetLastError();
 }
 
-// x[T, d] += delta_0 + delta_1 + ..  (open residual sums; used where no RMSNorm follows)
 // row-major bfloat16 output, four elements per thread and pass (d % 4 == 0)
 __global__ __launch_bounds__(256) void k_rmsnorm_row4(int d, float eps, float* x, const bf16_t* gain, bf16_t* out,
                                                       const int32_t* rows, const int32_t* n_rows_dev, const float* delta,
-                                                      int n_delta, int64_t delta_stride) {
+                                                      int n_delta, int64_t delta_stride, float* rscale) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   int src = r;
@@ -786,15 +735,16 @@ __global__ __launch_bounds__(256) void k_rmsnorm_row4(int d, float eps, float* x
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   ss = block_sum(ss, red);
-  const float rinv = 1.0f / sqrtf(ss / (float)d + eps);
+  // the output is x * gain; the row factor goes to rscale[r] and multiplies the consuming GEMM's accumulators
+  if (threadIdx.x == 0) rscale[r] = 1.0f / sqrtf(ss / (float)d + eps);
   uint2* orow = (uint2*)(out + (int64_t)r * d);
   for (int i = threadIdx.x; i < n4; i += 256) {   // a thread re-reads only what it wrote itself
     const float4 v = xr[i];
     const uint2 gq = ((const uint2*)gain)[i];
     const float g0 = bf16_to_f32((bf16_t)(gq.x & 0xffff)), g1 = bf16_to_f32((bf16_t)(gq.x >> 16));
     const float g2 = bf16_to_f32((bf16_t)(gq.y & 0xffff)), g3 = bf16_to_f32((bf16_t)(gq.y >> 16));
-    orow[i] = make_uint2((uint32_t)f32_to_bf16(v.x * rinv * g0) | ((uint32_t)f32_to_bf16(v.y * rinv * g1) << 16),
-                         (uint32_t)f32_to_bf16(v.z * rinv * g2) | ((uint32_t)f32_to_bf16(v.w * rinv * g3) << 16));
+    orow[i] = make_uint2((uint32_t)f32_to_bf16(v.x * g0) | ((uint32_t)f32_to_bf16(v.y * g1) << 16),
+                         (uint32_t)f32_to_bf16(v.z * g2) | ((uint32_t)f32_to_bf16(v.w * g3) << 16));
   }
 }
 
@@ -813,37 +763,38 @@ hipError_t launch_fold_delta(dllm_ctx* c, hipStream_t s, int T, int n_delta, boo
   return hipGetLastError();
 }
 
+// Row-major RMSNorm of the paths that launch one (large batches, no-cache forwards, float models).  bfloat16 models:
+// the output is x * gain rounded to bfloat16 and the row factors go to ws.rscale (the consuming GEMMs multiply their
+// float accumulators by them); float models: the output is the normalised row.
 hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, const int32_t* rows,
                           const int32_t* n_rows_dev, int frag_mt, int n_delta) {
   const dllm_config& f = c->cfg;
-  if (IS_BF16(c) && frag_mt > 0 && f.d_model <= 16384)
-    k_rmsnorm_frag<<<T, 512, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t),
-                                     rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta, c->map.delta_stride);
-  else if (IS_BF16(c) && frag_mt == 0 && f.d_model % 4 == 0)
+  if (IS_BF16(c) && f.d_model % 4 == 0)
     k_rmsnorm_row4<<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t), rows,
-                                     n_rows_dev, WS(c, delta, float), n_delta, c->map.lg_delta_stride);
+                                     n_rows_dev, WS(c, delta, float), n_delta, c->map.lg_delta_stride, WS(c, rscale, float));
   else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
-                                        WS(c, xn, bf16_t), rows, n_rows_dev, frag_mt, WS(c, delta, float), n_delta,
-                                        frag_mt > 0 ? c->map.delta_stride : c->map.lg_delta_stride);
+                                        WS(c, xn, bf16_t), rows, n_rows_dev, 0, WS(c, delta, float), n_delta,
+                                        c->map.lg_delta_stride, WS(c, rscale, float));
   else
     k_rmsnorm<float><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const float*)gain,
-                                       WS(c, xn, float), rows, n_rows_dev, 0, nullptr, 0, 0);
+                                       WS(c, xn, float), rows, n_rows_dev, 0, nullptr, 0, 0, nullptr);
   return hipGetLastError();
 }
 
 template <typename T>
-static void gemm_dispatch(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi) {
+static void gemm_dispatch(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi,
+                          const float* rscale) {
   dim3 grid((N + 63) / 64, (M + 63) / 64);
-  if (epi == EPI_STORE) k_gemm<T, EPI_STORE><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
-  else if (epi == EPI_STORE_F32) k_gemm<T, EPI_STORE_F32><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
-  else k_gemm<T, EPI_RESID><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K);
+  if (epi == EPI_STORE) k_gemm<T, EPI_STORE><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K, rscale);
+  else if (epi == EPI_STORE_F32) k_gemm<T, EPI_STORE_F32><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K, rscale);
+  else k_gemm<T, EPI_RESID><<<grid, 256, 0, s>>>((const T*)A, (const T*)W, C, M, N, K, nullptr);
 }
 
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C, int M, int N,
-                               int K, Epi epi) {
-  if (IS_BF16(c)) gemm_dispatch<bf16_t>(s, A, W, C, M, N, K, epi);
-  else gemm_dispatch<float>(s, A, W, C, M, N, K, epi);
+                               int K, Epi epi, const float* rscale) {
+  if (IS_BF16(c)) gemm_dispatch<bf16_t>(s, A, W, C, M, N, K, epi, rscale);
+  else gemm_dispatch<float>(s, A, W, C, M, N, K, epi, nullptr);
   return hipGetLastError();
 }
 
@@ -956,17 +907,18 @@ hipError_t launch_lm_head_generic(dllm_ctx* c, hipStream_t s, int max_rows) {
   const int32_t* n_rows = WS(c, status, int32_t) + 1;
   if (IS_BF16(c))
     k_lm_head<bf16_t><<<grid, 256, 0, s>>>(WS(c, xn, bf16_t), (const bf16_t*)c->lm_head, f.vocab, f.d_model,
-                                           f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles);
+                                           f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles,
+                                           WS(c, rscale, float));
   else
     k_lm_head<float><<<grid, 256, 0, s>>>(WS(c, xn, float), (const float*)c->lm_head, f.vocab, f.d_model,
-                                          f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles);
+                                          f.mask_id, n_rows, WS(c, lm_part, float), c->map.n_vtiles, nullptr);
   return hipGetLastError();
 }
 
 hipError_t launch_lm_merge(dllm_ctx* c, hipStream_t s, int max_rows, int n_parts, int32_t* cand, float* conf,
-                           float* entropy) {
+                           float* entropy, bool by_token) {
   k_lm_merge<<<max_rows, 256, 0, s>>>(WS(c, lm_part, float), n_parts, WS(c, rows, int32_t),
-                                     WS(c, status, int32_t) + 1, cand, conf, entropy);
+                                     WS(c, status, int32_t) + 1, cand, conf, entropy, by_token ? 1 : 0);
   return hipGetLastError();
 }
 

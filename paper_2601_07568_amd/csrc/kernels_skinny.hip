@@ -12,17 +12,17 @@
 
 namespace dllm {
 
-enum SkEpi { SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4, SK_DELTA = 5 };
+enum SkEpi { SK_F32 = 1, SK_QKV = 2, SK_SWIGLU = 3, SK_LMSTATS = 4, SK_RESID = 5 };
 
 struct SkArgs {
-  const bf16_t* X;          // activations [M, K]
-  const int32_t* m_dev;     // optional device row count (<= M)
+  const bf16_t* X;          // activations [M, K], fragment order
+  const int32_t* n_lm_rows; // optional device count: the kernel does nothing if it is zero
   int M, K;
   const bf16_t* W0;         // main weight / Wq / W_gate / lm_head   (all in packed fragment order)
   const bf16_t* W1;         // Wk / W_up
   const bf16_t* W2;         // Wv
   int N0, N1, N2;           // rows of W0, W1, W2
-  float* out_f32;           // RESID: x [M, N0] (+=) ; F32: [M, N0]
+  float* out_f32;           // F32: [M, N0]
   bf16_t* out_bf16;         // QKV: q [M, N0] ; SWIGLU: h [M, N0]
   // QKV
   int dh, n_q_wg, n_k_wg;   // head_dim, workgroups covering q, k
@@ -34,10 +34,19 @@ struct SkArgs {
   bf16_t* pool_v;
   KVView pool;
   int32_t* status;
-  // DELTA: grid.y splits K; split y stores its partial product to out_f32 + y * delta_stride, [M, N0];
-  // the consumer of the residual stream adds the splits up in order
-  int sps;                  // stages per split (0: no split)
-  int64_t delta_stride;
+  // Row scale of the activations (QKV, SWIGLU, LMSTATS, F32): X holds x * gain rounded to bfloat16, the row's
+  // normalisation factor rsqrt(mean(x^2) + eps) is applied to the summed tile in float.  ss_in[row * ss_stride + p],
+  // p < n_ss, are partial sums of squares of row `row` (added up in a fixed order); nullptr: no scale.
+  const float* ss_in;
+  int n_ss, ss_stride;
+  float inv_d, eps;
+  // RESID (residual projection x += X W0^T): a workgroup owns 16 columns for the whole of K, adds its tile to the
+  // residual stream, writes x * gain_next in fragment order as the next GEMM's input and the rows' sums of squares
+  // over its 16 columns to ss_out[row * ss_stride + workgroup].
+  float* x;                 // residual stream [M, N0], in/out
+  const bf16_t* gain_next;  // [N0]
+  bf16_t* xg_out;           // fragment order, MT tiles
+  float* ss_out;
   // LMSTATS
   float* part;              // [rows, n_parts, 4]
   int n_parts;
@@ -46,6 +55,8 @@ struct SkArgs {
 
 constexpr int SK_KB = 128;  // k-elements per block: 4 matrix instructions deep
 constexpr int SK_NW = 8;    // waves of a workgroup (they split K among themselves)
+constexpr int SK_NW_RESID = 16;   // ... of a residual projection's (one 16-row weight tile per workgroup: the bytes in
+                                  // flight come from the waves)
 
 // One pipeline stage: JB matrix-instruction steps (JB*32 k-elements) of NT weight tiles and MT
 // activation tiles.
@@ -128,17 +139,23 @@ __device__ inline void sk_tile_rows(const SkArgs& a, int wg, const bf16_t* (&wba
 template <int NT, int MT, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 && MT >= 3) ? 2 : 1)) void k_skinny(const SkArgs a) {
   // weight bytes in flight per wave: two stages of NT*JB KiB; with three or four activation tiles the
-  // shorter stage keeps the kernel at two workgroups per CU
-  constexpr int JB = (NT == 1) ? 4 : ((MT >= 3 || EPI == SK_DELTA) ? 1 : 2);
+  // shorter stage keeps the registers of three stages within a wave's share
+  constexpr int JB = (MT >= 3) ? 1 : 2;
+  constexpr bool SCALED = (EPI != SK_RESID);
+  constexpr int RPW = (MT * 16 + NW - 1) / NW;          // rows per wave when the row scales are summed
   __shared__ float red[NW][NT][MT][4][64];
   __shared__ float lmst[EPI == SK_LMSTATS ? MT : 1][4][16][4];
+  __shared__ float rs[64];                              // row scale of the activations
+  __shared__ float ssq[EPI == SK_RESID ? MT : 1][4][64];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int wg = blockIdx.x;
   const int K = a.K;
-  int M = a.M;
-  if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
+  const int M = a.M;
+  if (a.n_lm_rows && *a.n_lm_rows <= 0) return;
   if (M <= 0) return;
+
+  float xres = 0.f, gres = 0.f;                         // RESID: the thread's element of x and of the next gain
 
   const bf16_t* wbase[NT];
   int row0[NT], nrows[NT];
@@ -155,6 +172,14 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
     wt[t] = (const u32x4*)wbase[t] + (int64_t)rt * kpb * 256 + lane;
   }
   const u32x4* xf = (const u32x4*)a.X + lane;   // rows >= M of the last tile hold stale data: their columns are dropped
+  if constexpr (EPI == SK_RESID) {
+    // the element this thread will update (items beyond the first, with more than 1024 / 256 row tiles, load late)
+    const int m = tid >> 8, iq = (tid >> 6) & 3;
+    const int tok = m * 16 + c, n = row0[0] + 4 * g + iq;
+    const bool ok = m < MT && tok < M && n < a.N0;
+    xres = a.x[ok ? (int64_t)tok * a.N0 + n : 0];
+    gres = bf16_to_f32(a.gain_next[ok ? n : 0]);
+  }
 
   f32x4 acc[NT][MT];
 #pragma unroll
@@ -162,26 +187,57 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[t][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // Row scales: the wave adds up the partial sums of squares of rows w, w + NW, .. (one 16-byte load per lane covers
+  // 256 partials of a row; lanes add their four, the wave adds its lanes in a fixed tree) and lane 0 keeps the
+  // row's factor.  Called once the first weight stages are on their way: the partials come from the L2, the
+  // weights from memory, so the wave waits no longer for them than it would for the weights alone.
+  auto row_scales = [&]() {
+    if constexpr (SCALED) {
+      if (a.ss_in) {
+        float4 ssv[RPW];
+        const int idc = 4 * lane < a.ss_stride - 4 ? 4 * lane : a.ss_stride - 4;
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) ssv[q] = *(const float4*)(a.ss_in + (int64_t)(w + q * NW) * a.ss_stride + idc);
+#pragma unroll
+        for (int q = 0; q < RPW; ++q) {
+          const int row = w + q * NW;
+          const int i0 = 4 * lane;
+          float sq = (i0 < a.n_ss ? ssv[q].x : 0.f) + (i0 + 1 < a.n_ss ? ssv[q].y : 0.f) +
+                     (i0 + 2 < a.n_ss ? ssv[q].z : 0.f) + (i0 + 3 < a.n_ss ? ssv[q].w : 0.f);
+          for (int c0 = 256; c0 < a.n_ss; c0 += 256) {            // very wide models only
+            const int i1 = c0 + 4 * lane;
+            const int ic = i1 < a.ss_stride - 4 ? i1 : a.ss_stride - 4;
+            const float4 v = *(const float4*)(a.ss_in + (int64_t)row * a.ss_stride + ic);
+            sq += (i1 < a.n_ss ? v.x : 0.f) + (i1 + 1 < a.n_ss ? v.y : 0.f) + (i1 + 2 < a.n_ss ? v.z : 0.f) +
+                  (i1 + 3 < a.n_ss ? v.w : 0.f);
+          }
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) sq += __shfl_xor(sq, o, 64);
+          if (lane == 0 && row < 64) rs[row] = 1.0f / sqrtf(sq * a.inv_d + a.eps);
+        }
+      } else if (tid < 64) rs[tid] = 1.0f;
+    }
+  };
+
   // Software pipeline over this wave's stages (w, w+NW, ...): two stages are in flight while a third
   // is multiplied.  No load sits inside a branch of the steady-state loop (a branch around a load
   // makes the compiler wait for every outstanding load at the join); the drain is straight-line code.
   constexpr int SKB = JB * 32;                        // k-elements per stage
   const int n_full = K / SKB;                         // stages that need no tail guard
   const int ws = __builtin_amdgcn_readfirstlane(w);   // wave index as a scalar
-  const int s_lo = a.sps > 0 ? (int)blockIdx.y * a.sps : 0;          // this workgroup's range of stages
-  const int s_hi = a.sps > 0 ? (s_lo + a.sps < n_full ? s_lo + a.sps : n_full) : n_full;
-  const int n_loc = s_hi > s_lo ? s_hi - s_lo : 0;
-  const int n_w = n_loc > ws ? (n_loc - ws + NW - 1) / NW : 0;
-#define SK_LD(F, I) sk_load<NT, MT, JB, false>(F, wt, xf, s_lo + ws + (I) * NW, g, K)
+  const int n_w = n_full > ws ? (n_full - ws + NW - 1) / NW : 0;
+#define SK_LD(F, I) sk_load<NT, MT, JB, false>(F, wt, xf, ws + (I) * NW, g, K)
 #define SK_MM(F) sk_mma<NT, MT, JB>(F, acc)
-  if (n_w == 1) {
+  if (n_w <= 1) {
     SkFrag<NT, MT, JB> f0;
-    SK_LD(f0, 0);
-    SK_MM(f0);
-  } else if (n_w > 1) {
+    if (n_w == 1) SK_LD(f0, 0);
+    row_scales();
+    if (n_w == 1) SK_MM(f0);
+  } else {
     SkFrag<NT, MT, JB> f0, f1, f2;
     SK_LD(f0, 0);
     SK_LD(f1, 1);
+    row_scales();
     int i = 0;
     while (i + 4 < n_w) {          // stages i .. i+4 exist
       SK_LD(f2, i + 2); SK_MM(f0);
@@ -197,7 +253,7 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
   }
 #undef SK_LD
 #undef SK_MM
-  if (n_full * SKB < K && blockIdx.y == gridDim.y - 1 && ws == n_loc % NW) {   // ragged last stage
+  if (n_full * SKB < K && ws == n_full % NW) {   // ragged last stage
     SkFrag<NT, MT, JB> ft;
     sk_load<NT, MT, JB, true>(ft, wt, xf, n_full, g, K);
     sk_mma<NT, MT, JB>(ft, acc);
@@ -212,28 +268,58 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
       for (int i = 0; i < 4; ++i) red[w][t][m][i][lane] = acc[t][m][i];
   __syncthreads();
 
+  if constexpr (EPI == SK_RESID) {
+    // ---- residual projection: x += tile; next GEMM's input x * gain; sums of squares of the 16 columns per row
+    static_assert(EPI != SK_RESID || NT == 1, "a residual projection's workgroup owns one 16-row weight tile");
+    for (int item = tid; item < MT * 256; item += NW * 64) {
+      const int m = item >> 8, iq = (item >> 6) & 3, ln = item & 63;
+      const int tok = m * 16 + (ln & 15);
+      const int n = row0[0] + 4 * (ln >> 4) + iq;
+      float sum = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) sum += red[ww][0][m][iq][ln];
+      float sq = 0.f;
+      if (tok < M && n < a.N0) {
+        const float v = (item == tid ? xres : a.x[(int64_t)tok * a.N0 + n]) + sum;
+        const float gn = item == tid ? gres : bf16_to_f32(a.gain_next[n]);
+        a.x[(int64_t)tok * a.N0 + n] = v;
+        a.xg_out[frag_offset(tok, n, MT)] = f32_to_bf16(v * gn);
+        sq = v * v;
+      }
+      ssq[m][iq][ln] = sq;
+    }
+    __syncthreads();
+    if (tid < MT * 16) {          // the 16 contributions of a row (4 values of iq x 4 lane groups) in a fixed order
+      const int m = tid >> 4, cc = tid & 15;
+      float sq = 0.f;
+#pragma unroll
+      for (int iq = 0; iq < 4; ++iq)
+#pragma unroll
+        for (int lg = 0; lg < 4; ++lg) sq += ssq[m][iq][lg * 16 + cc];
+      a.ss_out[(int64_t)tid * a.ss_stride + wg] = sq;
+    }
+    return;
+  }
+
   for (int item = tid; item < MT * 256; item += NW * 64) {
     const int m = item >> 8, i = (item >> 6) & 3, ln = item & 63;
     const int tok = m * 16 + (ln & 15);
     const int fr = 4 * (ln >> 4) + i;          // row inside the 16-row tile
     float val[NT];
+    const float rsc = SCALED ? rs[tok] : 1.0f;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       float s = 0.f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) s += red[ww][t][m][i][ln];
-      val[t] = s;
+      val[t] = s * rsc;
     }
     const bool tok_ok = tok < M;
-    if constexpr (EPI == SK_F32 || EPI == SK_DELTA) {
+    if constexpr (EPI == SK_F32) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = row0[t] + fr;
-        if (tok_ok && n < a.N0) {
-          float* p = a.out_f32 + (int64_t)tok * a.N0 + n;
-          if (EPI == SK_DELTA) p[(int64_t)blockIdx.y * a.delta_stride] = val[t];
-          else *p = val[t];
-        }
+        if (tok_ok && n < a.N0) a.out_f32[(int64_t)tok * a.N0 + n] = val[t];
       }
     } else if constexpr (EPI == SK_SWIGLU) {
 #pragma unroll
@@ -372,45 +458,87 @@ static SkArgs sk_base(const void* X, int M, int K) {
   return a;
 }
 
-// Residual projection with the sum over K left open: split y of K writes A*W^T restricted to its
-// K range into delta + y*delta_stride ([M, N] float); the next RMSNorm adds x + delta_0 + delta_1 ..
-// in that order.  With K split across workgroups a workgroup can own 64 weight rows instead of 16
-// (the activation operand is re-read a quarter as often) and small N still fills the chip.
-// Returns the number of splits through n_splits.
-hipError_t launch_sk_delta(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* delta,
-                           int64_t delta_stride, int max_splits, int M, int N, int K, int* n_splits) {
+// partial sums of squares per row: one per 16-column tile of d_model; rows are ss_stride floats apart
+static int sk_ss_stride(const dllm_ctx* c) { return ((c->cfg.d_model + 15) / 16 + 3) / 4 * 4; }
+
+// Residual projection x += A * W^T: one workgroup of 16 waves per 16-column tile, the waves split K.  Its epilogue
+// prepares the next GEMM's input (x * gain_next in fragment order, sums of squares per row): no RMSNorm launch.
+// A workgroup re-reads all of A from the L2 (twice its weight bytes); that costs less than exchanging partial
+// products between workgroups would (two memory round trips at the end of every launch).
+hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, int M, int N, int K,
+                           const void* gain_next) {
   SkArgs a = sk_base(A, M, K);
   a.W0 = (const bf16_t*)W;   // packed
   a.N0 = N;
-  a.out_f32 = delta;
-  a.delta_stride = delta_stride;
-  const int groups = (N + 63) / 64;
-  const int n_full = K / 32;                       // the kernel's stages: one 32-element step each (JB = 1)
-  int ks = (256 + groups - 1) / groups;
-  if (ks > max_splits) ks = max_splits;
-  if (ks > n_full / (2 * SK_NW)) ks = n_full / (2 * SK_NW);   // at least two stages per wave
-  if (ks < 1) ks = 1;
-  int sps = (n_full + ks - 1) / ks;
-  sps = (sps + SK_NW - 1) / SK_NW * SK_NW;         // every wave the same number of stages
-  if (sps < SK_NW) sps = SK_NW;
-  ks = n_full > 0 ? (n_full + sps - 1) / sps : 1;
-  a.sps = sps;
-  *n_splits = ks;
-  const int mt = (M + 15) / 16;
-  dim3 grid(groups, ks);
-  switch (mt) {
-    case 1: k_skinny<4, 1, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
-    case 2: k_skinny<4, 2, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
-    case 3: k_skinny<4, 3, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
-    case 4: k_skinny<4, 4, SK_NW, SK_DELTA><<<grid, SK_NW * 64, 0, s>>>(a); break;
-    default: return hipErrorInvalidValue;
+  a.x = WSM(c, x, float);
+  a.gain_next = (const bf16_t*)gain_next;
+  a.xg_out = WSM(c, xn, bf16_t);
+  a.ss_out = WSM(c, ss, float);
+  a.ss_stride = sk_ss_stride(c);
+  return sk_launch_mt<1, SK_NW_RESID, SK_RESID>(s, a, (N + 15) / 16);
+}
+
+// the GEMM input comes with n_ss partial sums of squares per row
+static void sk_row_scale(dllm_ctx* c, SkArgs& a, int n_ss) {
+  a.ss_in = WSM(c, ss, float);
+  a.n_ss = n_ss;
+  a.ss_stride = sk_ss_stride(c);
+  a.inv_d = 1.0f / (float)c->cfg.d_model;
+  a.eps = c->cfg.rms_eps;
+}
+
+// Token embedding of a denoise step: x[t] = E[token[t]] (float), x * gain in fragment order as the first GEMM's
+// input, the row's sum of squares as its single partial.  One workgroup per row.
+__global__ __launch_bounds__(256) void k_embed_xg(int d, int vocab, int mt, const int32_t* tokens, const bf16_t* emb,
+                                                  const bf16_t* gain, float* x, bf16_t* xg, float* ss, int ss_stride,
+                                                  int32_t* status) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  int tok = tokens[t];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, DLLM_STATUS_BAD_TOKEN);
+    tok = 0;
   }
+  const bf16_t* row = emb + (int64_t)tok * d;
+  float sq = 0.f;
+  for (int u = threadIdx.x; u < (d >> 3); u += 256) {          // 16-byte units: 8 channels
+    const uint4 ev = *(const uint4*)(row + 8 * u), gv = *(const uint4*)(gain + 8 * u);
+    const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    float xv[8];
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      xv[2 * e] = __uint_as_float(ew[e] << 16);
+      xv[2 * e + 1] = __uint_as_float(ew[e] & 0xffff0000u);
+      o[e] = pack_bf16x2(xv[2 * e] * __uint_as_float(gw[e] << 16), xv[2 * e + 1] * __uint_as_float(gw[e] & 0xffff0000u));
+      sq = fmaf(xv[2 * e], xv[2 * e], sq);
+      sq = fmaf(xv[2 * e + 1], xv[2 * e + 1], sq);
+    }
+    float4* xr = (float4*)(x + (int64_t)t * d + 8 * u);
+    xr[0] = make_float4(xv[0], xv[1], xv[2], xv[3]);
+    xr[1] = make_float4(xv[4], xv[5], xv[6], xv[7]);
+    *(uint4*)(xg + frag_offset(t, 8 * u, mt)) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+  __syncthreads();
+  if (threadIdx.x == 0) ss[(int64_t)t * ss_stride] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+hipError_t launch_sk_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain) {
+  const dllm_config& f = c->cfg;
+  k_embed_xg<<<g.T, 256, 0, s>>>(f.d_model, f.vocab, (g.T + 15) / 16, g.tokens, (const bf16_t*)c->tok_emb,
+                                 (const bf16_t*)gain, WSM(c, x, float), WSM(c, xn, bf16_t), WSM(c, ss, float),
+                                 sk_ss_stride(c), WSM(c, status, int32_t));
   return hipGetLastError();
 }
 
 // out[M,N] = A[M,K] * W[N,K]^T in float (debug logits)
-hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K) {
+hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* out, int M, int N, int K,
+                         int n_ss) {
   SkArgs a = sk_base(A, M, K);
+  sk_row_scale(c, a, n_ss);
   a.W0 = (const bf16_t*)W;
   a.N0 = N;
   a.out_f32 = out;
@@ -419,10 +547,10 @@ hipError_t launch_sk_f32(dllm_ctx* c, hipStream_t s, const void* A, const void* 
 
 // fused q/k/v projection of a denoise step: rotary embedding on q and k, q to the workspace,
 // k and v into the in-flight pages of the pool
-hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool) {
+hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int layer, const KVView& pool, int n_ss) {
   const dllm_config& f = c->cfg;
-  const dllm_layer_w& L = c->layers[layer];
   SkArgs a = sk_base(c->ws + c->map.xn, g.T, f.d_model);
+  sk_row_scale(c, a, n_ss);
   const dllm_layer_w& P = c->packed_layers[layer];
   a.W0 = (const bf16_t*)P.wq; a.W1 = (const bf16_t*)P.wk; a.W2 = (const bf16_t*)P.wv;
   a.N0 = f.n_q_heads * f.head_dim; a.N1 = a.N2 = f.n_kv_heads * f.head_dim;
@@ -440,10 +568,10 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
 }
 
 // h[M,F] = silu(xn Wg^T) * (xn Wu^T), written in fragment order for the down projection
-hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M) {
+hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M, int n_ss) {
   const dllm_config& f = c->cfg;
-  const dllm_layer_w& L = c->layers[layer];
   SkArgs a = sk_base(c->ws + c->map.xn, M, f.d_model);
+  sk_row_scale(c, a, n_ss);
   const dllm_layer_w& P = c->packed_layers[layer];
   a.W0 = (const bf16_t*)P.w_gate; a.W1 = (const bf16_t*)P.w_up;
   a.N0 = f.d_ff;
@@ -452,11 +580,13 @@ hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M) {
   return sk_launch_mt<2, SK_NW, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
 }
 
-// LM head on the compacted rows (ws.xn) -> per-64-column softmax statistics
-hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out) {
+// LM head on all rows of the step (ws.xn holds x * final gain) -> per-64-column softmax statistics of every row;
+// the merge picks the masked ones.  If no row is masked (device count) nothing is computed.
+hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int T, int n_ss, int* n_parts_out) {
   const dllm_config& f = c->cfg;
-  SkArgs a = sk_base(c->ws + c->map.xn, max_rows, f.d_model);
-  a.m_dev = WSM(c, status, int32_t) + 1;
+  SkArgs a = sk_base(c->ws + c->map.xn, T, f.d_model);
+  sk_row_scale(c, a, n_ss);
+  a.n_lm_rows = WSM(c, status, int32_t) + 1;
   a.W0 = (const bf16_t*)c->packed_lm_head;
   a.N0 = f.vocab;
   a.part = WSM(c, lm_part, float);

@@ -84,9 +84,12 @@ def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, gpu_logits=None, e
     """GPU cand/conf/entropy of the masked rows against an oracle step record r (r comes from the
     oracle run in the model's storage precision, so that both sides decide in the same precision).
 
-    Token ids must agree wherever the oracle's top-2 probability margin exceeds 1e-3, and also
-    wherever its top-2 logit gap exceeds twice the logit tolerance (then any logits within
-    tolerance have the same arg max).
+    Token ids must agree wherever the oracle's top-2 logit gap exceeds twice the logit tolerance (then any
+    logits within tolerance have the same arg max).  float: also wherever its top-2 probability margin exceeds
+    1e-3 (with a logit tolerance of 1e-4 such a margin is always a gap far above the tolerance).  bfloat16: a
+    margin of 1e-3 on a flat distribution (p_max = 0.15: a logit gap of 0.008) lies inside the logit tolerance
+    itself (0.02 * max|z| = 0.2), so agreement on such rows cannot be required row by row; they are counted,
+    and at least nine in ten of them must agree.
 
     Tolerances follow from the logit tolerance eps (relative to the row's largest |z|): with
     delta = eps * max|z|, log(conf) = z_max - lse moves by at most 2*delta, and to first order the
@@ -99,16 +102,21 @@ def check_step_outputs(ms, r, masked, cand, conf, ent, dtype, gpu_logits=None, e
     pp = np.delete(p, ms.mask_id, axis=1)
     delta = eps * np.abs(z).max(axis=-1)
     spread = (pp * np.abs(zz - (pp * zz).sum(-1, keepdims=True))).sum(-1)
-    n_exact = 0
+    n_exact = n_margin = n_margin_ok = 0
     zs = np.sort(zz, axis=-1)
     gap = zs[:, -1] - zs[:, -2]
     for i in np.nonzero(masked)[0]:
-        if margin[i] > MARGIN or gap[i] > 2 * delta[i]:
+        if gap[i] > 2 * delta[i] or (dtype == "f32" and margin[i] > MARGIN):
             assert cand[i] == r["cand"][i], (i, cand[i], r["cand"][i], margin[i], gap[i], delta[i])
             n_exact += 1
+        elif margin[i] > MARGIN:
+            n_margin += 1
+            n_margin_ok += int(cand[i] == r["cand"][i])
         assert abs(np.log(conf[i] / oconf[i])) <= 2 * delta[i] + 1e-6, (i, conf[i], oconf[i], delta[i])
         if ent is not None:
             assert abs(ent[i] - oent[i]) <= 1.5 * delta[i] * spread[i] + 1e-5, (i, ent[i], oent[i])
+    assert n_margin_ok * 10 >= n_margin * 9, (n_margin_ok, n_margin)
+    n_exact += n_margin_ok
     if gpu_logits is not None:
         # property of the fused epilogue: its outputs are the softmax statistics of the logits the
         # same forward materialises through the debug hook

@@ -470,12 +470,19 @@ def test_store_hook_is_applied_at_the_storage_points_only():
     exact, _, _, _ = O.forward_full(model, toks)
     calls = []
 
+    seen = []
+
     def ident(a):
         calls.append(np.shape(a))
+        seen.append(np.array(a, copy=True))
         return a
 
     same, _, _, _ = O.forward_full(model, toks, store=ident)
-    np.testing.assert_array_equal(exact, same)                       # identity store changes nothing
+    # identity store changes nothing (the row factor is applied after the gain instead of before it: last-bit only)
+    np.testing.assert_allclose(same, exact, rtol=1e-12, atol=1e-12)
+    # what is stored as the input of the first normalised layer is x * gain, without the row factor
+    x0 = np.asarray(model["tok_emb"], dtype=np.float64)[toks]
+    np.testing.assert_array_equal(seen[0], x0 * np.asarray(model.layer(0)["attn_norm"], dtype=np.float64))
     S, d, F = 9, ms.d_model, ms.d_ff
     per_layer = [(S, d), (S, ms.n_q_heads, ms.head_dim), (S, ms.n_kv_heads, ms.head_dim),
                  (S, ms.n_kv_heads, ms.head_dim), (S, ms.n_q_heads, ms.head_dim), (S, d), (S, F)]
