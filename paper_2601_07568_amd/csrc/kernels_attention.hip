@@ -686,13 +686,12 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
   const int R = max_q * G;
   constexpr int QT = 2;
   const int n_rg = (R + 16 * QT - 1) / (16 * QT);
-  static const int no_lds = getenv("DLLM_NO_ATTN_LDS") ? 1 : 0;   // tuning aid
   int pt_shift = 0;
   if (g.Q > 0) {
     pt_shift = -1;
     for (int sft = 3; sft < 31; ++sft) if (f.page_tokens == (1 << sft)) pt_shift = sft;
   }
-  const bool staged = n_rg >= 4 && !no_lds && pt_shift >= 0;   // K/V staged in LDS, up to 8 row groups per workgroup
+  const bool staged = n_rg >= 4 && pt_shift >= 0;   // K/V staged in LDS, up to 8 row groups per workgroup
   const int rg_cap = staged ? 8 : 4;                           // the register-direct kernel runs at most 4 waves
   const int n_rg_wg = n_rg < rg_cap ? n_rg : rg_cap;
   const int n_chunks = (n_rg + n_rg_wg - 1) / n_rg_wg;

@@ -703,8 +703,7 @@ static hipError_t ts_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
 // rows for which the streaming tiles are the better form: more than the weight-streaming kernels take, fewer
 // than fill 256-row tiles
 static bool ts_usable(int M, int K) {
-  static const int off = getenv("DLLM_NO_TS") ? 1 : 0;   // tuning aid
-  return !off && M > 64 && M < 256 && K % 32 == 0 && K >= 128;
+  return M > 64 && M < 256 && K % 32 == 0 && K >= 128;
 }
 
 // the 256 x 256 form needs the whole ring in LDS: more than the default limit of a kernel
@@ -740,8 +739,7 @@ static hipError_t t2_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
   return hipGetLastError();
 }
 static bool t2_usable(int M, int K) {
-  static const int off = getenv("DLLM_NO_T256") ? 1 : 0;   // tuning aid
-  return t2_ready && !off && M >= 256 && K % 32 == 0 && K >= 128;
+  return t2_ready && M >= 256 && K % 32 == 0 && K >= 128;
 }
 
 template <int EPI>

@@ -576,7 +576,8 @@ hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M, int n_
   a.W0 = (const bf16_t*)P.w_gate; a.W1 = (const bf16_t*)P.w_up;
   a.N0 = f.d_ff;
   a.out_bf16 = WSM(c, h, bf16_t);
-  // (three tile pairs per workgroup -- 256 equal workgroups at F = 12288 -- measured no faster than one)
+  // (three tile pairs per workgroup -- 256 equal workgroups at F = 12288, a third of the activation reads --
+  // measured no faster than one: 40.8 against 41.7 us)
   return sk_launch_mt<2, SK_NW, SK_SWIGLU>(s, a, (f.d_ff + 15) / 16);
 }
 
