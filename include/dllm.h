@@ -290,6 +290,28 @@ int dllm_noisy_sequence(dllm_ctx *ctx, void *stream, int B, int n, const int32_t
 int dllm_eos_scan(dllm_ctx *ctx, void *stream, int B, int n, const int32_t *gen_tokens, int32_t eos_id,
                   int32_t *finished, int32_t *first_eos, int32_t *active_index, int32_t *n_active);
 
+/* Ragged batch after early stopping (Section 3.2, "Early Stopping on EOS Token": a finished sequence takes part in no
+ * further forward).  dllm_gather_rows moves the live sequences' rows to the front of a batch array, in the order of the
+ * list dllm_eos_scan writes: dst[i] = src[index[i]] for i < n_index[0], every other row of dst = fill; rows are row_len
+ * int32 values (generation tokens, prefix lengths with row_len 1, block-table rows, block states, ...).
+ * dllm_scatter_rows is the way back: dst[index[i]] = src[i] for i < n_index[0], other rows of dst untouched.  An index
+ * outside [0, B) addresses nothing (gather: that row is filled).
+ *   index dev int32 [B]; n_index dev int32 [1] (clamped to [0, B]); src, dst dev int32 [B, row_len], distinct buffers. */
+int dllm_gather_rows(dllm_ctx *ctx, void *stream, int B, int row_len, const int32_t *index, const int32_t *n_index,
+                     const int32_t *src, int32_t *dst, int32_t fill);
+int dllm_scatter_rows(dllm_ctx *ctx, void *stream, int B, int row_len, const int32_t *index, const int32_t *n_index,
+                      const int32_t *src, int32_t *dst);
+
+/* The denoise step over the live sequences of a compacted batch: as dllm_denoise_step_var (q_valid may be NULL: every
+ * row valid), but only sequences b < n_live[0] take part.  The others cost no attention and no cache write, get no
+ * LM-head row and report their own tokens with confidence 1; on the paths that tile over rows (more than 64 rows in
+ * the call) the rows past the live sequences are skipped by the GEMMs as well, so a finished sequence stops consuming
+ * work although B, which sizes the launches, stays a host value.
+ *   n_live dev int32 [1], clamped to [0, B] (n_active of dllm_eos_scan after dllm_gather_rows). */
+int dllm_denoise_step_live(dllm_ctx *ctx, void *stream, int B, int Q, int max_prefix_len, const int32_t *q_tokens,
+                           const int32_t *prefix_len, const int32_t *q_valid, const int32_t *n_live,
+                           const int32_t *block_table, int32_t *cand_token, float *conf, float *entropy);
+
 /* KV refresh (Section 3.2, "KV-Refresh"; the forward passes of the "Completed but Stabilizing"
  * state): the same no-cache forward as dllm_prefill_kv over the committed tokens, optionally
  * followed by in-flight ones, overwriting the cached K/V of positions [0, n_commit[b]) (all if

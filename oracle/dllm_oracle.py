@@ -440,3 +440,27 @@ def eos_state(gen, eos_id, mask_id):
         if tok == eos_id:
             return True, p
     return False, -1
+
+
+def live_sequences(gens, eos_id, mask_id):
+    """Early stop over a batch (Section 3.2, "Early Stopping on EOS Token"): indices, in order, of the sequences that
+    are not finished; a finished sequence takes part in no further forward."""
+    return [b for b, gen in enumerate(gens) if not eos_state(gen, eos_id, mask_id)[0]]
+
+
+def gather_rows(src, index, fill):
+    """Compaction of a batch array: row i of the result is row index[i] of src for i < len(index); the remaining
+    rows hold `fill`."""
+    src = np.asarray(src)
+    out = np.full_like(src, fill)
+    for i, j in enumerate(index):
+        out[i] = src[j]
+    return out
+
+
+def scatter_rows(dst, index, src):
+    """The way back: row index[i] of the result is row i of src for i < len(index); other rows are those of dst."""
+    out = np.array(dst, copy=True)
+    for i, j in enumerate(index):
+        out[j] = np.asarray(src)[i]
+    return out

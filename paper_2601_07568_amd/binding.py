@@ -64,6 +64,9 @@ def lib() -> C.CDLL:
         "dllm_unmask": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_unmask_entropy": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, vp, vp]),
         "dllm_denoise_step_var": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "dllm_denoise_step_live": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "dllm_gather_rows": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, i32]),
+        "dllm_scatter_rows": (i32, [vp, vp, i32, i32, vp, vp, vp, vp]),
         "dllm_fsm_window": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]),
         "dllm_fsm_scatter": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_unmask_traced": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]),
@@ -251,6 +254,23 @@ class Engine:
         self._check(lib().dllm_denoise_step_var(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
                                                 _ptr(prefix_len), _ptr(q_valid), _ptr(block_table), _ptr(cand),
                                                 _ptr(conf), _ptr(entropy)))
+
+    def denoise_step_live(self, q_tokens, prefix_len, q_valid, n_live, block_table, cand, conf, entropy=None, *,
+                          max_prefix_len):
+        B, Q = q_tokens.shape
+        self._check(lib().dllm_denoise_step_live(self.ctx, self._stream(), B, Q, max_prefix_len, _ptr(q_tokens),
+                                                 _ptr(prefix_len), _ptr(q_valid), _ptr(n_live), _ptr(block_table),
+                                                 _ptr(cand), _ptr(conf), _ptr(entropy)))
+
+    def gather_rows(self, index, n_index, src, dst, fill=0):
+        B = src.shape[0]
+        self._check(lib().dllm_gather_rows(self.ctx, self._stream(), B, src.numel() // B, _ptr(index), _ptr(n_index),
+                                           _ptr(src), _ptr(dst), fill))
+
+    def scatter_rows(self, index, n_index, src, dst):
+        B = src.shape[0]
+        self._check(lib().dllm_scatter_rows(self.ctx, self._stream(), B, src.numel() // B, _ptr(index), _ptr(n_index),
+                                            _ptr(src), _ptr(dst)))
 
     def fsm_window(self, gen_tokens, state, base_len, block_len, W, pad_token, win_tokens, win_floor, prefix_len,
                    q_valid, win_lo):

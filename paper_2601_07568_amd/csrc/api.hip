@@ -69,6 +69,7 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   if (m->attn_rows < 65536) m->attn_rows = 65536;
   m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
   if (c->dtype != DLLM_BF16) m->attn_rows = 0;
+  m->q_valid_eff = take((size_t)c->max_batch * 4);
   m->rscale = take(t_max * 4);
   m->ss = take((size_t)64 * ((((size_t)c->d_model + 15) / 16 + 3) / 4 * 4) * 4);
   m->delta_stride = (int64_t)SK_MAX_ROWS * c->d_model;
@@ -284,7 +285,7 @@ static hipError_t gemm_any(dllm_ctx* c, hipStream_t s, const void* A, const void
                            Epi epi, bool norm_in = false) {
   const float* rs = (norm_in && c->cfg.dtype == DLLM_BF16) ? (const float*)(c->ws + c->map.rscale) : nullptr;
   if (c->cfg.dtype == DLLM_BF16 && c->kernel_mode == 0 && N % 4 == 0 && K % 8 == 0)
-    return launch_gemm_mfma(s, A, W, C, M, N, K, epi, rs);
+    return launch_gemm_mfma(s, A, W, C, M, N, K, epi, rs, c->rows_dev);
   return launch_gemm_generic(c, s, A, W, C, M, N, K, epi, rs);
 }
 
@@ -296,12 +297,28 @@ struct HeadOut {
 
 // The forward shared by all calls: embed, n_layers_run transformer layers over the rows of g,
 // then optionally the residual stream, the raw logits or the fused confidence outputs.
-static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
+static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
+                             float* logits_out, float* hidden_out);
+
+static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g0, int n_layers_run, const HeadOut* head,
                        float* logits_out, float* hidden_out) {
+  TRY(launch_token_map(c, s, g0), "token_map");
+  if (!g0.n_live) return run_forward_inner(c, s, g0, n_layers_run, head, logits_out, hidden_out);
+  // a step over the live sequences only: the token map has left the valid rows per sequence (-1 for the sequences
+  // past the live count) and the number of live rows in the workspace
+  StepGeom g = g0;
+  g.q_valid = WSP(c, q_valid_eff, int32_t);
+  c->rows_dev = WSP(c, status, int32_t) + 2;
+  const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+  c->rows_dev = nullptr;
+  return rc;
+}
+
+static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
+                             float* logits_out, float* hidden_out) {
   const dllm_config& f = c->cfg;
   const int T = g.T;
   const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
-  TRY(launch_token_map(c, s, g), "token_map");
   // matrix-core kernels: bfloat16 denoise steps of at most SK_MAX_ROWS rows (weight streaming)
   // (their activation operands are kept in fragment order, which only these kernels write).  On this path no
   // RMSNorm is launched: the producer of the residual stream (embedding, output projection, down projection)
@@ -330,7 +347,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
         // q | k | v left as partial sums over K; the rotary kernel adds them
       } else if (big_mfma && f.d_model % 8 == 0 && dq % 4 == 0 && dkv % 4 == 0) {
         TRY(launch_gemm_qkv(s, c->ws + c->map.xn, L.wq, L.wk, L.wv, WSP(c, q32, float), WSP(c, k32, float),
-                            c->ws + c->map.v, T, dq, dkv, f.d_model, WSP(c, rscale, float)), "wqkv");
+                            c->ws + c->map.v, T, dq, dkv, f.d_model, WSP(c, rscale, float), c->rows_dev), "wqkv");
       } else {
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.wq, c->ws + c->map.q32, T, dq, f.d_model, EPI_STORE_F32, true), "wq");
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.wk, c->ws + c->map.k32, T, dkv, f.d_model, EPI_STORE_F32, true), "wk");
@@ -369,7 +386,7 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_laye
       if (big_mfma) {
         ProfScope p(c, s, 2, 2.0 * T * 2.0 * f.d_ff * f.d_model);
         TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model,
-                               WSP(c, rscale, float)), "gate_up");
+                               WSP(c, rscale, float), c->rows_dev), "gate_up");
       } else {
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_gate");
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_up");
@@ -433,6 +450,7 @@ static StepGeom step_geom(int B, int Q, int max_prefix_len, const int32_t* q_tok
   g.B = B; g.T = B * Q; g.Q = Q; g.max_kv = max_prefix_len + Q;
   g.tokens = q_tokens; g.prefix_len = prefix_len; g.cu_seqlens = nullptr; g.n_cache = nullptr;
   g.q_valid = nullptr;
+  g.n_live = nullptr;
   g.block_table = block_table;
   return g;
 }
@@ -517,6 +535,44 @@ extern "C" int dllm_denoise_step_static(dllm_ctx* c, void* stream, int B, int Q,
   return DLLM_OK;
 }
 
+extern "C" int dllm_denoise_step_live(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
+                                      const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* q_valid,
+                                      const int32_t* n_live, const int32_t* block_table, int32_t* cand_token,
+                                      float* conf, float* entropy) {
+  int rc = check_step_args(c, B, Q, max_prefix_len, q_tokens, prefix_len, block_table, true);
+  if (rc != DLLM_OK) return rc;
+  if (!cand_token || !conf || !n_live) return DLLM_EINVAL;
+  StepGeom g = step_geom(B, Q, max_prefix_len, q_tokens, prefix_len, block_table);
+  g.q_valid = q_valid;
+  g.n_live = n_live;
+  HeadOut h{cand_token, conf, entropy};
+  return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, &h, nullptr, nullptr);
+}
+
+static int check_rows_args(dllm_ctx* c, int B, int row_len, const void* index, const void* n_index, const void* src,
+                           const void* dst) {
+  if (!c || !index || !n_index || !src || !dst || src == dst) return DLLM_EINVAL;
+  if (B < 1 || row_len < 1) return DLLM_EINVAL;
+  if (B > (1 << 24) || row_len > (1 << 24)) return DLLM_ESHAPE;
+  return DLLM_OK;
+}
+
+extern "C" int dllm_gather_rows(dllm_ctx* c, void* stream, int B, int row_len, const int32_t* index,
+                                const int32_t* n_index, const int32_t* src, int32_t* dst, int32_t fill) {
+  int rc = check_rows_args(c, B, row_len, index, n_index, src, dst);
+  if (rc != DLLM_OK) return rc;
+  TRY(launch_gather_rows((hipStream_t)stream, B, row_len, index, n_index, src, dst, fill, false), "gather_rows");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_scatter_rows(dllm_ctx* c, void* stream, int B, int row_len, const int32_t* index,
+                                 const int32_t* n_index, const int32_t* src, int32_t* dst) {
+  int rc = check_rows_args(c, B, row_len, index, n_index, src, dst);
+  if (rc != DLLM_OK) return rc;
+  TRY(launch_gather_rows((hipStream_t)stream, B, row_len, index, n_index, src, dst, 0, true), "scatter_rows");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_debug_logits(dllm_ctx* c, void* stream, int B, int Q, int max_prefix_len,
                                  const int32_t* q_tokens, const int32_t* prefix_len, const int32_t* block_table,
                                  float* logits) {
@@ -549,6 +605,7 @@ static int packed_forward(dllm_ctx* c, void* stream, int B, int total_tokens, in
   g.B = B; g.T = total_tokens; g.Q = 0; g.max_kv = max_seqlen;
   g.tokens = tokens; g.prefix_len = nullptr; g.cu_seqlens = cu_seqlens; g.n_cache = n_cache;
   g.q_valid = nullptr;
+  g.n_live = nullptr;
   g.block_table = block_table;
   return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, head, nullptr, nullptr);
 }

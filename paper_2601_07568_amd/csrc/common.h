@@ -145,6 +145,7 @@ struct Workspace {
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
   size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
   int64_t attn_rows;   // capacity in (token, head, unit) rows
+  size_t q_valid_eff;  // int32 [max_batch]             valid rows per sequence of a step with a live count (-1: not live)
   size_t rscale;       // float [Tmax]                  row normalisation factors of the current GEMM input (bfloat16 models)
   size_t ss;           // float [64][d/16 rounded up to 4]   partial sums of squares of the rows of the skinny path's GEMM input
   size_t delta;        // float open residual sums of K-split residual projections: [LG_MAX_DELTA][lg_delta_rows, d]
@@ -174,6 +175,7 @@ struct dllm_ctx {
   char* ws;
   dllm::Workspace map;
   int kernel_mode;
+  const int32_t* rows_dev;   // during a step with a live count: device count of rows the large GEMMs compute; else nullptr
   char hip_error[256];
   // per-kernel event timing (dllm_profile_*)
   int prof_on, prof_n, prof_cap;
@@ -200,6 +202,8 @@ struct StepGeom {           // which tokens a forward runs over
   const int32_t* prefix_len;   // dev [B] (step) or nullptr
   const int32_t* q_valid;      // dev [B] or nullptr (step): rows of a sequence past q_valid[b] are padding - they are
                                // no keys for the other rows and get no LM-head row
+  const int32_t* n_live;       // dev [1] or nullptr (step): sequences b >= n_live[0] are not part of the call (no
+                               // attention, no cache write, no LM-head row; GEMM rows past the live ones are skipped)
   const int32_t* cu_seqlens;   // dev [B+1] (packed) or nullptr
   const int32_t* n_cache;      // dev [B] or nullptr (packed: how many positions go to the pool)
   const int32_t* block_table;  // dev [B, max_pages]
@@ -250,6 +254,8 @@ hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, 
                              int32_t* state, int32_t* counter, int need_add, int need_full, int delay, int nocache_round,
                              int32_t* floor_next, int32_t* summary);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
+hipError_t launch_gather_rows(hipStream_t s, int B, int row_len, const int32_t* index, const int32_t* n_index,
+                              const int32_t* src, int32_t* dst, int32_t fill, bool scatter);
 
 // ---- launchers implemented in kernels_skinny.hip / kernels_attention.hip / kernels_gemm.hip (bf16, matrix cores) --
 bool mfma_supported(const dllm_ctx* c);
@@ -265,7 +271,7 @@ hipError_t launch_sk_qkv(dllm_ctx* c, hipStream_t s, const StepGeom& g, int laye
 hipError_t launch_sk_swiglu(dllm_ctx* c, hipStream_t s, int layer, int M, int n_ss);
 hipError_t launch_sk_lmstats(dllm_ctx* c, hipStream_t s, int T, int n_ss, int* n_parts_out);
 hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi,
-                            const float* rscale = nullptr);
+                            const float* rscale = nullptr, const int32_t* m_dev = nullptr);
 hipError_t init_attn_kernels();   // once per process (raises a kernel's LDS limit)
 hipError_t init_gemm_t256();   // once per process, before the first large GEMM (raises a kernel's LDS limit)
 hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, const void* W, float* x, int M, int N, int K,
@@ -273,9 +279,10 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
 hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv,
                                  int M, int dq, int dkv, int K, int* n_part);
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
-                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale);
+                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale,
+                           const int32_t* m_dev);
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K, const float* rscale);
+                              int K, const float* rscale, const int32_t* m_dev);
 hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g);
 hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out);

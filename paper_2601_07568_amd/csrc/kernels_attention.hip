@@ -104,6 +104,7 @@ __global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
   const int n_q = paged ? a.Q : a.cu[b + 1] - a.cu[b];          // its query rows
   const int R = n_q * G;
   if (rg * 16 * QT >= R) return;
+  if (paged && a.q_valid && a.q_valid[b] < 0) return;       // the sequence is not part of this call
   const int kv_len = paged ? a.prefix_len[b] + (a.q_valid ? min(max(a.q_valid[b], 0), a.Q) : a.Q) : n_q;
   const KVView& kv = a.kv;
   const int pt = paged ? kv.page_tokens : 1;
@@ -415,6 +416,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   const int kv_len = PAGED ? a.prefix_len[b] + (a.q_valid ? min(max(a.q_valid[b], 0), a.Q) : a.Q) : n_q;
   const bool active = w < a.n_rg_wg && rg * 16 * QT < R;     // waves beyond the rows only help loading
   if (blockIdx.y * a.n_rg_wg * 16 * QT >= R) return;         // whole workgroup beyond this sequence's rows
+  if (PAGED && a.q_valid && a.q_valid[b] < 0) return;        // the sequence is not part of this call
   const KVView& kv = a.kv;
   const int sh = a.pt_shift, pt = 1 << sh;                   // page size (a power of two)
   const bf16_t* kslab = (const bf16_t*)kv.k;

@@ -761,10 +761,11 @@ static hipError_t lg_launch(hipStream_t s, LgArgs a, int k_splits = 1) {
 
 // C[M,N] (=, +=) A[M,K] W[N,K]^T for bfloat16 operands; N % 4 == 0 and K % 8 == 0
 hipError_t launch_gemm_mfma(hipStream_t s, const void* A, const void* W, void* C, int M, int N, int K, Epi epi,
-                            const float* rscale) {
+                            const float* rscale, const int32_t* m_dev) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = C; a.M = M; a.N = N; a.K = K;
+  a.m_dev = m_dev;
   a.rscale = epi == EPI_RESID ? nullptr : rscale;
   if (epi == EPI_STORE) return lg_launch<LG_STORE>(s, a);
   if (epi == EPI_STORE_F32) return lg_launch<LG_STORE_F32>(s, a);
@@ -779,6 +780,7 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)W; a.C = x; a.M = M; a.N = N; a.K = K;
+  a.m_dev = c->rows_dev;
   if (ts_usable(M, K) && M <= c->map.lg_delta_rows && N == c->cfg.d_model) {
     // streaming tiles: K split until about three workgroups per CU are in flight
     const int tiles = ((M + 127) / 128) * ((N + 63) / 64);
@@ -820,6 +822,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
     a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
     a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
     a.rscale = WSM(c, rscale, float);
+    a.m_dev = c->rows_dev;
     const bool wide = dq % 128 == 0 && dkv % 128 == 0 && (dq + 2 * dkv) / 128 >= 64;   // 128 x 128 tiles still fill the chip
     const int tiles = ((M + 127) / 128) * ((dq + 2 * dkv) / (wide ? 128 : 64));
     int splits = 768 / tiles;
@@ -841,6 +844,7 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
   a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
   a.rscale = WSM(c, rscale, float);
+  a.m_dev = c->rows_dev;
   const int tiles = ((M + 255) / 256) * ((dq + 2 * dkv) / 256);
   int splits = 256 / tiles;
   if (splits > LG_QKV_SPLITS) splits = LG_QKV_SPLITS;
@@ -857,10 +861,12 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
 
 // q32[M,dq], k32[M,dkv] (float) and v[M,dkv] (bfloat16) = A[M,K] times the three projections, one launch
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
-                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale) {
+                           float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale,
+                           const int32_t* m_dev) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.rscale = rscale;
+  a.m_dev = m_dev;
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wq; a.W2 = (const bf16_t*)Wk; a.W3 = (const bf16_t*)Wv;
   a.C = q32; a.C2 = k32; a.C3 = v;
   a.M = M; a.N = dq; a.N2 = dkv; a.K = K;
@@ -869,10 +875,11 @@ hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const v
 
 // h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K, const float* rscale) {
+                              int K, const float* rscale, const int32_t* m_dev) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.rscale = rscale;
+  a.m_dev = m_dev;
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
   if (ts_usable(M, K)) return ts_launch<LG_SWIGLU, 2>(s, a);
   if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);

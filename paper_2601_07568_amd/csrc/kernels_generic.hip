@@ -40,9 +40,20 @@ __device__ inline float block_max(float v, float* red) {
 
 // ------------------------------------------------------------------------------------------
 // token map: sequence and position of every row of the forward
+// With a live count (steps only) the valid rows per sequence are written out as well: q_valid[b] (or Q) for the
+// live sequences b < n_live[0], -1 for the others (every row of theirs is padding and their attention is skipped),
+// and the number of rows up to the last live sequence for the GEMMs that can skip rows.
 __global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, const int32_t* cu,
-                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad, const int32_t* q_valid) {
+                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad, const int32_t* q_valid,
+                            const int32_t* n_live, int32_t* q_valid_eff, int32_t* rows_dev) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
+  int nl = B;
+  if (n_live) {
+    nl = n_live[0];
+    nl = nl < 0 ? 0 : (nl > B ? B : nl);
+    if (t < B) q_valid_eff[t] = t < nl ? (q_valid ? q_valid[t] : Q) : -1;
+    if (t == 0) rows_dev[0] = nl * Q;
+  }
   if (t == 0 && Q == 0) {   // padded column offsets of the packed K/V scratch
     int acc = 0;
     for (int b = 0; b < B; ++b) { cu_pad[b] = acc; acc += (cu[b + 1] - cu[b] + 31) / 32 * 32; }
@@ -53,7 +64,8 @@ __global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, cons
     int b = t / Q;
     tok_seq[t] = b;
     // padding rows of a step (past q_valid of their sequence) have no position: nothing of theirs is cached
-    tok_pos[t] = (q_valid && (t - b * Q) >= q_valid[b]) ? -1 : prefix_len[b] + (t - b * Q);
+    const bool pad = b >= nl || (q_valid && (t - b * Q) >= q_valid[b]);
+    tok_pos[t] = pad ? -1 : prefix_len[b] + (t - b * Q);
   } else {
     int lo = 0, hi = B;  // largest b with cu[b] <= t
     while (hi - lo > 1) {
@@ -94,9 +106,10 @@ __global__ void k_rope_table(int T, int half, double log2_base, const int32_t* t
 template <typename T>
 __global__ void k_rmsnorm(int d, float eps, float* x, const T* gain, T* out, const int32_t* rows,
                           const int32_t* n_rows_dev, int frag_mt, const float* delta, int n_delta, int64_t delta_stride,
-                          float* rscale) {
+                          float* rscale, const int32_t* live_rows) {
   __shared__ float red[16];
   int r = blockIdx.x;
+  if (live_rows && r >= *live_rows) return;
   int src = r;
   if (rows) {
     if (r >= *n_rows_dev) return;
@@ -391,6 +404,7 @@ __global__ __launch_bounds__(256) void k_attention(int Hq, int dh, int Q, const 
   __shared__ float osum[256];
   const int t = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
   const int b = tok_seq[t];
+  if (Q > 0 && q_valid && q_valid[b] < 0) return;      // the sequence is not part of this call
   const int kv_len = (Q > 0) ? prefix_len[b] + (q_valid ? min(max(q_valid[b], 0), Q) : Q) : cu[b + 1] - cu[b];
   const int kvh = h / (Hq / kv.n_kv_heads);
   const T* kbase = (const T*)kv.k;
@@ -683,9 +697,12 @@ __global__ void k_set_i32(int32_t* p, int n, int32_t v) {
 #define IS_BF16(c) ((c)->cfg.dtype == DLLM_BF16)
 
 hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
-  k_token_map<<<(g.T + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
-                                                WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
-                                                WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr);
+  const int n = g.T > g.B ? g.T : g.B;
+  k_token_map<<<(n + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
+                                              WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
+                                              WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr,
+                                              g.Q > 0 ? g.n_live : nullptr, WS(c, q_valid_eff, int32_t),
+                                              WS(c, status, int32_t) + 2);
   return hipGetLastError();
 }
 
@@ -712,9 +729,11 @@ hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
 // row-major bfloat16 output, four elements per thread and pass (d % 4 == 0)
 __global__ __launch_bounds__(256) void k_rmsnorm_row4(int d, float eps, float* x, const bf16_t* gain, bf16_t* out,
                                                       const int32_t* rows, const int32_t* n_rows_dev, const float* delta,
-                                                      int n_delta, int64_t delta_stride, float* rscale) {
+                                                      int n_delta, int64_t delta_stride, float* rscale,
+                                                      const int32_t* live_rows) {
   __shared__ float red[16];
   const int r = blockIdx.x;
+  if (live_rows && r >= *live_rows) return;
   int src = r;
   if (rows) {
     if (r >= *n_rows_dev) return;
@@ -771,14 +790,16 @@ hipError_t launch_rmsnorm(dllm_ctx* c, hipStream_t s, const void* gain, int T, c
   const dllm_config& f = c->cfg;
   if (IS_BF16(c) && f.d_model % 4 == 0)
     k_rmsnorm_row4<<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain, WS(c, xn, bf16_t), rows,
-                                     n_rows_dev, WS(c, delta, float), n_delta, c->map.lg_delta_stride, WS(c, rscale, float));
+                                     n_rows_dev, WS(c, delta, float), n_delta, c->map.lg_delta_stride, WS(c, rscale, float),
+                                     rows ? nullptr : c->rows_dev);
   else if (IS_BF16(c))
     k_rmsnorm<bf16_t><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const bf16_t*)gain,
                                         WS(c, xn, bf16_t), rows, n_rows_dev, 0, WS(c, delta, float), n_delta,
-                                        c->map.lg_delta_stride, WS(c, rscale, float));
+                                        c->map.lg_delta_stride, WS(c, rscale, float), rows ? nullptr : c->rows_dev);
   else
     k_rmsnorm<float><<<T, 256, 0, s>>>(f.d_model, f.rms_eps, WS(c, x, float), (const float*)gain,
-                                       WS(c, xn, float), rows, n_rows_dev, 0, nullptr, 0, 0, nullptr);
+                                       WS(c, xn, float), rows, n_rows_dev, 0, nullptr, 0, 0, nullptr,
+                                       rows ? nullptr : c->rows_dev);
   return hipGetLastError();
 }
 
@@ -1112,6 +1133,30 @@ hipError_t launch_eos_scan(hipStream_t s, int B, int n, const int32_t* gen, int3
 
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n) {
   k_copy_f32<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+
+// dst[i] = src[index[i]] for i < n_index (rows of row_len int32), the other rows of dst = fill; scatter: dst[index[i]]
+// = src[i] for i < n_index.  Index values outside [0, B) address nothing (gather: the row is filled).
+__global__ void k_gather_rows(int B, int row_len, const int32_t* index, const int32_t* n_index, const int32_t* src,
+                              int32_t* dst, int32_t fill, int scatter) {
+  const int i = blockIdx.x;
+  int n = n_index[0];
+  n = n < 0 ? 0 : (n > B ? B : n);
+  const int j = i < n ? index[i] : -1;
+  const bool ok = j >= 0 && j < B;
+  if (scatter) {
+    if (!ok) return;
+    for (int e = threadIdx.x; e < row_len; e += blockDim.x) dst[(int64_t)j * row_len + e] = src[(int64_t)i * row_len + e];
+  } else {
+    for (int e = threadIdx.x; e < row_len; e += blockDim.x)
+      dst[(int64_t)i * row_len + e] = ok ? src[(int64_t)j * row_len + e] : fill;
+  }
+}
+
+hipError_t launch_gather_rows(hipStream_t s, int B, int row_len, const int32_t* index, const int32_t* n_index,
+                              const int32_t* src, int32_t* dst, int32_t fill, bool scatter) {
+  k_gather_rows<<<B, row_len >= 256 ? 256 : 64, 0, s>>>(B, row_len, index, n_index, src, dst, fill, scatter ? 1 : 0);
   return hipGetLastError();
 }
 

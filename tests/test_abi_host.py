@@ -128,6 +128,13 @@ def test_calls_validate_before_launching():
     assert L.dllm_fsm_window(ctx, None, 1, 8, 32, 2, p, p, p, -1, p, p, p, p, p) == E               # pad token in the vocabulary
     assert L.dllm_fsm_window(ctx, None, 1, 8, 32, 2, p, p, None, 0, p, p, p, p, p) == E
     assert L.dllm_fsm_scatter(ctx, None, 1, 8, 32, 2, p, p, None, p) == E
+    # batch compaction and the step over the live sequences
+    assert L.dllm_gather_rows(ctx, None, 2, 4, p, p, p, p, 0) == E                                   # src and dst must differ
+    assert L.dllm_gather_rows(ctx, None, 2, 0, p, p, p, p + 64, 0) == E
+    assert L.dllm_gather_rows(ctx, None, 2, 4, p, None, p, p + 64, 0) == E
+    assert L.dllm_scatter_rows(ctx, None, 0, 4, p, p, p, p + 64) == E
+    assert L.dllm_denoise_step_live(ctx, None, 1, 32, 64, p, p, None, None, p, p, p, None) == E      # the live count is required
+    assert L.dllm_denoise_step_live(ctx, None, 3, 32, 64, p, p, None, p, p, p, p, None) == S
     # trajectory recording, noisy sequences, early stop
     assert L.dllm_unmask_traced(ctx, None, 1, 32, 32, p, p, p, 2.0, 0, 1, 1, None, None, None) == E   # order is required
     assert L.dllm_noisy_sequence(ctx, None, 1, 32, p, p, p, 8, 1.5, p) == E                         # 0 <= t <= 1

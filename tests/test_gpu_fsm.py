@@ -332,3 +332,90 @@ def test_batched_multiblock_rounds_with_ragged_windows():
     assert checked >= 6 and batched_wide >= 2
     assert eng.read_status() == 0
     eng.close()
+
+
+@pytest.mark.parametrize("ms_name,Bn,Q", [("tiny", 3, 16), ("small", 2, 32), ("small", 4, 32), ("small", 10, 32)])
+def test_early_stop_compaction_and_step_over_the_live_sequences(ms_name, Bn, Q):
+    """Section 3.2, early stopping: dllm_eos_scan lists the live sequences, dllm_gather_rows brings their tokens,
+    prefix lengths and block-table rows to the front, dllm_denoise_step_live runs the step over the live count (a
+    device value; B stays the launch size), dllm_scatter_rows puts the results back.  Against the oracle: the live
+    list and the compacted arrays bit for bit, the step of every live sequence as its own oracle step, and for the
+    finished ones nothing: own tokens reported, nothing written to their cache.  Batches of 2 (at most 64 rows), 4
+    (128 rows) and 10 sequences (320 rows) take the three GEMM forms of a bfloat16 step."""
+    from tests.test_gpu_bf16 import SMALL
+    ms = TINY if ms_name == "tiny" else SMALL
+    dtype = "f32" if ms_name == "tiny" else "bf16"
+    W, ST = (None, None) if dtype == "f32" else (synth.as_float, synth.round_bf16)
+    w = synth.Weights(ms, 3)
+    rng = np.random.default_rng(11)
+    lens = [int(x) for x in rng.integers(20, 60, Bn)]
+    mp, pt = 8, 16
+    eng = H.make_engine(ms, w, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+                        max_tokens=sum(lens))
+    prompts = [synth.random_tokens(ms, 70 + b, lens[b]) for b in range(Bn)]
+    table = H.identity_table(eng, Bn)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), eng.i32(table), None, total_tokens=int(cu[-1]),
+                   max_seqlen=max(lens))
+    eos = 5
+    gen = np.stack([synth.masked_block(ms, 80 + b, Q, Q // 2) for b in range(Bn)]).astype(np.int32)
+    gen[gen == eos] = 6
+    finished_want = [b for b in range(Bn) if b % 3 == 1]
+    for b in finished_want:                              # an EOS with nothing masked before it
+        gen[b, :3] = [11, 12, eos]
+    live = O.live_sequences(gen, eos, ms.mask_id)
+    assert live == [b for b in range(Bn) if b not in finished_want] and 0 < len(live) < Bn
+    dev = eng.device
+    fin = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    act = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    nact = torch.zeros(1, dtype=torch.int32, device=dev)
+    eng.eos_scan(eng.i32(gen), eos, fin, None, act, nact)
+    assert int(nact) == len(live) and act.cpu().numpy()[:len(live)].tolist() == live
+    # compaction on the device == the oracle's
+    g_gen, g_len, g_tab = eng.i32(gen), eng.i32(np.array(lens)[:, None]), eng.i32(table)
+    c_gen, c_len, c_tab = torch.zeros_like(g_gen), torch.zeros_like(g_len), torch.zeros_like(g_tab)
+    eng.gather_rows(act, nact, g_gen, c_gen, 7)
+    eng.gather_rows(act, nact, g_len, c_len, 0)
+    eng.gather_rows(act, nact, g_tab, c_tab, -1)
+    assert (c_gen.cpu().numpy() == O.gather_rows(gen, live, 7)).all()
+    assert (c_len.cpu().numpy() == O.gather_rows(np.array(lens)[:, None], live, 0)).all()
+    assert (c_tab.cpu().numpy() == O.gather_rows(table, live, -1)).all()
+    # sentinel K/V in the in-flight positions of every sequence: only live ones may be overwritten
+    for l in range(ms.n_layers):
+        for which in (0, 1):
+            slab = eng.kv_slab(l, which)
+            for b in range(Bn):
+                for p in range(lens[b], lens[b] + Q):
+                    slab[int(table[b][p // pt]), :, p % pt, :] = 3.0
+    cand = torch.full((Bn, Q), -5, dtype=torch.int32, device=dev)
+    conf = torch.full((Bn, Q), -5.0, dtype=torch.float32, device=dev)
+    ent = torch.full((Bn, Q), -5.0, dtype=torch.float32, device=dev)
+    eng.denoise_step_live(c_gen, c_len.view(-1), None, nact, c_tab, cand, conf, ent, max_prefix_len=max(lens))
+    assert eng.read_status() == 0
+    c, f, e = cand.cpu().numpy(), conf.cpu().numpy(), ent.cpu().numpy()
+    n_dec = 0
+    for i, b in enumerate(live):
+        ck, cv = O.prefill(w, prompts[b], widen=W, store=ST)
+        r = O.denoise_step(w, gen[b], ck, cv, 0.9, 1, widen=W, store=ST)
+        n_dec += H.check_step_outputs(ms, r, gen[b] == ms.mask_id, c[i], f[i], e[i], dtype)
+        got = H.gather_cache(eng, table[b], lens[b] + Q, ms.n_layers - 1, 0)
+        assert not (got[lens[b]:] == 3.0).all()                      # the live sequence's rows were cached
+    assert n_dec >= len(live) * Q // 8
+    for i in range(len(live), Bn):                                     # rows past the live count: filled tokens reported
+        assert (c[i] == 7).all() and (f[i] == 1).all()
+    for b in finished_want:
+        for l in range(ms.n_layers):
+            for which in (0, 1):
+                got = H.gather_cache(eng, table[b], lens[b] + Q, l, which)
+                assert (got[lens[b]:] == 3.0).all()                    # nothing of a finished sequence was touched
+    # unmask on the compacted batch, then back to the original order
+    eng.unmask(c_gen, cand, conf, 0.9, 1)
+    back = eng.i32(gen)
+    eng.scatter_rows(act, nact, c_gen, back)
+    want = gen.copy()
+    for i, b in enumerate(live):
+        want[b] = c_gen.cpu().numpy()[i]
+    assert (back.cpu().numpy() == want).all()
+    for b in finished_want:
+        assert (back.cpu().numpy()[b] == gen[b]).all()
+    eng.close()

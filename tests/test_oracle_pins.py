@@ -659,6 +659,29 @@ def test_eos_state():
 
 # ------------------------------------------------------------------ stored trajectory
 
+def test_live_list_and_batch_compaction_on_a_hand_worked_batch():
+    """Five sequences (mask id 9, end-of-sequence id 7): finished are those with an EOS and no [MASK] before it."""
+    gens = np.array([[1, 2, 9, 9],      # live: masks left
+                     [3, 7, 9, 9],      # finished: EOS at 1, nothing masked before it
+                     [9, 7, 4, 4],      # live: the EOS is decoded ahead of a masked position
+                     [5, 5, 5, 7],      # finished
+                     [6, 6, 6, 6]])     # live: complete but no EOS
+    live = O.live_sequences(gens, 7, 9)
+    assert live == [0, 2, 4]
+    lens = np.array([[10], [20], [30], [40], [50]])
+    got = O.gather_rows(gens, live, 0)
+    assert got.tolist() == [[1, 2, 9, 9], [9, 7, 4, 4], [6, 6, 6, 6], [0, 0, 0, 0], [0, 0, 0, 0]]
+    assert O.gather_rows(lens, live, -1).ravel().tolist() == [10, 30, 50, -1, -1]
+    # the way back puts updated live rows where they came from and leaves the finished ones alone
+    upd = got.copy()
+    upd[:3, 2] = [8, 8, 8]
+    back = O.scatter_rows(gens, live, upd[:3])
+    assert back.tolist() == [[1, 2, 8, 9], [3, 7, 9, 9], [9, 7, 8, 4], [5, 5, 5, 7], [6, 6, 8, 6]]
+    # gather then scatter of unchanged rows is the identity; an empty live list fills everything
+    assert (O.scatter_rows(gens, live, O.gather_rows(gens, live, 0)[:3]) == gens).all()
+    assert (O.gather_rows(gens, [], 3) == 3).all()
+
+
 def test_oracle_reproduces_the_stored_tiny_trajectory():
     """tests/golden/tiny_decode_trajectory.json was written by tests/golden/make_golden.py from the oracle alone
     (the paper prints no value for this path); the oracle must still produce it: unmask order and token ids
