@@ -69,7 +69,7 @@ MFMA_PEAK_TFLOPS = 2500.0
 
 
 def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev, theta=0.45, add_at=0.1, full_at=0.95,
-                          delay=1):
+                          delay=1, refresh_every=32):
     """One generation with the multi-block decoding of Section 3.2 (entropy threshold 0.45 nats, block-add at 10 %,
     fully-activate at 95 %, one stabilizing round): the block states live on the device (dllm_fsm_update), the host
     reads four integers per round to pick the window and the kind of forward.  With random weights the entropies
@@ -83,6 +83,10 @@ def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev
     floor = torch.full((1, NB), -1, dtype=torch.int32, device=dev)
     floor[0, 0] = 1
     summary = torch.zeros(1, 4, dtype=torch.int32, device=dev)
+    since = torch.zeros(1, dtype=torch.int32, device=dev)           # cached rounds since the last forward without cache
+    nocache = torch.zeros(1, dtype=torch.int32, device=dev)         # the next forward must not use the cache
+    n_commit = torch.zeros(1, dtype=torch.int32, device=dev)        # positions the cache holds after such a forward
+    base = eng.i32([P])
     Qmax = 4 * Q
     cand = torch.zeros(1, Qmax, dtype=torch.int32, device=dev)
     conf = torch.zeros(1, Qmax, dtype=torch.float32, device=dev)
@@ -103,14 +107,9 @@ def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev
         window = gen[:, lo * Q:(hi + 1) * Q]
         fl = floor[:, lo:hi + 1]
         if stab:
-            st, ct = state[0].tolist(), counter[0].tolist()
-            for b in range(NB):                                    # blocks this round will complete (host mirror)
-                if st[b] == 3 and ct[b] - 1 <= 0 and (b == 0 or st[b - 1] == 4):
-                    st[b] = 4
             n_tok = P + (hi + 1) * Q
             seq = torch.cat([prompt, gen[0, :(hi + 1) * Q]])
-            eng.refresh_cache(seq, eng.i32([0, n_tok]), table, eng.i32([P + st.count(4) * Q]), c2, f2, e2,
-                              total_tokens=n_tok, max_seqlen=n_tok)
+            eng.refresh_cache(seq, eng.i32([0, n_tok]), table, n_commit, c2, f2, e2, total_tokens=n_tok, max_seqlen=n_tok)
             s0 = P + lo * Q
             eng.unmask_blocks(window, c2[s0:n_tok][None], e2[s0:n_tok][None], theta, fl, True, Q)
             nocache_rounds += 1
@@ -118,8 +117,10 @@ def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev
             eng.denoise_step(window, eng.i32([P + lo * Q]), table, cand[:, :nw * Q], conf[:, :nw * Q], ent[:, :nw * Q],
                              max_prefix_len=P + lo * Q)
             eng.unmask_blocks(window, cand[:, :nw * Q], ent[:, :nw * Q], theta, fl, True, Q)
-        eng.fsm_update(gen, state, counter, Q, add_at, full_at, delay, bool(stab), floor, summary)
-        lo, hi, stab, _ = summary[0].tolist()
+        eng.fsm_update(gen, state, counter, Q, add_at, full_at, delay, None, floor, summary)
+        eng.fsm_plan(state, counter, base, Q, refresh_every, since, nocache, n_commit)
+        lo, hi, _, _ = summary[0].tolist()
+        stab = int(nocache.item())
         rounds += 1
         wide_rounds += nw > 1
         if rounds > 8 * NB * Q:
@@ -130,7 +131,7 @@ def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev
     return {"tokens": NB * Q, "forwards": rounds, "forwards_without_cache": nocache_rounds,
             "forwards_with_more_than_one_block": wide_rounds, "seconds": sec, "tokens_per_s": NB * Q / sec,
             "tokens_per_forward": NB * Q / rounds, "rule": f"entropy <= {theta}", "block_add": add_at,
-            "fully_activate": full_at, "stabilizing_rounds": delay}
+            "fully_activate": full_at, "stabilizing_rounds": delay, "periodic_refresh_every": refresh_every}
 
 
 def large_batch(args, torch, np, synth, Engine, dev):

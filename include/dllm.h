@@ -234,6 +234,21 @@ int dllm_fsm_update(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_
  * counts: running that forward (dllm_refresh_cache with the step outputs) for those sequences before this call
  * is the caller's part. */
 
+/* The plan of the next round of multi-block decoding, per sequence, from the block states dllm_fsm_update has left
+ * (Section 3.2: forward passes without the cache while a block is Completed but Stabilizing, which refresh the previous
+ * caches, and a periodic refresh that updates the cache every few rounds).  On entry nocache[b] tells whether the
+ * round just done ran without the cache (0 before the first round); rounds_since[b] counts the cached rounds since
+ * the last forward without cache and is updated.  On exit nocache[b] = 1 if the next forward must not use the cache:
+ * a block is Stabilizing, or refresh_every > 0 and rounds_since[b] >= refresh_every.  n_commit_next[b] = base_len[b]
+ * + block_len * (blocks that are Completed when the transitions of such a round are done: the Completed ones and the
+ * Stabilizing ones behind them whose count-down ends with it) - the n_commit of the dllm_refresh_cache call of that
+ * round, whose tokens are base_len[b] + (last active block + 1) * block_len long.
+ *   state, counter dev int32 [B, n_blocks]; base_len dev int32 [B] or NULL (0); rounds_since, nocache dev int32 [B]
+ *   in/out; n_commit_next dev int32 [B]; refresh_every >= 0 (0: no periodic refresh). */
+int dllm_fsm_plan(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, const int32_t *state,
+                  const int32_t *counter, const int32_t *base_len, int refresh_every, int32_t *rounds_since,
+                  int32_t *nocache, int32_t *n_commit_next);
+
 /* A denoise step whose sequences have different numbers of query rows (multi-block decoding: the windows of
  * the sequences of a batch differ): as dllm_denoise_step, but rows j >= q_valid[b] of sequence b are padding.
  * Padding rows are no keys for the other rows (sequence b attends to prefix_len[b] + q_valid[b] keys), get no

@@ -329,16 +329,41 @@ def fsm_update(state, counter, filled, block_len, add_at, full_at, delay, nocach
     return st, ct
 
 
+def fsm_plan(state, counter, block_len, base_len, refresh_every, since, was_nocache):
+    """What the next round of one sequence looks like, from its block states after the transitions of the round just
+    done.  since: cached rounds since the last forward without cache, before the round just done; was_nocache: that
+    round's forward did not use the cache.  Returns (since updated, whether the next forward must skip the cache,
+    how many positions the cache holds after such a forward).
+    The next forward skips the cache if a block is Stabilizing, or if refresh_every > 0 cached rounds have passed
+    since the last one that did (the periodic refresh of Section 3.2: the cache is updated every few rounds).  A
+    forward without cache rewrites the cache of the prompt and of every block that is Completed once its round's
+    transitions are done: the Completed blocks, and the Stabilizing ones behind them whose count-down ends with it."""
+    since = 0 if was_nocache else since + 1
+    nocache = any(s == STABILIZING for s in state) or (refresh_every > 0 and since >= refresh_every)
+    done = 0
+    for b, s in enumerate(state):
+        if s == COMPLETED or (s == STABILIZING and counter[b] - 1 <= 0):
+            done += 1
+        else:
+            break
+    return since, nocache, base_len + done * block_len
+
+
 def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", add_at=0.1, full_at=0.95,
-                      delay=1, widen=None, n_layers=None, store=None, record=None, max_rounds=None):
+                      delay=1, widen=None, n_layers=None, store=None, record=None, max_rounds=None,
+                      refresh_every=0):
     """Multi-block decoding of n_blocks blocks after the prompt.  Every round: one forward over the
     window of Activated / Fully-Activated blocks (against the cache, or without it while a block is
     Stabilizing, in which case the cache is rewritten from that forward), selection per block with
     a floor of 0 (Activated) or 1 (Fully-Activated), then the state transitions.
+    refresh_every > 0: the periodic refresh, a forward without cache after that many cached rounds in a row.
+    Every forward without cache rewrites the cache of the prompt and of the blocks Completed at the end of its round
+    ("forward passes without using the KV cache and refresh previous caches", Section 3.2).
     Returns (tokens of prompt + generation, number of forwards)."""
     ms = model.ms
     prompt = np.asarray(prompt, dtype=np.int64)
     P = len(prompt)
+    since = 0                                                           # cached rounds since the last forward without cache
     gen = np.full(n_blocks * block_len, ms.mask_id, dtype=np.int64)
     state = [INACTIVE] * n_blocks
     counter = [0] * n_blocks
@@ -351,7 +376,8 @@ def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", a
         assert rounds < limit, "multi-block decoding does not terminate"
         active = [b for b in range(n_blocks) if state[b] in (ACTIVATED, FULLY_ACTIVATED)]
         lo, hi = active[0], active[-1]
-        nocache = any(s == STABILIZING for s in state)
+        nocache = any(s == STABILIZING for s in state) or (refresh_every > 0 and since >= refresh_every)
+        since = 0 if nocache else since + 1
         if nocache:
             seq = np.concatenate([prompt, gen[:(hi + 1) * block_len]])
             logits_all, Ks, Vs, _ = forward_full(model, seq, n_layers, widen, store=store)
@@ -377,13 +403,14 @@ def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", a
         filled = [int((gen[b * block_len:(b + 1) * block_len] != ms.mask_id).sum()) for b in range(n_blocks)]
         new_state, counter = fsm_update(state, counter, filled, block_len, add_at, full_at, delay, nocache)
         n_done_new = sum(1 for s in new_state if s == COMPLETED)
-        if nocache and n_done_new > n_done:
+        if nocache:
             # the blocks that became Completed take their K/V from this round's no-cache forward, which
             # also rewrites the cache of everything before them
             n = P + n_done_new * block_len
             ck, cv = [k[:n] for k in Ks], [v[:n] for v in Vs]
         if record is not None:
             record.append({"before": before, "lo": lo, "hi": hi, "nocache": nocache, "state": list(state),
+                           "n_cached": P + n_done_new * block_len if nocache else P + n_done * block_len,
                            "cand": cand, "conf": conf, "entropy": ent, "chosen": chosen,
                            "state_after": list(new_state), "counter_after": list(counter)})
         state, n_done = new_state, n_done_new

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
         "dllm_denoise_step_live": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "dllm_gather_rows": (i32, [vp, vp, i32, i32, vp, vp, vp, vp, i32]),
         "dllm_scatter_rows": (i32, [vp, vp, i32, i32, vp, vp, vp, vp]),
+        "dllm_fsm_plan": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp]),
         "dllm_fsm_window": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]),
         "dllm_fsm_scatter": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_unmask_traced": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]),
@@ -271,6 +272,12 @@ class Engine:
         B = src.shape[0]
         self._check(lib().dllm_scatter_rows(self.ctx, self._stream(), B, src.numel() // B, _ptr(index), _ptr(n_index),
                                             _ptr(src), _ptr(dst)))
+
+    def fsm_plan(self, state, counter, base_len, block_len, refresh_every, rounds_since, nocache, n_commit_next):
+        B, NB = state.shape
+        self._check(lib().dllm_fsm_plan(self.ctx, self._stream(), B, NB, block_len, _ptr(state), _ptr(counter),
+                                        _ptr(base_len), refresh_every, _ptr(rounds_since), _ptr(nocache),
+                                        _ptr(n_commit_next)))
 
     def fsm_window(self, gen_tokens, state, base_len, block_len, W, pad_token, win_tokens, win_floor, prefix_len,
                    q_valid, win_lo):

@@ -679,6 +679,17 @@ extern "C" int dllm_fsm_update(dllm_ctx* c, void* stream, int B, int n_blocks, i
   return DLLM_OK;
 }
 
+extern "C" int dllm_fsm_plan(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, const int32_t* state,
+                             const int32_t* counter, const int32_t* base_len, int refresh_every, int32_t* rounds_since,
+                             int32_t* nocache, int32_t* n_commit_next) {
+  if (!c || !state || !counter || !rounds_since || !nocache || !n_commit_next) return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || refresh_every < 0) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || block_len > (1 << 20)) return DLLM_ESHAPE;
+  TRY(launch_fsm_plan((hipStream_t)stream, B, n_blocks, block_len, state, counter, base_len, refresh_every, rounds_since,
+                      nocache, n_commit_next), "fsm_plan");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_fsm_window(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, int W,
                                const int32_t* gen_tokens, const int32_t* state, const int32_t* base_len,
                                int32_t pad_token, int32_t* win_tokens, int32_t* win_floor, int32_t* prefix_len,

@@ -253,6 +253,9 @@ hipError_t launch_eos_scan(hipStream_t s, int B, int n, const int32_t* gen, int3
 hipError_t launch_fsm_update(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* gen, int32_t mask_id,
                              int32_t* state, int32_t* counter, int need_add, int need_full, int delay, int nocache_round,
                              int32_t* floor_next, int32_t* summary);
+hipError_t launch_fsm_plan(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* state,
+                           const int32_t* counter, const int32_t* base_len, int refresh_every, int32_t* rounds_since,
+                           int32_t* nocache, int32_t* n_commit_next);
 hipError_t launch_copy_f32(hipStream_t s, const float* src, float* dst, size_t n);
 hipError_t launch_gather_rows(hipStream_t s, int B, int row_len, const int32_t* index, const int32_t* n_index,
                               const int32_t* src, int32_t* dst, int32_t fill, bool scatter);

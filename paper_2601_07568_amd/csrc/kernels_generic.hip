@@ -1006,6 +1006,37 @@ __global__ __launch_bounds__(64) void k_fsm_update(int n_blocks, int block_len, 
   }
 }
 
+// The next round of every sequence from its block states: cached rounds since the last forward without cache, whether
+// the next forward must skip the cache (a Stabilizing block, or the periodic refresh is due), and how many positions
+// the cache holds after such a forward (prompt + the blocks Completed once its round's transitions are done).
+__global__ void k_fsm_plan(int B, int n_blocks, int block_len, const int32_t* state, const int32_t* counter,
+                           const int32_t* base_len, int refresh_every, int32_t* rounds_since, int32_t* nocache,
+                           int32_t* n_commit_next) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int32_t* st = state + (int64_t)b * n_blocks;
+  const int32_t* ct = counter + (int64_t)b * n_blocks;
+  const int since = nocache[b] != 0 ? 0 : rounds_since[b] + 1;     // on entry nocache[b] tells how the round just done ran
+  rounds_since[b] = since;
+  bool stab = false;
+  for (int k = 0; k < n_blocks; ++k) stab |= st[k] == DLLM_BLOCK_STABILIZING;
+  int done = 0;
+  for (int k = 0; k < n_blocks; ++k) {
+    if (st[k] == DLLM_BLOCK_COMPLETED || (st[k] == DLLM_BLOCK_STABILIZING && ct[k] - 1 <= 0)) ++done;
+    else break;
+  }
+  nocache[b] = (stab || (refresh_every > 0 && since >= refresh_every)) ? 1 : 0;
+  n_commit_next[b] = (base_len ? base_len[b] : 0) + done * block_len;
+}
+
+hipError_t launch_fsm_plan(hipStream_t s, int B, int n_blocks, int block_len, const int32_t* state,
+                           const int32_t* counter, const int32_t* base_len, int refresh_every, int32_t* rounds_since,
+                           int32_t* nocache, int32_t* n_commit_next) {
+  k_fsm_plan<<<(B + 63) / 64, 64, 0, s>>>(B, n_blocks, block_len, state, counter, base_len, refresh_every, rounds_since,
+                                         nocache, n_commit_next);
+  return hipGetLastError();
+}
+
 // Window of a cached round, per sequence: the run of active blocks (at most W), as the tokens, floors,
 // prefix length and valid-row count that dllm_denoise_step_var / dllm_unmask_blocks take.  A sequence that
 // has a stabilizing block (its round must not use the cache) or no active block gets an empty window.

@@ -603,6 +603,59 @@ def test_multiblock_invariants(theta, delay):
         assert rounds <= 4 + 1
 
 
+def test_round_plan_on_hand_made_states():
+    """fsm_plan: forward type and cache length of the next round, on states written by hand (block length 4, prompt 10)."""
+    I, A, F, S, C = O.INACTIVE, O.ACTIVATED, O.FULLY_ACTIVATED, O.STABILIZING, O.COMPLETED
+    # nothing stabilizing, no periodic refresh: cached round, count of cached rounds goes up
+    assert O.fsm_plan([C, F, A, I], [0, 0, 0, 0], 4, 10, 0, 2, False) == (3, False, 14)
+    # a stabilizing block whose count-down ends with the next no-cache round joins the cache: prompt + 2 blocks
+    assert O.fsm_plan([C, S, F, I], [0, 1, 0, 0], 4, 10, 0, 0, False) == (1, True, 18)
+    # ... but not one that needs two more rounds, and nothing behind it either
+    assert O.fsm_plan([C, S, S, I], [0, 2, 1, 0], 4, 10, 0, 5, True) == (0, True, 14)
+    # two in a row ending together
+    assert O.fsm_plan([S, S, F, A], [1, 0, 0, 0], 4, 10, 0, 0, True) == (0, True, 18)
+    # periodic refresh: due after 3 cached rounds in a row, whatever the block states; the count restarts after it
+    assert O.fsm_plan([C, F, A, I], [0, 0, 0, 0], 4, 10, 3, 1, False) == (2, False, 14)
+    assert O.fsm_plan([C, F, A, I], [0, 0, 0, 0], 4, 10, 3, 2, False) == (3, True, 14)
+    assert O.fsm_plan([C, F, A, I], [0, 0, 0, 0], 4, 10, 3, 3, True) == (0, False, 14)
+
+
+@pytest.mark.parametrize("refresh_every", [0, 1, 2, 5])
+def test_periodic_refresh_schedule_and_plan_agree_with_the_decode(refresh_every):
+    """Periodic refresh (Section 3.2: the cache is updated every few rounds): between two forwards without cache
+    there are at most refresh_every cached ones, a stabilizing block still forces one, and the round plan computed
+    from the recorded states alone predicts every next round's forward type and cache length."""
+    model = small_model()
+    ms = model.ms
+    toks = synth.random_tokens(ms, 12, 16)
+    rec = []
+    seq, rounds = O.decode_multiblock(model, toks[:7], 4, 4, 0.5, "entropy", add_at=0.25, full_at=0.75, delay=1,
+                                      record=rec, refresh_every=refresh_every)
+    assert (seq != ms.mask_id).all() and rounds == len(rec)
+    run = 0
+    since, was = 0, False
+    for i, r in enumerate(rec):
+        stab = O.STABILIZING in r["state"]
+        if refresh_every == 0:
+            assert r["nocache"] == stab
+        else:
+            assert r["nocache"] == (stab or run >= refresh_every)
+        run = 0 if r["nocache"] else run + 1
+        assert run <= max(refresh_every, 10 ** 9 if refresh_every == 0 else refresh_every)
+        since, nxt, n_commit = O.fsm_plan(r["state_after"], r["counter_after"], 4, 7, refresh_every, since, r["nocache"])
+        if i + 1 < len(rec):
+            assert nxt == rec[i + 1]["nocache"]
+            if nxt:
+                assert n_commit == rec[i + 1]["n_cached"]
+    if refresh_every == 1:
+        # every other round at least is a forward without cache
+        assert sum(r["nocache"] for r in rec) >= len(rec) // 2
+    # never re-mask, whatever the refresh schedule
+    for a, b in zip(rec, rec[1:]):
+        keep = a["before"] != ms.mask_id
+        assert (b["before"][keep] == a["before"][keep]).all()
+
+
 # ------------------------------------------------------------------ teacher trajectory, noisy sequence, early stop
 
 def test_teacher_trajectory_is_a_one_token_per_step_order():
