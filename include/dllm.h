@@ -67,6 +67,10 @@ extern "C" {
 #define DLLM_STATUS_BAD_PAGE  2  /* a block-table entry outside [0, n_pages), or a position beyond
                                     max_pages_per_seq * page_tokens (access skipped)              */
 #define DLLM_STATUS_ROWS_CAP  4  /* more masked rows than max_batch * max_q in a refresh call      */
+#define DLLM_STATUS_BAD_LENGTH 8 /* a device-resident length disagrees with the host value that sized the
+                                    launch: prefix_len[b] outside [0, max_prefix_len], a sequence longer than
+                                    max_seqlen, cu_seqlens[0] != 0 or cu_seqlens[B] != total_tokens (the
+                                    length was clamped; rows left without a sequence are skipped)          */
 
 typedef struct dllm_ctx dllm_ctx; /* opaque, host memory; holds descriptors only */
 

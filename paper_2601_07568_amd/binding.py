@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libdllm.so")
 
 DLLM_OK, DLLM_EINVAL, DLLM_ESHAPE, DLLM_ENOSPACE, DLLM_EHIP = 0, -1, -2, -3, -4
 DLLM_F32, DLLM_BF16 = 0, 1
-STATUS_BAD_TOKEN, STATUS_BAD_PAGE, STATUS_ROWS_CAP = 1, 2, 4
+STATUS_BAD_TOKEN, STATUS_BAD_PAGE, STATUS_ROWS_CAP, STATUS_BAD_LENGTH = 1, 2, 4, 8
 
 
 class Config(C.Structure):

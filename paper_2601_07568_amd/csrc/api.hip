@@ -69,6 +69,7 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   if (m->attn_rows < 65536) m->attn_rows = 65536;
   m->attn_part = take(c->dtype == DLLM_BF16 ? (size_t)m->attn_rows * (c->head_dim + 2) * 4 : 0);
   if (c->dtype != DLLM_BF16) m->attn_rows = 0;
+  m->len_safe = take(((size_t)c->max_batch + 1) * 4);
   m->q_valid_eff = take((size_t)c->max_batch * 4);
   m->rscale = take(t_max * 4);
   m->ss = take((size_t)64 * ((((size_t)c->d_model + 15) / 16 + 3) / 4 * 4) * 4);
@@ -139,6 +140,8 @@ extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_we
   c->map = m;
   c->kernel_mode = 0;
   if (cfg->dtype == DLLM_BF16) {
+    // raising two kernels' LDS limits; a failure (e.g. no device in this process) is not an error of the call: the
+    // launchers check the flags these leave and take the kernels that need no raised limit
     (void)init_gemm_t256();      // without it the 128-row kernels serve every size
     (void)init_attn_kernels();   // without it every wave of the batch-1 attention writes its own partial
   }
@@ -240,8 +243,20 @@ extern "C" int dllm_profile_enable(dllm_ctx* c, int on) {
     c->prof_ev = (hipEvent_t*)calloc(2 * cap, sizeof(hipEvent_t));
     c->prof_cls = (int*)calloc(cap, sizeof(int));
     c->prof_bytes = (double*)calloc(cap, sizeof(double));
-    if (!c->prof_ev || !c->prof_cls || !c->prof_bytes) return DLLM_ENOSPACE;
-    for (int i = 0; i < 2 * cap; ++i) TRY(hipEventCreate(&c->prof_ev[i]), "hipEventCreate");
+    if (!c->prof_ev || !c->prof_cls || !c->prof_bytes) {
+      free(c->prof_ev); free(c->prof_cls); free(c->prof_bytes);
+      c->prof_ev = nullptr; c->prof_cls = nullptr; c->prof_bytes = nullptr;
+      return DLLM_ENOSPACE;
+    }
+    for (int i = 0; i < 2 * cap; ++i) {
+      hipError_t e = hipEventCreate(&c->prof_ev[i]);
+      if (e != hipSuccess) {
+        c->prof_cap = (i + 1) / 2;          // prof_free destroys 2 * prof_cap events: only those that exist
+        for (int j = 2 * c->prof_cap; j < i; ++j) (void)hipEventDestroy(c->prof_ev[j]);
+        prof_free(c);
+        return hip_fail(c, e, "hipEventCreate");
+      }
+    }
     c->prof_cap = cap;
   }
   c->prof_n = 0;
@@ -302,11 +317,15 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
 
 static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g0, int n_layers_run, const HeadOut* head,
                        float* logits_out, float* hidden_out) {
+  // the first launches check the device-resident lengths against the host values that size the launches and leave
+  // clamped copies in the workspace: every kernel after them addresses memory with those
   TRY(launch_token_map(c, s, g0), "token_map");
-  if (!g0.n_live) return run_forward_inner(c, s, g0, n_layers_run, head, logits_out, hidden_out);
-  // a step over the live sequences only: the token map has left the valid rows per sequence (-1 for the sequences
-  // past the live count) and the number of live rows in the workspace
   StepGeom g = g0;
+  if (g.Q > 0) g.prefix_len = WSP(c, len_safe, int32_t);
+  else g.cu_seqlens = WSP(c, len_safe, int32_t);
+  if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+  // a step over the live sequences only: the valid rows per sequence (-1 for the sequences past the live count) and
+  // the number of live rows are in the workspace as well
   g.q_valid = WSP(c, q_valid_eff, int32_t);
   c->rows_dev = WSP(c, status, int32_t) + 2;
   const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);

@@ -145,6 +145,7 @@ struct Workspace {
   size_t lm_part;      // float [Rmax, n_vtiles, 4] per-tile (max, argmax, sumexp, sum e*z)
   size_t attn_part;    // float [attn_rows, dh] partial outputs, then [attn_rows, 2] (max, sum) of split-KV units
   int64_t attn_rows;   // capacity in (token, head, unit) rows
+  size_t len_safe;     // int32 [max_batch + 1]         checked prefix lengths (step) or sequence offsets (packed forward)
   size_t q_valid_eff;  // int32 [max_batch]             valid rows per sequence of a step with a live count (-1: not live)
   size_t rscale;       // float [Tmax]                  row normalisation factors of the current GEMM input (bfloat16 models)
   size_t ss;           // float [64][d/16 rounded up to 4]   partial sums of squares of the rows of the skinny path's GEMM input

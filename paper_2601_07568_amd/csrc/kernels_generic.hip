@@ -40,40 +40,69 @@ __device__ inline float block_max(float v, float* red) {
 
 // ------------------------------------------------------------------------------------------
 // token map: sequence and position of every row of the forward
-// With a live count (steps only) the valid rows per sequence are written out as well: q_valid[b] (or Q) for the
-// live sequences b < n_live[0], -1 for the others (every row of theirs is padding and their attention is skipped),
-// and the number of rows up to the last live sequence for the GEMMs that can skip rows.
-__global__ void k_token_map(int T, int B, int Q, const int32_t* prefix_len, const int32_t* cu,
-                            int32_t* tok_seq, int32_t* tok_pos, int32_t* cu_pad, const int32_t* q_valid,
-                            const int32_t* n_live, int32_t* q_valid_eff, int32_t* rows_dev) {
+// Sequence lengths of a call, checked before anything addresses memory with them (one workgroup, first launch of
+// every forward).  Steps: len_safe[b] = prefix_len[b] clamped to [0, max_len] (max_len = the host's max_prefix_len).
+// Packed forwards: len_safe[0..B] = the cu_seqlens with every length clamped to [0, max_len] (max_len = the host's
+// max_seqlen) and the total to T; cu_pad = the padded column offsets of the packed K/V scratch.  Any clamp, and a
+// packed total different from T, sets DLLM_STATUS_BAD_LENGTH.  With a live count (steps only): the valid rows per
+// sequence (q_valid[b] or Q for the live sequences b < n_live[0], -1 for the others: every row of theirs is padding
+// and their attention is skipped) and the number of rows up to the last live sequence for the GEMMs that can skip rows.
+__global__ void k_seq_check(int T, int B, int Q, int max_len, const int32_t* prefix_len, const int32_t* cu,
+                            int32_t* len_safe, int32_t* cu_pad, const int32_t* q_valid, const int32_t* n_live,
+                            int32_t* q_valid_eff, int32_t* status) {
+  __shared__ int s_bad;
+  if (threadIdx.x == 0) s_bad = 0;
+  __syncthreads();
+  if (Q > 0) {
+    int nl = B;
+    if (n_live) { nl = n_live[0]; nl = nl < 0 ? 0 : (nl > B ? B : nl); }
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+      const int p = prefix_len[b];
+      const int pc = p < 0 ? 0 : (p > max_len ? max_len : p);
+      if (pc != p && b < nl) s_bad = 1;
+      len_safe[b] = pc;
+      if (n_live) q_valid_eff[b] = b < nl ? (q_valid ? q_valid[b] : Q) : -1;
+    }
+    if (n_live && threadIdx.x == 0) status[2] = nl * Q;
+  } else if (threadIdx.x == 0) {
+    int acc = 0, pad = 0, bad = cu[0] != 0;
+    len_safe[0] = 0;
+    for (int b = 0; b < B; ++b) {
+      int len = cu[b + 1] - cu[b];
+      if (len < 0 || len > max_len) { bad = 1; len = len < 0 ? 0 : max_len; }
+      if (acc + len > T) { bad = 1; len = T - acc; }
+      cu_pad[b] = pad;
+      acc += len;
+      pad += (len + 31) / 32 * 32;
+      len_safe[b + 1] = acc;
+    }
+    cu_pad[B] = pad;
+    if (acc != T) bad = 1;
+    if (bad) s_bad = 1;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && s_bad) atomicOr(status, DLLM_STATUS_BAD_LENGTH);
+}
+
+// token map: sequence and position of every row of the forward, from the checked lengths.  Rows of a packed forward
+// past the last sequence's end and padding rows of a step have no position (-1): nothing of theirs is cached or attended.
+__global__ void k_token_map(int T, int B, int Q, const int32_t* len_safe, int32_t* tok_seq, int32_t* tok_pos,
+                            const int32_t* q_valid) {
   int t = blockIdx.x * blockDim.x + threadIdx.x;
-  int nl = B;
-  if (n_live) {
-    nl = n_live[0];
-    nl = nl < 0 ? 0 : (nl > B ? B : nl);
-    if (t < B) q_valid_eff[t] = t < nl ? (q_valid ? q_valid[t] : Q) : -1;
-    if (t == 0) rows_dev[0] = nl * Q;
-  }
-  if (t == 0 && Q == 0) {   // padded column offsets of the packed K/V scratch
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { cu_pad[b] = acc; acc += (cu[b + 1] - cu[b] + 31) / 32 * 32; }
-    cu_pad[B] = acc;
-  }
   if (t >= T) return;
   if (Q > 0) {
     int b = t / Q;
     tok_seq[t] = b;
-    // padding rows of a step (past q_valid of their sequence) have no position: nothing of theirs is cached
-    const bool pad = b >= nl || (q_valid && (t - b * Q) >= q_valid[b]);
-    tok_pos[t] = pad ? -1 : prefix_len[b] + (t - b * Q);
+    // padding rows of a step (past q_valid of their sequence; q_valid < 0: the whole sequence) have no position
+    tok_pos[t] = (q_valid && (t - b * Q) >= q_valid[b]) ? -1 : len_safe[b] + (t - b * Q);
   } else {
     int lo = 0, hi = B;  // largest b with cu[b] <= t
     while (hi - lo > 1) {
       int mid = (lo + hi) >> 1;
-      if (cu[mid] <= t) lo = mid; else hi = mid;
+      if (len_safe[mid] <= t) lo = mid; else hi = mid;
     }
     tok_seq[t] = lo;
-    tok_pos[t] = t - cu[lo];
+    tok_pos[t] = t < len_safe[lo + 1] ? t - len_safe[lo] : -1;
   }
 }
 
@@ -235,7 +264,7 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
         Elem<T>::store(pool_k + ko + j + half, r1);
       } else atomicOr(status, DLLM_STATUS_BAD_PAGE);
     }
-    if (to_pack) {
+    if (to_pack && pos >= 0) {
       kv_locate(pack, b, pos, h, ko, vo, vs);
       Elem<T>::store(pack_k + ko + j, r0);
       Elem<T>::store(pack_k + ko + j + half, r1);
@@ -254,7 +283,7 @@ __global__ void k_rope_kv(int Hq, int Hkv, int dh, const float* qf, const float*
       val = vt[h * dh + j];
     }
     if (cached && kv_locate(pool, b, pos, h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = val;
-    if (to_pack) {
+    if (to_pack && pos >= 0) {
       kv_locate(pack, b, pos, h, ko, vo, vs);
       pack_v[vo + (int64_t)j * vs] = val;
     }
@@ -326,14 +355,14 @@ __global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh
         *(uint2*)(pool_k + ko + half + j4 * 4) = hi;
       } else bad = true;
     }
-    if (to_pack) {
+    if (to_pack && s_pos[e] >= 0) {
       kv_locate(pack, s_b[e], s_pos[e], h, ko, vo, vs);
       *(uint2*)(pack_k + ko + j4 * 4) = lo;
       *(uint2*)(pack_k + ko + half + j4 * 4) = hi;
     }
   }
   // ---- V: eight rows of a channel at once where they are eight consecutive aligned positions
-  bool group = t0 + 8 <= T && (s_pos[0] & 7) == 0;
+  bool group = t0 + 8 <= T && s_pos[0] >= 0 && (s_pos[0] & 7) == 0;
   for (int e = 1; e < 8 && group; ++e) group = s_b[e] == s_b[0] && s_pos[e] == s_pos[0] + e && s_cached[e] == s_cached[0];
   for (int i = tid; i < dkv; i += nthr) {
     const int h = i / dh, j = i - h * dh;
@@ -370,7 +399,7 @@ __global__ __launch_bounds__(256) void k_rope_kv8(int T, int Hq, int Hkv, int dh
           if (kv_locate(pool, s_b[e], s_pos[e], h, ko, vo, vs)) pool_v[vo + (int64_t)j * vs] = val[e];
           else bad = true;
         }
-        if (to_pack) {
+        if (to_pack && s_pos[e] >= 0) {
           kv_locate(pack, s_b[e], s_pos[e], h, ko, vo, vs);
           pack_v[vo + (int64_t)j * vs] = val[e];
         }
@@ -697,12 +726,15 @@ __global__ void k_set_i32(int32_t* p, int n, int32_t v) {
 #define IS_BF16(c) ((c)->cfg.dtype == DLLM_BF16)
 
 hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
-  const int n = g.T > g.B ? g.T : g.B;
-  k_token_map<<<(n + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, g.prefix_len, g.cu_seqlens,
-                                              WS(c, tok_seq, int32_t), WS(c, tok_pos, int32_t),
-                                              WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr,
-                                              g.Q > 0 ? g.n_live : nullptr, WS(c, q_valid_eff, int32_t),
-                                              WS(c, status, int32_t) + 2);
+  const bool live = g.Q > 0 && g.n_live != nullptr;
+  k_seq_check<<<1, 256, 0, s>>>(g.T, g.B, g.Q, g.Q > 0 ? g.max_kv - g.Q : g.max_kv, g.prefix_len, g.cu_seqlens,
+                                WS(c, len_safe, int32_t), WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr,
+                                live ? g.n_live : nullptr, WS(c, q_valid_eff, int32_t), WS(c, status, int32_t));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int32_t* qv = g.Q > 0 ? (live ? WS(c, q_valid_eff, int32_t) : g.q_valid) : nullptr;
+  k_token_map<<<(g.T + 255) / 256, 256, 0, s>>>(g.T, g.B, g.Q, WS(c, len_safe, int32_t), WS(c, tok_seq, int32_t),
+                                                WS(c, tok_pos, int32_t), qv);
   return hipGetLastError();
 }
 

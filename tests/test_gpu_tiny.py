@@ -234,3 +234,39 @@ def test_device_side_bounds_checks_set_status_instead_of_faulting(world):
     assert eng.read_status() & 2
     eng.reset_status()
     assert eng.read_status() == 0
+
+
+def test_device_side_lengths_are_checked_against_the_host_values(world):
+    """Lengths that live in device memory and disagree with the host values that sized the launch (a prefix longer
+    than max_prefix_len or negative, a packed sequence longer than max_seqlen, cu_seqlens that do not add up to
+    total_tokens or go backwards) are clamped on the device and reported as a status bit; nothing faults, and a
+    consistent call afterwards is clean and correct."""
+    from paper_2601_07568_amd.binding import STATUS_BAD_LENGTH
+    eng = world["eng"]
+    table = H.identity_table(eng, 2)
+    tab = eng.i32(table)
+    seqs = [world["prompt"], synth.random_tokens(TINY, 9, 40)]
+    gpu_prefill(eng, seqs, table)
+    assert eng.read_status() == 0
+    blk = np.stack([synth.masked_block(TINY, 5, Q, 20), synth.masked_block(TINY, 6, Q, 20)])
+    cand = torch.zeros(2, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(2, Q, dtype=torch.float32, device=eng.device)
+    for bad_prefix in ([P, 1000], [P, -3], [P + 1, 40]):
+        eng.denoise_step(eng.i32(blk), eng.i32(bad_prefix), tab, cand, conf, max_prefix_len=max(P, 40))
+        assert eng.read_status() & STATUS_BAD_LENGTH, bad_prefix
+        eng.reset_status()
+    toks = eng.i32(np.concatenate(seqs))
+    n = P + 40
+    for bad_cu, max_seqlen in (([0, P, n], P - 1),          # a sequence longer than max_seqlen
+                               ([0, P, n - 5], P),           # does not add up to total_tokens
+                               ([0, P, n + 7], P),           # beyond total_tokens
+                               ([0, 70, 50], 70),            # goes backwards
+                               ([3, P, n], P)):              # does not start at 0
+        eng.prefill_kv(toks, eng.i32(bad_cu), tab, None, total_tokens=n, max_seqlen=max_seqlen)
+        assert eng.read_status() & STATUS_BAD_LENGTH, bad_cu
+        eng.reset_status()
+    # a consistent call afterwards: clean status, cache as the oracle's
+    gpu_prefill(eng, seqs, table)
+    assert eng.read_status() == 0
+    got = H.gather_cache(eng, table[0], P, TINY.n_layers - 1, 0)
+    assert np.abs(got - world["ck"][-1]).max() <= 1e-5 * max(1.0, np.abs(world["ck"][-1]).max())
