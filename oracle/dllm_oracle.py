@@ -213,11 +213,12 @@ def confidence(logits, mask_id):
 def unmask(tokens, cand, conf, mask_id, tau, m):
     """Threshold + floor selection on one block.  Masked positions with conf >= tau are
     unmasked, and so are the m' = min(m, #masked) most confident masked positions (highest
-    confidence first, lowest index first among equals).  Returns (new tokens, chosen indices)."""
+    confidence first, lowest index first among equals; a NaN confidence passes no threshold and ranks
+    behind every number).  Returns (new tokens, chosen indices)."""
     tokens = np.array(tokens, copy=True)
     masked = [i for i in range(len(tokens)) if tokens[i] == mask_id]
     chosen = {i for i in masked if conf[i] >= tau}
-    order = sorted(masked, key=lambda i: (-conf[i], i))
+    order = sorted(masked, key=lambda i: (1, 0.0, i) if conf[i] != conf[i] else (0, -conf[i], i))
     chosen.update(order[:min(m, len(masked))])
     for i in chosen:
         tokens[i] = cand[i]
@@ -233,7 +234,7 @@ def unmask_entropy(tokens, cand, entropy, mask_id, theta, m):
     tokens = np.array(tokens, copy=True)
     masked = [i for i in range(len(tokens)) if tokens[i] == mask_id]
     chosen = {i for i in masked if entropy[i] <= theta}
-    order = sorted(masked, key=lambda i: (entropy[i], i))
+    order = sorted(masked, key=lambda i: (1, 0.0, i) if entropy[i] != entropy[i] else (0, entropy[i], i))   # NaN last
     chosen.update(order[:min(m, len(masked))])
     for i in chosen:
         tokens[i] = cand[i]

@@ -171,3 +171,47 @@ def selection_is_decided(conf, masked, tau, m):
     if mm < len(c) and s[mm - 1] - s[mm] <= MARGIN:
         return False
     return True
+
+
+def layerwise_oracle_step(ms, g, layers, prompt, blk, caches=None):
+    """The oracle on a model whose weights live on the device (too large to hold on the host in float64 all at
+    once): layer by layer, a layer's weights are on the host only while it is used.  Runs the no-cache forward over
+    `prompt` (its K/V are the cache: what dllm_prefill_kv computes) and the denoise-step forward of the block `blk`
+    against that cache, both exactly and with bfloat16 storage at the library's rounding points.  With `caches`
+    (per layer (K, V) float64 arrays) the prompt pass is skipped and those are the cache.
+    Returns {"exact": logits, "stored": logits, "k_last": last layer's prompt K of the storage variant}."""
+    import torch
+    host = lambda t: t.float().cpu().numpy().astype(np.float64)
+    ident = lambda a: a
+    dev = g["tok_emb"].device
+    Q = len(blk)
+    P = len(prompt) if caches is None else caches[0][0].shape[0]
+    emb = lambda toks: host(g["tok_emb"][torch.from_numpy(np.asarray(toks, dtype=np.int64)).to(dev)])
+    xb = {None: emb(blk), "st": emb(blk)}
+    xp = {None: emb(prompt), "st": emb(prompt)} if caches is None else None
+    k_last = None
+    for l in range(ms.n_layers):
+        lw = {n: host(t) for n, t in layers[l].items()}
+        for key in (None, "st"):
+            st = synth.round_bf16 if key else None
+            if caches is None:
+                q, k, v = O.layer_qkv(ms, lw, xp[key], np.arange(P), ident, st)
+                xp[key] = O.layer_finish(ms, lw, xp[key], O.attention(q, k, v), ident, st)
+                ck, cv = k, v
+                if key and l == ms.n_layers - 1:
+                    k_last = k
+            else:
+                ck, cv = caches[l]
+            q, k, v = O.layer_qkv(ms, lw, xb[key], np.arange(Q) + P, ident, st)
+            xb[key] = O.layer_finish(ms, lw, xb[key], O.attention(q, np.concatenate([ck, k]), np.concatenate([cv, v])),
+                                     ident, st)
+        del lw
+
+    class Head:
+        pass
+    head = Head()
+    head.ms = ms
+    hw = {"final_norm": host(g["final_norm"]), "lm_head": host(g["lm_head"])}
+    Head.__getitem__ = lambda self, k: hw[k]
+    return {"exact": O.head_logits(head, xb[None], ident), "stored": O.head_logits(head, xb["st"], ident, synth.round_bf16),
+            "k_last": k_last}

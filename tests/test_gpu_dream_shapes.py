@@ -189,3 +189,72 @@ def test_full_depth_batch_32_prefix_8192_sampled_sequences():
         print(f"seq {b}: {n_exact} of {int(masked.sum())} masked rows decided by margin and equal")
         assert (cand.cpu().numpy()[b][~masked] == blks[b][~masked]).all()
     eng.close()
+
+
+def test_full_depth_batch_16_prefill_and_two_blocks_in_flight_sampled_sequence():
+    """The batch-16 workload at its own size and in the launch configuration bench.py times (Dream-7B-shaped, 28
+    layers, 16 prompts prefilled in ONE dllm_prefill_kv call, then a step with two blocks of 32 in flight per sequence,
+    threshold 0.85, floor 1 per block): fifteen prompts have the workload's 2048 tokens, one has 192 so that the
+    oracle can recompute it at full depth (prefill and step chained, layer by layer from host copies of the
+    device-drawn weights; 28 layers of a 2048-token prompt in float64 are out of reach in a test).  Checked for that
+    sequence: the deepest cached K, the logits (materialised by the debug call for the whole batch), candidates,
+    confidences, entropies and the per-block unmask sets."""
+    from paper_2601_07568_amd.binding import Engine
+    ms = synth.DREAM_7B
+    Bn, S, Q, bl, pt = 16, 2048, 64, 32, 64
+    sample, S_short = 5, 192
+    lens = [S] * Bn
+    lens[sample] = S_short
+    dev = torch.device("cuda:0")
+    mp = (S + Q + pt - 1) // pt
+    g, layers = synth.device_weights(ms, torch, dev, 4)
+    eng = Engine(ms, None, page_tokens=pt, max_pages_per_seq=mp, n_pages=Bn * mp, max_batch=Bn, max_q=Q,
+                 max_tokens=sum(lens), device_weights=(g, layers), pack=False)
+    table_np = np.arange(Bn * mp).reshape(Bn, mp)
+    table = eng.i32(table_np)
+    prompts = [synth.random_tokens(ms, 40 + b, lens[b]) for b in range(Bn)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), table, None, total_tokens=int(cu[-1]), max_seqlen=S)
+    blks = np.stack([np.concatenate([synth.masked_block(ms, 5, bl, 24, stream=2 * b),
+                                     synth.masked_block(ms, 5, bl, 32, stream=2 * b + 1)]) for b in range(Bn)])
+    qt = eng.i32(blks)
+    cand = torch.zeros(Bn, Q, dtype=torch.int32, device=dev)
+    conf = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    ent = torch.zeros(Bn, Q, dtype=torch.float32, device=dev)
+    prefix = eng.i32(lens)
+    eng.denoise_step(qt, prefix, table, cand, conf, ent, max_prefix_len=S)
+    logits = eng.debug_logits(qt, prefix, table, max_prefix_len=S)[sample].cpu().numpy()
+    nun = torch.zeros(Bn, 2, dtype=torch.int32, device=dev)
+    eng.unmask(qt, cand, conf, 0.85, 1, block_len=bl, n_unmasked=nun)
+    assert eng.read_status() == 0
+    ref = H.layerwise_oracle_step(ms, g, layers, prompts[sample], blks[sample])
+    exact, stored = ref["exact"], ref["stored"]
+    got_k = H.gather_cache_rows(eng, table_np[sample], S_short, ms.n_layers - 1, 0)
+    assert np.abs(got_k - ref["k_last"]).max() <= H.logit_tol("bf16", ms.n_layers, "storage") * np.abs(ref["k_last"]).max()
+    err_exact, err_store = H.rel_err_rows(logits, exact).max(), H.rel_err_rows(logits, stored).max()
+    print(f"28 layers, batch 16: logit rel err vs exact oracle {err_exact:.3e}, vs bf16-storage oracle {err_store:.3e}; "
+          f"bf16-storage oracle vs exact oracle {H.rel_err_rows(stored, exact).max():.3e}")
+    eps_exact, eps_store = H.logit_tol("bf16", ms.n_layers), H.logit_tol("bf16", ms.n_layers, "storage")
+    assert err_store <= eps_store and err_exact <= eps_exact
+    masked = blks[sample] == ms.mask_id
+    c, f, e = cand.cpu().numpy()[sample], conf.cpu().numpy()[sample], ent.cpu().numpy()[sample]
+    n_gap, n_rows, _, _ = H.check_exact_decisions(ms, exact, masked, c, eps_exact)
+    ocand, oconf, oent, _ = O.confidence(stored, ms.mask_id)
+    r = {"logits": stored, "cand": ocand, "conf": oconf, "entropy": oent}
+    n_exact = H.check_step_outputs(ms, r, masked, c, f, e, "bf16", gpu_logits=logits, eps=eps_store)
+    print(f"{n_gap} of {n_rows} masked rows decided against the exact oracle, {n_exact} against the oracle with "
+          f"bfloat16 storage")
+    # the per-block selection (threshold cannot fire at this vocabulary size: the floor of each block)
+    after = qt.cpu().numpy()[sample]
+    for k in range(2):
+        sl = slice(k * bl, (k + 1) * bl)
+        _, ch = O.unmask(blks[sample][sl], ocand[sl], oconf[sl], ms.mask_id, 0.85, 1)
+        assert int(nun[sample, k]) == len(ch) == 1
+        if H.selection_is_decided(oconf[sl], masked[sl], 0.85, 1):
+            assert np.nonzero(after[sl] != blks[sample][sl])[0].tolist() == ch
+    # every other sequence: outputs well-formed
+    call = cand.cpu().numpy()
+    mall = blks == ms.mask_id
+    assert ((call[mall] >= 0) & (call[mall] < ms.vocab) & (call[mall] != ms.mask_id)).all()
+    assert (call[~mall] == blks[~mall]).all() and (nun.cpu().numpy() == 1).all()
+    eng.close()

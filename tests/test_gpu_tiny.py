@@ -270,3 +270,78 @@ def test_device_side_lengths_are_checked_against_the_host_values(world):
     assert eng.read_status() == 0
     got = H.gather_cache(eng, table[0], P, TINY.n_layers - 1, 0)
     assert np.abs(got - world["ck"][-1]).max() <= 1e-5 * max(1.0, np.abs(world["ck"][-1]).max())
+
+
+def test_peaked_model_threshold_fires_on_model_confidences():
+    """The tiny model with its LM head scaled by 48 instead of 8: the distributions are peaked, so the threshold 0.9
+    selects rows on confidences the model itself produced (twelve in the first step, more later) and the floor only
+    carries the steps in between.  Two blocks with a refresh at the boundary, teacher-forced (every step from the
+    oracle's state: logits, candidates, confidences, the unmask set with its threshold part) and free-running (the GPU
+    carries its own state; it is put back on the oracle's trajectory only after a step the oracle leaves within 1e-3
+    of a tie)."""
+    import dataclasses
+    ms = dataclasses.replace(TINY, lm_head_scale=48.0, name="tiny-peaked")
+    w = synth.Weights(ms, 0)
+    eng = H.make_engine(ms, w, page_tokens=16, max_pages_per_seq=16, n_pages=16, max_batch=1, max_q=Q, max_tokens=256)
+    prompt = synth.random_tokens(ms, 0, P)
+    table = H.identity_table(eng, 1)
+    tab = eng.i32(table)
+    rec = []
+    seq, steps = O.decode(w, prompt, 2, Q, 0.9, 1, record=rec)
+    by_threshold = [sum(1 for i in r["chosen"] if r["conf"][i] >= 0.9) for r in rec]
+    assert sum(1 for n in by_threshold if n >= 2) >= 3 and steps < 2 * Q // 2      # the threshold really drives it
+    cand = torch.zeros(1, Q, dtype=torch.int32, device=eng.device)
+    conf = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    ent = torch.zeros(1, Q, dtype=torch.float32, device=eng.device)
+    nun = torch.zeros(1, 1, dtype=torch.int32, device=eng.device)
+    for mode in ("teacher-forced", "free-running"):
+        cur = P
+        eng.prefill_kv(eng.i32(prompt), eng.i32([0, P]), tab, None, total_tokens=P, max_seqlen=P)
+        qt = eng.i32(np.full((1, Q), ms.mask_id))
+        decided = thresholded = thr_rows = 0
+        n_exact = 0
+        for n, r in enumerate(rec):
+            if mode == "teacher-forced":
+                qt = eng.i32(r["before"][None])
+            before = qt.cpu().numpy()[0]
+            assert (before == r["before"]).all()
+            masked = before == ms.mask_id
+            eng.denoise_step(qt, eng.i32([cur]), tab, cand, conf, ent, max_prefix_len=cur)
+            c, cf, en = cand.cpu().numpy()[0], conf.cpu().numpy()[0], ent.cpu().numpy()[0]
+            if mode == "teacher-forced":
+                logits = eng.debug_logits(qt, eng.i32([cur]), tab, max_prefix_len=cur).cpu().numpy()[0]
+                assert H.rel_err_rows(logits, r["logits"]).max() <= H.logit_tol("f32", ms.n_layers)
+                n_exact += H.check_step_outputs(ms, r, masked, c, cf, en, "f32")
+            eng.unmask(qt, cand, conf, 0.9, 1, n_unmasked=nun)
+            after = qt.cpu().numpy()[0]
+            _, _, _, p = O.confidence(r["logits"], ms.mask_id)
+            sure_ids = (H.top2_margin(p) > H.MARGIN)[r["chosen"]].all()
+            if mode == "teacher-forced":
+                # row by row, whatever the rest of the step: a row clearly above the threshold is decoded to the
+                # oracle's token, a row clearly below it is decoded only if the floor could pick it
+                top = max(r["conf"][masked]) if masked.any() else 0.0
+                for i in np.nonzero(masked)[0]:
+                    if r["conf"][i] >= 0.9 + H.MARGIN and H.top2_margin(p)[i] > H.MARGIN:
+                        assert after[i] == r["cand"][i], (n, i)
+                        thr_rows += 1
+                    elif r["conf"][i] <= 0.9 - H.MARGIN and r["conf"][i] < top - H.MARGIN:
+                        assert after[i] == ms.mask_id, (n, i)
+            if H.selection_is_decided(r["conf"], masked, 0.9, 1) and sure_ids:
+                assert (after == r["tokens"]).all(), (mode, n)
+                assert int(nun) == len(r["chosen"])
+                decided += 1
+                thresholded += by_threshold[n] >= 2
+            elif mode == "free-running":
+                qt = eng.i32(r["tokens"][None])
+            if not (r["tokens"] == ms.mask_id).any():                          # block boundary: refresh, next block
+                cur += Q
+                full = eng.i32(np.concatenate([prompt, seq[P:cur]]))
+                eng.refresh_cache(full, eng.i32([0, cur]), tab, None, total_tokens=cur, max_seqlen=cur)
+                qt = eng.i32(np.full((1, Q), ms.mask_id))
+        print(f"{mode}: {decided} of {len(rec)} steps decided and equal, {thresholded} of them with two or more rows "
+              f"taken by the threshold" + (f", {n_exact} rows' candidates decided, {thr_rows} rows decoded by the "
+                                           f"threshold alone" if mode == "teacher-forced" else ""))
+        assert decided >= (2 * len(rec)) // 3 and thresholded >= 1
+        assert mode != "teacher-forced" or thr_rows >= 30
+    assert eng.read_status() == 0
+    eng.close()

@@ -1,5 +1,5 @@
-"""dllm_unmask alone against the oracle's selection on synthetic confidences (exact ties, NaN-free),
-single and multiple blocks, all thresholds and floors."""
+"""dllm_unmask alone against the oracle's selection on synthetic confidences (exact ties; NaN values in a test of
+their own), single and multiple blocks, all thresholds and floors."""
 import numpy as np
 import pytest
 import torch
@@ -87,3 +87,33 @@ def test_threshold_only_floor_zero(eng):
     ref, ch = O.unmask(tokens[0], cand[0], conf[0], ms.mask_id, np.float32(0.5), 0)
     eng.unmask(qt, eng.i32(cand), torch.from_numpy(conf).to(eng.device), 0.5, 0)
     assert (qt.cpu().numpy()[0] == ref).all() and len(ch) > 0
+
+
+@pytest.mark.parametrize("by_entropy", [False, True])
+def test_nan_statistics_pass_no_threshold_and_rank_last(eng, by_entropy):
+    """NaN confidences / entropies: never selected by the threshold, taken by the floor only after every number
+    (lowest index first) - the same sets as the oracle, on blocks where a third of the values are NaN and on a block
+    that holds nothing but NaN."""
+    ms = eng.ms
+    rng = np.random.default_rng(99 + by_entropy)
+    Bn, bl, nblk = 3, 32, 2
+    Qn = bl * nblk
+    for trial in range(4):
+        tokens = np.where(rng.random((Bn, Qn)) < 0.7, ms.mask_id, rng.integers(0, 4000, (Bn, Qn))).astype(np.int32)
+        stat = rng.random((Bn, Qn)).astype(np.float32)
+        stat[rng.random((Bn, Qn)) < 0.35] = np.nan
+        stat[0, :bl] = np.nan
+        cand = rng.integers(0, 4000, (Bn, Qn)).astype(np.int32)
+        for thr, m in ((0.5, 1), (0.5, 0), (0.2, 7), (2.0, 40), (-1.0, 3)):
+            qt = eng.i32(tokens)
+            nun = torch.zeros(Bn, nblk, dtype=torch.int32, device=eng.device)
+            fn = eng.unmask_entropy if by_entropy else eng.unmask
+            fn(qt, eng.i32(cand), torch.from_numpy(stat).to(eng.device), thr, m, block_len=bl, n_unmasked=nun)
+            got = qt.cpu().numpy()
+            for b in range(Bn):
+                for k in range(nblk):
+                    sl = slice(k * bl, (k + 1) * bl)
+                    ofn = O.unmask_entropy if by_entropy else O.unmask
+                    ref, ch = ofn(tokens[b, sl], cand[b, sl], stat[b, sl], ms.mask_id, np.float32(thr), m)
+                    assert (got[b, sl] == ref).all(), (trial, thr, m, b, k)
+                    assert int(nun[b, k]) == len(ch)

@@ -365,6 +365,29 @@ def test_unmask_against_sort_reference_with_ties(seed):
                 assert len(ca) == nm
 
 
+def test_unmask_with_nan_statistics_hand_worked():
+    """A NaN confidence (or entropy) passes no threshold and is the last resort of the floor."""
+    nan = float("nan")
+    tok = np.array([9, 9, 9, 9, 5, 9])                       # mask id 9; position 4 is decoded
+    cand = np.array([1, 2, 3, 4, 0, 6])
+    conf = np.array([nan, 0.3, 0.95, nan, nan, 0.3])
+    new, ch = O.unmask(tok, cand, conf, 9, 0.9, 1)            # threshold takes 2, the floor is already met
+    assert ch == [2] and new.tolist() == [9, 9, 3, 9, 5, 9]
+    _, ch = O.unmask(tok, cand, conf, 9, 0.9, 3)              # floor 3: 0.95, then the two 0.3 by index
+    assert ch == [1, 2, 5]
+    _, ch = O.unmask(tok, cand, conf, 9, 0.9, 4)              # floor 4: the NaN rows come last, lowest index first
+    assert ch == [0, 1, 2, 5]
+    _, ch = O.unmask(tok, cand, conf, 9, 0.0, 0)              # NaN >= 0 is false
+    assert ch == [1, 2, 5]
+    _, ch = O.unmask(np.array([9, 9]), cand[:2], np.array([nan, nan]), 9, 0.5, 1)
+    assert ch == [0]
+    ent = np.array([nan, 0.3, 0.05, nan, nan, 0.3])
+    _, ch = O.unmask_entropy(tok, cand, ent, 9, 0.1, 4)
+    assert ch == [0, 1, 2, 5]
+    _, ch = O.unmask_entropy(tok, cand, ent, 9, 10.0, 0)
+    assert ch == [1, 2, 5]
+
+
 def test_unmask_set_is_monotone_in_threshold():
     rng = np.random.default_rng(11)
     tokens = np.full(32, 7); conf = rng.random(32); cand = np.arange(32)
