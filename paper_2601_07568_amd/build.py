@@ -50,6 +50,34 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_check() -> str:
+    """Sanitizer build of the host side of the library: every source compiled with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST code only (device code as usual), linked with csrc/host_check_main.cpp into
+    _build/host_check, an executable that drives every entry point's validation without a GPU."""
+    objdir = os.path.join(HERE, "_build", "san")
+    os.makedirs(objdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined", "-g"]
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1"] + san
+
+    def compile_one(src):
+        obj = os.path.join(objdir, src.replace(".hip", ".o").replace(".cpp", ".o"))
+        extra = ["-x", "hip"] if src.endswith(".cpp") else []
+        r = subprocess.run([_hipcc(), *flags, "-c", *extra, os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src} (sanitizer build):\n" + r.stderr[-3000:])
+        return obj
+
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(compile_one, SOURCES + ["host_check_main.cpp"]))
+    exe = os.path.join(HERE, "_build", "host_check")
+    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-fno-gpu-sanitize", "-Xarch_host", "-fsanitize=address",
+                        "-Xarch_host", "-fsanitize=undefined", "-o", exe, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed (sanitizer build):\n" + r.stderr[-3000:])
+    return exe
+
+
 def declared_symbols() -> list[str]:
     """Names of the functions include/dllm.h declares."""
     text = open(HEADER).read()

@@ -168,3 +168,16 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=60)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_host_side_code_under_address_and_undefined_behaviour_sanitizers():
+    """The library's host code (argument validation, workspace map, context life cycle, launch geometry up to the
+    first launch) compiled with AddressSanitizer + UndefinedBehaviorSanitizer on the host side only and driven by
+    csrc/host_check_main.cpp through every entry point, without a GPU: the sanitizers abort on a finding, the
+    driver counts wrong return codes."""
+    import subprocess
+    exe = build.build_host_check()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.stdout[-2000:], r.stderr[-4000:])
+    assert "host check: 0 failure(s)" in r.stdout
+    assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr
