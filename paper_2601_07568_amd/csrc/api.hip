@@ -770,6 +770,18 @@ extern "C" int dllm_eos_scan(dllm_ctx* c, void* stream, int B, int n, const int3
   return DLLM_OK;
 }
 
+extern "C" int dllm_probe_hbm_read(dllm_ctx* c, void* stream, const void* buf, size_t bytes, void* sink) {
+  if (!c || !buf || !sink || bytes < 16 || ((uintptr_t)buf & 15) != 0) return DLLM_EINVAL;
+  TRY(launch_probe_read((hipStream_t)stream, buf, bytes, sink), "probe_read");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_probe_mfma(dllm_ctx* c, void* stream, int iters, void* sink, double* flops) {
+  if (!c || !sink || !flops || iters < 1 || iters > (1 << 24)) return DLLM_EINVAL;
+  TRY(launch_probe_mfma((hipStream_t)stream, iters, sink, flops), "probe_mfma");
+  return DLLM_OK;
+}
+
 extern "C" int dllm_reset_status(dllm_ctx* c, void* stream) {
   if (!c) return DLLM_EINVAL;
   TRY(launch_set_i32((hipStream_t)stream, WSP(c, status, int32_t), 16, 0), "reset_status");

@@ -904,4 +904,64 @@ hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_
   return lg_launch<LG_LMSTATS>(s, a);
 }
 
+// ------------------------------------------------------------------------------------------
+// Probes for the benchmark: what this chip sustains on a plain stream read and on a loop of nothing but matrix
+// instructions, measured in the same run as the kernels that are held against those figures.
+__global__ __launch_bounds__(512) void k_probe_read(const u32x4* __restrict__ p, size_t n_vec, uint32_t* sink) {
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  u32x4 acc = {0, 0, 0, 0};
+  size_t i = tid;
+  for (; i + 7 * stride < n_vec; i += 8 * stride) {      // eight 16-byte loads in flight per lane
+    u32x4 t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= t[u];
+  }
+  for (; i < n_vec; i += stride) acc ^= p[i];
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = 1;   // keeps the loads alive
+}
+
+// one wave per SIMD, sixteen independent 32x32x16 bfloat16 products in flight, operands in registers
+__global__ __launch_bounds__(256) void k_probe_mfma(int iters, float* sink) {
+  f32x16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  // operand bits that are ordinary finite bfloat16 values and differ from lane to lane and from tile to tile
+  u32x4 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t s0 = 0x3f803f80u + (((threadIdx.x * 2654435761u) >> 20) & 0x007f007fu) + i * 0x00010001u;
+    a[i] = u32x4{s0, s0 ^ 0x00100010u, s0 + 0x00020002u, s0 ^ 0x80008000u};
+    b[i] = u32x4{s0 ^ 0x80000000u, s0 + 0x00030003u, s0 ^ 0x00008000u, s0 + 0x00040004u};
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]),
+                                                                 __builtin_bit_cast(bf16x8, b[j]), acc[i * 4 + j], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum += acc[i][0] + acc[i][7];
+  if (sum == 1.2345e-30f) sink[0] = sum;
+}
+
+hipError_t launch_probe_read(hipStream_t s, const void* buf, size_t bytes, void* sink) {
+  k_probe_read<<<t2_cus * 2, 512, 0, s>>>((const u32x4*)buf, bytes / 16, (uint32_t*)sink);
+  return hipGetLastError();
+}
+
+// flops of one launch: workgroups * 4 waves * iters * 16 products * 2*32*32*16
+hipError_t launch_probe_mfma(hipStream_t s, int iters, void* sink, double* flops) {
+  const int wgs = t2_cus;
+  k_probe_mfma<<<wgs, 256, 0, s>>>(iters, (float*)sink);
+  *flops = (double)wgs * 4.0 * iters * 16.0 * 2.0 * 32 * 32 * 16;
+  return hipGetLastError();
+}
+
 }  // namespace dllm
