@@ -29,6 +29,7 @@ struct AttnArgs {
   int n_parts;              // partials per row = workgroups along the keys
   int n_rg_wg;              // row groups per workgroup
   int pt_shift;             // log2(page_tokens) if that is a power of two (0 for the packed scratch), else -1
+  int pg_cap;               // k_attn_dl: page ids of a sequence that its LDS copy of the block table holds
   float scale_log2;         // log2(e) / sqrt(DH)
   float* part_o;            // [T*Hq, n_units, DH]
   float* part_ml;           // [T*Hq, n_units, 2]
@@ -59,8 +60,7 @@ __device__ __forceinline__ void attn_softmax_block(f32x4 (&s)[2][QT], int k0, in
   for (int t = 0; t < QT; ++t) {
     float mx = fmaxf(fmaxf(fmaxf(s[0][t][0], s[0][t][1]), fmaxf(s[0][t][2], s[0][t][3])),
                      fmaxf(fmaxf(s[1][t][0], s[1][t][1]), fmaxf(s[1][t][2], s[1][t][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = rows_max(mx);
     const float m_new = fmaxf(m_run[t], mx * scale_log2);   // finite: every block has at least one valid key
     if (__builtin_amdgcn_ballot_w64(m_new > m_run[t]) != 0) {
       const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_new);   // exp2(-inf) = 0 on the first block
@@ -572,36 +572,53 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
 #pragma unroll
   for (int t = 0; t < QT; ++t) { m_run[t] = -DEV_INF; l_run[t] = 0.f; }
 
+  // One 64-key block.  The waves of a workgroup leave the block's barrier in the same phase, so the
+  // pipes (LDS, matrix, vector) only overlap where one wave's instruction order lets them: all K
+  // fragments of the block are requested first, the scores of both 32-key halves are issued back to
+  // back, and each half's V^T fragments are requested before its softmax (vector arithmetic, no LDS: its
+  // reductions are row swaps), which runs while the matrix pipe still works on the other half.  A half beyond the sequence is multiplied like any
+  // other: its scores are masked to -inf (the running maximum is finite after the first half) and its
+  // V^T columns are zero in LDS.
   auto compute = [&](int buf, int kb64) {
+    const int k0 = kb64 << 6;
+    const int lk = lane ^ (4 * g);
+    u32x4 kf[2][2][KK];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int k0 = (kb64 << 6) + half * 32;
-      if (k0 >= kv_len) break;
-      f32x4 s[2][QT];
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kf[half][tt][kk] = sk[buf][half][tt][kk][lk ^ kk];
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 s[2][2][QT];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        u32x4 kf[KK];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kf[kk] = sk[buf][half][tt][kk][lane ^ (4 * g) ^ kk];
+        for (int t = 0; t < QT; ++t) s[half][tt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-          for (int kk = 0; kk < KK; ++kk) acc = mfma16(kf[kk], qf[t][kk], acc);
-          s[tt][t] = acc;
-        }
+          for (int t = 0; t < QT; ++t) s[half][tt][t] = mfma16(kf[half][tt][kk], qf[t][kk], s[half][tt][t]);
       }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      u32x4 vf[DT];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vf[d] = sv[buf][half][d][lk ^ (2 * half)];
+      __builtin_amdgcn_sched_barrier(0);
       u32x4 pf[QT], pl[QT];
-      attn_softmax_block<DT, QT>(s, k0, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
+      attn_softmax_block<DT, QT>(s[half], k0 + half * 32, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
 #pragma unroll
       for (int d = 0; d < DT; ++d) {
-        const u32x4 vf = sv[buf][half][d][lane ^ (4 * g) ^ (2 * half)];
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          oacc[d][t] = mfma16(vf, pf[t], oacc[d][t]);
-          oacc[d][t] = mfma16(vf, pl[t], oacc[d][t]);
-        }
+        for (int t = 0; t < QT; ++t) oacc[d][t] = mfma16(vf[d], pf[t], oacc[d][t]);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[d][t] = mfma16(vf[d], pl[t], oacc[d][t]);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -664,6 +681,253 @@ __global__ __launch_bounds__(NW * 64) void k_attn_lds(const AttnArgs a) {
   if (bad) atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
 }
 
+// ------------------------------------------------------------------------------------------
+// The staged attention with the K and V^T blocks copied from memory straight into LDS (no register pass,
+// no LDS stores from registers - those cost bank conflicts whatever the layout - and no registers held
+// for data in flight).  A 64-key block is NF one-KiB operand fragments (lane l's 16 bytes at byte 16 l);
+// one copy instruction of a wave fills one fragment, each lane fetching the 16 bytes its slot holds: for
+// a K fragment (half, tile tt, k-step kk) row 8(c/4) + c%4 + 4tt of the half, bytes 64 kk + 16 g ..,
+// for a V^T fragment (half, channel tile d) channel 16 d + c, keys 8g .. 8g+7 of the half (c = l%16,
+// g = l/16).  NB buffers form a ring with NB-1 blocks in flight; the only wait on memory is "the block
+// about to be multiplied has landed", once per block, before the barrier that also frees the oldest
+// buffer.  Needs blocks that never straddle a page (page size a multiple of 64) or the packed scratch.
+// The page ids of the sequence are copied into LDS once; rows of a block past the sequence end are read
+// as they lie in the page (or workspace) and the V^T columns of such keys are zeroed in LDS before use,
+// as are those of a block whose page id is not addressable.
+#define DL_VMCNT(n) (((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+template <int DH, int NW, bool PAGED>
+__global__ __launch_bounds__(NW * 64) void k_attn_dl(const AttnArgs a) {
+  constexpr int KK = DH / 32, DT = DH / 16, QT = 2;
+  constexpr int NB = NW >= 8 ? 3 : 2;
+  constexpr int NKF = 4 * KK, NVF = 2 * DT, NF = NKF + NVF, FPW = NF / NW;
+  static_assert(NF % NW == 0 && NKF % FPW == 0, "a wave's i-th fragment is K for all of a wave or V^T for all");
+  constexpr int BLK = NF * 1024, nthr = NW * 64;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char dl_smem[];
+  int32_t* s_pg = (int32_t*)(dl_smem + NB * BLK);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int rg = blockIdx.y * a.n_rg_wg + w;
+  const int unit = blockIdx.x;
+  const int b = blockIdx.z / a.Hkv, kvh = blockIdx.z - b * a.Hkv;
+  const int G = a.Hq / a.Hkv;
+  const int row_base = PAGED ? b * a.Q : a.cu[b];
+  const int n_q = PAGED ? a.Q : a.cu[b + 1] - a.cu[b];
+  const int R = n_q * G;
+  const int kv_len = PAGED ? a.prefix_len[b] + (a.q_valid ? min(max(a.q_valid[b], 0), a.Q) : a.Q) : n_q;
+  const bool active = w < a.n_rg_wg && rg * 16 * QT < R;     // waves beyond the rows only help loading
+  if (blockIdx.y * a.n_rg_wg * 16 * QT >= R) return;         // whole workgroup beyond this sequence's rows
+  if (PAGED && a.q_valid && a.q_valid[b] < 0) return;        // the sequence is not part of this call
+  const KVView& kv = a.kv;
+  const int sh = a.pt_shift, pt = 1 << sh;
+  const bf16_t* kslab = (const bf16_t*)kv.k;
+  const bf16_t* vslab = (const bf16_t*)kv.v;
+  const int64_t pcol = PAGED ? 0 : kv.cu_pad[b];
+  bool bad = false;
+  const int nkb = (kv_len + 63) >> 6;
+
+  int np = 0;
+  if constexpr (PAGED) {
+    np = (kv_len + pt - 1) >> sh;
+    np = np < a.pg_cap ? np : a.pg_cap;
+    np = np < kv.max_pages ? np : kv.max_pages;
+    const int32_t* table = kv.table + (int64_t)b * kv.max_pages;
+    for (int i = tid; i < np; i += nthr) s_pg[i] = table[i];
+  }
+
+  u32x4 qf[QT][KK];
+  int64_t row_out[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int r = rg * 16 * QT + t * 16 + c;
+    const bool ok = active && r < R;
+    if (!ok) r = 0;
+    const int hg = r / n_q, j = r - hg * n_q;
+    const int64_t ro = (int64_t)(row_base + j) * a.Hq + kvh * G + hg;
+    row_out[t] = ok ? ro : -1;
+    const bf16_t* qp = a.q + ro * DH + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[t][kk] = *(const u32x4*)(qp + kk * 32);
+  }
+  __syncthreads();                                            // page ids are in LDS (and the q loads have landed)
+
+  // this lane's source offsets (elements from the block's K or V^T base) for the wave's FPW fragments
+  int foff[FPW];
+#pragma unroll
+  for (int i = 0; i < FPW; ++i) {
+    const int f = w * FPW + i;
+    if (f < NKF) {
+      const int half = f / (2 * KK), tt = (f / KK) & 1, kk = f % KK;
+      foff[i] = (half * 32 + 8 * (c >> 2) + (c & 3) + 4 * tt) * DH + (kk * 4 + g) * 8;
+    } else {
+      const int fv = f - NKF, half = fv / DT, d = fv % DT;
+      foff[i] = (d * 16 + c) * (PAGED ? pt : kv.tpad) + half * 32 + g * 8;
+    }
+  }
+  const bool wave_k = w * FPW < NKF;
+  uint32_t badbuf = 0;                                        // buffers whose block came from a page id out of range
+  auto page_of = [&](int kb64) -> int {
+    if constexpr (!PAGED) return 0;
+    const int pi = (kb64 << 6) >> sh;
+    return pi < np ? s_pg[pi] : -1;
+  };
+  auto issue = [&](int kb64, int buf, int page_v) {
+    const int k0 = kb64 << 6;
+    int64_t kb, vb;
+    if constexpr (PAGED) {
+      const int page = __builtin_amdgcn_readfirstlane(page_v);
+      const bool ok = (uint32_t)page < (uint32_t)kv.n_pages;
+      bad |= !ok;
+      badbuf = ok ? (badbuf & ~(1u << buf)) : (badbuf | (1u << buf));
+      const int64_t rows = (((int64_t)(ok ? page : 0) * kv.n_kv_heads + kvh) << sh);
+      kb = (rows + (k0 & (pt - 1))) * DH;
+      vb = rows * DH + (k0 & (pt - 1));
+    } else {
+      kb = ((int64_t)kvh * kv.tpad + pcol + k0) * DH;
+      vb = (int64_t)kvh * DH * kv.tpad + pcol + k0;
+    }
+    const bf16_t* src = wave_k ? kslab + kb : vslab + vb;
+    unsigned char* dst = dl_smem + buf * BLK + w * FPW * 1024;
+#pragma unroll
+    for (int i = 0; i < FPW; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + foff[i]),
+                                       (__attribute__((address_space(3))) void*)(dst + i * 1024), 16, 0, 0);
+  };
+
+  f32x4 oacc[DT][QT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int t = 0; t < QT; ++t) oacc[d][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) { m_run[t] = -DEV_INF; l_run[t] = 0.f; }
+
+  // One 64-key block; the instruction order lets one wave's LDS reads, matrix and vector work overlap
+  // (the waves of a workgroup leave the barrier in the same phase): all K fragments are requested first,
+  // the scores of both halves issued back to back, each half's V^T fragments requested before its
+  // softmax (no LDS traffic: its reductions are row swaps), which runs while the matrix pipe still works.
+  auto compute = [&](int buf, int kb64) {
+    const int k0 = kb64 << 6;
+    const u32x4* fk = (const u32x4*)(dl_smem + buf * BLK) + lane;
+    const u32x4* fv = fk + NKF * 64;
+    u32x4 kf[2][2][KK];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kf[half][tt][kk] = fk[((half * 2 + tt) * KK + kk) * 64];
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 s[2][2][QT];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+        for (int t = 0; t < QT; ++t) s[half][tt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+          for (int t = 0; t < QT; ++t) s[half][tt][t] = mfma16(kf[half][tt][kk], qf[t][kk], s[half][tt][t]);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      u32x4 vf[DT];
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vf[d] = fv[(half * DT + d) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+      u32x4 pf[QT], pl[QT];
+      attn_softmax_block<DT, QT>(s[half], k0 + half * 32, kv_len, g, a.scale_log2, m_run, l_run, oacc, pf, pl);
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[d][t] = mfma16(vf[d], pf[t], oacc[d][t]);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[d][t] = mfma16(vf[d], pl[t], oacc[d][t]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  if (unit < nkb) {          // (a unit without keys still writes its empty partial below)
+    const int last = unit + ((nkb - 1 - unit) / a.n_units) * a.n_units;
+    auto clampb = [&](int kb) { return kb <= last ? kb : last; };
+    // the ring's first NB-1 blocks (past the end: repeats of the last block into buffers nobody reads)
+#pragma unroll
+    for (int j = 0; j < NB - 1; ++j) {
+      const int kb = clampb(unit + j * a.n_units);
+      issue(kb, j, page_of(kb));
+    }
+    int pg_next = page_of(clampb(unit + (NB - 1) * a.n_units));
+    int buf = 0;
+    for (int kb = unit; kb < nkb; kb += a.n_units) {
+      __builtin_amdgcn_s_waitcnt(DL_VMCNT((NB - 2) * FPW));   // this wave's copies of block kb have landed
+      __builtin_amdgcn_s_barrier();                            // everybody's have; the previous block's buffer is free
+      const int nbuf = buf == 0 ? NB - 1 : buf - 1;            // (buf + NB - 1) % NB: the buffer of the block before
+      const int kn = clampb(kb + (NB - 1) * a.n_units);
+      issue(kn, nbuf, pg_next);
+      pg_next = page_of(clampb(kb + NB * a.n_units));
+      if ((kb << 6) + 64 > kv_len || ((badbuf >> buf) & 1u)) {
+        // zero the V^T columns of keys past the sequence end (all keys of a block without a page)
+        const bool nopage = (badbuf >> buf) & 1u;
+        u32x4* vb = (u32x4*)(dl_smem + buf * BLK + NKF * 1024);
+        for (int q = tid; q < NVF * 64; q += nthr) {
+          const int half = (q >> 6) / DT, gg = (q & 63) >> 4;
+          const int valid = nopage ? 0 : kv_len - ((kb << 6) + half * 32 + gg * 8);
+          if (valid < 8) {
+            u32x4 v = vb[q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              uint32_t x = v[e];
+              x = valid > 2 * e + 1 ? x : (x & 0x0000ffffu);
+              x = valid > 2 * e ? x : 0u;
+              v[e] = x;
+            }
+            vb[q] = v;
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+      }
+      if (active) compute(buf, kb);
+      buf = buf + 1 == NB ? 0 : buf + 1;
+    }
+    __builtin_amdgcn_s_waitcnt(DL_VMCNT(0));   // the trailing repeats must not outlive the workgroup
+  }
+
+  if (active) {
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      float l = l_run[t];
+      l += __shfl_xor(l, 16, 64);
+      l += __shfl_xor(l, 32, 64);
+      if (row_out[t] < 0) continue;
+      if (a.n_units == 1) {
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        const int64_t ro = row_out[t];
+        const int tok = (int)(ro / a.Hq), head = (int)(ro - (int64_t)tok * a.Hq);
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+          const int ch = d * 16 + 4 * g;
+          const int64_t at = a.out_mt > 0 ? frag_offset(tok, head * DH + ch, a.out_mt) : ro * DH + ch;
+          *(uint2*)(a.o + at) = make_uint2(
+              (uint32_t)f32_to_bf16(oacc[d][t][0] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][1] * inv) << 16),
+              (uint32_t)f32_to_bf16(oacc[d][t][2] * inv) | ((uint32_t)f32_to_bf16(oacc[d][t][3] * inv) << 16));
+        }
+        continue;
+      }
+      const int64_t slot = row_out[t] * a.n_units + unit;
+      float* po = a.part_o + slot * DH + 4 * g;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) *(f32x4*)(po + d * 16) = oacc[d][t];
+      if (g == 0) { a.part_ml[slot * 2] = m_run[t]; a.part_ml[slot * 2 + 1] = l; }
+    }
+  }
+  if (bad) atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
+}
+
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
   const dllm_config& f = c->cfg;
   if (!(f.dtype == DLLM_BF16 && c->kernel_mode == 0 && c->map.attn_rows > 0)) return false;
@@ -673,10 +937,17 @@ bool attn_step_supported(const dllm_ctx* c, const StepGeom& g) {
 // Attention of a denoise step (paged pool) or of a no-cache forward (packed scratch).
 // merging four waves' partial results takes a little more LDS than a kernel gets by default
 static bool attn_merge_ready = false;
+constexpr int DL_LDS_MAX = 128 * 1024;          // ring of k_attn_dl plus its copy of a sequence's page ids
 hipError_t init_attn_kernels() {
   if (attn_merge_ready) return hipSuccess;
   hipError_t e = hipFuncSetAttribute((const void*)k_attn_step<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void*)k_attn_step<64, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+#define DL_ATTR(DHV, NWV, PG)                                                                                     \
+  if (e == hipSuccess)                                                                                            \
+    e = hipFuncSetAttribute((const void*)k_attn_dl<DHV, NWV, PG>, hipFuncAttributeMaxDynamicSharedMemorySize, DL_LDS_MAX)
+  DL_ATTR(128, 8, true); DL_ATTR(128, 8, false); DL_ATTR(128, 4, true); DL_ATTR(128, 4, false);
+  DL_ATTR(64, 8, true); DL_ATTR(64, 8, false); DL_ATTR(64, 4, true); DL_ATTR(64, 4, false);
+#undef DL_ATTR
   attn_merge_ready = e == hipSuccess;
   return e;
 }
@@ -741,9 +1012,17 @@ hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const
     // many rows per kv head: K/V staged once per workgroup in LDS (at least 4 waves load)
     const bool paged = g.Q > 0;
     const bool fast = !paged || a.pt_shift >= 6;     // a 64-key block never straddles pages
+    // blocks inside one page (or the packed scratch): straight-to-LDS copies, if the ring and the sequence's
+    // page ids fit; otherwise the loader that goes through registers
+    a.pg_cap = paged ? (g.max_kv + f.page_tokens - 1) / f.page_tokens : 0;
+    const size_t ring = (size_t)(n_rg_wg <= 4 ? 2 : 3) * (size_t)(f.head_dim / 4) * 1024;   // NB buffers of head_dim/4 one-KiB fragments
+    const size_t dl_lds = ring + (size_t)a.pg_cap * sizeof(int32_t);
+    const bool direct = fast && attn_merge_ready && dl_lds <= (size_t)DL_LDS_MAX;
 #define ATTN_LDS(DHV, NWV)                                                                                 \
   do {                                                                                                     \
-    if (!paged) k_attn_lds<DHV, NWV, false, true><<<grid, NWV * 64, 0, s>>>(a);                            \
+    if (direct && paged) k_attn_dl<DHV, NWV, true><<<grid, NWV * 64, dl_lds, s>>>(a);                      \
+    else if (direct) k_attn_dl<DHV, NWV, false><<<grid, NWV * 64, dl_lds, s>>>(a);                         \
+    else if (!paged) k_attn_lds<DHV, NWV, false, true><<<grid, NWV * 64, 0, s>>>(a);                       \
     else if (fast) k_attn_lds<DHV, NWV, true, true><<<grid, NWV * 64, 0, s>>>(a);                          \
     else k_attn_lds<DHV, NWV, true, false><<<grid, NWV * 64, 0, s>>>(a);                                   \
   } while (0)

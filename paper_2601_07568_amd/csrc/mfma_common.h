@@ -30,6 +30,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 
+// Maximum over the four 16-lane rows of a wave, returned in every lane, without a trip through LDS: the
+// row swap exchanges rows 1 and 3 of its first operand with rows 0 and 2 of its second, the half swap the
+// upper half of the first with the lower half of the second, so the two results of a swap of x with
+// itself hold, lane by lane, x of both rows (halves) of a pair.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float x) {
+  const uint32_t xi = __float_as_uint(x);
+  const u32x2_t a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+  const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const uint32_t mi = __float_as_uint(m);
+  const u32x2_t b = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 #define WSM(c, field, type) ((type*)((c)->ws + (c)->map.field))
 
 }  // namespace dllm
