@@ -38,8 +38,10 @@
  *     slots of one channel contiguous, which is the operand layout of the P*V matrix
  *     instruction).  K is stored after the rotary embedding.  Position j of sequence b lives in
  *     page block_table[b * max_pages_per_seq + j / page_tokens], slot j % page_tokens.
- *   - Rounding points of a DLLM_BF16 model (everything else is float): the normalised GEMM input,
- *     q and k after the rotary embedding, v, the attention output, silu(gate) * up.
+ *   - Rounding points of a DLLM_BF16 model (everything else is float): the gain-scaled input of a
+ *     normalised product, bf16(x * gain) - the row factor 1/sqrt(mean(x^2) + eps) stays float and
+ *     multiplies the product's float sums -, q and k after the rotary embedding, v, the attention
+ *     output, silu(gate) * up.
  *   - Rotary embedding: half-split pairing (c, c + head_dim/2), angle = position * rope_base^(-2c/head_dim),
  *     positions counted from the start of the sequence.
  */
