@@ -104,13 +104,27 @@ def cpu_baseline(ms, P, Q, n_masked, budget_s=24.0):
                      f"confidence + unmask ({t_head*1e3:.0f} ms), numpy float64, all cores; step time extrapolated as "
                      f"{ms.n_layers} x layer + head",
            "one_layer_plus_head_step_s": t_layer + t_head}
+    # the tiny workload's whole decode (64 prompt tokens, one block of 32, threshold 0.9, floor 1), timed in full
+    tiny_w = synth.Weights(synth.TINY, 0)
+    tiny_p = synth.random_tokens(synth.TINY, 0, 64)
+
+    def tiny_decode():
+        t0 = time.perf_counter()
+        _, n_fw = O.decode(tiny_w, tiny_p, 1, 32, 0.9, 1)
+        return time.perf_counter() - t0, n_fw
+
+    tiny_decode()
+    t_tiny, n_fw = tiny_decode()
+    out["tiny_whole_decode_s"] = t_tiny
+    out["tiny_whole_decode_forwards"] = int(n_fw)
     if threadpool_limits is not None:
         with threadpool_limits(limits=1):
             n1, t1_layer, t1_head = timed(budget_s * 0.4, 4)
+            t1_tiny, _ = tiny_decode()
         out["single_thread"] = {"value": 1.0 / (ms.n_layers * t1_layer + t1_head), "unit": "steps/s", "cores": 1,
                                 "sample": f"{n1} layer forward(s) ({t1_layer*1e3:.0f} ms each) and one head "
                                           f"({t1_head*1e3:.0f} ms), one BLAS thread",
-                                "one_layer_plus_head_step_s": t1_layer + t1_head}
+                                "one_layer_plus_head_step_s": t1_layer + t1_head, "tiny_whole_decode_s": t1_tiny}
     return out
 
 

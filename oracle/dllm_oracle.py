@@ -359,7 +359,7 @@ def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", a
     a floor of 0 (Activated) or 1 (Fully-Activated), then the state transitions.
     refresh_every > 0: the periodic refresh, a forward without cache after that many cached rounds in a row.
     Every forward without cache rewrites the cache of the prompt and of the blocks Completed at the end of its round
-    ("forward passes without using the KV cache and refresh previous caches", Section 3.2).
+    (Section 3.2, multi-block paragraph: such a forward is also what renews the earlier caches).
     Returns (tokens of prompt + generation, number of forwards)."""
     ms = model.ms
     prompt = np.asarray(prompt, dtype=np.int64)
