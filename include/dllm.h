@@ -281,6 +281,48 @@ int dllm_fsm_window(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_
 int dllm_fsm_scatter(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, int W, const int32_t *win_tokens,
                      const int32_t *win_lo, const int32_t *q_valid, int32_t *gen_tokens);
 
+/* A whole round of multi-block decoding without a host read (Section 3.2, multi-block paragraph): the plan of
+ * dllm_fsm_plan decides on the device which sequences of the batch run the cached step and which the forward without
+ * cache; every launch is sized by host capacities, so the same sequence of calls serves every round (and replays as
+ * a captured graph):
+ *   dllm_fsm_round_windows  windows as dllm_fsm_window, but for every sequence that has an active block, whatever its
+ *                           forward; q_valid_cached[b] = q_valid[b] for the sequences of the cached step, 0 for those
+ *                           with nocache[b] != 0 (they take no part in dllm_denoise_step_var);
+ *   dllm_fsm_pack           the packed batch of the forward without cache: sequence b contributes, iff nocache[b] != 0
+ *                           and it has an active block, its prompt (prompt_tokens[b, 0 .. base_len[b])) followed by
+ *                           its generation up to the end of its window; cu_seqlens[b+1] - cu_seqlens[b] is that
+ *                           length or 0, n_commit[b] = n_commit_plan[b] (dllm_fsm_plan) or 0, rows of `tokens` behind
+ *                           the last sequence hold pad_token.  A sequence longer than max_seqlen, or one that does
+ *                           not fit token_capacity any more, is left out and DLLM_STATUS_BAD_LENGTH is set;
+ *   dllm_refresh_cache_dev  dllm_refresh_cache whose total is device-resident: token_capacity (a host value, at most
+ *                           max_tokens) sizes the launches, cu_seqlens[B] <= token_capacity rows are sequences, the
+ *                           rest is padding (no position, nothing cached, no LM-head row; GEMMs that tile over rows
+ *                           skip them); cu_seqlens[B] = 0 is legal: the call then does nothing but launch;
+ *   dllm_fsm_unpack         the step outputs of that forward (indexed by packed row) into the window layout [B, Q] of
+ *                           the sequences that took part: row j < q_valid[b] of sequence b is packed row
+ *                           cu_seqlens[b] + prefix_len[b] + j; the other sequences' entries are left as the cached
+ *                           step wrote them.
+ * Followed by dllm_unmask_blocks, dllm_fsm_scatter, dllm_fsm_update (nocache_round < 0) and dllm_fsm_plan.
+ *   prompt_tokens dev int32 [B, max_prompt]; nocache, n_commit_plan dev int32 [B] (dllm_fsm_plan);
+ *   tokens dev int32 [token_capacity]; cu_seqlens dev int32 [B + 1]; n_commit dev int32 [B];
+ *   packed_cand / packed_conf / packed_entropy dev [token_capacity] (packed_entropy and entropy may be NULL);
+ *   other arguments as for dllm_fsm_window / dllm_refresh_cache. */
+int dllm_fsm_round_windows(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, int W,
+                           const int32_t *gen_tokens, const int32_t *state, const int32_t *base_len,
+                           const int32_t *nocache, int32_t pad_token, int32_t *win_tokens, int32_t *win_floor,
+                           int32_t *prefix_len, int32_t *q_valid, int32_t *q_valid_cached, int32_t *win_lo);
+int dllm_fsm_pack(dllm_ctx *ctx, void *stream, int B, int n_blocks, int block_len, int W, int max_prompt,
+                  int token_capacity, int max_seqlen, const int32_t *prompt_tokens, const int32_t *gen_tokens,
+                  const int32_t *state, const int32_t *base_len, const int32_t *nocache, const int32_t *n_commit_plan,
+                  int32_t pad_token, int32_t *tokens, int32_t *cu_seqlens, int32_t *n_commit);
+int dllm_refresh_cache_dev(dllm_ctx *ctx, void *stream, int B, int token_capacity, int max_seqlen,
+                           const int32_t *tokens, const int32_t *cu_seqlens, const int32_t *n_commit,
+                           const int32_t *block_table, int32_t *cand_token, float *conf, float *entropy);
+int dllm_fsm_unpack(dllm_ctx *ctx, void *stream, int B, int Q, int token_capacity, const int32_t *cu_seqlens,
+                    const int32_t *prefix_len, const int32_t *q_valid, const int32_t *nocache,
+                    const int32_t *packed_cand, const float *packed_conf, const float *packed_entropy,
+                    int32_t *cand_token, float *conf, float *entropy);
+
 /* The selection of dllm_unmask / dllm_unmask_entropy that also records the decoding order (Section 3.1:
  * the teacher's pseudo-trajectory is the order in which its tokens are decoded, one per step, for the
  * full output length): order[b, i] = step_index for every position this call unmasks, other entries are

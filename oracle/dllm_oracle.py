@@ -419,6 +419,35 @@ def decode_multiblock(model, prompt, n_blocks, block_len, thr, rule="entropy", a
     return np.concatenate([prompt, gen]), rounds
 
 
+def round_batches(prompts, gens, states, nocache, n_commit_plan, block_len, max_window=None):
+    """How one round of multi-block decoding looks for a batch of sequences that each follow decode_multiblock
+    (Section 3.2, multi-block paragraph): sequence b with an active block runs either the cached step over its window
+    (nocache[b] false) or the forward without cache over prompt + generation up to the end of the window, which also
+    rewrites the first n_commit_plan[b] cached positions.  Returns a list, per sequence, of None (no active block: no
+    forward) or a dict with the window (lo, hi in blocks), the forward type, the tokens the forward runs over, the
+    number of cached positions it attends to (cached step) or rewrites (forward without cache), and the index of the
+    window's first row within those tokens."""
+    out = []
+    for b, (prompt, gen, st) in enumerate(zip(prompts, gens, states)):
+        active = [k for k, s in enumerate(st) if s in (ACTIVATED, FULLY_ACTIVATED)]
+        if not active:
+            out.append(None)
+            continue
+        lo, hi = active[0], active[-1]
+        if max_window is not None:
+            hi = min(hi, lo + max_window - 1)
+        P = len(prompt)
+        if nocache[b]:
+            toks = np.concatenate([np.asarray(prompt), np.asarray(gen)[:(hi + 1) * block_len]])
+            out.append({"lo": lo, "hi": hi, "nocache": True, "tokens": toks, "n_cached": int(n_commit_plan[b]),
+                        "window_row": P + lo * block_len})
+        else:
+            out.append({"lo": lo, "hi": hi, "nocache": False,
+                        "tokens": np.asarray(gen)[lo * block_len:(hi + 1) * block_len].copy(),
+                        "n_cached": P + lo * block_len, "window_row": 0})
+    return out
+
+
 # ---------------------------------------------------------------------------------------------
 # Teacher pseudo-trajectory (Section 3.1; appendix "Extracting Pseudo Trajectory of the Teacher
 # dLLM") and early stopping (Section 3.2, "Early Stopping on EOS Token").

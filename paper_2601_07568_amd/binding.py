@@ -69,6 +69,10 @@ def lib() -> C.CDLL:
         "dllm_scatter_rows": (i32, [vp, vp, i32, i32, vp, vp, vp, vp]),
         "dllm_fsm_plan": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp]),
         "dllm_fsm_window": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "dllm_fsm_round_windows": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "dllm_fsm_pack": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]),
+        "dllm_refresh_cache_dev": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "dllm_fsm_unpack": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "dllm_fsm_scatter": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
         "dllm_unmask_traced": (i32, [vp, vp, i32, i32, i32, vp, vp, vp, f32, i32, i32, i32, vp, vp, vp]),
         "dllm_noisy_sequence": (i32, [vp, vp, i32, i32, vp, vp, vp, i32, C.c_double, vp]),
@@ -287,6 +291,37 @@ class Engine:
         self._check(lib().dllm_fsm_window(self.ctx, self._stream(), B, NB, block_len, W, _ptr(gen_tokens), _ptr(state),
                                           _ptr(base_len), pad_token, _ptr(win_tokens), _ptr(win_floor),
                                           _ptr(prefix_len), _ptr(q_valid), _ptr(win_lo)))
+
+    def fsm_round_windows(self, gen_tokens, state, base_len, nocache, block_len, W, pad_token, win_tokens, win_floor,
+                          prefix_len, q_valid, q_valid_cached, win_lo):
+        B, NB = state.shape
+        self._check(lib().dllm_fsm_round_windows(self.ctx, self._stream(), B, NB, block_len, W, _ptr(gen_tokens),
+                                                 _ptr(state), _ptr(base_len), _ptr(nocache), pad_token,
+                                                 _ptr(win_tokens), _ptr(win_floor), _ptr(prefix_len), _ptr(q_valid),
+                                                 _ptr(q_valid_cached), _ptr(win_lo)))
+
+    def fsm_pack(self, prompt_tokens, gen_tokens, state, base_len, nocache, n_commit_plan, block_len, W, pad_token,
+                 tokens, cu_seqlens, n_commit, *, max_seqlen):
+        B, NB = state.shape
+        self._check(lib().dllm_fsm_pack(self.ctx, self._stream(), B, NB, block_len, W, prompt_tokens.shape[1],
+                                        tokens.numel(), max_seqlen, _ptr(prompt_tokens), _ptr(gen_tokens), _ptr(state),
+                                        _ptr(base_len), _ptr(nocache), _ptr(n_commit_plan), pad_token, _ptr(tokens),
+                                        _ptr(cu_seqlens), _ptr(n_commit)))
+
+    def refresh_cache_dev(self, tokens, cu_seqlens, block_table, n_commit, cand=None, conf=None, entropy=None,
+                          *, max_seqlen):
+        B = cu_seqlens.numel() - 1
+        self._check(lib().dllm_refresh_cache_dev(self.ctx, self._stream(), B, tokens.numel(), max_seqlen, _ptr(tokens),
+                                                 _ptr(cu_seqlens), _ptr(n_commit), _ptr(block_table), _ptr(cand),
+                                                 _ptr(conf), _ptr(entropy)))
+
+    def fsm_unpack(self, cu_seqlens, prefix_len, q_valid, nocache, packed_cand, packed_conf, packed_entropy, cand, conf,
+                   entropy=None):
+        B, Q = cand.shape
+        self._check(lib().dllm_fsm_unpack(self.ctx, self._stream(), B, Q, packed_cand.numel(), _ptr(cu_seqlens),
+                                          _ptr(prefix_len), _ptr(q_valid), _ptr(nocache), _ptr(packed_cand),
+                                          _ptr(packed_conf), _ptr(packed_entropy), _ptr(cand), _ptr(conf),
+                                          _ptr(entropy)))
 
     def fsm_scatter(self, win_tokens, win_lo, q_valid, gen_tokens, n_blocks, block_len, W):
         B = win_lo.numel()

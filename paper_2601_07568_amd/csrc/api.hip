@@ -323,6 +323,13 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g0, int n_lay
   StepGeom g = g0;
   if (g.Q > 0) g.prefix_len = WSP(c, len_safe, int32_t);
   else g.cu_seqlens = WSP(c, len_safe, int32_t);
+  if (g0.Q == 0 && g0.total_is_cap) {
+    // the sequences may end before the buffer does: the row count is in the workspace for the GEMMs that can skip rows
+    c->rows_dev = WSP(c, status, int32_t) + 2;
+    const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+    c->rows_dev = nullptr;
+    return rc;
+  }
   if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
   // a step over the live sequences only: the valid rows per sequence (-1 for the sequences past the live count) and
   // the number of live rows are in the workspace as well
@@ -614,7 +621,7 @@ extern "C" int dllm_debug_hidden(dllm_ctx* c, void* stream, int B, int Q, int ma
 
 static int packed_forward(dllm_ctx* c, void* stream, int B, int total_tokens, int max_seqlen,
                           const int32_t* tokens, const int32_t* cu_seqlens, const int32_t* n_cache,
-                          const int32_t* block_table, const HeadOut* head) {
+                          const int32_t* block_table, const HeadOut* head, bool total_is_cap = false) {
   if (!c || !tokens || !cu_seqlens || !block_table) return DLLM_EINVAL;
   if (B < 1 || total_tokens < 1 || max_seqlen < 1 || max_seqlen > total_tokens) return DLLM_EINVAL;
   if (B > c->cfg.max_batch || total_tokens > c->cfg.max_tokens) return DLLM_ESHAPE;
@@ -626,6 +633,7 @@ static int packed_forward(dllm_ctx* c, void* stream, int B, int total_tokens, in
   g.q_valid = nullptr;
   g.n_live = nullptr;
   g.block_table = block_table;
+  g.total_is_cap = total_is_cap;
   return run_forward(c, (hipStream_t)stream, g, c->cfg.n_layers, head, nullptr, nullptr);
 }
 
@@ -643,6 +651,17 @@ extern "C" int dllm_refresh_cache(dllm_ctx* c, void* stream, int B, int total_to
   if (!conf || !n_commit) return DLLM_EINVAL;   // step outputs only make sense for rows past n_commit
   HeadOut h{cand_token, conf, entropy};
   return packed_forward(c, stream, B, total_tokens, max_seqlen, tokens, cu_seqlens, n_commit, block_table, &h);
+}
+
+extern "C" int dllm_refresh_cache_dev(dllm_ctx* c, void* stream, int B, int token_capacity, int max_seqlen,
+                                      const int32_t* tokens, const int32_t* cu_seqlens, const int32_t* n_commit,
+                                      const int32_t* block_table, int32_t* cand_token, float* conf, float* entropy) {
+  if (!n_commit) return DLLM_EINVAL;
+  if (cand_token == nullptr)
+    return packed_forward(c, stream, B, token_capacity, max_seqlen, tokens, cu_seqlens, n_commit, block_table, nullptr, true);
+  if (!conf) return DLLM_EINVAL;
+  HeadOut h{cand_token, conf, entropy};
+  return packed_forward(c, stream, B, token_capacity, max_seqlen, tokens, cu_seqlens, n_commit, block_table, &h, true);
 }
 
 extern "C" int dllm_unmask(dllm_ctx* c, void* stream, int B, int Q, int block_len, int32_t* q_tokens,
@@ -720,6 +739,54 @@ extern "C" int dllm_fsm_window(dllm_ctx* c, void* stream, int B, int n_blocks, i
   if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || (int64_t)W * block_len > (1 << 24)) return DLLM_ESHAPE;
   TRY(launch_fsm_window((hipStream_t)stream, B, n_blocks, block_len, W, gen_tokens, state, base_len, pad_token,
                         win_tokens, win_floor, prefix_len, q_valid, win_lo), "fsm_window");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_round_windows(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, int W,
+                                      const int32_t* gen_tokens, const int32_t* state, const int32_t* base_len,
+                                      const int32_t* nocache, int32_t pad_token, int32_t* win_tokens, int32_t* win_floor,
+                                      int32_t* prefix_len, int32_t* q_valid, int32_t* q_valid_cached, int32_t* win_lo) {
+  if (!c || !gen_tokens || !state || !base_len || !nocache || !win_tokens || !win_floor || !prefix_len || !q_valid ||
+      !q_valid_cached || !win_lo)
+    return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || W < 1) return DLLM_EINVAL;
+  if (pad_token < 0 || pad_token >= c->cfg.vocab || pad_token == c->cfg.mask_id) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 24) || (int64_t)W * block_len > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_fsm_window((hipStream_t)stream, B, n_blocks, block_len, W, gen_tokens, state, base_len, pad_token,
+                        win_tokens, win_floor, prefix_len, q_valid, win_lo, nocache, q_valid_cached), "fsm_round_windows");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_pack(dllm_ctx* c, void* stream, int B, int n_blocks, int block_len, int W, int max_prompt,
+                             int token_capacity, int max_seqlen, const int32_t* prompt_tokens,
+                             const int32_t* gen_tokens, const int32_t* state, const int32_t* base_len,
+                             const int32_t* nocache, const int32_t* n_commit_plan, int32_t pad_token,
+                             int32_t* tokens, int32_t* cu_seqlens, int32_t* n_commit) {
+  if (!c || !prompt_tokens || !gen_tokens || !state || !base_len || !nocache || !n_commit_plan || !tokens ||
+      !cu_seqlens || !n_commit)
+    return DLLM_EINVAL;
+  if (B < 1 || n_blocks < 1 || block_len < 1 || W < 1 || max_prompt < 1 || token_capacity < 1 || max_seqlen < 1)
+    return DLLM_EINVAL;
+  if (pad_token < 0 || pad_token >= c->cfg.vocab || pad_token == c->cfg.mask_id) return DLLM_EINVAL;
+  if (n_blocks > DLLM_FSM_MAX_BLOCKS || B > (1 << 16) || (int64_t)n_blocks * block_len > (1 << 24) ||
+      token_capacity > (1 << 28))
+    return DLLM_ESHAPE;
+  TRY(launch_fsm_pack((hipStream_t)stream, B, n_blocks, block_len, W, max_prompt, token_capacity, max_seqlen, state,
+                      base_len, nocache, n_commit_plan, prompt_tokens, gen_tokens, pad_token, tokens, cu_seqlens,
+                      n_commit, WSP(c, status, int32_t)), "fsm_pack");
+  return DLLM_OK;
+}
+
+extern "C" int dllm_fsm_unpack(dllm_ctx* c, void* stream, int B, int Q, int token_capacity, const int32_t* cu_seqlens,
+                               const int32_t* prefix_len, const int32_t* q_valid, const int32_t* nocache,
+                               const int32_t* packed_cand, const float* packed_conf, const float* packed_entropy,
+                               int32_t* cand_token, float* conf, float* entropy) {
+  if (!c || !cu_seqlens || !prefix_len || !q_valid || !nocache || !packed_cand || !packed_conf || !cand_token || !conf)
+    return DLLM_EINVAL;
+  if (B < 1 || Q < 1 || token_capacity < 1) return DLLM_EINVAL;
+  if (B > (1 << 24) || Q > (1 << 24)) return DLLM_ESHAPE;
+  TRY(launch_fsm_unpack((hipStream_t)stream, B, Q, token_capacity, cu_seqlens, prefix_len, q_valid, nocache, packed_cand,
+                        packed_conf, packed_entropy, cand_token, conf, entropy), "fsm_unpack");
   return DLLM_OK;
 }
 

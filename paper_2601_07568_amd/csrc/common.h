@@ -206,6 +206,7 @@ struct StepGeom {           // which tokens a forward runs over
   const int32_t* n_live;       // dev [1] or nullptr (step): sequences b >= n_live[0] are not part of the call (no
                                // attention, no cache write, no LM-head row; GEMM rows past the live ones are skipped)
   const int32_t* cu_seqlens;   // dev [B+1] (packed) or nullptr
+  bool total_is_cap = false;   // packed: T is the capacity of the token buffer, the device-resident total may be smaller
   const int32_t* n_cache;      // dev [B] or nullptr (packed: how many positions go to the pool)
   const int32_t* block_table;  // dev [B, max_pages]
 };
@@ -244,7 +245,15 @@ hipError_t launch_unmask(hipStream_t s, int B, int Q, int block_len, int32_t* q_
                          int32_t* order = nullptr, int32_t step_index = 0);
 hipError_t launch_fsm_window(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* gen,
                              const int32_t* state, const int32_t* base_len, int32_t pad_token, int32_t* win_tokens,
-                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo);
+                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo,
+                             const int32_t* nocache = nullptr, int32_t* q_valid_cached = nullptr);
+hipError_t launch_fsm_pack(hipStream_t s, int B, int n_blocks, int block_len, int W, int max_prompt, int cap,
+                           int max_seqlen, const int32_t* state, const int32_t* base_len, const int32_t* nocache,
+                           const int32_t* n_commit_plan, const int32_t* prompt, const int32_t* gen, int32_t pad_token,
+                           int32_t* tokens, int32_t* cu, int32_t* n_commit, int32_t* status);
+hipError_t launch_fsm_unpack(hipStream_t s, int B, int Q, int cap, const int32_t* cu, const int32_t* prefix_len,
+                             const int32_t* q_valid, const int32_t* nocache, const int32_t* src_cand,
+                             const float* src_conf, const float* src_ent, int32_t* cand, float* conf, float* ent);
 hipError_t launch_fsm_scatter(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* win_tokens,
                               const int32_t* win_lo, const int32_t* q_valid, int32_t* gen);
 hipError_t launch_noisy_sequence(hipStream_t s, int B, int n, const int32_t* y, const int32_t* order, const int32_t* s_dev,

@@ -84,6 +84,13 @@ int main() {
     EXPECT(dllm_fsm_plan(ctx, nullptr, 1, 8, 32, ip, ip, nullptr, 4, nullptr, ip, ip), DLLM_EINVAL);
     EXPECT(dllm_fsm_window(ctx, nullptr, 1, 8, 32, 0, ip, ip, ip, 0, ip, ip, ip, ip, ip), DLLM_EINVAL);
     EXPECT(dllm_fsm_scatter(ctx, nullptr, 1, 8, 32, 2, ip, ip, nullptr, ip), DLLM_EINVAL);
+    EXPECT(dllm_fsm_round_windows(ctx, nullptr, 1, 8, 32, 2, ip, ip, ip, nullptr, 0, ip, ip, ip, ip, ip, ip), DLLM_EINVAL);
+    EXPECT(dllm_fsm_round_windows(ctx, nullptr, 1, 8, 32, 2, ip, ip, ip, ip, cfg.mask_id, ip, ip, ip, ip, ip, ip), DLLM_EINVAL);
+    EXPECT(dllm_fsm_pack(ctx, nullptr, 1, 8, 32, 2, 0, 128, 128, ip, ip, ip, ip, ip, ip, 0, ip, ip, ip), DLLM_EINVAL);
+    EXPECT(dllm_fsm_pack(ctx, nullptr, 1, 300, 32, 2, 64, 128, 128, ip, ip, ip, ip, ip, ip, 0, ip, ip, ip), DLLM_ESHAPE);
+    EXPECT(dllm_fsm_unpack(ctx, nullptr, 1, 0, 128, ip, ip, ip, ip, ip, fp, nullptr, ip, fp, nullptr), DLLM_EINVAL);
+    EXPECT(dllm_refresh_cache_dev(ctx, nullptr, 1, 64, 64, ip, ip, nullptr, ip, ip, fp, nullptr), DLLM_EINVAL);
+    EXPECT(dllm_refresh_cache_dev(ctx, nullptr, 1, 129, 129, ip, ip, ip, ip, ip, fp, nullptr), DLLM_ESHAPE);
     EXPECT(dllm_noisy_sequence(ctx, nullptr, 1, 32, ip, ip, ip, 8, 1.5, ip), DLLM_EINVAL);
     EXPECT(dllm_eos_scan(ctx, nullptr, 1, 32, ip, 5, ip, nullptr, ip, nullptr), DLLM_EINVAL);
     EXPECT(dllm_gather_rows(ctx, nullptr, 2, 4, ip, ip, ip, ip, 0), DLLM_EINVAL);

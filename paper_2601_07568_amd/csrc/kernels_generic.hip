@@ -47,9 +47,11 @@ __device__ inline float block_max(float v, float* red) {
 // packed total different from T, sets DLLM_STATUS_BAD_LENGTH.  With a live count (steps only): the valid rows per
 // sequence (q_valid[b] or Q for the live sequences b < n_live[0], -1 for the others: every row of theirs is padding
 // and their attention is skipped) and the number of rows up to the last live sequence for the GEMMs that can skip rows.
+// total_is_cap (packed forwards): T is only the capacity of the token buffer; the sequences may end before it, the
+// rows behind them are padding (no position) and the row count goes to status[2] for the GEMMs that can skip rows.
 __global__ void k_seq_check(int T, int B, int Q, int max_len, const int32_t* prefix_len, const int32_t* cu,
                             int32_t* len_safe, int32_t* cu_pad, const int32_t* q_valid, const int32_t* n_live,
-                            int32_t* q_valid_eff, int32_t* status) {
+                            int32_t* q_valid_eff, int32_t* status, int total_is_cap) {
   __shared__ int s_bad;
   if (threadIdx.x == 0) s_bad = 0;
   __syncthreads();
@@ -77,7 +79,8 @@ __global__ void k_seq_check(int T, int B, int Q, int max_len, const int32_t* pre
       len_safe[b + 1] = acc;
     }
     cu_pad[B] = pad;
-    if (acc != T) bad = 1;
+    if (acc != T && !total_is_cap) bad = 1;
+    if (total_is_cap) status[2] = acc;
     if (bad) s_bad = 1;
   }
   __syncthreads();
@@ -729,7 +732,8 @@ hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g) {
   const bool live = g.Q > 0 && g.n_live != nullptr;
   k_seq_check<<<1, 256, 0, s>>>(g.T, g.B, g.Q, g.Q > 0 ? g.max_kv - g.Q : g.max_kv, g.prefix_len, g.cu_seqlens,
                                 WS(c, len_safe, int32_t), WS(c, cu_pad, int32_t), g.Q > 0 ? g.q_valid : nullptr,
-                                live ? g.n_live : nullptr, WS(c, q_valid_eff, int32_t), WS(c, status, int32_t));
+                                live ? g.n_live : nullptr, WS(c, q_valid_eff, int32_t), WS(c, status, int32_t),
+                                g.Q == 0 && g.total_is_cap);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int32_t* qv = g.Q > 0 ? (live ? WS(c, q_valid_eff, int32_t) : g.q_valid) : nullptr;
@@ -1072,9 +1076,13 @@ hipError_t launch_fsm_plan(hipStream_t s, int B, int n_blocks, int block_len, co
 // Window of a cached round, per sequence: the run of active blocks (at most W), as the tokens, floors,
 // prefix length and valid-row count that dllm_denoise_step_var / dllm_unmask_blocks take.  A sequence that
 // has a stabilizing block (its round must not use the cache) or no active block gets an empty window.
+// With the plan of the round (nocache != nullptr) every sequence that has an active block gets its window, whatever
+// forward the round uses; q_valid_cached is the row count for the cached step (0 for the sequences the plan sends
+// through the forward without cache).
 __global__ void k_fsm_window(int n_blocks, int block_len, int W, const int32_t* gen, const int32_t* state,
                              const int32_t* base_len, int32_t pad_token, int32_t* win_tokens, int32_t* win_floor,
-                             int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo) {
+                             int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo, const int32_t* nocache,
+                             int32_t* q_valid_cached) {
   const int b = blockIdx.x;
   const int32_t* st = state + (int64_t)b * n_blocks;
   int lo = -1, hi = -1, stab = 0, done = 0;
@@ -1084,13 +1092,14 @@ __global__ void k_fsm_window(int n_blocks, int block_len, int W, const int32_t* 
     stab |= sk == DLLM_BLOCK_STABILIZING;
     done += sk == DLLM_BLOCK_COMPLETED;
   }
-  int nw = (lo < 0 || stab) ? 0 : hi - lo + 1;
+  int nw = (lo < 0 || (stab && !nocache)) ? 0 : hi - lo + 1;
   if (nw > W) nw = W;
   if (nw == 0) lo = done;                              // an empty window sits right behind the cached blocks
   if (threadIdx.x == 0) {
     prefix_len[b] = base_len[b] + lo * block_len;
     q_valid[b] = nw * block_len;
     win_lo[b] = lo;
+    if (q_valid_cached) q_valid_cached[b] = (nocache && nocache[b]) ? 0 : nw * block_len;
   }
   for (int k = threadIdx.x; k < W; k += blockDim.x) {
     const int sk = k < nw ? st[lo + k] : DLLM_BLOCK_INACTIVE;
@@ -1110,9 +1119,97 @@ __global__ void k_fsm_scatter(int n_blocks, int block_len, int W, const int32_t*
 
 hipError_t launch_fsm_window(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* gen,
                              const int32_t* state, const int32_t* base_len, int32_t pad_token, int32_t* win_tokens,
-                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo) {
+                             int32_t* win_floor, int32_t* prefix_len, int32_t* q_valid, int32_t* win_lo,
+                             const int32_t* nocache, int32_t* q_valid_cached) {
   k_fsm_window<<<B, 256, 0, s>>>(n_blocks, block_len, W, gen, state, base_len, pad_token, win_tokens, win_floor,
-                                 prefix_len, q_valid, win_lo);
+                                 prefix_len, q_valid, win_lo, nocache, q_valid_cached);
+  return hipGetLastError();
+}
+
+// The packed batch of a round's forward without cache: sequence b takes part iff the plan says so (nocache[b]) and it
+// has an active block; its tokens are the prompt followed by the generation up to the end of its window.  One thread
+// lays out the lengths (a sequence longer than max_seqlen, or one that does not fit the capacity any more, is left out
+// with DLLM_STATUS_BAD_LENGTH), the grid then copies the tokens; rows behind the last sequence hold pad_token.
+__global__ void k_fsm_pack_cu(int B, int n_blocks, int block_len, int W, int cap, int max_seqlen, const int32_t* state,
+                              const int32_t* base_len, const int32_t* nocache, const int32_t* n_commit_plan,
+                              int32_t* cu, int32_t* n_commit, int32_t* status) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int acc = 0, bad = 0;
+  cu[0] = 0;
+  for (int b = 0; b < B; ++b) {
+    const int32_t* st = state + (int64_t)b * n_blocks;
+    int lo = -1, hi = -1;
+    for (int k = 0; k < n_blocks; ++k) {
+      const int sk = st[k];
+      if (sk == DLLM_BLOCK_ACTIVATED || sk == DLLM_BLOCK_FULLY_ACTIVATED) { if (lo < 0) lo = k; hi = k; }
+    }
+    if (lo >= 0 && hi - lo + 1 > W) hi = lo + W - 1;
+    int len = 0;
+    if (nocache[b] && lo >= 0) {
+      const int base = base_len[b];
+      const int64_t want = (int64_t)base + (int64_t)(hi + 1) * block_len;
+      if (base < 0 || want > max_seqlen || acc + want > cap) bad = 1;
+      else len = (int)want;
+    }
+    int nc = len > 0 ? n_commit_plan[b] : 0;
+    if (nc < 0 || nc > len) { bad = 1; nc = nc < 0 ? 0 : len; }
+    n_commit[b] = nc;
+    acc += len;
+    cu[b + 1] = acc;
+  }
+  if (bad) atomicOr(status, DLLM_STATUS_BAD_LENGTH);
+}
+__global__ void k_fsm_pack_tokens(int B, int n_blocks, int block_len, int max_prompt, int cap, const int32_t* cu,
+                                  const int32_t* base_len, const int32_t* prompt, const int32_t* gen, int32_t pad_token,
+                                  int32_t* out) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= cap) return;
+  if (r >= cu[B]) { out[r] = pad_token; return; }
+  int lo = 0, hi = B;                                  // largest b with cu[b] <= r (its sequence is not empty: r < cu[B])
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= r) lo = mid; else hi = mid;
+  }
+  const int i = r - cu[lo], base = base_len[lo];
+  int32_t tok = pad_token;
+  if (i < base) { if (i < max_prompt) tok = prompt[(int64_t)lo * max_prompt + i]; }
+  else if (i - base < n_blocks * block_len) tok = gen[(int64_t)lo * n_blocks * block_len + (i - base)];
+  out[r] = tok;
+}
+// The way back: the step outputs of such a forward, indexed by packed row, into the window layout [B, Q] of the
+// sequences that took part (row j of sequence b's window is packed row cu[b] + prefix_len[b] + j).
+__global__ void k_fsm_unpack(int Q, int cap, const int32_t* cu, const int32_t* prefix_len, const int32_t* q_valid,
+                             const int32_t* nocache, const int32_t* src_cand, const float* src_conf, const float* src_ent,
+                             int32_t* cand, float* conf, float* ent) {
+  const int b = blockIdx.x;
+  if (!nocache[b] || cu[b + 1] == cu[b]) return;
+  int nv = q_valid[b];
+  nv = nv < 0 ? 0 : (nv > Q ? Q : nv);
+  const int64_t r0 = (int64_t)cu[b] + prefix_len[b];
+  for (int j = threadIdx.x; j < nv; j += blockDim.x) {
+    const int64_t r = r0 + j;
+    if (r < 0 || r >= cu[b + 1] || r >= cap) continue;
+    cand[(int64_t)b * Q + j] = src_cand[r];
+    conf[(int64_t)b * Q + j] = src_conf[r];
+    if (ent && src_ent) ent[(int64_t)b * Q + j] = src_ent[r];
+  }
+}
+hipError_t launch_fsm_pack(hipStream_t s, int B, int n_blocks, int block_len, int W, int max_prompt, int cap,
+                           int max_seqlen, const int32_t* state, const int32_t* base_len, const int32_t* nocache,
+                           const int32_t* n_commit_plan, const int32_t* prompt, const int32_t* gen, int32_t pad_token,
+                           int32_t* tokens, int32_t* cu, int32_t* n_commit, int32_t* status) {
+  k_fsm_pack_cu<<<1, 64, 0, s>>>(B, n_blocks, block_len, W, cap, max_seqlen, state, base_len, nocache, n_commit_plan, cu,
+                                 n_commit, status);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_fsm_pack_tokens<<<(cap + 255) / 256, 256, 0, s>>>(B, n_blocks, block_len, max_prompt, cap, cu, base_len, prompt, gen,
+                                                      pad_token, tokens);
+  return hipGetLastError();
+}
+hipError_t launch_fsm_unpack(hipStream_t s, int B, int Q, int cap, const int32_t* cu, const int32_t* prefix_len,
+                             const int32_t* q_valid, const int32_t* nocache, const int32_t* src_cand,
+                             const float* src_conf, const float* src_ent, int32_t* cand, float* conf, float* ent) {
+  k_fsm_unpack<<<B, 256, 0, s>>>(Q, cap, cu, prefix_len, q_valid, nocache, src_cand, src_conf, src_ent, cand, conf, ent);
   return hipGetLastError();
 }
 hipError_t launch_fsm_scatter(hipStream_t s, int B, int n_blocks, int block_len, int W, const int32_t* win_tokens,

@@ -223,3 +223,53 @@ def test_step_with_padding_rows(lens, qvalid):
         n_exact = H.check_step_outputs(ms, r, blks[b, :nv] == ms.mask_id, c[b, :nv], f[b, :nv], e[b, :nv], "bf16")
         assert n_exact >= 1
     eng.close()
+
+
+@pytest.mark.parametrize("lens,extra", [([70, 0, 55], 40), ([0, 0, 0], 96), ([130, 90, 60], 17)])
+def test_refresh_with_a_device_resident_total_equals_the_sized_call(lens, extra):
+    """dllm_refresh_cache_dev takes a token buffer that is larger than the packed batch (its capacity sizes the
+    launches, cu_seqlens[B] says where the batch ends, sequences may be empty): the cache it writes and the step
+    outputs of the real rows are those of dllm_refresh_cache called with the exact sizes; an empty batch changes
+    nothing.  (Capacity and total stay within the same tile class of the GEMMs, so the results are bit-identical.)"""
+    ms = SMALL
+    w = synth.Weights(ms, 21)
+    Bn = len(lens)
+    total = sum(lens)
+    cap = total + extra
+    eng = H.make_engine(ms, w, page_tokens=32, max_pages_per_seq=8, n_pages=Bn * 8, max_batch=Bn, max_q=64,
+                        max_tokens=cap)
+    table = eng.i32(H.identity_table(eng, Bn))
+    seqs = [synth.random_tokens(ms, 30 + b, n) for b, n in enumerate(lens)]
+    for s in seqs:                                              # the last 16 positions of a sequence are in flight
+        s[-16::2] = ms.mask_id
+    ncommit = eng.i32([max(n - 16, 0) for n in lens])
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    packed = np.concatenate(seqs + [np.zeros(0, dtype=np.int64)]).astype(np.int32)
+    dev = eng.device
+    pool0 = eng.kv_pool.clone()
+
+    def outs(n):
+        return (torch.full((n,), -7, dtype=torch.int32, device=dev), torch.full((n,), -7.0, device=dev),
+                torch.full((n,), -7.0, device=dev))
+
+    want = None
+    if total > 0:
+        c1, f1, e1 = outs(total)
+        eng.refresh_cache(eng.i32(packed), eng.i32(cu), table, ncommit, c1, f1, e1, total_tokens=total,
+                          max_seqlen=max(lens))
+        want = (eng.kv_pool.clone(), c1, f1, e1)
+        eng.kv_pool.copy_(pool0)
+    buf = np.full(cap, 3, dtype=np.int32)                      # rows behind the batch: any valid token
+    buf[:total] = packed
+    c2, f2, e2 = outs(cap)
+    eng.refresh_cache_dev(eng.i32(buf), eng.i32(cu), table, ncommit, c2, f2, e2, max_seqlen=max(max(lens), 1))
+    torch.cuda.synchronize()
+    assert eng.read_status() == 0
+    if total == 0:
+        assert torch.equal(eng.kv_pool, pool0)
+        assert int((c2 != -7).sum()) == 0                       # no row is a sequence's: nothing reported
+    else:
+        assert torch.equal(eng.kv_pool, want[0])
+        assert torch.equal(c2[:total], want[1]) and torch.equal(f2[:total], want[2]) and torch.equal(e2[:total], want[3])
+        assert int((c2[total:] != -7).sum()) == 0 and int((c2[:total] != -7).sum()) > 0
+    eng.close()

@@ -436,3 +436,106 @@ def test_early_stop_compaction_and_step_over_the_live_sequences(ms_name, Bn, Q):
     for b in finished_want:
         assert (back.cpu().numpy()[b] == gen[b]).all()
     eng.close()
+
+
+class RoundBuffers:
+    """Device state of a batch under multi-block decoding and the scratch of one round; nothing in here is read by the
+    host while rounds run."""
+
+    def __init__(self, eng, ms, prompts, NB, Wn, cap):
+        dev = eng.device
+        Bn = len(prompts)
+        lens = [len(p) for p in prompts]
+        self.Bn, self.NB, self.Wn, self.Q, self.cap = Bn, NB, Wn, Wn * BL, cap
+        self.max_seqlen = max(lens) + NB * BL
+        pt = np.zeros((Bn, max(lens)), dtype=np.int32)
+        for b, p in enumerate(prompts):
+            pt[b, :lens[b]] = p
+        self.prompts = eng.i32(pt)
+        self.base = eng.i32(lens)
+        i32 = dict(dtype=torch.int32, device=dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.gen = torch.full((Bn, NB * BL), ms.mask_id, **i32)
+        self.state = torch.zeros(Bn, NB, **i32)
+        self.state[:, 0] = O.FULLY_ACTIVATED
+        self.counter = torch.zeros(Bn, NB, **i32)
+        self.since, self.nocache, self.plan_commit = (torch.zeros(Bn, **i32) for _ in range(3))
+        self.win, self.wfl = torch.zeros(Bn, self.Q, **i32), torch.zeros(Bn, Wn, **i32)
+        self.pre, self.qv, self.qvc, self.wlo = (torch.zeros(Bn, **i32) for _ in range(4))
+        self.cand, self.conf, self.ent = torch.zeros(Bn, self.Q, **i32), torch.zeros(Bn, self.Q, **f32), torch.zeros(Bn, self.Q, **f32)
+        self.ptok, self.cu, self.ncommit = torch.zeros(cap, **i32), torch.zeros(Bn + 1, **i32), torch.zeros(Bn, **i32)
+        self.c2, self.f2, self.e2 = torch.zeros(cap, **i32), torch.zeros(cap, **f32), torch.zeros(cap, **f32)
+
+
+def device_round(eng, rb, table, thr, delay, refresh_every):
+    """One round of multi-block decoding of a batch as a fixed sequence of calls: no value comes back to the host."""
+    eng.fsm_round_windows(rb.gen, rb.state, rb.base, rb.nocache, BL, rb.Wn, 0, rb.win, rb.wfl, rb.pre, rb.qv, rb.qvc, rb.wlo)
+    eng.denoise_step_var(rb.win, rb.pre, rb.qvc, table, rb.cand, rb.conf, rb.ent, max_prefix_len=rb.max_seqlen)
+    eng.fsm_pack(rb.prompts, rb.gen, rb.state, rb.base, rb.nocache, rb.plan_commit, BL, rb.Wn, 0, rb.ptok, rb.cu,
+                 rb.ncommit, max_seqlen=rb.max_seqlen)
+    eng.refresh_cache_dev(rb.ptok, rb.cu, table, rb.ncommit, rb.c2, rb.f2, rb.e2, max_seqlen=rb.max_seqlen)
+    eng.fsm_unpack(rb.cu, rb.pre, rb.qv, rb.nocache, rb.c2, rb.f2, rb.e2, rb.cand, rb.conf, rb.ent)
+    eng.unmask_blocks(rb.win, rb.cand, rb.ent, thr, rb.wfl, True, BL)
+    eng.fsm_scatter(rb.win, rb.wlo, rb.qv, rb.gen, rb.NB, BL, rb.Wn)
+    eng.fsm_update(rb.gen, rb.state, rb.counter, BL, 0.1, 0.95, delay, None, None, None)
+    eng.fsm_plan(rb.state, rb.counter, rb.base, BL, refresh_every, rb.since, rb.nocache, rb.plan_commit)
+
+
+@pytest.mark.parametrize("refresh_every", [0, 3])
+def test_whole_multiblock_decode_of_a_batch_without_host_reads(refresh_every):
+    """Three sequences decoded to the end by one fixed sequence of calls per round: the plan on the device sends each
+    sequence through the cached step or through the packed forward without cache (whose total is device-resident), the
+    host reads nothing until the last round is enqueued.  Snapshots taken on the device after every round are then held
+    against the oracle's rounds, sequence by sequence, for as long as the two agree; they may part only on a round whose
+    selection was a near-tie in the oracle."""
+    ms = TINY
+    w = synth.Weights(ms, 0)
+    NB, Wn, thr, delay = 3, 3, 5.443, 1
+    lens = [64, 40, 57]
+    Bn = len(lens)
+    cap = sum(lens) + Bn * NB * BL
+    eng = H.make_engine(ms, w, page_tokens=16, max_pages_per_seq=12, n_pages=12 * Bn, max_batch=Bn, max_q=Wn * BL,
+                        max_tokens=cap)
+    prompts = [synth.random_tokens(ms, 50 + b, lens[b]) for b in range(Bn)]
+    recs, finals = [], []
+    for b in range(Bn):
+        rec = []
+        seq, _ = O.decode_multiblock(w, prompts[b], NB, BL, thr, "entropy", delay=delay, record=rec,
+                                     refresh_every=refresh_every)
+        recs.append(rec)
+        finals.append(seq[lens[b]:])
+    tab = eng.i32(H.identity_table(eng, Bn))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), tab, None, total_tokens=int(cu[-1]), max_seqlen=max(lens))
+    rb = RoundBuffers(eng, ms, prompts, NB, Wn, cap)
+    n_rounds = max(len(r) for r in recs) + 2
+    snaps = []
+    for _ in range(n_rounds):
+        flag = rb.nocache.clone()                      # forward type of the round about to run (device copy, no read)
+        device_round(eng, rb, tab, thr, delay, refresh_every)
+        snaps.append((flag, rb.gen.clone(), rb.state.clone(), rb.cu.clone()))
+    assert eng.read_status() == 0                      # the first host read
+    snaps = [tuple(t.cpu().numpy() for t in s) for s in snaps]
+    compared = mixed = nocache_seen = 0
+    for b in range(Bn):
+        rec = recs[b]
+        for rnd, r in enumerate(rec):
+            flag, gen, state, cu_d = snaps[rnd]
+            assert bool(flag[b]) == r["nocache"], (b, rnd)
+            n_packed = int(cu_d[b + 1] - cu_d[b])
+            assert n_packed == (lens[b] + (r["hi"] + 1) * BL if r["nocache"] else 0)
+            after = rec[rnd + 1]["before"] if rnd + 1 < len(rec) else finals[b]
+            if not (gen[b] == after).all():
+                # only a near-tie of the oracle's selection may go the other way; the trajectories part here
+                assert not decided(r, thr, "entropy", BL), (b, rnd, np.nonzero(gen[b] != r["before"])[0].tolist(), r["chosen"])
+                break
+            assert state[b].tolist() == r["state_after"]
+            compared += 1
+            nocache_seen += r["nocache"]
+            others = [flag[o] for o in range(Bn) if o != b and rnd < len(recs[o])]
+            mixed += bool(r["nocache"] and others and not all(others))
+        else:
+            # in step with the oracle to the end: the same text, and the rounds after the last one changed nothing
+            assert (snaps[-1][1][b] == finals[b]).all()
+    assert compared >= 12 and nocache_seen >= 2 and mixed >= 1, (compared, nocache_seen, mixed)
+    eng.close()

@@ -115,3 +115,58 @@ def test_cached_multiblock_round_as_one_graph(ms):
         progressed += int((gen != ms.mask_id).sum())
     assert progressed > 0 and eng.read_status() == 0
     eng.close()
+
+
+@pytest.mark.parametrize("ms", [synth.TINY, SMALL], ids=["tiny-f32", "small-bf16"])
+def test_whole_decode_round_as_one_graph(ms):
+    """The round that needs no host read - plan-driven windows, cached step, packed forward without cache with a
+    device-resident total, selection, write-back, transitions, next plan - captured once and replayed until the batch
+    is decoded: after every replay the tokens, states and plan equal those of the same rounds run eagerly."""
+    from tests.test_gpu_fsm import BL, RoundBuffers, device_round
+    NB, Wn, delay, refresh_every = 3, 3, 1, 4
+    lens = [48, 33, 64]
+    Bn = len(lens)
+    thr = 100.0 if ms is SMALL else 5.46
+    cap = sum(lens) + Bn * NB * BL
+    w = synth.Weights(ms, 12)
+    eng = H.make_engine(ms, w, page_tokens=16, max_pages_per_seq=12, n_pages=12 * Bn, max_batch=Bn, max_q=Wn * BL,
+                        max_tokens=cap)
+    table = eng.i32(H.identity_table(eng, Bn))
+    prompts = [synth.random_tokens(ms, 70 + b, lens[b]) for b in range(Bn)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+
+    def prefill():
+        eng.prefill_kv(eng.i32(np.concatenate(prompts)), eng.i32(cu), table, None, total_tokens=int(cu[-1]),
+                       max_seqlen=max(lens))
+
+    n_rounds = 14
+    prefill()
+    rb = RoundBuffers(eng, ms, prompts, NB, Wn, cap)
+    eager = []
+    for _ in range(n_rounds):
+        device_round(eng, rb, table, thr, delay, refresh_every)
+        eager.append([t.clone() for t in (rb.gen, rb.state, rb.counter, rb.nocache, rb.plan_commit, rb.cu)])
+    torch.cuda.synchronize()
+    assert any(int(e[5][-1]) > 0 for e in eager) and any(int(e[5][-1]) == 0 for e in eager)   # both kinds of round
+    assert int((eager[-1][0] == ms.mask_id).sum()) < int((eager[0][0] == ms.mask_id).sum())
+
+    prefill()
+    rg = RoundBuffers(eng, ms, prompts, NB, Wn, cap)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        device_round(eng, rg, table, thr, delay, refresh_every)
+    torch.cuda.synchronize()
+    fresh = RoundBuffers(eng, ms, prompts, NB, Wn, cap)        # the capture itself runs nothing, but start clean anyway
+    for name in ("gen", "state", "counter", "since", "nocache", "plan_commit"):
+        getattr(rg, name).copy_(getattr(fresh, name))
+    prefill()
+    for rnd in range(n_rounds):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [rg.gen, rg.state, rg.counter, rg.nocache, rg.plan_commit, rg.cu]
+        for g, e in zip(got, eager[rnd]):
+            assert torch.equal(g, e), rnd
+        _ = (rg.gen + 1).sum().item()                          # eager work and a synchronisation between replays
+    assert eng.read_status() == 0
+    eng.close()

@@ -779,3 +779,39 @@ def test_oracle_reproduces_the_stored_tiny_trajectory():
             assert x["chosen"] == y["chosen"] and x["tokens"] == y["tokens"]
             np.testing.assert_allclose(x["conf"], y["conf"], rtol=0, atol=2e-6)
             np.testing.assert_allclose(x["entropy"], y["entropy"], rtol=0, atol=2e-5)
+
+
+def test_round_batches_on_a_hand_worked_batch():
+    """The per-sequence forwards of one round of a batch (cached step over the window, or forward without cache over
+    prompt + generation up to the window's end), written out by hand for three sequences; the second case cross-checks
+    the forward type and cache length against a decode_multiblock record."""
+    BL = 2
+    prompts = [[1, 2, 3], [4], [5, 6]]
+    gens = [[10, 11, 9, 9, 9, 9], [20, 9, 9, 9, 9, 9], [30, 31, 32, 33, 34, 35]]
+    A, F, S, C, I = O.ACTIVATED, O.FULLY_ACTIVATED, O.STABILIZING, O.COMPLETED, O.INACTIVE
+    states = [[S, F, A], [F, A, I], [C, C, S]]
+    rb = O.round_batches(prompts, gens, states, [True, False, True], [3, 0, 6], BL)
+    assert rb[2] is None                                              # no active block: no forward at all
+    assert rb[0]["nocache"] and (rb[0]["lo"], rb[0]["hi"]) == (1, 2)
+    assert rb[0]["tokens"].tolist() == [1, 2, 3, 10, 11, 9, 9, 9, 9] and rb[0]["n_cached"] == 3
+    assert rb[0]["window_row"] == 3 + 1 * BL                          # prompt, then the stabilizing block, then the window
+    assert not rb[1]["nocache"] and (rb[1]["lo"], rb[1]["hi"]) == (0, 1)
+    assert rb[1]["tokens"].tolist() == [20, 9, 9, 9] and rb[1]["n_cached"] == 1 and rb[1]["window_row"] == 0
+    # a window cap cuts the forward's extent with the window
+    rb = O.round_batches(prompts, gens, states, [True, False, True], [3, 0, 6], BL, max_window=1)
+    assert rb[0]["hi"] == 1 and rb[0]["tokens"].tolist() == [1, 2, 3, 10, 11, 9, 9]
+    assert rb[1]["hi"] == 0 and rb[1]["tokens"].tolist() == [20, 9]
+    # against a decode: every recorded round's forward is what round_batches derives from its state and the plan
+    w = synth.Weights(synth.TINY, 0)
+    prompt = synth.random_tokens(synth.TINY, 0, 24)
+    rec = []
+    O.decode_multiblock(w, prompt, 2, 8, 5.443, "entropy", delay=1, record=rec, refresh_every=3)
+    since, noc, ncp = 0, False, 0
+    for i, r in enumerate(rec):
+        (one,) = O.round_batches([prompt], [r["before"]], [r["state"]], [noc], [ncp], 8)
+        assert one["nocache"] == r["nocache"] and (one["lo"], one["hi"]) == (r["lo"], r["hi"])
+        if r["nocache"]:
+            assert one["n_cached"] == r["n_cached"] and len(one["tokens"]) == 24 + (r["hi"] + 1) * 8
+        else:
+            assert one["n_cached"] == r["n_cached"]
+        since, noc, ncp = O.fsm_plan(r["state_after"], r["counter_after"], 8, 24, 3, since, r["nocache"])
