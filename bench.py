@@ -219,6 +219,70 @@ def multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev
             "fully_activate": full_at, "stabilizing_rounds": delay, "periodic_refresh_every": refresh_every}
 
 
+def multiblock_generation_device(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev, theta=0.45, add_at=0.1,
+                                 full_at=0.95, delay=1, refresh_every=16, W=2, max_rounds=400):
+    """The same multi-block generation with no host read inside the decode: one fixed sequence of calls per round (the
+    plan on the device picks, per sequence, the cached step or the packed forward without cache, whose total is
+    device-resident), captured once as a HIP graph and replayed; the host looks at the tokens every 16 rounds only to
+    stop.  Windows are at most W blocks; every launch is sized for that and for the longest sequence, which is what a
+    round costs when nothing comes back to the host to size it."""
+    NB, Bn = n_blocks, 1
+    cap = P + NB * Q
+    i32 = dict(dtype=torch.int32, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    gen = torch.full((Bn, NB * Q), ms.mask_id, **i32)
+    state = torch.zeros(Bn, NB, **i32)
+    state[:, 0] = 2
+    counter = torch.zeros(Bn, NB, **i32)
+    since, nocache, plan_commit = (torch.zeros(Bn, **i32) for _ in range(3))
+    base = eng.i32([P])
+    prompts = prompt.reshape(1, P).contiguous()
+    win, wfl = torch.zeros(Bn, W * Q, **i32), torch.zeros(Bn, W, **i32)
+    pre, qv, qvc, wlo = (torch.zeros(Bn, **i32) for _ in range(4))
+    cand, conf, ent = torch.zeros(Bn, W * Q, **i32), torch.zeros(Bn, W * Q, **f32), torch.zeros(Bn, W * Q, **f32)
+    ptok, cu, ncommit = torch.zeros(cap, **i32), torch.zeros(Bn + 1, **i32), torch.zeros(Bn, **i32)
+    c2, f2, e2 = torch.zeros(cap, **i32), torch.zeros(cap, **f32), torch.zeros(cap, **f32)
+
+    def one_round():
+        eng.fsm_round_windows(gen, state, base, nocache, Q, W, 0, win, wfl, pre, qv, qvc, wlo)
+        eng.denoise_step_var(win, pre, qvc, table, cand, conf, ent, max_prefix_len=cap)
+        eng.fsm_pack(prompts, gen, state, base, nocache, plan_commit, Q, W, 0, ptok, cu, ncommit, max_seqlen=cap)
+        eng.refresh_cache_dev(ptok, cu, table, ncommit, c2, f2, e2, max_seqlen=cap)
+        eng.fsm_unpack(cu, pre, qv, nocache, c2, f2, e2, cand, conf, ent)
+        eng.unmask_blocks(win, cand, ent, theta, wfl, True, Q)
+        eng.fsm_scatter(win, wlo, qv, gen, NB, Q, W)
+        eng.fsm_update(gen, state, counter, Q, add_at, full_at, delay, None, None, None)
+        eng.fsm_plan(state, counter, base, Q, refresh_every, since, nocache, plan_commit)
+
+    eng.prefill_kv(prompt, eng.i32([0, P]), table, None, total_tokens=P, max_seqlen=P)
+    one_round()                                                    # warm-up outside the capture, then start over
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_round()
+    gen.fill_(ms.mask_id)
+    state.zero_()
+    state[:, 0] = 2
+    for t in (counter, since, nocache, plan_commit):
+        t.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.prefill_kv(prompt, eng.i32([0, P]), table, None, total_tokens=P, max_seqlen=P)
+    rounds = 0
+    while rounds < max_rounds:
+        for _ in range(16):
+            graph.replay()
+        rounds += 16
+        if int((gen == ms.mask_id).sum()) == 0:
+            break
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    assert int((gen == ms.mask_id).sum()) == 0 and eng.read_status() == 0
+    return {"tokens": NB * Q, "rounds_replayed": rounds, "seconds": sec, "tokens_per_s": NB * Q / sec,
+            "ms_per_round": sec * 1e3 / rounds, "window_blocks": W, "launch": "one HIP graph per round, replayed",
+            "host_reads": "the token array once per 16 rounds, to stop"}
+
+
 def batch1(args, torch, np, synth, Engine, dev, workload, steps, warmup, extras):
     """Batch-1 step of the LLaDA-8B-shaped model: "c3" = the whole model, prompt 1024 (headline), "c2" = one layer +
     LM head, prefix 512.  extras: generation legs, attainable rates (they need the engine)."""
@@ -379,6 +443,7 @@ def batch1(args, torch, np, synth, Engine, dev, workload, steps, warmup, extras)
                            "TFLOPs": refresh_flops / refresh_s / 1e12}}
         # ---- the same generation with multi-block decoding (entropy rule, block state machine on the device)
         gen_mb = multiblock_generation(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev)
+        gen_mb["without_host_reads"] = multiblock_generation_device(eng, ms, prompt, P, Q, n_blocks, table, torch, np, dev)
     out["generation"] = gen
     out["generation_multiblock"] = gen_mb
     out["attainable"] = attainable(eng, torch, dev)
