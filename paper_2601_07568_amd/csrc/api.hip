@@ -56,7 +56,8 @@ static bool build_map(const dllm_config* c, Workspace* m) {
   m->vpack = take(((size_t)m->tpad * dkv + 64) * es);
   m->cu_pad = take(((size_t)c->max_batch + 1) * 4);
   m->o = take((t_max + 16) * (dq + 128) * es);
-  m->g = take(t_max * c->d_ff * 4);
+  m->g_bytes = t_max * c->d_ff * 4;
+  m->g = take(m->g_bytes);
   m->u = take(t_max * c->d_ff * 4);
   m->h = take((t_max + 16) * ((size_t)c->d_ff + 128) * es);
   m->rope_cos = take(t_max * half * 4);
@@ -411,8 +412,9 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
     } else {
       if (big_mfma) {
         ProfScope p(c, s, 2, 2.0 * T * 2.0 * f.d_ff * f.d_model);
+        // (the float gate buffer of the generic path is free here: scratch for the K-split tail tiles)
         TRY(launch_gemm_swiglu(s, c->ws + c->map.xn, L.w_gate, L.w_up, c->ws + c->map.h, T, f.d_ff, f.d_model,
-                               WSP(c, rscale, float), c->rows_dev), "gate_up");
+                               WSP(c, rscale, float), c->rows_dev, WSP(c, g, float), c->map.g_bytes), "gate_up");
       } else {
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_gate, c->ws + c->map.g, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_gate");
         TRY(gemm_any(c, s, c->ws + c->map.xn, L.w_up, c->ws + c->map.u, T, f.d_ff, f.d_model, EPI_STORE_F32, true), "w_up");

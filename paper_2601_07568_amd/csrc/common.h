@@ -160,6 +160,7 @@ struct Workspace {
   int64_t t_max, r_max, t_step, tpad;
   int32_t n_vtiles, max_splits;
   size_t scratch_bytes;
+  size_t g_bytes;      // size of the g region (bfloat16 models on the matrix-core path use it for K-split tail tiles)
 };
 
 }  // namespace dllm
@@ -294,8 +295,10 @@ hipError_t launch_gemm_qkv_split(dllm_ctx* c, hipStream_t s, const void* A, cons
 hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const void* Wk, const void* Wv, float* q32,
                            float* k32, void* v, int M, int dq, int dkv, int K, const float* rscale,
                            const int32_t* m_dev);
+// tail / tail_bytes: optional float scratch for the K-split tail tiles of the 256-row kernel (nullptr: none)
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K, const float* rscale, const int32_t* m_dev);
+                              int K, const float* rscale, const int32_t* m_dev, float* tail = nullptr,
+                              size_t tail_bytes = 0);
 hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 hipError_t launch_probe_read(hipStream_t s, const void* buf, size_t bytes, void* sink);
 hipError_t launch_probe_mfma(hipStream_t s, int iters, void* sink, double* flops);

@@ -36,6 +36,7 @@ struct LgArgs {
   const float* rscale;     // optional [M]: A holds x * gain rounded to bfloat16; the row's normalisation factor
                            // multiplies the float accumulators (every epilogue but RESID, whose input is not a norm's)
   int M, N, K, tiles_m, tiles_n;
+  float* tail;             // 256-row SWIGLU: scratch for the accumulators of K-split tail tiles, or nullptr
   float* part;             // LMSTATS: [rows, n_parts, 4]
   int n_parts;
   int32_t mask_id;
@@ -297,6 +298,24 @@ __device__ __forceinline__ void t2_copy16(const void* g, void* l) {
                                    (__attribute__((address_space(3))) void*)l, 16, 0, 0);
 }
 
+// The last, partly filled round of the persistent workgroups: when the tiles do not divide by the workgroups, the
+// tiles of the last round are split along K so that every workgroup gets a share of them (at most T2_TAIL_SPLITS
+// shares per tile); their accumulators go to scratch in register order and k_swiglu_tail adds the shares and applies
+// the epilogue.  Derived from the device-resident row count, the same way in both kernels.
+constexpr int T2_TAIL_SPLITS = 3, T2_TAIL_FLOATS = 256 * 256;
+struct T2Tail { int n_full, n_tail, splits; };
+__device__ __forceinline__ T2Tail t2_tail_plan(int n_tiles, int n_wg, bool enabled) {
+  T2Tail t{n_tiles, 0, 1};
+  if (!enabled || n_tiles <= n_wg) return t;
+  const int nf = (n_tiles / n_wg) * n_wg, nt = n_tiles - nf;
+  if (nt == 0) return t;
+  int sp = n_wg / nt;
+  sp = sp > T2_TAIL_SPLITS ? T2_TAIL_SPLITS : sp;
+  if (sp < 2) return t;
+  t.n_full = nf; t.n_tail = nt; t.splits = sp;
+  return t;
+}
+
 template <int EPI>
 __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char t2_smem[];
@@ -314,18 +333,33 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   // share a weight tile run at the same time next to the same L2.
   const int tiles_m = (M + 255) / 256;
   const int n_tiles = tiles_m * a.tiles_n;
-  const int n_items = n_tiles * a.k_splits;
-  const int per_xcd = (n_items + 7) / 8;
-  for (int iw = blockIdx.x >> 3; iw < per_xcd; iw += gridDim.x >> 3) {
+  // two passes over the work items, each dealt the same way: the whole tiles (all K splits of the launch), then the
+  // K shares of the tail tiles (SiLU*up launches with scratch only)
+  const T2Tail tp = t2_tail_plan(n_tiles, gridDim.x, EPI == LG_SWIGLU && a.tail != nullptr);
+  const int n_items_a = tp.n_full * a.k_splits, n_items_b = tp.n_tail * tp.splits;
+  const int per_xcd_a = (n_items_a + 7) / 8, per_xcd_b = (n_items_b + 7) / 8;
+  const int step = gridDim.x >> 3;
+  const int iters_a = (per_xcd_a + step - 1) / step, iters_b = (per_xcd_b + step - 1) / step;
+  for (int it = 0; it < iters_a + iters_b; ++it) {
+  const bool is_tail = it >= iters_a;
+  const int iw = (blockIdx.x >> 3) + (is_tail ? it - iters_a : it) * step;
+  const int per_xcd = is_tail ? per_xcd_b : per_xcd_a;
   const int item = (blockIdx.x & 7) * per_xcd + iw;
-  if (item >= n_items) break;
-  const int split = item / n_tiles, tile = item - split * n_tiles;
+  if (iw >= per_xcd || item >= (is_tail ? n_items_b : n_items_a)) continue;
+  int split, tile;
+  if (is_tail) { split = item / tp.n_tail; tile = tp.n_full + (item - split * tp.n_tail); }
+  else { split = item / tp.n_full; tile = item - split * tp.n_full; }
   const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
   const int m0 = tm * 256, n0 = tn * TILE_N;
   int k_begin = 0, k_end = K;
   if constexpr (EPI == LG_RESID || EPI == LG_QKV) {
     k_begin = split * a.k_per;
     k_end = k_begin + a.k_per < K ? k_begin + a.k_per : K;
+  }
+  if (is_tail) {
+    const int per = ((K / 32) + tp.splits - 1) / tp.splits * 32;
+    k_begin = split * per;
+    k_end = k_begin + per < K ? k_begin + per : K;
   }
   // the ring is free once every wave has read the previous item's last operands
   __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
@@ -426,6 +460,20 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
 #undef T2_MMA
   __builtin_amdgcn_s_waitcnt(T2_VMCNT(0));   // the ring's trailing repeats must not outlive the workgroup
 
+  if (EPI == LG_SWIGLU && is_tail) {
+    // a K share of a tail tile: the raw accumulators, in register order (a lane's 16 floats contiguous)
+    float* dst = a.tail + ((int64_t)split * tp.n_tail + (tile - tp.n_full)) * T2_TAIL_FLOATS;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4* d = (f32x4*)(dst + ((((w * 4 + i) * 4 + j) * 64 + lane) << 4));
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          d[e4] = f32x4{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+      }
+    continue;
+  }
   // lane holds token column l%32 of token tile j; features (e/4)*8 + (l/32)*4 + e%4 of weight tile i
   if constexpr (EPI == LG_LMSTATS) {
 #pragma unroll
@@ -531,6 +579,55 @@ __global__ __launch_bounds__(256) void k_gemm_t256(const LgArgs a) {
   }
   }   // store epilogues
   }   // work items
+}
+
+// The K shares of the tail tiles of a SiLU(gate)*up launch of k_gemm_t256: one workgroup of 64 lanes per (tail tile,
+// wave, gate tile i, token tile j) adds the shares in order, applies the row factor and the activation and stores the
+// 32 x 32 outputs exactly as the fused epilogue would.
+__global__ __launch_bounds__(64) void k_swiglu_tail(const LgArgs a, int n_wg) {
+  int M = a.M;
+  if (a.m_dev) { const int md = *a.m_dev; M = md < M ? md : M; }
+  const int tiles_m = (M + 255) / 256;
+  const T2Tail tp = t2_tail_plan(tiles_m * a.tiles_n, n_wg, true);
+  const int tail = blockIdx.x >> 5, sub = blockIdx.x & 31;
+  if (tail >= tp.n_tail) return;
+  const int w = sub >> 3, i = (sub >> 2) & 1, j = sub & 3, lane = threadIdx.x;
+  const int wm = w & 1, wn = w >> 1, r = lane & 31, h = lane >> 5;
+  const int tile = tp.n_full + tail;
+  const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+  const int m = tm * 256 + wm * 128 + j * 32 + r;
+  if (m >= M) return;
+  const int N = a.N;
+  float gt[16], up[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { gt[e] = 0.f; up[e] = 0.f; }
+  for (int sp = 0; sp < tp.splits; ++sp) {
+    const float* src = a.tail + ((int64_t)sp * tp.n_tail + tail) * T2_TAIL_FLOATS;
+    const f32x4* g4 = (const f32x4*)(src + ((((w * 4 + i) * 4 + j) * 64 + lane) << 4));
+    const f32x4* u4 = (const f32x4*)(src + ((((w * 4 + i + 2) * 4 + j) * 64 + lane) << 4));
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const f32x4 gv = g4[e4], uv = u4[e4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { gt[e4 * 4 + e] += gv[e]; up[e4 * 4 + e] += uv[e]; }
+    }
+  }
+  const float rs = a.rscale ? a.rscale[m] : 1.0f;
+#pragma unroll
+  for (int e4 = 0; e4 < 4; ++e4) {
+    const int n = tn * 128 + wn * 64 + i * 32 + e4 * 8 + h * 4;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float gg = gt[e4 * 4 + e] * rs;
+      v[e] = gg * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gg)) * (up[e4 * 4 + e] * rs);
+    }
+    if (n + 4 <= N) {
+      *(uint2*)((bf16_t*)a.C + (int64_t)m * N + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    } else {
+      for (int e = 0; e < 4 && n + e < N; ++e) ((bf16_t*)a.C)[(int64_t)m * N + n + e] = f32_to_bf16(v[e]);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -875,14 +972,25 @@ hipError_t launch_gemm_qkv(hipStream_t s, const void* A, const void* Wq, const v
 
 // h[M,F] = silu(A Wg^T) * (A Wu^T), bfloat16 row-major
 hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, const void* Wu, void* H, int M, int F,
-                              int K, const float* rscale, const int32_t* m_dev) {
+                              int K, const float* rscale, const int32_t* m_dev, float* tail, size_t tail_bytes) {
   LgArgs a;
   memset(&a, 0, sizeof(a));
   a.rscale = rscale;
   a.m_dev = m_dev;
   a.A = (const bf16_t*)A; a.W = (const bf16_t*)Wg; a.W2 = (const bf16_t*)Wu; a.C = H; a.M = M; a.N = F; a.K = K;
   if (ts_usable(M, K)) return ts_launch<LG_SWIGLU, 2>(s, a);
-  if (t2_usable(M, K)) return t2_launch<LG_SWIGLU>(s, a);
+  if (t2_usable(M, K)) {
+    // K-split tail tiles need scratch for one share per workgroup; worth it only if whole rounds come before them
+    const int tiles = ((M + 255) / 256) * ((F + 127) / 128);
+    const bool split_tail = tail != nullptr && tail_bytes >= (size_t)t2_cus * T2_TAIL_FLOATS * sizeof(float) &&
+                            tiles > t2_cus && tiles % t2_cus != 0 && K >= 32 * 8 * T2_TAIL_SPLITS;
+    a.tail = split_tail ? tail : nullptr;
+    hipError_t e = t2_launch<LG_SWIGLU>(s, a);
+    if (e != hipSuccess || !split_tail) return e;
+    a.tiles_n = (F + 127) / 128;
+    k_swiglu_tail<<<(t2_cus - 1) * 32, 64, 0, s>>>(a, t2_cus);
+    return hipGetLastError();
+  }
   return lg_launch<LG_SWIGLU>(s, a);
 }
 
