@@ -143,8 +143,10 @@ extern "C" int dllm_create(dllm_ctx** out, const dllm_config* cfg, const dllm_we
   if (cfg->dtype == DLLM_BF16) {
     // raising two kernels' LDS limits; a failure (e.g. no device in this process) is not an error of the call: the
     // launchers check the flags these leave and take the kernels that need no raised limit
-    (void)init_gemm_t256();      // without it the 128-row kernels serve every size
-    (void)init_attn_kernels();   // without it every wave of the batch-1 attention writes its own partial
+    const hipError_t e1 = init_gemm_t256();      // without it the 128-row kernels serve every size
+    const hipError_t e2 = init_attn_kernels();   // without it every wave of the batch-1 attention writes its own partial
+    // such a failure must not surface later as the "last error" of an unrelated launch
+    if (e1 != hipSuccess || e2 != hipSuccess) (void)hipGetLastError();
   }
   *out = c;
   return DLLM_OK;
