@@ -144,10 +144,14 @@ def attainable(eng, torch, dev):
     del buf, small
     fl = eng.probe_mfma(20000, sink)
     tm = event_times_ms(torch, lambda i: eng.probe_mfma(20000, sink), 3)
+    eng.probe_mfma(20000, sink, True)
+    tr = event_times_ms(torch, lambda i: eng.probe_mfma(20000, sink, True), 3)
     return {"hbm_GBps": gbs, "hbm_read_100MB_us": statistics.median(t100) * 1e3,
             "mfma_bf16_TFLOPs": fl / (statistics.median(tm) * 1e-3) / 1e12,
+            "mfma_bf16_random_operands_TFLOPs": fl / (statistics.median(tr) * 1e-3) / 1e12,
             "how": "dllm_probe_hbm_read over 2 GiB and over 100 MB (one launch each, events); dllm_probe_mfma: "
-                   "32x32x16 bf16 products on register operands, one wave per SIMD"}
+                   "32x32x16 bf16 products on register operands, one wave per SIMD, with operands of one sign and exponent and "
+                   "with random signs, exponents and mantissas (what the chip sustains depends on the switching activity)"}
 
 
 # ----------------------------------------------------------------------------------------------- batch-1 workloads

@@ -423,10 +423,12 @@ int dllm_profile_read(dllm_ctx *ctx, void *stream, int cls, int32_t *n_launches,
  * bytes at buf (dev, 16-byte aligned; every lane keeps eight 16-byte loads in flight; nothing is written but, at
  * most, one word of sink).  dllm_probe_mfma enqueues a kernel of nothing but 32x32x16 bfloat16 matrix instructions
  * on register operands (one wave per SIMD, sixteen independent accumulators) and returns the floating-point
- * operations of that launch in *flops (host).  The caller times them with events on `stream`.
+ * operations of that launch in *flops (host); random_bits != 0 gives the operands random signs, mantissas and
+ * exponents (the switching activity of real data; the rate the chip sustains depends on it), 0 values that share
+ * sign and exponent.  The caller times them with events on `stream`.
  *   sink dev, at least 4 bytes. */
 int dllm_probe_hbm_read(dllm_ctx *ctx, void *stream, const void *buf, size_t bytes, void *sink);
-int dllm_probe_mfma(dllm_ctx *ctx, void *stream, int iters, void *sink, double *flops);
+int dllm_probe_mfma(dllm_ctx *ctx, void *stream, int iters, int random_bits, void *sink, double *flops);
 
 const char *dllm_strerror(int code);
 const char *dllm_last_hip_error(const dllm_ctx *ctx);

@@ -89,7 +89,7 @@ def lib() -> C.CDLL:
         "dllm_profile_read": (i32, [vp, vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                     C.POINTER(C.c_double)]),
         "dllm_probe_hbm_read": (i32, [vp, vp, vp, sz, vp]),
-        "dllm_probe_mfma": (i32, [vp, vp, i32, vp, C.POINTER(C.c_double)]),
+        "dllm_probe_mfma": (i32, [vp, vp, i32, i32, vp, C.POINTER(C.c_double)]),
         "dllm_strerror": (C.c_char_p, [i32]),
         "dllm_last_hip_error": (C.c_char_p, [vp]),
     }
@@ -378,9 +378,9 @@ class Engine:
         self._check(lib().dllm_probe_hbm_read(self.ctx, self._stream(), _ptr(buf), buf.numel() * buf.element_size(),
                                               _ptr(sink)))
 
-    def probe_mfma(self, iters, sink) -> float:
+    def probe_mfma(self, iters, sink, random_bits=False) -> float:
         fl = C.c_double(0)
-        self._check(lib().dllm_probe_mfma(self.ctx, self._stream(), iters, _ptr(sink), C.byref(fl)))
+        self._check(lib().dllm_probe_mfma(self.ctx, self._stream(), iters, int(random_bits), _ptr(sink), C.byref(fl)))
         return fl.value
 
     def set_kernel_mode(self, mode: int):

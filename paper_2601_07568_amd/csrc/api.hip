@@ -847,9 +847,9 @@ extern "C" int dllm_probe_hbm_read(dllm_ctx* c, void* stream, const void* buf, s
   return DLLM_OK;
 }
 
-extern "C" int dllm_probe_mfma(dllm_ctx* c, void* stream, int iters, void* sink, double* flops) {
+extern "C" int dllm_probe_mfma(dllm_ctx* c, void* stream, int iters, int random_bits, void* sink, double* flops) {
   if (!c || !sink || !flops || iters < 1 || iters > (1 << 24)) return DLLM_EINVAL;
-  TRY(launch_probe_mfma((hipStream_t)stream, iters, sink, flops), "probe_mfma");
+  TRY(launch_probe_mfma((hipStream_t)stream, iters, random_bits != 0, sink, flops), "probe_mfma");
   return DLLM_OK;
 }
 

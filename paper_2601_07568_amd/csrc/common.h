@@ -301,7 +301,7 @@ hipError_t launch_gemm_swiglu(hipStream_t s, const void* A, const void* Wg, cons
                               size_t tail_bytes = 0);
 hipError_t launch_gemm_lmstats(dllm_ctx* c, hipStream_t s, int max_rows, int* n_parts_out);
 hipError_t launch_probe_read(hipStream_t s, const void* buf, size_t bytes, void* sink);
-hipError_t launch_probe_mfma(hipStream_t s, int iters, void* sink, double* flops);
+hipError_t launch_probe_mfma(hipStream_t s, int iters, int random_bits, void* sink, double* flops);
 bool attn_step_supported(const dllm_ctx* c, const StepGeom& g);
 hipError_t launch_attn_step(dllm_ctx* c, hipStream_t s, const StepGeom& g, const KVView& kv, bool frag_out);
 

@@ -1031,7 +1031,9 @@ __global__ __launch_bounds__(512) void k_probe_read(const u32x4* __restrict__ p,
 }
 
 // one wave per SIMD, sixteen independent 32x32x16 bfloat16 products in flight, operands in registers
-__global__ __launch_bounds__(256) void k_probe_mfma(int iters, float* sink) {
+// random_bits: operands with random signs, mantissas and exponents 2^-9 .. 1 (the switching activity of real
+// weights and activations) instead of values that share sign and exponent
+__global__ __launch_bounds__(256) void k_probe_mfma(int iters, int random_bits, float* sink) {
   f32x16 acc[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i)
@@ -1044,6 +1046,18 @@ __global__ __launch_bounds__(256) void k_probe_mfma(int iters, float* sink) {
     const uint32_t s0 = 0x3f803f80u + (((threadIdx.x * 2654435761u) >> 20) & 0x007f007fu) + i * 0x00010001u;
     a[i] = u32x4{s0, s0 ^ 0x00100010u, s0 + 0x00020002u, s0 ^ 0x80008000u};
     b[i] = u32x4{s0 ^ 0x80000000u, s0 + 0x00030003u, s0 ^ 0x00008000u, s0 + 0x00040004u};
+    if (random_bits) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint32_t hsh = (threadIdx.x * 8u + blockIdx.x * 2048u + i * 16u + e) * 2654435761u;
+        hsh ^= hsh >> 15; hsh *= 2246822519u; hsh ^= hsh >> 13;
+        // per 16-bit half: sign, exponent 118 + (0 .. 9), 7 mantissa bits
+        const uint32_t lo = (hsh & 0x807fu) | ((118u + ((hsh >> 8) & 0xfu) % 10u) << 7);
+        const uint32_t hi = ((hsh >> 16) & 0x807fu) | ((118u + ((hsh >> 24) & 0xfu) % 10u) << 7);
+        const uint32_t v = lo | (hi << 16);
+        if (e < 4) a[i][e] = v; else b[i][e - 4] = v;
+      }
+    }
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
@@ -1065,9 +1079,9 @@ hipError_t launch_probe_read(hipStream_t s, const void* buf, size_t bytes, void*
 }
 
 // flops of one launch: workgroups * 4 waves * iters * 16 products * 2*32*32*16
-hipError_t launch_probe_mfma(hipStream_t s, int iters, void* sink, double* flops) {
+hipError_t launch_probe_mfma(hipStream_t s, int iters, int random_bits, void* sink, double* flops) {
   const int wgs = t2_cus;
-  k_probe_mfma<<<wgs, 256, 0, s>>>(iters, (float*)sink);
+  k_probe_mfma<<<wgs, 256, 0, s>>>(iters, random_bits, (float*)sink);
   *flops = (double)wgs * 4.0 * iters * 16.0 * 2.0 * 32 * 32 * 16;
   return hipGetLastError();
 }
