@@ -672,8 +672,17 @@ def main():
         # the small HBM-bound workload and the matrix-core-bound one, each with its own roofline object
         out["c2"] = trimmed(batch1(args, torch, np, synth, Engine, dev, "c2", max(args.steps, 50), args.warmup, extras=False))
         torch.cuda.empty_cache()
-        out["large_batch"] = trimmed(large_batch(args, torch, np, synth, Engine, dev, 6, 2))
+        out["large_batch"] = trimmed(large_batch(args, torch, np, synth, Engine, dev, 16, 3))
         torch.cuda.empty_cache()
+    att = out.get("attainable")
+    if att:
+        # the same fractions against what the probes of this run reached (stream read; matrix loop on random operands)
+        out["roofline"]["step_frac_of_attainable_hbm"] = out["step_GBps"] / att["hbm_GBps"]
+        if "c2" in out:
+            out["c2"]["roofline"]["step_frac_of_attainable_hbm"] = out["c2"]["step_GBps"] / att["hbm_GBps"]
+        if "large_batch" in out:
+            out["large_batch"]["roofline"]["step_frac_of_attainable_mfma"] = \
+                out["large_batch"]["step_TFLOPs"] / att["mfma_bf16_random_operands_TFLOPs"]
     if not args.no_cpu_baseline:
         base = cpu_baseline(synth.LLADA_8B if args.workload == "c3" else synth.LLADA_8B.with_layers(1),
                             1024 if args.workload == "c3" else 512, 32, 32 if args.workload == "c3" else 24)
