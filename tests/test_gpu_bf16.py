@@ -273,3 +273,52 @@ def test_refresh_with_a_device_resident_total_equals_the_sized_call(lens, extra)
         assert torch.equal(c2[:total], want[1]) and torch.equal(f2[:total], want[2]) and torch.equal(e2[:total], want[3])
         assert int((c2[total:] != -7).sum()) == 0 and int((c2[:total] != -7).sum()) > 0
     eng.close()
+
+
+@pytest.mark.parametrize("ms,Q,pt", [(SMALL64, 32, 32), (SMALL, 32, 64), (SMALL, 64, 64), (SMALL, 64, 16)],
+                         ids=["register-direct", "staged-4-waves", "staged-8-waves", "staged-small-pages"])
+def test_page_ids_out_of_range_in_the_matrix_core_attention(ms, Q, pt):
+    """A block table with page ids that address no page (too large, negative) in one sequence, on every bfloat16
+    attention kernel: the status bit is raised, nothing faults (the kernels check every id before they address the
+    pool with it), the sequence with the clean table gets bit for bit what it gets without the bad neighbour, and the
+    bad sequence's outputs are finite."""
+    from paper_2601_07568_amd.binding import STATUS_BAD_PAGE
+    lens = [150, 200]
+    mp = (max(lens) + Q + pt - 1) // pt + 1
+    w = synth.Weights(ms, 9)
+    eng = H.make_engine(ms, w, page_tokens=pt, max_pages_per_seq=mp, n_pages=2 * mp, max_batch=2, max_q=Q,
+                        max_tokens=sum(lens) + 2 * Q)
+    table = H.identity_table(eng, 2)
+    seqs = [synth.random_tokens(ms, 40 + i, n) for i, n in enumerate(lens)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    eng.prefill_kv(eng.i32(np.concatenate(seqs)), eng.i32(cu), eng.i32(table), None, total_tokens=int(cu[-1]),
+                   max_seqlen=max(lens))
+    qt = eng.i32(np.stack([synth.masked_block(ms, 60 + i, Q, Q // 2) for i in range(2)]))
+    dev = eng.device
+
+    def step(tab):
+        c = torch.zeros(2, Q, dtype=torch.int32, device=dev)
+        f = torch.zeros(2, Q, dtype=torch.float32, device=dev)
+        e = torch.zeros(2, Q, dtype=torch.float32, device=dev)
+        pool = eng.kv_pool.clone()                      # a step writes its rows' K/V: same starting cache for both runs
+        eng.denoise_step(qt.clone(), eng.i32(lens), eng.i32(tab), c, f, e, max_prefix_len=max(lens))
+        torch.cuda.synchronize()
+        eng.kv_pool.copy_(pool)
+        return c.cpu().numpy(), f.cpu().numpy(), e.cpu().numpy()
+
+    clean = step(table)
+    assert eng.read_status() == 0
+    bad = table.copy()
+    bad[1, 1] = 2 * mp + 7                               # past the pool
+    bad[1, 2] = -1
+    got = step(bad)
+    assert eng.read_status() & STATUS_BAD_PAGE
+    eng.reset_status()
+    for g, c in zip(got, clean):
+        assert (g[0] == c[0]).all()
+        assert np.isfinite(g[1].astype(np.float64)).all()
+    again = step(table)                                  # and a clean call afterwards is clean
+    assert eng.read_status() == 0
+    for g, c in zip(again, clean):
+        assert (g == c).all()
+    eng.close()
