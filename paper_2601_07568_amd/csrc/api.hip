@@ -316,35 +316,46 @@ struct HeadOut {
 // The forward shared by all calls: embed, n_layers_run transformer layers over the rows of g,
 // then optionally the residual stream, the raw logits or the fused confidence outputs.
 static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
-                             float* logits_out, float* hidden_out);
+                             float* logits_out, float* hidden_out, bool prologue_done);
+
+// the weight-streaming path: bfloat16 denoise steps of at most SK_MAX_ROWS rows
+static bool skinny_path(const dllm_ctx* c, const StepGeom& g) {
+  return mfma_supported(c) && g.Q > 0 && g.T <= SK_MAX_ROWS && attn_step_supported(c, g);
+}
 
 static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g0, int n_layers_run, const HeadOut* head,
                        float* logits_out, float* hidden_out) {
   // the first launches check the device-resident lengths against the host values that size the launches and leave
   // clamped copies in the workspace: every kernel after them addresses memory with those
-  TRY(launch_token_map(c, s, g0), "token_map");
+  // (one launch together with the token map, the rotary table and the embedding on the weight-streaming path)
+  const bool pro = skinny_path(c, g0);
+  if (pro)
+    TRY(launch_sk_prologue(c, s, g0, n_layers_run > 0 ? c->layers[0].attn_norm : c->final_norm,
+                           head ? head->cand : nullptr, head ? head->conf : nullptr, head ? head->entropy : nullptr),
+        "prologue");
+  else TRY(launch_token_map(c, s, g0), "token_map");
   StepGeom g = g0;
   if (g.Q > 0) g.prefix_len = WSP(c, len_safe, int32_t);
   else g.cu_seqlens = WSP(c, len_safe, int32_t);
   if (g0.Q == 0 && g0.total_is_cap) {
     // the sequences may end before the buffer does: the row count is in the workspace for the GEMMs that can skip rows
     c->rows_dev = WSP(c, status, int32_t) + 2;
-    const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+    const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
     c->rows_dev = nullptr;
     return rc;
   }
-  if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+  if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
   // a step over the live sequences only: the valid rows per sequence (-1 for the sequences past the live count) and
   // the number of live rows are in the workspace as well
   g.q_valid = WSP(c, q_valid_eff, int32_t);
   c->rows_dev = WSP(c, status, int32_t) + 2;
-  const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
+  const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
   c->rows_dev = nullptr;
   return rc;
 }
 
 static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
-                             float* logits_out, float* hidden_out) {
+                             float* logits_out, float* hidden_out, bool prologue_done) {
   const dllm_config& f = c->cfg;
   const int T = g.T;
   const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
@@ -353,13 +364,15 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
   // RMSNorm is launched: the producer of the residual stream (embedding, output projection, down projection)
   // leaves x * gain of the next norm in fragment order plus partial sums of squares per row, and the consuming
   // GEMM applies the row's normalisation factor to its float accumulators.
-  const bool sk = mfma_supported(c) && g.Q > 0 && T <= SK_MAX_ROWS && attn_step_supported(c, g);
+  const bool sk = skinny_path(c, g);
   const bool big_mfma = f.dtype == DLLM_BF16 && c->kernel_mode == 0 && f.d_ff % 4 == 0 && f.vocab % 4 == 0;
   const int ss_groups = (f.d_model + 15) / 16;
   int n_ss = 1;      // partial sums of squares the current skinny-path GEMM input comes with
-  if (sk) TRY(launch_sk_embed(c, s, g, n_layers_run > 0 ? c->layers[0].attn_norm : c->final_norm), "embed");
-  else TRY(launch_embed(c, s, g), "embed");
-  TRY(launch_rope_table(c, s, g), "rope_table");
+  if (!prologue_done) {
+    if (sk) TRY(launch_sk_embed(c, s, g, n_layers_run > 0 ? c->layers[0].attn_norm : c->final_norm), "embed");
+    else TRY(launch_embed(c, s, g), "embed");
+    TRY(launch_rope_table(c, s, g), "rope_table");
+  }
   int pending = 0;   // open residual sums (K splits of the last residual projection) not yet added to x
   for (int l = 0; l < n_layers_run; ++l) {
     const dllm_layer_w& L = c->layers[l];
@@ -444,7 +457,7 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
-    TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
+    if (!(prologue_done && sk)) TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
     if (!sk) {
       TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1, 0, pending),
           "final_norm");

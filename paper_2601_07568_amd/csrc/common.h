@@ -213,6 +213,10 @@ struct StepGeom {           // which tokens a forward runs over
 };
 
 hipError_t launch_token_map(dllm_ctx* c, hipStream_t s, const StepGeom& g);
+// steps of at most 64 rows on the matrix-core path: length checks, token map, rotary table, embedding and (cand != nullptr)
+// the LM head's row list with the fixed outputs of the rows that are not masked, in one launch
+hipError_t launch_sk_prologue(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain, int32_t* cand,
+                              float* conf, float* entropy);
 hipError_t launch_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 hipError_t launch_rope_table(dllm_ctx* c, hipStream_t s, const StepGeom& g);
 // out[T or n_rows, d] = rmsnorm(x[row]) * gain; rows == nullptr: identity row map, n = T

@@ -526,6 +526,126 @@ __global__ __launch_bounds__(256) void k_embed_xg(int d, int vocab, int mt, cons
   if (threadIdx.x == 0) ss[(int64_t)t * ss_stride] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Everything a denoise step of at most 64 rows needs before its first GEMM, in one launch of one workgroup per row:
+// the checks of the device-resident lengths (workgroup 0 writes the clamped copies, the live-row count and the status
+// bit, exactly as k_seq_check does; every workgroup derives its own sequence's values the same way), the row's
+// sequence and position (k_token_map), its rotary table entries (k_rope_table) and its embedding (k_embed_xg).
+__global__ __launch_bounds__(256) void k_sk_prologue(int T, int B, int Q, int max_len, int d, int vocab, int mt, int half,
+                                                     double log2_base, const int32_t* tokens, const int32_t* prefix_len,
+                                                     const int32_t* q_valid, const int32_t* n_live, const bf16_t* emb,
+                                                     const bf16_t* gain, float* x, bf16_t* xg, float* ss, int ss_stride,
+                                                     int32_t* len_safe, int32_t* q_valid_eff, int32_t* tok_seq,
+                                                     int32_t* tok_pos, float* cs, float* sn, int32_t* status,
+                                                     int32_t mask_id, int cap, int32_t* rows, int32_t* cand, float* conf,
+                                                     float* entropy) {
+  __shared__ float red[4];
+  __shared__ int s_bad;
+  const int t = blockIdx.x;
+  int nl = B;
+  if (n_live) { nl = n_live[0]; nl = nl < 0 ? 0 : (nl > B ? B : nl); }
+  if (t == 0) {
+    if (threadIdx.x == 0) s_bad = 0;
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+      const int p = prefix_len[b];
+      const int pc = p < 0 ? 0 : (p > max_len ? max_len : p);
+      if (pc != p && b < nl) s_bad = 1;
+      len_safe[b] = pc;
+      if (n_live) q_valid_eff[b] = b < nl ? (q_valid ? q_valid[b] : Q) : -1;
+    }
+    if (n_live && threadIdx.x == 0) status[2] = nl * Q;
+    __syncthreads();
+    if (threadIdx.x == 0 && s_bad) atomicOr(status, DLLM_STATUS_BAD_LENGTH);
+    // the rows of the LM head (k_mask_rows for a step of at most 64 rows: one wave, row r in lane r): the masked rows
+    // that are not padding, in ascending order; every other row reports its own token with confidence 1
+    if (cand && threadIdx.x < 64) {
+      const int r = threadIdx.x;
+      bool flag = false;
+      if (r < T) {
+        const int b2 = r / Q, j2 = r - b2 * Q;
+        const bool hq = n_live != nullptr || q_valid != nullptr;
+        const int qv2 = n_live ? (b2 < nl ? (q_valid ? q_valid[b2] : Q) : -1) : (q_valid ? q_valid[b2] : Q);
+        const int tk = tokens[r];
+        flag = !(hq && j2 >= qv2) && tk == mask_id;
+        if (!flag) {
+          cand[r] = tk;
+          conf[r] = 1.0f;
+          if (entropy) entropy[r] = 0.f;
+        }
+      }
+      const unsigned long long bal = __ballot(flag);
+      const int pre = __popcll(bal & ((1ull << r) - 1ull));
+      if (flag && pre < cap) rows[pre] = r;
+      if (r == 0) {
+        int n = __popcll(bal);
+        if (n > cap) { atomicOr(status, DLLM_STATUS_ROWS_CAP); n = cap; }
+        status[1] = n;
+      }
+    }
+  }
+  // this row's sequence, position (padding rows have none) and rotary angles
+  const int b = t / Q, jrow = t - b * Q;
+  const int p = prefix_len[b];
+  const int pc = p < 0 ? 0 : (p > max_len ? max_len : p);
+  const bool have_qv = n_live != nullptr || q_valid != nullptr;
+  const int qve = n_live ? (b < nl ? (q_valid ? q_valid[b] : Q) : -1) : (q_valid ? q_valid[b] : Q);
+  const int pos = (have_qv && jrow >= qve) ? -1 : pc + jrow;
+  if (threadIdx.x == 0) { tok_seq[t] = b; tok_pos[t] = pos; }
+  for (int j = threadIdx.x; j < half; j += blockDim.x) {
+    const double theta = exp2(-(double)j / (double)half * log2_base);
+    const double ang = (double)pos * theta;
+    double sv, cv;
+    sincos(ang, &sv, &cv);
+    cs[t * half + j] = (float)cv;
+    sn[t * half + j] = (float)sv;
+  }
+  // embedding: x[t] = E[token[t]] (float), x * gain in fragment order, the row's sum of squares
+  int tok = tokens[t];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, DLLM_STATUS_BAD_TOKEN);
+    tok = 0;
+  }
+  const bf16_t* row = emb + (int64_t)tok * d;
+  float sq = 0.f;
+  for (int u = threadIdx.x; u < (d >> 3); u += 256) {          // 16-byte units: 8 channels
+    const uint4 ev = *(const uint4*)(row + 8 * u), gv = *(const uint4*)(gain + 8 * u);
+    const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    float xv[8];
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      xv[2 * e] = __uint_as_float(ew[e] << 16);
+      xv[2 * e + 1] = __uint_as_float(ew[e] & 0xffff0000u);
+      o[e] = pack_bf16x2(xv[2 * e] * __uint_as_float(gw[e] << 16), xv[2 * e + 1] * __uint_as_float(gw[e] & 0xffff0000u));
+      sq = fmaf(xv[2 * e], xv[2 * e], sq);
+      sq = fmaf(xv[2 * e + 1], xv[2 * e + 1], sq);
+    }
+    float4* xr = (float4*)(x + (int64_t)t * d + 8 * u);
+    xr[0] = make_float4(xv[0], xv[1], xv[2], xv[3]);
+    xr[1] = make_float4(xv[4], xv[5], xv[6], xv[7]);
+    *(uint4*)(xg + frag_offset(t, 8 * u, mt)) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+  __syncthreads();
+  if (threadIdx.x == 0) ss[(int64_t)t * ss_stride] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+hipError_t launch_sk_prologue(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain, int32_t* cand,
+                              float* conf, float* entropy) {
+  const dllm_config& f = c->cfg;
+  const bool live = g.n_live != nullptr;
+  k_sk_prologue<<<g.T, 256, 0, s>>>(g.T, g.B, g.Q, g.max_kv - g.Q, f.d_model, f.vocab, (g.T + 15) / 16, f.head_dim / 2,
+                                    log2((double)f.rope_base), g.tokens, g.prefix_len, g.q_valid, live ? g.n_live : nullptr,
+                                    (const bf16_t*)c->tok_emb, (const bf16_t*)gain, WSM(c, x, float), WSM(c, xn, bf16_t),
+                                    WSM(c, ss, float), sk_ss_stride(c), WSM(c, len_safe, int32_t),
+                                    WSM(c, q_valid_eff, int32_t), WSM(c, tok_seq, int32_t), WSM(c, tok_pos, int32_t),
+                                    WSM(c, rope_cos, float), WSM(c, rope_sin, float), WSM(c, status, int32_t),
+                                    f.mask_id, (int)c->map.r_max, WSM(c, rows, int32_t), cand, conf, entropy);
+  return hipGetLastError();
+}
+
 hipError_t launch_sk_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain) {
   const dllm_config& f = c->cfg;
   k_embed_xg<<<g.T, 256, 0, s>>>(f.d_model, f.vocab, (g.T + 15) / 16, g.tokens, (const bf16_t*)c->tok_emb,
