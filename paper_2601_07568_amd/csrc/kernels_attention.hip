@@ -863,6 +863,8 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dl(const AttnArgs a) {
     int pg_next = page_of(clampb(unit + (NB - 1) * a.n_units));
     int buf = 0;
     for (int kb = unit; kb < nkb; kb += a.n_units) {
+      // (the count is exact only while the loop issues no other vector memory instruction: no spills to scratch,
+      // which the build's resource report shows)
       __builtin_amdgcn_s_waitcnt(DL_VMCNT((NB - 2) * FPW));   // this wave's copies of block kb have landed
       __builtin_amdgcn_s_barrier();                            // everybody's have; the previous block's buffer is free
       const int nbuf = buf == 0 ? NB - 1 : buf - 1;            // (buf + NB - 1) % NB: the buffer of the block before
