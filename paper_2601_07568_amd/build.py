@@ -23,6 +23,35 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Kernels that wait on their own count of outstanding memory instructions (s_waitcnt vmcnt(n) against copies
+# straight into LDS).  A spill to scratch between such a kernel's first and last copy would add instructions the
+# count does not know (and stores may complete out of order with the loads), so the build looks at the generated code
+# and refuses it.  Scratch traffic before the first copy or after the loop's final wait is harmless.
+COUNTED = {"kernels_gemm.hip": ("k_gemm_t256", "k_gemm_ts"), "kernels_attention.hip": ("k_attn_dl",)}
+
+
+def _check_counted_loops(src: str, asm: str) -> None:
+    name, body = None, []
+    def check():
+        if name is None or not any(k in name for k in COUNTED[src]):
+            return
+        copies = [i for i, l in enumerate(body) if "global_load_lds" in l]
+        if not copies:
+            return
+        for l in body[copies[0]:copies[-1] + 1]:
+            if "scratch_" in l:
+                raise RuntimeError(f"{src}: kernel {name} spills to scratch between its copies into LDS "
+                                   f"({l.strip()}); its explicit memory-instruction counts do not allow that")
+    for line in asm.splitlines():
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            check()
+            name, body = m.group(1), []
+        elif name is not None:
+            body.append(line)
+    check()
+
+
 def build(verbose: bool = False) -> str:
     """Compiles every source (always, also when a built library exists) and links libdllm.so."""
     objdir = os.path.join(HERE, "_build")
@@ -41,8 +70,21 @@ def build(verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
+    def check_one(src):
+        asm = os.path.join(objdir, src.replace(".hip", ".s"))
+        cmd = [_hipcc(), *FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {src}:\n" + r.stderr[-2000:])
+        with open(asm) as f:
+            _check_counted_loops(src, f.read())
+        os.remove(asm)
+
     with ThreadPoolExecutor(max_workers=4) as ex:
+        checks = [ex.submit(check_one, s) for s in srcs if s in COUNTED]
         objs = list(ex.map(compile_one, srcs))
+        for c in checks:
+            c.result()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
