@@ -316,7 +316,7 @@ struct HeadOut {
 // The forward shared by all calls: embed, n_layers_run transformer layers over the rows of g,
 // then optionally the residual stream, the raw logits or the fused confidence outputs.
 static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
-                             float* logits_out, float* hidden_out, bool prologue_done);
+                             float* logits_out, float* hidden_out);
 
 // the weight-streaming path: bfloat16 denoise steps of at most SK_MAX_ROWS rows
 static bool skinny_path(const dllm_ctx* c, const StepGeom& g) {
@@ -340,22 +340,22 @@ static int run_forward(dllm_ctx* c, hipStream_t s, const StepGeom& g0, int n_lay
   if (g0.Q == 0 && g0.total_is_cap) {
     // the sequences may end before the buffer does: the row count is in the workspace for the GEMMs that can skip rows
     c->rows_dev = WSP(c, status, int32_t) + 2;
-    const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
+    const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
     c->rows_dev = nullptr;
     return rc;
   }
-  if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
+  if (!g0.n_live) return run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
   // a step over the live sequences only: the valid rows per sequence (-1 for the sequences past the live count) and
   // the number of live rows are in the workspace as well
   g.q_valid = WSP(c, q_valid_eff, int32_t);
   c->rows_dev = WSP(c, status, int32_t) + 2;
-  const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out, pro);
+  const int rc = run_forward_inner(c, s, g, n_layers_run, head, logits_out, hidden_out);
   c->rows_dev = nullptr;
   return rc;
 }
 
 static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int n_layers_run, const HeadOut* head,
-                             float* logits_out, float* hidden_out, bool prologue_done) {
+                             float* logits_out, float* hidden_out) {
   const dllm_config& f = c->cfg;
   const int T = g.T;
   const int dq = f.n_q_heads * f.head_dim, dkv = f.n_kv_heads * f.head_dim;
@@ -368,9 +368,8 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
   const bool big_mfma = f.dtype == DLLM_BF16 && c->kernel_mode == 0 && f.d_ff % 4 == 0 && f.vocab % 4 == 0;
   const int ss_groups = (f.d_model + 15) / 16;
   int n_ss = 1;      // partial sums of squares the current skinny-path GEMM input comes with
-  if (!prologue_done) {
-    if (sk) TRY(launch_sk_embed(c, s, g, n_layers_run > 0 ? c->layers[0].attn_norm : c->final_norm), "embed");
-    else TRY(launch_embed(c, s, g), "embed");
+  if (!sk) {            // (on the weight-streaming path run_forward's prologue launch has done both)
+    TRY(launch_embed(c, s, g), "embed");
     TRY(launch_rope_table(c, s, g), "rope_table");
   }
   int pending = 0;   // open residual sums (K splits of the last residual projection) not yet added to x
@@ -457,7 +456,7 @@ static int run_forward_inner(dllm_ctx* c, hipStream_t s, const StepGeom& g, int 
   }
   if (head) {
     const int max_rows = T < c->map.r_max ? T : (int)c->map.r_max;
-    if (!(prologue_done && sk)) TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
+    if (!sk) TRY(launch_mask_rows(c, s, g, head->cand, head->conf, head->entropy), "mask_rows");
     if (!sk) {
       TRY(launch_rmsnorm(c, s, c->final_norm, max_rows, WSP(c, rows, int32_t), WSP(c, status, int32_t) + 1, 0, pending),
           "final_norm");

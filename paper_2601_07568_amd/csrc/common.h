@@ -230,7 +230,6 @@ constexpr int LG_MAX_DELTA = 3;        // large path: a residual projection is s
 constexpr int LG_DELTA_ROWS = 2048;    // ... and only when the token count leaves the chip underfilled
 hipError_t launch_sk_resid(dllm_ctx* c, hipStream_t s, const void* A, const void* W, int M, int N, int K,
                            const void* gain_next);
-hipError_t launch_sk_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain);
 enum Epi { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_RESID = 2 };
 // C[M,N] (=, or +=) A[M,K] * W[N,K]^T ; A and W of the model dtype
 hipError_t launch_gemm_generic(dllm_ctx* c, hipStream_t s, const void* A, const void* W, void* C,

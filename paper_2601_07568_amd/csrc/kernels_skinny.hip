@@ -487,49 +487,11 @@ static void sk_row_scale(dllm_ctx* c, SkArgs& a, int n_ss) {
   a.eps = c->cfg.rms_eps;
 }
 
-// Token embedding of a denoise step: x[t] = E[token[t]] (float), x * gain in fragment order as the first GEMM's
-// input, the row's sum of squares as its single partial.  One workgroup per row.
-__global__ __launch_bounds__(256) void k_embed_xg(int d, int vocab, int mt, const int32_t* tokens, const bf16_t* emb,
-                                                  const bf16_t* gain, float* x, bf16_t* xg, float* ss, int ss_stride,
-                                                  int32_t* status) {
-  __shared__ float red[4];
-  const int t = blockIdx.x;
-  int tok = tokens[t];
-  if (tok < 0 || tok >= vocab) {
-    if (threadIdx.x == 0) atomicOr(status, DLLM_STATUS_BAD_TOKEN);
-    tok = 0;
-  }
-  const bf16_t* row = emb + (int64_t)tok * d;
-  float sq = 0.f;
-  for (int u = threadIdx.x; u < (d >> 3); u += 256) {          // 16-byte units: 8 channels
-    const uint4 ev = *(const uint4*)(row + 8 * u), gv = *(const uint4*)(gain + 8 * u);
-    const uint32_t ew[4] = {ev.x, ev.y, ev.z, ev.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
-    float xv[8];
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      xv[2 * e] = __uint_as_float(ew[e] << 16);
-      xv[2 * e + 1] = __uint_as_float(ew[e] & 0xffff0000u);
-      o[e] = pack_bf16x2(xv[2 * e] * __uint_as_float(gw[e] << 16), xv[2 * e + 1] * __uint_as_float(gw[e] & 0xffff0000u));
-      sq = fmaf(xv[2 * e], xv[2 * e], sq);
-      sq = fmaf(xv[2 * e + 1], xv[2 * e + 1], sq);
-    }
-    float4* xr = (float4*)(x + (int64_t)t * d + 8 * u);
-    xr[0] = make_float4(xv[0], xv[1], xv[2], xv[3]);
-    xr[1] = make_float4(xv[4], xv[5], xv[6], xv[7]);
-    *(uint4*)(xg + frag_offset(t, 8 * u, mt)) = make_uint4(o[0], o[1], o[2], o[3]);
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
-  __syncthreads();
-  if (threadIdx.x == 0) ss[(int64_t)t * ss_stride] = (red[0] + red[1]) + (red[2] + red[3]);
-}
-
 // Everything a denoise step of at most 64 rows needs before its first GEMM, in one launch of one workgroup per row:
 // the checks of the device-resident lengths (workgroup 0 writes the clamped copies, the live-row count and the status
 // bit, exactly as k_seq_check does; every workgroup derives its own sequence's values the same way), the row's
-// sequence and position (k_token_map), its rotary table entries (k_rope_table) and its embedding (k_embed_xg).
+// sequence and position (k_token_map), its rotary table entries (k_rope_table) and its embedding: x[t] = E[token[t]] in float, x * gain of the first norm in
+// fragment order as the first GEMM's input, the row's sum of squares as its single partial.
 __global__ __launch_bounds__(256) void k_sk_prologue(int T, int B, int Q, int max_len, int d, int vocab, int mt, int half,
                                                      double log2_base, const int32_t* tokens, const int32_t* prefix_len,
                                                      const int32_t* q_valid, const int32_t* n_live, const bf16_t* emb,
@@ -643,14 +605,6 @@ hipError_t launch_sk_prologue(dllm_ctx* c, hipStream_t s, const StepGeom& g, con
                                     WSM(c, q_valid_eff, int32_t), WSM(c, tok_seq, int32_t), WSM(c, tok_pos, int32_t),
                                     WSM(c, rope_cos, float), WSM(c, rope_sin, float), WSM(c, status, int32_t),
                                     f.mask_id, (int)c->map.r_max, WSM(c, rows, int32_t), cand, conf, entropy);
-  return hipGetLastError();
-}
-
-hipError_t launch_sk_embed(dllm_ctx* c, hipStream_t s, const StepGeom& g, const void* gain) {
-  const dllm_config& f = c->cfg;
-  k_embed_xg<<<g.T, 256, 0, s>>>(f.d_model, f.vocab, (g.T + 15) / 16, g.tokens, (const bf16_t*)c->tok_emb,
-                                 (const bf16_t*)gain, WSM(c, x, float), WSM(c, xn, bf16_t), WSM(c, ss, float),
-                                 sk_ss_stride(c), WSM(c, status, int32_t));
   return hipGetLastError();
 }
 
