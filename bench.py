@@ -672,7 +672,7 @@ def main():
         # the small HBM-bound workload and the matrix-core-bound one, each with its own roofline object
         out["c2"] = trimmed(batch1(args, torch, np, synth, Engine, dev, "c2", max(args.steps, 50), args.warmup, extras=False))
         torch.cuda.empty_cache()
-        out["large_batch"] = trimmed(large_batch(args, torch, np, synth, Engine, dev, 16, 3))
+        out["large_batch"] = trimmed(large_batch(args, torch, np, synth, Engine, dev, 50, 3))
         torch.cuda.empty_cache()
     att = out.get("attainable")
     if att:
