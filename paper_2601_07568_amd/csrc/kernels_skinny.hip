@@ -180,6 +180,38 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
     xres = a.x[ok ? (int64_t)tok * a.N0 + n : 0];
     gres = bf16_to_f32(a.gain_next[ok ? n : 0]);
   }
+  // QKV with one epilogue item per thread: what that item needs besides the sums - the row's position, its rotary
+  // factors, the page of its cache slot - is requested now and arrives while the weights stream
+  constexpr bool QKV_PRE = EPI == SK_QKV && MT * 256 <= NW * 64;
+  float pcs = 0.f, psn = 0.f;
+  int ppos = -1, ppage = -1;
+  if constexpr (QKV_PRE) {
+    const int m = tid >> 8, iq = (tid >> 6) & 3;
+    const int tok = m * 16 + c;
+    if (m < MT && tok < M) {
+      ppos = a.tok_pos[tok];
+      if (wg < a.n_q_wg + a.n_k_wg) {
+        const int hj = row0[0] + 4 * g + iq;
+        const int j = hj - (hj / a.dh) * a.dh;
+        const int half = a.dh >> 1;
+        pcs = a.rope_cos[(int64_t)tok * half + j];
+        psn = a.rope_sin[(int64_t)tok * half + j];
+      }
+      const int pi = ppos >= 0 ? ppos / a.pool.page_tokens : a.pool.max_pages;
+      if (pi < a.pool.max_pages) ppage = a.pool.table[(int64_t)a.tok_seq[tok] * a.pool.max_pages + pi];
+    }
+  }
+  // kv_locate for that item from the values fetched above
+  auto locate_pre = [&](int h, int64_t& k_off, int64_t& v_off, int& v_stride) -> bool {
+    const KVView& kv = a.pool;
+    if (ppos < 0 || ppage < 0 || ppage >= kv.n_pages) return false;
+    const int slot = ppos - (ppos / kv.page_tokens) * kv.page_tokens;
+    const int64_t ph = (int64_t)ppage * kv.n_kv_heads + h;
+    k_off = (ph * kv.page_tokens + slot) * kv.head_dim;
+    v_off = ph * kv.head_dim * kv.page_tokens + slot;
+    v_stride = kv.page_tokens;
+    return true;
+  };
 
   f32x4 acc[NT][MT];
 #pragma unroll
@@ -337,7 +369,8 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
           const int half = a.dh >> 1;
           const int hj = row0[0] + fr;                 // h*dh + j, j < half
           const int h = hj / a.dh, j = hj - h * a.dh;
-          const float cs = a.rope_cos[(int64_t)tok * half + j], sn = a.rope_sin[(int64_t)tok * half + j];
+          const float cs = QKV_PRE ? pcs : a.rope_cos[(int64_t)tok * half + j];
+          const float sn = QKV_PRE ? psn : a.rope_sin[(int64_t)tok * half + j];
           const float v0 = val[0], v1 = val[1];
           const bf16_t r0 = f32_to_bf16(v0 * cs - v1 * sn), r1 = f32_to_bf16(v1 * cs + v0 * sn);
           if (isq) {
@@ -346,9 +379,10 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
           } else {
             int64_t ko, vo;
             int vs;
-            if (a.tok_pos[tok] < 0) {
+            const int pos = QKV_PRE ? ppos : a.tok_pos[tok];
+            if (pos < 0) {
               // a padding row: nothing of it is cached
-            } else if (kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs)) {
+            } else if (QKV_PRE ? locate_pre(h, ko, vo, vs) : kv_locate(a.pool, a.tok_seq[tok], pos, h, ko, vo, vs)) {
               a.pool_k[ko + j] = r0;
               a.pool_k[ko + j + half] = r1;
             } else atomicOr(a.status, DLLM_STATUS_BAD_PAGE);
@@ -359,7 +393,8 @@ __global__ __launch_bounds__(NW * 64, (NT + MT == 4 && NW == 8) ? 4 : ((NW == 4 
           const int h = n / a.dh, ch = n - h * a.dh;
           int64_t ko, vo;
           int vs;
-          if (a.tok_pos[tok] >= 0 && kv_locate(a.pool, a.tok_seq[tok], a.tok_pos[tok], h, ko, vo, vs))
+          const int pos = QKV_PRE ? ppos : a.tok_pos[tok];
+          if (pos >= 0 && (QKV_PRE ? locate_pre(h, ko, vo, vs) : kv_locate(a.pool, a.tok_seq[tok], pos, h, ko, vo, vs)))
             a.pool_v[vo + (int64_t)ch * vs] = f32_to_bf16(val[NT - 1]);
         }
       }
