@@ -242,18 +242,45 @@ __global__ __launch_bounds__(256) void k_attn_step(const AttnArgs a) {
   };
 
   const int nkb = (kv_len + 31) >> 5;
-  for (int kb = unit; kb < nkb; kb += 2 * a.n_units) {
-    const int kb2 = kb + a.n_units;
-    const bool two = kb2 < nkb;
-    const int kbb = two ? kb2 : kb;               // a repeat of the first block's loads: no branch around a load
+  if (paged && pt % 32 == 0) {
+    // A 32-key block lies inside one page, so its page id does not depend on where the sequence ends: the ids of a
+    // wave's first two blocks are requested before the sequence length is known (the table row has max_pages
+    // entries whatever the length), one memory round trip less in front of the K/V loads; later pairs' ids are
+    // requested a pair ahead.
+    auto block_page = [&](int kb, int (&pg)[3]) {
+      const int pi = (kb << 5) / pt;
+      const int v = table[pi < kv.max_pages ? pi : kv.max_pages - 1];
+      pg[0] = pg[1] = pg[2] = pi < kv.max_pages ? v : -1;
+    };
     int pga[3], pgb[3];
-    pages(kb, pga);
-    pages(kbb, pgb);
-    Blk ba, bb;
-    issue(kb, pga, ba);
-    issue(kbb, pgb, bb);
-    compute(kb, ba);
-    if (two) compute(kb2, bb);
+    block_page(unit, pga);
+    block_page(unit + a.n_units, pgb);
+    for (int kb = unit; kb < nkb; kb += 2 * a.n_units) {
+      const int kb2 = kb + a.n_units;
+      const bool two = kb2 < nkb;
+      Blk ba, bb;
+      issue(kb, pga, ba);
+      if (two) issue(kb2, pgb, bb);
+      else issue(kb, pga, bb);                    // a repeat of the first block's loads: no branch around a load
+      block_page(kb + 2 * a.n_units, pga);
+      block_page(kb2 + 2 * a.n_units, pgb);
+      compute(kb, ba);
+      if (two) compute(kb2, bb);
+    }
+  } else {
+    for (int kb = unit; kb < nkb; kb += 2 * a.n_units) {
+      const int kb2 = kb + a.n_units;
+      const bool two = kb2 < nkb;
+      const int kbb = two ? kb2 : kb;             // a repeat of the first block's loads: no branch around a load
+      int pga[3], pgb[3];
+      pages(kb, pga);
+      pages(kbb, pgb);
+      Blk ba, bb;
+      issue(kb, pga, ba);
+      issue(kbb, pgb, bb);
+      compute(kb, ba);
+      if (two) compute(kb2, bb);
+    }
   }
 
   // ---- results: lane holds query column c, channels d*16 + 4g + i
