@@ -892,8 +892,14 @@ hipError_t launch_gemm_resid_split(dllm_ctx* c, hipStream_t s, const void* A, co
     *n_delta = splits - 1;
     return ts_launch<LG_RESID, 1>(s, a, splits);
   }
-  // short sums over few rows: the 128-row tiles fill the chip better
-  const bool t2 = t2_usable(M, K) && (K >= 8192 || ((M + 255) / 256) * ((N + 255) / 256) >= 192);
+  // short sums over few rows: the 128-row tiles fill the chip better, unless the 256-row tiles' K shares still are
+  // long enough to pay for their fill and drain (measured at K = 4096: 5 row tiles, three shares of 1365, do; 4 row
+  // tiles, four shares of 1024, do not)
+  const int tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+  int shares256 = tiles256 > 0 ? 256 / tiles256 : 1;
+  shares256 = shares256 > LG_MAX_DELTA + 1 ? LG_MAX_DELTA + 1 : (shares256 < 1 ? 1 : shares256);
+  const bool shares_pay = shares256 > 1 && K / shares256 >= 1280 && M <= c->map.lg_delta_rows && N == c->cfg.d_model;
+  const bool t2 = t2_usable(M, K) && (K >= 8192 || tiles256 >= 192 || shares_pay);
   const int tiles = t2 ? ((M + 255) / 256) * ((N + 255) / 256) : ((M + 127) / 128) * ((N + LG_BN - 1) / LG_BN);
   int splits = (t2 ? 256 : 512) / tiles;                      // one 256-row workgroup or two 128-row ones fit a CU
   if (splits > LG_MAX_DELTA + 1) splits = LG_MAX_DELTA + 1;
