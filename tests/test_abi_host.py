@@ -181,3 +181,19 @@ def test_host_side_code_under_address_and_undefined_behaviour_sanitizers():
     assert r.returncode == 0, (r.stdout[-2000:], r.stderr[-4000:])
     assert "host check: 0 failure(s)" in r.stdout
     assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr
+
+
+def test_build_refuses_spills_between_lds_copies():
+    """The build's check of the generated code: a kernel that counts its own outstanding memory instructions must not
+    spill to scratch between its first and last copy into LDS; spills outside that window and in other kernels pass."""
+    from paper_2601_07568_amd import build
+    head = "_ZN4dllm9k_attn_dlILi128ELi8ELb1EEEvNS_8AttnArgsE:\n"
+    bad = head + " global_load_lds_dwordx4 v[0:1], off\n scratch_store_dword off, v3, off\n global_load_lds_dwordx4 v[2:3], off\n s_endpgm\n"
+    with pytest.raises(RuntimeError):
+        build._check_counted_loops("kernels_attention.hip", bad)
+    ok = head + " scratch_load_dword v3, off, off\n global_load_lds_dwordx4 v[0:1], off\n global_load_lds_dwordx4 v[2:3], off\n" \
+                " s_waitcnt vmcnt(0)\n scratch_store_dword off, v3, off\n s_endpgm\n"
+    build._check_counted_loops("kernels_attention.hip", ok)
+    other = "_ZN4dllm14k_attn_combineILi128EEEvPKfS2_iPtiil:\n global_load_lds_dwordx4 v[0:1], off\n scratch_store_dword off, v3, off\n" \
+            " global_load_lds_dwordx4 v[2:3], off\n"
+    build._check_counted_loops("kernels_attention.hip", other)
